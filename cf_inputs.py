@@ -1,0 +1,75 @@
+"""Seeded synthetic inputs for the decode block (shared by tests, smoke and bench).
+
+This module holds no arithmetic of the method: it only names the Llama-shaped
+configurations and draws tensors with the stated shapes and distributions.
+Both the CPU oracle's tests and the HIP path's tests feed on the same arrays.
+
+Recipe: one numpy PCG64 generator per (seed); draw order x, W_qkv, W_o,
+k_cache, v_cache; every tensor is drawn in float32 and rounded to fp16 with
+round-to-nearest-even.  x ~ N(0,1); weights ~ N(0, std 0.02); cached K/V rows
+[0, L) ~ N(0,1); rows >= L are fp16 NaN when `poison` is set (correctness
+runs: nothing may read them) and zero otherwise (timing runs).  The cache
+capacity max_seq is L+1 rounded up to a multiple of 128.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class BlockShape:
+    name: str
+    d_model: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    rope_base: float
+    kv_len: int          # default number of cached tokens L (== pos of the new token)
+    batch: int = 1
+
+    @property
+    def n_qkv(self) -> int:
+        return (self.n_q_heads + 2 * self.n_kv_heads) * self.head_dim
+
+
+SHAPES = {
+    "tiny": BlockShape("tiny", 512, 8, 8, 64, 10000.0, 256),
+    "llama2_7b": BlockShape("llama2_7b", 4096, 32, 32, 128, 10000.0, 4096),
+    "llama3_8b": BlockShape("llama3_8b", 4096, 32, 8, 128, 500000.0, 8192),
+    "llama2_70b": BlockShape("llama2_70b", 8192, 64, 8, 128, 10000.0, 32768),
+}
+
+
+def default_max_seq(kv_len: int) -> int:
+    return ((kv_len + 1 + 127) // 128) * 128
+
+
+def make_inputs(shape: BlockShape, seed: int, batch: int | None = None, kv_len: int | None = None,
+                max_seq: int | None = None, poison: bool = True) -> dict:
+    """Draw one layer's inputs as fp16 numpy arrays (host memory)."""
+    B = shape.batch if batch is None else int(batch)
+    L = shape.kv_len if kv_len is None else int(kv_len)
+    S = default_max_seq(L) if max_seq is None else int(max_seq)
+    assert 0 <= L < S
+    rng = np.random.Generator(np.random.PCG64(seed))
+
+    def normal(shp, std):
+        a = rng.standard_normal(size=shp, dtype=np.float32)
+        if std != 1.0:
+            a *= np.float32(std)
+        return a.astype(np.float16)
+
+    D, nq, nkv, d = shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    x = normal((B, D), 1.0)
+    w_qkv = normal((D, shape.n_qkv), 0.02)
+    w_o = normal((nq * d, D), 0.02)
+    fill = np.float16(np.nan) if poison else np.float16(0.0)
+    k_cache = np.full((B, nkv, S, d), fill, dtype=np.float16)
+    v_cache = np.full((B, nkv, S, d), fill, dtype=np.float16)
+    if L > 0:
+        k_cache[:, :, :L, :] = normal((B, nkv, L, d), 1.0)
+        v_cache[:, :, :L, :] = normal((B, nkv, L, d), 1.0)
+    return {"x": x, "w_qkv": w_qkv, "w_o": w_o, "k_cache": k_cache, "v_cache": v_cache,
+            "pos": L, "batch": B, "max_seq": S, "shape": shape}
