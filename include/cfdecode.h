@@ -1,0 +1,133 @@
+/*
+ * cfdecode - one decode step of a transformer attention block as a single fused
+ * HIP kernel for AMD MI355X (gfx950).
+ *
+ * The block is the one the ClusterFusion paper fuses (Alg. 3; definition Eq. 1,
+ * decode semantics Sec. 2.1): QKV projection of the new token's hidden state,
+ * RoPE on q and k, append of the new key/value to the KV cache, split-KV
+ * attention over cached + new token with an online-softmax merge, and the
+ * output projection, summed over heads.
+ *
+ * C ABI, plain pointers and sizes.  Every tensor pointer is a DEVICE pointer to
+ * IEEE binary16 ("fp16") data unless stated otherwise, 16-byte aligned, dense
+ * row-major with the shapes given below.  The caller owns all tensors; the
+ * library owns only a per-handle workspace in device memory.
+ *
+ * All functions return 0 (CF_OK) or a negative CF_E* code; nothing aborts or
+ * throws across this boundary.
+ */
+#ifndef CFDECODE_H
+#define CFDECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CF_OK = 0,
+    CF_EINVAL = -1,        /* null or misaligned pointer, bad shape, pos or batch out of range */
+    CF_EUNSUPPORTED = -2,  /* shape outside the compiled kernel variants, or the grid cannot be co-resident */
+    CF_EHIP = -3,          /* a HIP runtime call failed; see cf_last_hip_error */
+    CF_ENOMEM = -4,        /* host or device allocation failed */
+    CF_ETIMEOUT = -5       /* a cross-workgroup wait inside the kernel gave up (reported by cf_status) */
+};
+
+/* Shape of the block (paper Alg. 3 "Require": hidden size D, heads, head dim). */
+typedef struct cf_config {
+    int32_t d_model;      /* D; multiple of 8 */
+    int32_t n_q_heads;    /* query heads */
+    int32_t n_kv_heads;   /* key/value heads; n_q_heads % n_kv_heads == 0, ratio in {1,2,4,8} */
+    int32_t head_dim;     /* 64 or 128 */
+    int32_t max_batch;    /* largest batch a call may use (1..16) */
+    int32_t max_seq;      /* capacity (rows) of each KV-cache head slice */
+    float   rope_base;    /* RoPE frequency base, e.g. 10000 or 500000 */
+    int32_t flags;        /* bit 0: keep q_rot / attention vectors of the last call for cf_debug_export */
+} cf_config;
+
+#define CF_FLAG_DEBUG_EXPORT 1
+
+typedef struct cf_handle_s *cf_handle;
+
+/*
+ * Create a handle on the current HIP device: validates the shape, allocates and
+ * clears the workspace (exchange slots and counters used between workgroups).
+ * Synchronous.  A handle must not be used from two streams at the same time.
+ */
+int cf_create(const cf_config *cfg, cf_handle *out);
+
+/* Free the workspace.  The caller must have synchronised the streams that used it. */
+int cf_destroy(cf_handle h);
+
+/*
+ * Enqueue one decode step on `stream` (a hipStream_t, NULL for the default
+ * stream) and return without waiting.  Paper Alg. 3 with Eq. 1:
+ *
+ *   [q | k_new | v_new] = x . W_qkv        columns ordered Q heads, K heads, V heads
+ *   q, k_new <- RoPE at position pos       pairs (i, i + head_dim/2), angle pos * rope_base^(-2i/head_dim)
+ *   k_cache[b, g, pos, :] = fp16(k_new),  v_cache[b, g, pos, :] = fp16(v_new)
+ *   a_i = softmax(K_g q_i / sqrt(head_dim))^T V_g   over rows 0..pos (cached rows + the new one),
+ *                                                   g = i / (n_q_heads / n_kv_heads)
+ *   out = concat_i(a_i) . W_o
+ *
+ *   x        [batch, d_model]                                  read
+ *   W_qkv    [d_model, (n_q_heads + 2 n_kv_heads) * head_dim]  read
+ *   W_o      [n_q_heads * head_dim, d_model]                   read
+ *   k_cache  [batch, n_kv_heads, max_seq, head_dim]            rows < pos read, row pos written
+ *   v_cache  same
+ *   pos      number of tokens already cached == index of the new token, 0 <= pos < max_seq
+ *   out      [batch, d_model] fp16, fully overwritten (needs no clearing)
+ *
+ * Storage is fp16, accumulation fp32.  Rows > pos of the caches are neither
+ * read nor written.  No allocation and no host synchronisation happen here.
+ * Errors: CF_EINVAL for null/misaligned pointers, batch outside 1..max_batch,
+ * pos outside 0..max_seq-1; CF_EHIP if the launch fails.
+ */
+int cf_decode_block(cf_handle h, int32_t batch, const void *x, const void *W_qkv, const void *W_o,
+                    void *k_cache, void *v_cache, int32_t pos, void *out, void *stream);
+
+/*
+ * Wait for `stream` and report whether any kernel launched through this handle
+ * gave up on a cross-workgroup wait (CF_ETIMEOUT) since the last cf_status
+ * call.  The fused kernel relies on all its workgroups being resident at once
+ * (Alg. 3 has the same requirement for the blocks of a cluster); a wait that
+ * exceeds the spin limit sets a flag instead of hanging.
+ */
+int cf_status(cf_handle h, void *stream);
+
+/*
+ * Copy intermediate vectors of the most recent call to HOST memory (handle must
+ * have CF_FLAG_DEBUG_EXPORT).  what = 0: rotated queries [batch, n_q_heads,
+ * head_dim]; what = 1: per-head attention outputs a_i, same shape (Alg. 3 step
+ * 7 result).  fp32.  Synchronises `stream`.  `bytes` must equal the tensor size.
+ */
+int cf_debug_export(cf_handle h, int32_t what, void *host_dst, size_t bytes, void *stream);
+
+/*
+ * Tuning knobs (all optional; 0 keeps the default): workgroups per launch,
+ * split count of the projection's reduction dimension, split count of the KV
+ * sequence, spin limit of the in-kernel waits in microseconds.  Alg. 3's
+ * "cluster size" corresponds to workgroups / n_kv_heads.  Returns CF_EINVAL for
+ * values the shape cannot use.
+ */
+int cf_set_tuning(cf_handle h, int32_t workgroups, int32_t k_splits, int32_t kv_splits, int32_t spin_limit_us);
+
+/* Plan of the most recent call, for reports: fills up to n ints
+ * {workgroups, team_size, k_splits, rows_per_split, kv_splits, tokens_per_split,
+ *  out_col_blocks, out_cols_per_block, out_row_splits, lds_bytes}. */
+int cf_get_plan(cf_handle h, int32_t *dst, int32_t n);
+
+/* Algorithmic HBM bytes of one call (weights + cached K/V rows + appended rows + x + out). */
+int64_t cf_algorithmic_bytes(const cf_config *cfg, int32_t batch, int32_t pos);
+
+const char *cf_strerror(int code);
+
+/* hipError_t of the most recent failing HIP call made through this handle (0 if none). */
+int cf_last_hip_error(cf_handle h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CFDECODE_H */

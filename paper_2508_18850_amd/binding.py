@@ -1,0 +1,122 @@
+"""ctypes binding of the C ABI declared in include/cfdecode.h.
+
+Argument marshalling only: every step of the decode block runs inside the HIP
+library.  There is no fallback: if the library is missing or a call fails, an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libcfdecode.so")
+_lib = None
+
+EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_status", "cf_debug_export",
+                    "cf_set_tuning", "cf_get_plan", "cf_algorithmic_bytes", "cf_strerror", "cf_last_hip_error")
+
+CF_FLAG_DEBUG_EXPORT = 1
+
+
+class CfConfig(ctypes.Structure):
+    _fields_ = [("d_model", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("max_batch", ctypes.c_int32), ("max_seq", ctypes.c_int32),
+                ("rope_base", ctypes.c_float), ("flags", ctypes.c_int32)]
+
+
+class CfError(RuntimeError):
+    def __init__(self, code, msg, hip=0):
+        super().__init__("cfdecode error %d (%s)%s" % (code, msg, " hip=%d" % hip if hip else ""))
+        self.code = code
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libcfdecode.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError("%s not built: run `python -c 'import __graft_entry__ as g; g.build()'`" % _LIB_PATH)
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        lib.cf_create.argtypes = [ctypes.POINTER(CfConfig), ctypes.POINTER(vp)]
+        lib.cf_destroy.argtypes = [vp]
+        lib.cf_decode_block.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp]
+        lib.cf_status.argtypes = [vp, vp]
+        lib.cf_debug_export.argtypes = [vp, i32, vp, ctypes.c_size_t, vp]
+        lib.cf_set_tuning.argtypes = [vp, i32, i32, i32, i32]
+        lib.cf_get_plan.argtypes = [vp, ctypes.POINTER(i32), i32]
+        lib.cf_algorithmic_bytes.argtypes = [ctypes.POINTER(CfConfig), i32, i32]
+        lib.cf_algorithmic_bytes.restype = ctypes.c_int64
+        lib.cf_strerror.argtypes = [ctypes.c_int]
+        lib.cf_strerror.restype = ctypes.c_char_p
+        lib.cf_last_hip_error.argtypes = [vp]
+        for name in ("cf_create", "cf_destroy", "cf_decode_block", "cf_status", "cf_debug_export",
+                     "cf_set_tuning", "cf_get_plan", "cf_last_hip_error"):
+            getattr(lib, name).restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def algorithmic_bytes(cfg: CfConfig, batch: int, pos: int) -> int:
+    return int(load_library().cf_algorithmic_bytes(ctypes.byref(cfg), batch, pos))
+
+
+PLAN_FIELDS = ("workgroups", "team_size", "k_splits", "rows_per_split", "kv_splits", "tokens_per_split",
+               "out_col_blocks", "out_cols_per_block", "out_row_splits", "lds_bytes")
+
+
+class DecodeBlock:
+    """One handle of the library.  Tensors are passed as raw device addresses
+    (e.g. torch_tensor.data_ptr()); `stream` is a hipStream_t value."""
+
+    def __init__(self, d_model, n_q_heads, n_kv_heads, head_dim, max_batch, max_seq, rope_base, debug=False):
+        self._lib = load_library()
+        self.cfg = CfConfig(d_model, n_q_heads, n_kv_heads, head_dim, max_batch, max_seq, rope_base,
+                            CF_FLAG_DEBUG_EXPORT if debug else 0)
+        self._h = ctypes.c_void_p()
+        self._check(self._lib.cf_create(ctypes.byref(self.cfg), ctypes.byref(self._h)))
+
+    def _check(self, rc):
+        if rc != 0:
+            hip = self._lib.cf_last_hip_error(self._h) if self._h else 0
+            raise CfError(rc, self._lib.cf_strerror(rc).decode(), hip)
+
+    def decode_block(self, batch, x, w_qkv, w_o, k_cache, v_cache, pos, out, stream=0):
+        rc = self._lib.cf_decode_block(self._h, batch, x, w_qkv, w_o, k_cache, v_cache, pos, out, stream)
+        if rc != 0:
+            self._check(rc)
+
+    def decode_block_rc(self, batch, x, w_qkv, w_o, k_cache, v_cache, pos, out, stream=0) -> int:
+        """Same call, returning the library's code instead of raising (for error-path tests)."""
+        return int(self._lib.cf_decode_block(self._h, batch, x, w_qkv, w_o, k_cache, v_cache, pos, out, stream))
+
+    def status(self, stream=0):
+        self._check(self._lib.cf_status(self._h, stream))
+
+    def set_tuning(self, workgroups=0, k_splits=0, kv_splits=0, spin_limit_us=0):
+        self._check(self._lib.cf_set_tuning(self._h, workgroups, k_splits, kv_splits, spin_limit_us))
+
+    def plan(self) -> dict:
+        arr = (ctypes.c_int32 * len(PLAN_FIELDS))()
+        self._check(self._lib.cf_get_plan(self._h, arr, len(PLAN_FIELDS)))
+        return dict(zip(PLAN_FIELDS, list(arr)))
+
+    def debug_export(self, what, host_array, stream=0):
+        """host_array: contiguous float32 numpy array of shape [batch, n_q_heads, head_dim]."""
+        self._check(self._lib.cf_debug_export(self._h, what, host_array.ctypes.data, host_array.nbytes, stream))
+
+    def close(self):
+        if self._h:
+            self._lib.cf_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

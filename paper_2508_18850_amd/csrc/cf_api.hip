@@ -1,0 +1,378 @@
+// C ABI of libcfdecode: handle, argument validation, work plan, launch.
+#include "../../include/cfdecode.h"
+#include "cf_params.h"
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using cf::Params;
+
+struct cf_handle_s {
+    cf_config cfg;
+    int device = 0;
+    int num_cu = 0;
+    int G = 1;
+    int nqkv = 0;
+    int nch = 0;
+    // workspace (one allocation)
+    char *ws = nullptr;
+    size_t ws_bytes = 0;
+    size_t counters_bytes = 0;
+    uint32_t *cnt1 = nullptr, *cnt2 = nullptr, *cnt3 = nullptr, *done = nullptr, *err = nullptr;
+    float *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *dbg_q = nullptr, *dbg_attn = nullptr;
+    double *inv_freq = nullptr;
+    // tuning
+    int tune_w = 0, tune_ks = 0, tune_ns = 0;
+    long long spin_ticks = 200000000LL;   // 2 s of the 100 MHz wall clock
+    int wg_per_cu[3] = {0, 0, 0};         // resident workgroups per CU for batch tiles 1, 4, 16 (0 = not probed)
+    int last_batch = 0;
+    int last_plan[10] = {0};
+    int last_hip = 0;
+};
+
+namespace {
+
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int batch_tile(int batch) { return batch <= 1 ? 1 : batch <= 4 ? 4 : 16; }
+int tile_index(int bt) { return bt == 1 ? 0 : bt == 4 ? 1 : 2; }
+
+constexpr int kMaxKS = 32;
+constexpr size_t kLdsLimit = 160 * 1024 - 256;   // LDS per workgroup on gfx950, minus the static flags
+
+bool aligned16(const void *p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int default_workgroups(const cf_handle_s *h)
+{
+    int w = h->tune_w > 0 ? h->tune_w : h->num_cu;
+    w -= w % h->cfg.n_kv_heads;
+    return w;
+}
+
+// Fill the work split of one call.  Returns CF_OK or an error.
+int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
+{
+    const cf_config &c = h->cfg;
+    const int hd = c.head_dim, G = h->G, bt = batch_tile(batch);
+    const int W = default_workgroups(h);
+    if (W <= 0) return CF_EUNSUPPORTED;
+    const int TS = W / c.n_kv_heads;
+    p->W = W;
+    p->TS = TS;
+
+    // projection: split the reduction dimension so that (G+2)*KS items balance over TS members
+    {
+        int best = 0;
+        long best_cost = 0;
+        for (int ks = 1; ks <= kMaxKS; ks *= 2) {
+            if (h->tune_ks > 0 && ks != h->tune_ks) continue;
+            const int rps = ceil_div(c.d_model, ks);
+            if (rps < 8 && ks > 1) continue;
+            const size_t lds = ((size_t)bt * rps + (size_t)cf::kWaves * bt * hd) * sizeof(float);
+            if (lds > kLdsLimit) continue;
+            const long cost = (long)ceil_div((G + 2) * ks, TS) * rps;
+            if (!best || cost < best_cost) {
+                best = ks;
+                best_cost = cost;
+            }
+        }
+        if (!best) return h->tune_ks > 0 ? CF_EINVAL : CF_EUNSUPPORTED;
+        p->KS = best;
+        p->RPS = ceil_div(c.d_model, best);
+    }
+    // attention: split the cached sequence so that B*NS items balance over TS members
+    {
+        const int rows_per_step = cf::kThreads / (hd / 8);
+        int best = 0;
+        long best_cost = 0;
+        for (int ns = 1; ns <= cf::kMaxKvSplits; ns *= 2) {
+            if (h->tune_ns > 0 && ns != h->tune_ns) continue;
+            int tps = ceil_div(ceil_div(pos, ns), rows_per_step) * rows_per_step;
+            if (tps == 0) tps = rows_per_step;
+            const long cost = (long)ceil_div(batch * ns, TS) * (tps + 64);
+            if (!best || cost < best_cost) {
+                best = ns;
+                best_cost = cost;
+            }
+        }
+        if (!best) return CF_EINVAL;
+        p->NS = best;
+        int tps = ceil_div(ceil_div(pos, best), rows_per_step) * rows_per_step;
+        p->TPS = tps ? tps : rows_per_step;
+    }
+    // output projection: G heads x NC3 column blocks x RS3 row splits per team
+    {
+        const int nch = h->nch;
+        int best_nc = 0, best_rs = 0;
+        double best_cost = 0;
+        for (int rs = 1; rs <= 8 && hd / rs >= cf::kWaves; rs *= 2) {
+            for (int nc = 1; nc <= nch; nc *= 2) {
+                const int cw = ceil_div(nch, nc) * cf::kOutChunk;
+                const double cost = (double)ceil_div(G * nc * rs, TS) * (hd / rs) * cw;
+                if (!best_nc || cost < best_cost * 0.999) {
+                    best_nc = nc;
+                    best_rs = rs;
+                    best_cost = cost;
+                }
+            }
+        }
+        p->NC3 = best_nc;
+        p->RS3 = best_rs;
+        p->CW3 = ceil_div(nch, best_nc) * cf::kOutChunk;
+        p->NC3 = ceil_div(nch * cf::kOutChunk, p->CW3);
+    }
+    p->NCH = h->nch;
+    return CF_OK;
+}
+
+void fill_static(const cf_handle_s *h, Params *p)
+{
+    const cf_config &c = h->cfg;
+    p->cnt1 = h->cnt1;
+    p->cnt2 = h->cnt2;
+    p->cnt3 = h->cnt3;
+    p->done = h->done;
+    p->err = h->err;
+    p->p1 = h->p1;
+    p->p2 = h->p2;
+    p->p3 = h->p3;
+    p->inv_freq = h->inv_freq;
+    p->dbg_q = (c.flags & CF_FLAG_DEBUG_EXPORT) ? h->dbg_q : nullptr;
+    p->dbg_attn = (c.flags & CF_FLAG_DEBUG_EXPORT) ? h->dbg_attn : nullptr;
+    p->D = c.d_model;
+    p->nq = c.n_q_heads;
+    p->nkv = c.n_kv_heads;
+    p->max_seq = c.max_seq;
+    p->nqkv = h->nqkv;
+    p->qk_scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)c.head_dim));
+    p->spin_ticks = h->spin_ticks;
+}
+
+int hip_fail(cf_handle_s *h, hipError_t e)
+{
+    if (h) h->last_hip = (int)e;
+    return CF_EHIP;
+}
+
+// Check (once per batch tile) that the whole grid can be resident at the same time.
+int check_residency(cf_handle_s *h, const Params &p, int bt, size_t lds_bytes)
+{
+    int &slot = h->wg_per_cu[tile_index(bt)];
+    if (slot == 0) {
+        int n = 0;
+        hipError_t e = cf::max_workgroups_per_cu(h->cfg.head_dim, h->G, bt, lds_bytes, &n);
+        if (e != hipSuccess) return hip_fail(h, e);
+        slot = n > 0 ? n : -1;
+    }
+    if (slot < 0 || (long)slot * h->num_cu < p.W) return CF_EUNSUPPORTED;
+    return CF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cf_create(const cf_config *cfg, cf_handle *out)
+{
+    if (!cfg || !out) return CF_EINVAL;
+    *out = nullptr;
+    const cf_config &c = *cfg;
+    if (c.d_model < 8 || c.d_model % 8 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.n_q_heads % c.n_kv_heads ||
+        c.max_batch < 1 || c.max_batch > 16 || c.max_seq < 1 || !(c.rope_base > 1.0f))
+        return CF_EINVAL;
+    if (c.head_dim != 64 && c.head_dim != 128) return CF_EUNSUPPORTED;
+    const int G = c.n_q_heads / c.n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return CF_EUNSUPPORTED;
+
+    cf_handle_s *h = new (std::nothrow) cf_handle_s();
+    if (!h) return CF_ENOMEM;
+    h->cfg = c;
+    h->G = G;
+    h->nqkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    h->nch = ceil_div(c.d_model, cf::kOutChunk);
+
+    hipError_t e = hipGetDevice(&h->device);
+    hipDeviceProp_t prop;
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, h->device);
+    if (e != hipSuccess) {
+        delete h;
+        return CF_EHIP;
+    }
+    h->num_cu = prop.multiProcessorCount;
+    if (c.n_kv_heads > h->num_cu) {
+        delete h;
+        return CF_EUNSUPPORTED;
+    }
+
+    const size_t B = (size_t)c.max_batch, hd = (size_t)c.head_dim;
+    const size_t line = cf::kCounterStride * sizeof(uint32_t);
+    const size_t n_counters = 2 * (size_t)c.n_kv_heads + (size_t)h->nch + 2;
+    h->counters_bytes = align_up(n_counters * line, 256);
+    const size_t p1_bytes = align_up((size_t)kMaxKS * B * h->nqkv * sizeof(float), 256);
+    const size_t p2_bytes = align_up(B * c.n_q_heads * cf::kMaxKvSplits * (hd + cf::kP2Stride) * sizeof(float), 256);
+    const size_t p3_bytes = align_up((size_t)c.n_q_heads * 8 * B * c.d_model * sizeof(float), 256);
+    const size_t dbg_bytes = align_up(B * c.n_q_heads * hd * sizeof(float), 256);
+    const size_t freq_bytes = align_up(hd / 2 * sizeof(double), 256);
+    h->ws_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes + 2 * dbg_bytes + freq_bytes;
+    e = hipMalloc(reinterpret_cast<void **>(&h->ws), h->ws_bytes);
+    if (e != hipSuccess) {
+        delete h;
+        return e == hipErrorOutOfMemory ? CF_ENOMEM : CF_EHIP;
+    }
+    char *cur = h->ws;
+    h->cnt1 = reinterpret_cast<uint32_t *>(cur);
+    h->cnt2 = h->cnt1 + (size_t)c.n_kv_heads * cf::kCounterStride;
+    h->cnt3 = h->cnt2 + (size_t)c.n_kv_heads * cf::kCounterStride;
+    h->done = h->cnt3 + (size_t)h->nch * cf::kCounterStride;
+    h->err = h->done + cf::kCounterStride;
+    cur += h->counters_bytes;
+    h->p1 = reinterpret_cast<float *>(cur);
+    cur += p1_bytes;
+    h->p2 = reinterpret_cast<float *>(cur);
+    cur += p2_bytes;
+    h->p3 = reinterpret_cast<float *>(cur);
+    cur += p3_bytes;
+    h->dbg_q = reinterpret_cast<float *>(cur);
+    cur += dbg_bytes;
+    h->dbg_attn = reinterpret_cast<float *>(cur);
+    cur += dbg_bytes;
+    h->inv_freq = reinterpret_cast<double *>(cur);
+
+    std::vector<double> freq(hd / 2);
+    for (size_t i = 0; i < hd / 2; ++i) freq[i] = std::pow((double)c.rope_base, -2.0 * (double)i / (double)hd);
+    e = hipMemset(h->ws, 0, h->ws_bytes);
+    if (e == hipSuccess) e = hipMemcpy(h->inv_freq, freq.data(), freq.size() * sizeof(double), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        (void)hipFree(h->ws);
+        delete h;
+        return CF_EHIP;
+    }
+    *out = h;
+    return CF_OK;
+}
+
+int cf_destroy(cf_handle h)
+{
+    if (!h) return CF_EINVAL;
+    hipError_t e = hipFree(h->ws);
+    delete h;
+    return e == hipSuccess ? CF_OK : CF_EHIP;
+}
+
+int cf_decode_block(cf_handle h, int32_t batch, const void *x, const void *W_qkv, const void *W_o, void *k_cache,
+                    void *v_cache, int32_t pos, void *out, void *stream)
+{
+    if (!h) return CF_EINVAL;
+    if (batch < 1 || batch > h->cfg.max_batch || pos < 0 || pos >= h->cfg.max_seq) return CF_EINVAL;
+    if (!aligned16(x) || !aligned16(W_qkv) || !aligned16(W_o) || !aligned16(k_cache) || !aligned16(v_cache) ||
+        !aligned16(out))
+        return CF_EINVAL;
+    Params p;
+    std::memset(&p, 0, sizeof p);
+    fill_static(h, &p);
+    p.x = static_cast<const uint16_t *>(x);
+    p.wqkv = static_cast<const uint16_t *>(W_qkv);
+    p.wo = static_cast<const uint16_t *>(W_o);
+    p.kc = static_cast<uint16_t *>(k_cache);
+    p.vc = static_cast<uint16_t *>(v_cache);
+    p.out = static_cast<uint16_t *>(out);
+    p.B = batch;
+    p.pos = pos;
+    int rc = make_plan(h, batch, pos, &p);
+    if (rc != CF_OK) return rc;
+    const int bt = batch_tile(batch);
+    const size_t lds = cf::lds_floats(p, h->cfg.head_dim, h->G, bt) * sizeof(float);
+    if (lds > kLdsLimit) return CF_EUNSUPPORTED;
+    rc = check_residency(h, p, bt, lds);
+    if (rc != CF_OK) return rc;
+    const int plan[10] = {p.W, p.TS, p.KS, p.RPS, p.NS, p.TPS, p.NC3, p.CW3, p.RS3, (int)lds};
+    std::memcpy(h->last_plan, plan, sizeof plan);
+    h->last_batch = batch;
+    hipError_t e = cf::launch_fused(p, h->cfg.head_dim, h->G, bt, lds, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e);
+    return CF_OK;
+}
+
+int cf_status(cf_handle h, void *stream)
+{
+    if (!h) return CF_EINVAL;
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(h, e);
+    uint32_t flag = 0;
+    e = hipMemcpy(&flag, h->err, sizeof flag, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(h, e);
+    if (flag) {
+        // a wait gave up: the counters may be inconsistent, start from a clean slate
+        e = hipMemset(h->ws, 0, h->counters_bytes);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) return hip_fail(h, e);
+        return CF_ETIMEOUT;
+    }
+    return CF_OK;
+}
+
+int cf_debug_export(cf_handle h, int32_t what, void *host_dst, size_t bytes, void *stream)
+{
+    if (!h || !host_dst || (what != 0 && what != 1)) return CF_EINVAL;
+    if (!(h->cfg.flags & CF_FLAG_DEBUG_EXPORT) || h->last_batch < 1) return CF_EINVAL;
+    const size_t want = (size_t)h->last_batch * h->cfg.n_q_heads * h->cfg.head_dim * sizeof(float);
+    if (bytes != want) return CF_EINVAL;
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    if (e == hipSuccess) e = hipMemcpy(host_dst, what == 0 ? h->dbg_q : h->dbg_attn, bytes, hipMemcpyDeviceToHost);
+    return e == hipSuccess ? CF_OK : hip_fail(h, e);
+}
+
+int cf_set_tuning(cf_handle h, int32_t workgroups, int32_t k_splits, int32_t kv_splits, int32_t spin_limit_us)
+{
+    if (!h || workgroups < 0 || k_splits < 0 || kv_splits < 0 || spin_limit_us < 0) return CF_EINVAL;
+    auto pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
+    if (workgroups && (workgroups % h->cfg.n_kv_heads || workgroups > 8 * h->num_cu)) return CF_EINVAL;
+    if (k_splits && (!pow2(k_splits) || k_splits > kMaxKS)) return CF_EINVAL;
+    if (kv_splits && (!pow2(kv_splits) || kv_splits > cf::kMaxKvSplits)) return CF_EINVAL;
+    h->tune_w = workgroups;
+    h->tune_ks = k_splits;
+    h->tune_ns = kv_splits;
+    h->wg_per_cu[0] = h->wg_per_cu[1] = h->wg_per_cu[2] = 0;   // LDS size may change: probe residency again
+    if (spin_limit_us) h->spin_ticks = (long long)spin_limit_us * 100;
+    return CF_OK;
+}
+
+int cf_get_plan(cf_handle h, int32_t *dst, int32_t n)
+{
+    if (!h || !dst || n < 0) return CF_EINVAL;
+    for (int i = 0; i < n && i < 10; ++i) dst[i] = h->last_plan[i];
+    return CF_OK;
+}
+
+int64_t cf_algorithmic_bytes(const cf_config *cfg, int32_t batch, int32_t pos)
+{
+    if (!cfg) return 0;
+    const int64_t D = cfg->d_model, nq = cfg->n_q_heads, nkv = cfg->n_kv_heads, d = cfg->head_dim, B = batch;
+    const int64_t weights = 2 * D * (nq + 2 * nkv) * d + 2 * nq * d * D;
+    const int64_t kv_read = B * 2 * nkv * (int64_t)pos * d * 2;
+    const int64_t appended = B * 2 * nkv * d * 2;
+    const int64_t io = 2 * B * D * 2;
+    return weights + kv_read + appended + io;
+}
+
+const char *cf_strerror(int code)
+{
+    switch (code) {
+    case CF_OK: return "ok";
+    case CF_EINVAL: return "invalid argument";
+    case CF_EUNSUPPORTED: return "unsupported shape or launch configuration";
+    case CF_EHIP: return "HIP runtime error";
+    case CF_ENOMEM: return "out of memory";
+    case CF_ETIMEOUT: return "a cross-workgroup wait inside the kernel timed out";
+    default: return "unknown error";
+    }
+}
+
+int cf_last_hip_error(cf_handle h) { return h ? h->last_hip : 0; }
+
+}  // extern "C"

@@ -1,0 +1,51 @@
+// Internal: kernel argument block and launcher interface shared by the host
+// side (cf_api.hip) and the device side (cf_fused_kernel.hip) of libcfdecode.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cf {
+
+constexpr int kThreads = 512;              // threads per workgroup (8 wavefronts of 64)
+constexpr int kWaves = kThreads / 64;
+constexpr int kOutChunk = 512;             // output columns one wavefront covers with one 128-bit load per lane
+constexpr int kP2Stride = 4;               // floats in front of the accumulator in a split-KV partial: m, l, pad, pad
+constexpr int kCounterStride = 32;         // uint32 words between two counters (one 128-byte line each)
+constexpr int kMaxKSplits = 64;
+constexpr int kMaxKvSplits = 64;
+
+// Everything the fused kernel needs, passed by value.
+struct Params {
+    const uint16_t *x, *wqkv, *wo;
+    uint16_t *kc, *vc, *out;
+    // workspace
+    uint32_t *cnt1;        // [n_kv]  arrivals of projection items per team
+    uint32_t *cnt2;        // [n_kv]  arrivals of attention items per team
+    uint32_t *cnt3;        // [ceil(D/512)] arrivals of output-projection partials per 512-column chunk
+    uint32_t *done;        // workgroups that have finished
+    uint32_t *err;         // set to 1 when a wait gave up
+    float *p1;             // [k_splits][B][Nqkv] partial projections
+    float *p2;             // [B][n_q][kv_splits][head_dim + kP2Stride] split-KV partials
+    float *p3;             // [n_q * row_splits][B][D] per-head partial outputs
+    const double *inv_freq;// [head_dim/2] RoPE frequencies base^(-2i/d)
+    float *dbg_q, *dbg_attn;   // [B][n_q][head_dim] or null
+    int D, nq, nkv, B, pos, max_seq, nqkv;
+    int W, TS;             // workgroups, workgroups per team (team = one KV head)
+    int KS, RPS;           // projection: splits of the reduction dimension, rows per split
+    int NS, TPS;           // attention: splits of the cached sequence, tokens per split
+    int NC3, CW3, RS3;     // output projection: column blocks, columns per block, row splits per head
+    int NCH;               // number of 512-column chunks of the output
+    float qk_scale_log2e;  // log2(e)/sqrt(head_dim)
+    long long spin_ticks;  // wait limit in 100 MHz ticks
+};
+
+// Launch the variant for (head_dim, group size, batch tile).  Returns a hipError_t.
+hipError_t launch_fused(const Params &p, int head_dim, int group, int batch_tile, size_t lds_bytes,
+                        hipStream_t stream);
+// Workgroups of that variant that fit on one CU with `lds_bytes` of LDS each (0 = variant missing).
+hipError_t max_workgroups_per_cu(int head_dim, int group, int batch_tile, size_t lds_bytes, int *out);
+// LDS floats needed by the three phases for the given plan.
+size_t lds_floats(const Params &p, int head_dim, int group, int batch_tile);
+
+}  // namespace cf

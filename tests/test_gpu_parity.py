@@ -1,0 +1,194 @@
+"""GPU parity: the fused HIP decode block against the CPU oracle, through the C ABI.
+
+Tolerance on the block output (fp16 storage, fp32 accumulation):
+    max|err| <= 1e-2 * max|ref| + 1e-3
+plus tighter stage-wise checks (rotated queries, per-head attention vectors,
+appended cache rows), because the absolute term above is loose for outputs of
+magnitude ~0.1.
+"""
+import dataclasses
+import sys
+
+import numpy as np
+import pytest
+
+import cf_inputs
+from oracle import decode_block as orc
+from oracle import c_oracle
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def _log(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+class Runner:
+    """Uploads one case, runs the library, downloads everything the checks need."""
+
+    def __init__(self, shape, batch, max_seq, debug=True):
+        from paper_2508_18850_amd import DecodeBlock
+        self.shape, self.batch, self.max_seq = shape, batch, max_seq
+        self.blk = DecodeBlock(shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, batch, max_seq,
+                               shape.rope_base, debug=debug)
+        self.stream = torch.cuda.current_stream().cuda_stream
+
+    def run(self, inp, pos, out_fill=None):
+        dev = torch.device("cuda:0")
+        t = {k: torch.from_numpy(inp[k]).to(dev) for k in ("x", "w_qkv", "w_o", "k_cache", "v_cache")}
+        out = torch.empty((self.batch, self.shape.d_model), dtype=torch.float16, device=dev)
+        if out_fill is not None:
+            out.fill_(out_fill)
+        self.blk.decode_block(self.batch, t["x"].data_ptr(), t["w_qkv"].data_ptr(), t["w_o"].data_ptr(),
+                              t["k_cache"].data_ptr(), t["v_cache"].data_ptr(), pos, out.data_ptr(), self.stream)
+        self.blk.status(self.stream)
+        res = {"out": out.cpu().numpy(), "k_cache": t["k_cache"].cpu().numpy(), "v_cache": t["v_cache"].cpu().numpy()}
+        shp = (self.batch, self.shape.n_q_heads, self.shape.head_dim)
+        for what, key in ((0, "q_rot"), (1, "attn")):
+            a = np.empty(shp, dtype=np.float32)
+            self.blk.debug_export(what, a, self.stream)
+            res[key] = a
+        return res
+
+
+def oracle(inp, shape, pos, use_c=False):
+    fn = c_oracle.decode_block if use_c else orc.decode_block
+    return fn(inp["x"], inp["w_qkv"], inp["w_o"], inp["k_cache"], inp["v_cache"], pos,
+              shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.rope_base)
+
+
+def check(res, ref, inp, pos, label):
+    out = res["out"].astype(np.float64)
+    mref = np.abs(ref["out"]).max()
+    err = np.abs(out - ref["out"]).max()
+    tol = 1e-2 * mref + 1e-3
+    rel_rms = np.sqrt(np.mean((out - ref["out"]) ** 2) / np.mean(ref["out"] ** 2))
+    _log("%s: max|err| %.3e tol %.3e max|ref| %.3e rel-rms %.2e" % (label, err, tol, mref, rel_rms))
+    assert np.isfinite(out).all()
+    assert err <= tol
+    assert rel_rms < 5e-3                      # fp16 output rounding alone is ~3e-4
+    # stage-wise: fp32 on-chip values against the fp64 oracle
+    for key, rtol in (("q_rot", 2e-5), ("attn", 2e-4)):
+        e = np.abs(res[key].astype(np.float64) - ref[key]).max()
+        assert e <= rtol * np.abs(ref[key]).max() + 1e-6, (key, e)
+    # appended rows: fp16 rounding of the oracle's values (1 ulp slack), all other rows untouched bit for bit
+    for cache, refrow in (("k_cache", ref["k_rot"]), ("v_cache", ref["v_new"])):
+        got = res[cache][:, :, pos, :].astype(np.float64)
+        assert np.all(np.abs(got - refrow) <= np.abs(refrow) * 2.0 ** -10 + 2.0 ** -24), cache
+        before = inp[cache].view(np.uint16).copy()
+        after = res[cache].view(np.uint16).copy()
+        before[:, :, pos, :] = 0
+        after[:, :, pos, :] = 0
+        assert np.array_equal(before, after), cache + ": rows other than pos were modified"
+
+
+SMALL = cf_inputs.BlockShape("small", 264, 4, 2, 64, 10000.0, 77)
+
+
+@pytest.mark.parametrize("name,shape,batch,kv_len", [
+    ("tiny", cf_inputs.SHAPES["tiny"], 1, 256),
+    ("ragged_d64_g2_b3", SMALL, 3, 77),
+    ("d128_g4_b2", cf_inputs.BlockShape("s", 1024, 16, 4, 128, 500000.0, 333), 2, 333),
+    ("d128_g8_b1", cf_inputs.BlockShape("s", 512, 16, 2, 128, 10000.0, 1000), 1, 1000),
+    ("d128_g1_b16", cf_inputs.BlockShape("s", 512, 8, 8, 128, 10000.0, 130), 16, 130),
+    ("d64_g8_b5", cf_inputs.BlockShape("s", 256, 8, 1, 64, 10000.0, 45), 5, 45),
+])
+def test_small_shapes_match_oracle(name, shape, batch, kv_len):
+    _log("case %s B=%d L=%d" % (name, batch, kv_len))
+    inp = cf_inputs.make_inputs(shape, seed=11, batch=batch, kv_len=kv_len)
+    r = Runner(shape, batch, inp["max_seq"])
+    res = r.run(inp, kv_len, out_fill=float("nan"))
+    _log("plan %s" % r.blk.plan())
+    check(res, oracle(inp, shape, kv_len), inp, kv_len, name)
+
+
+@pytest.mark.parametrize("pos", [0, 1, 2, 31, 32, 33, 255])
+def test_edge_positions(pos):
+    """Empty cache (KV length 1 = the V projection), fewer tokens than splits,
+    one wave-step boundary, and the last row of the cache capacity."""
+    shape = cf_inputs.SHAPES["tiny"]
+    _log("edge pos=%d" % pos)
+    inp = cf_inputs.make_inputs(shape, seed=3, kv_len=pos, max_seq=256)
+    r = Runner(shape, 1, 256)
+    res = r.run(inp, pos)
+    ref = oracle(inp, shape, pos)
+    check(res, ref, inp, pos, "pos=%d" % pos)
+    if pos == 0:
+        y = inp["x"].astype(np.float64) @ inp["w_qkv"].astype(np.float64)
+        v = y[:, (shape.n_q_heads + shape.n_kv_heads) * shape.head_dim:]
+        want = v @ inp["w_o"].astype(np.float64)            # MHA: concat of v_new per head is v itself
+        assert np.abs(res["out"].astype(np.float64) - want).max() <= 1e-2 * np.abs(want).max() + 1e-3
+
+
+def test_repeated_calls_and_decode_sequence():
+    """Three consecutive steps on one handle: each step's appended row is read by the next."""
+    shape = dataclasses.replace(cf_inputs.SHAPES["tiny"], n_kv_heads=4)
+    L = 100
+    inp = cf_inputs.make_inputs(shape, seed=5, batch=2, kv_len=L, max_seq=128)
+    r = Runner(shape, 2, 128)
+    cur = dict(inp)
+    rng = np.random.default_rng(0)
+    for step in range(3):
+        _log("sequence step %d" % step)
+        pos = L + step
+        cur["x"] = rng.standard_normal(inp["x"].shape).astype(np.float16)
+        ref = oracle(cur, shape, pos)
+        res = r.run(cur, pos)
+        check(res, ref, cur, pos, "step%d" % step)
+        cur["k_cache"], cur["v_cache"] = res["k_cache"], res["v_cache"]   # carry the GPU-written cache forward
+
+
+def test_planted_dominant_keys():
+    """A key that dominates the softmax at the first cached token, at a split
+    boundary, at the last cached token and at the NEW token must select its value."""
+    shape = cf_inputs.SHAPES["tiny"]
+    L = 256
+    inp = cf_inputs.make_inputs(shape, seed=8, kv_len=L)
+    base = oracle(inp, shape, L)
+    r = Runner(shape, 1, inp["max_seq"])
+    for t in (0, 63, 64, L - 1):
+        _log("planted key at %d" % t)
+        mod = dict(inp)
+        kc = inp["k_cache"].copy()
+        for h in range(shape.n_kv_heads):
+            q = base["q_rot"][0, h]
+            kc[0, h, t] = (60.0 * q / (q @ q) * np.sqrt(shape.head_dim)).astype(np.float16)
+        mod["k_cache"] = kc
+        ref = oracle(mod, shape, L)
+        res = r.run(mod, L)
+        check(res, ref, mod, L, "planted@%d" % t)
+        assert np.abs(res["attn"][0] - inp["v_cache"][0, :, t].astype(np.float64)).max() < 1e-3
+    # new token dominant: scale x so that q.k_new is huge compared with cached scores
+    _log("planted key at the new token")
+    mod = dict(inp)
+    mod["x"] = (inp["x"].astype(np.float32) * 12.0).astype(np.float16)
+    mod["w_qkv"] = inp["w_qkv"].copy()
+    nq, nkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    mod["w_qkv"][:, nq * d:(nq + nkv) * d] = mod["w_qkv"][:, :nq * d]      # k_new == q  ->  score |q|^2/sqrt(d)
+    ref = oracle(mod, shape, L)
+    res = r.run(mod, L)
+    check(res, ref, mod, L, "planted@new")
+    w_new_min = min(orc.attention_weights(ref["q_rot"][0, h], np.concatenate(
+        [mod["k_cache"][0, h, :L].astype(np.float64), ref["k_rot"][0, h][None]], 0))[-1] for h in range(nq))
+    assert w_new_min > 0.99
+
+
+def test_error_paths_do_not_launch():
+    from paper_2508_18850_amd import DecodeBlock, CfError
+    shape = cf_inputs.SHAPES["tiny"]
+    blk = DecodeBlock(shape.d_model, 8, 8, 64, 2, 128, 10000.0)
+    buf = torch.zeros(1 << 20, dtype=torch.float16, device="cuda:0")
+    p = buf.data_ptr()
+    assert blk.decode_block_rc(3, p, p, p, p, p, 0, p) == -1          # batch > max_batch
+    assert blk.decode_block_rc(1, p, p, p, p, p, 128, p) == -1        # pos == max_seq
+    assert blk.decode_block_rc(1, p, p, p, p, p, -1, p) == -1
+    assert blk.decode_block_rc(1, p + 2, p, p, p, p, 0, p) == -1      # misaligned
+    assert blk.decode_block_rc(1, 0, p, p, p, p, 0, p) == -1          # null
+    with pytest.raises(CfError):
+        DecodeBlock(512, 8, 8, 96, 1, 128, 10000.0)                    # head_dim not compiled
+    with pytest.raises(CfError):
+        DecodeBlock(512, 8, 3, 64, 1, 128, 10000.0)                    # n_q % n_kv != 0
+    blk.status()
+    blk.close()
