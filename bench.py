@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused decode block on one MI355X.
+
+A step is one call of cf_decode_block (the whole hot path: QKV projection, RoPE,
+KV append, split-KV attention, output projection) on one layer's buffers.  The
+steps rotate over a stack of distinct layers whose total size exceeds the 256 MB
+Infinity Cache, so weights and KV rows really come from HBM, as in a model with
+many layers.  All inputs are synthetic, generated on the device before timing.
+
+Prints ONE JSON line on stdout (details go to stderr).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "µs per fused decode-block step and achieved HBM GB/s (% of peak), batch 1"
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
+# keyed by workload name; None = not measured for that workload.
+MEASURED_TRAFFIC = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="llama2_7b", help="shape name from cf_inputs.SHAPES")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--kv-len", type=int, default=None)
+    ap.add_argument("--layers", type=int, default=0, help="distinct layer buffer sets to rotate over (0 = auto)")
+    ap.add_argument("--workgroups", type=int, default=0)
+    ap.add_argument("--k-splits", type=int, default=0)
+    ap.add_argument("--kv-splits", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg")
+    return ap.parse_args()
+
+
+def cpu_baseline(shape, batch, kv_len, budget_s):
+    """Time the plain C oracle on the host cores for the same workload (one layer)."""
+    import numpy as np
+    import cf_inputs
+    from oracle import c_oracle
+    inp = cf_inputs.make_inputs(shape, seed=1000, batch=batch, kv_len=kv_len, poison=False)
+    args = (inp["x"], inp["w_qkv"], inp["w_o"], inp["k_cache"], inp["v_cache"], kv_len,
+            shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.rope_base)
+    cores = len(os.sched_getaffinity(0))
+    c_oracle.set_num_threads(cores)
+    t0 = time.perf_counter()
+    c_oracle.decode_block(*args)                      # warm-up
+    first = time.perf_counter() - t0
+    reps = max(1, min(20, int(budget_s / max(first, 1e-3)) - 1))
+    times = []
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        c_oracle.decode_block(*args)
+        times.append(time.perf_counter() - t0)
+    med = float(np.median(times))
+    return {"value": med * 1e6, "unit": "us/step", "cores": int(c_oracle.num_threads()), "kind": "oracle",
+            "sample": "%d full steps of the same workload (one layer, B=%d, L=%d), median; C oracle, fp64 accumulation"
+                      % (reps, batch, kv_len)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        log("bench.py measures one GPU only: this build has no multi-GPU path (--gpus %d refused)" % args.gpus)
+        sys.exit(2)
+    import torch
+    import cf_inputs
+    from paper_2508_18850_amd import DecodeBlock, algorithmic_bytes
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    shape = cf_inputs.SHAPES[args.workload]
+    B = args.batch or shape.batch
+    L = args.kv_len if args.kv_len is not None else shape.kv_len
+    S = cf_inputs.default_max_seq(L)
+    dev = torch.device("cuda:0")
+    D, nq, nkv, d = shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+
+    blk = DecodeBlock(D, nq, nkv, d, B, S, shape.rope_base)
+    if args.workgroups or args.k_splits or args.kv_splits:
+        blk.set_tuning(args.workgroups, args.k_splits, args.kv_splits, 0)
+    alg_bytes = algorithmic_bytes(blk.cfg, B, L)
+    layer_bytes = 2 * (D * shape.n_qkv + nq * d * D + 2 * B * nkv * S * d)
+    n_layers = args.layers or max(8, -(-3 * 2 ** 30 // layer_bytes))       # >= 3 GiB of distinct buffers
+    log("workload %s B=%d L=%d: %.1f MiB algorithmic bytes/step, %d layers (%.2f GiB resident)"
+        % (shape.name, B, L, alg_bytes / 2 ** 20, n_layers, n_layers * layer_bytes / 2 ** 30))
+
+    gen = torch.Generator(device=dev)
+    layers = []
+    for i in range(n_layers):
+        gen.manual_seed(1000 + i)
+        w_qkv = (torch.randn((D, shape.n_qkv), generator=gen, device=dev) * 0.02).half()
+        w_o = (torch.randn((nq * d, D), generator=gen, device=dev) * 0.02).half()
+        kc = torch.zeros((B, nkv, S, d), dtype=torch.float16, device=dev)
+        vc = torch.zeros((B, nkv, S, d), dtype=torch.float16, device=dev)
+        kc[:, :, :L] = torch.randn((B, nkv, L, d), generator=gen, device=dev).half()
+        vc[:, :, :L] = torch.randn((B, nkv, L, d), generator=gen, device=dev).half()
+        layers.append((w_qkv, w_o, kc, vc))
+    gen.manual_seed(999)
+    x = torch.randn((B, D), generator=gen, device=dev).half()
+    out = torch.empty((B, D), dtype=torch.float16, device=dev)
+
+    stream = torch.cuda.Stream(device=dev)
+    ptrs = [(w.data_ptr(), o.data_ptr(), k.data_ptr(), v.data_ptr()) for (w, o, k, v) in layers]
+    xp, op = x.data_ptr(), out.data_ptr()
+    torch.cuda.synchronize()
+
+    with torch.cuda.stream(stream):
+        sh = stream.cuda_stream
+
+        def step(i):
+            w, o, k, v = ptrs[i % n_layers]
+            blk.decode_block(B, xp, w, o, k, v, L, op, sh)
+
+        for i in range(args.warmup):
+            step(i)
+        blk.status(sh)
+        # timed region: exactly `steps` launches between two events on the launch stream
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        for i in range(args.steps):
+            step(args.warmup + i)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        blk.status(sh)
+        ms_total = ev0.elapsed_time(ev1)
+    assert torch.isfinite(out.float()).all(), "non-finite output"
+    plan = blk.plan()
+
+    ms_per_step = ms_total / args.steps
+    us = ms_per_step * 1e3
+    achieved = alg_bytes / (ms_per_step * 1e-3) / 1e9
+    name = "%s_b%d_kv%d" % (shape.name, B, L)
+    res = {
+        "metric": METRIC, "value": us, "unit": "us/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
+        "config": {"workload": name, "d_model": D, "n_q_heads": nq, "n_kv_heads": nkv, "head_dim": d,
+                   "batch": B, "kv_len": L, "layers_rotated": n_layers, "plan": plan},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(name),
+                     "algorithmic_bytes": alg_bytes, "kernel": "fused_decode_block"},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(shape, B, L, args.cpu_seconds)
+    print(json.dumps(res), flush=True)
+    blk.close()
+
+
+if __name__ == "__main__":
+    main()

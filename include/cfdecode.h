@@ -101,7 +101,11 @@ int cf_status(cf_handle h, void *stream);
  * Copy intermediate vectors of the most recent call to HOST memory (handle must
  * have CF_FLAG_DEBUG_EXPORT).  what = 0: rotated queries [batch, n_q_heads,
  * head_dim]; what = 1: per-head attention outputs a_i, same shape (Alg. 3 step
- * 7 result).  fp32.  Synchronises `stream`.  `bytes` must equal the tensor size.
+ * 7 result).  fp32.  what = 2: [workgroups][8] uint64 stamps of the 100 MHz wall
+ * clock taken by every workgroup at its phase boundaries (start, projection done,
+ * projection of the team visible, attention done, attention of the team visible,
+ * output projection done, exit; one unused).  Synchronises `stream`.  `bytes` must
+ * equal the tensor size.
  */
 int cf_debug_export(cf_handle h, int32_t what, void *host_dst, size_t bytes, void *stream);
 

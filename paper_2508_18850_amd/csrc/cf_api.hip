@@ -21,9 +21,13 @@ struct cf_handle_s {
     char *ws = nullptr;
     size_t ws_bytes = 0;
     size_t counters_bytes = 0;
-    uint32_t *cnt1 = nullptr, *cnt2 = nullptr, *cnt3 = nullptr, *done = nullptr, *err = nullptr;
-    float *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *dbg_q = nullptr, *dbg_attn = nullptr;
+    size_t exchange_bytes = 0;   // counters + exchange slots: cleared together (stamps restart at 1)
+    uint32_t *err = nullptr;
+    unsigned long long *done = nullptr;
+    uint64_t *p1 = nullptr, *p2 = nullptr, *p3 = nullptr;
+    float *dbg_q = nullptr, *dbg_attn = nullptr;
     double *inv_freq = nullptr;
+    unsigned long long *dbg_t = nullptr;
     // tuning
     int tune_w = 0, tune_ks = 0, tune_ns = 0;
     long long spin_ticks = 200000000LL;   // 2 s of the 100 MHz wall clock
@@ -68,13 +72,16 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
     {
         int best = 0;
         long best_cost = 0;
-        for (int ks = 1; ks <= kMaxKS; ks *= 2) {
+        for (int ks = 1; ks <= kMaxKS && ks <= TS; ++ks) {
+            if (TS % ks) continue;              // every member keeps one slice for all its selectors
             if (h->tune_ks > 0 && ks != h->tune_ks) continue;
             const int rps = ceil_div(c.d_model, ks);
             if (rps < 8 && ks > 1) continue;
-            const size_t lds = ((size_t)bt * rps + (size_t)cf::kWaves * bt * hd) * sizeof(float);
+            const int maxi = bt == 1 ? 4 : (bt <= 4 ? 2 : 1);
+            const size_t lds = ((size_t)bt * rps + (size_t)maxi * cf::kWaves * bt * hd) * sizeof(float);
             if (lds > kLdsLimit) continue;
-            const long cost = (long)ceil_div((G + 2) * ks, TS) * rps;
+            const int dsel = TS / ks;
+            const long cost = (long)(ceil_div(G, dsel) + ceil_div(2, dsel)) * rps;
             if (!best || cost < best_cost) {
                 best = ks;
                 best_cost = cost;
@@ -132,9 +139,6 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
 void fill_static(const cf_handle_s *h, Params *p)
 {
     const cf_config &c = h->cfg;
-    p->cnt1 = h->cnt1;
-    p->cnt2 = h->cnt2;
-    p->cnt3 = h->cnt3;
     p->done = h->done;
     p->err = h->err;
     p->p1 = h->p1;
@@ -143,6 +147,7 @@ void fill_static(const cf_handle_s *h, Params *p)
     p->inv_freq = h->inv_freq;
     p->dbg_q = (c.flags & CF_FLAG_DEBUG_EXPORT) ? h->dbg_q : nullptr;
     p->dbg_attn = (c.flags & CF_FLAG_DEBUG_EXPORT) ? h->dbg_attn : nullptr;
+    p->dbg_t = (c.flags & CF_FLAG_DEBUG_EXPORT) ? h->dbg_t : nullptr;
     p->D = c.d_model;
     p->nq = c.n_q_heads;
     p->nkv = c.n_kv_heads;
@@ -209,38 +214,37 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     }
 
     const size_t B = (size_t)c.max_batch, hd = (size_t)c.head_dim;
-    const size_t line = cf::kCounterStride * sizeof(uint32_t);
-    const size_t n_counters = 2 * (size_t)c.n_kv_heads + (size_t)h->nch + 2;
-    h->counters_bytes = align_up(n_counters * line, 256);
-    const size_t p1_bytes = align_up((size_t)kMaxKS * B * h->nqkv * sizeof(float), 256);
-    const size_t p2_bytes = align_up(B * c.n_q_heads * cf::kMaxKvSplits * (hd + cf::kP2Stride) * sizeof(float), 256);
-    const size_t p3_bytes = align_up((size_t)c.n_q_heads * 8 * B * c.d_model * sizeof(float), 256);
+    h->counters_bytes = 256;   // finished-workgroup counter and error flag
+    const size_t p1_bytes = align_up((size_t)kMaxKS * B * h->nqkv * sizeof(uint64_t), 256);
+    const size_t p2_bytes = align_up(B * c.n_q_heads * cf::kMaxKvSplits * (hd + cf::kP2Stride) * sizeof(uint64_t), 256);
+    const size_t p3_bytes = align_up((size_t)c.n_q_heads * 8 * B * c.d_model * sizeof(uint64_t), 256);
     const size_t dbg_bytes = align_up(B * c.n_q_heads * hd * sizeof(float), 256);
     const size_t freq_bytes = align_up(hd / 2 * sizeof(double), 256);
-    h->ws_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes + 2 * dbg_bytes + freq_bytes;
+    const size_t times_bytes = align_up((size_t)8 * h->num_cu * 8 * sizeof(unsigned long long), 256);
+    h->exchange_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes;
+    h->ws_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes + 2 * dbg_bytes + freq_bytes + times_bytes;
     e = hipMalloc(reinterpret_cast<void **>(&h->ws), h->ws_bytes);
     if (e != hipSuccess) {
         delete h;
         return e == hipErrorOutOfMemory ? CF_ENOMEM : CF_EHIP;
     }
     char *cur = h->ws;
-    h->cnt1 = reinterpret_cast<uint32_t *>(cur);
-    h->cnt2 = h->cnt1 + (size_t)c.n_kv_heads * cf::kCounterStride;
-    h->cnt3 = h->cnt2 + (size_t)c.n_kv_heads * cf::kCounterStride;
-    h->done = h->cnt3 + (size_t)h->nch * cf::kCounterStride;
-    h->err = h->done + cf::kCounterStride;
+    h->done = reinterpret_cast<unsigned long long *>(cur);
+    h->err = reinterpret_cast<uint32_t *>(cur + 128);
     cur += h->counters_bytes;
-    h->p1 = reinterpret_cast<float *>(cur);
+    h->p1 = reinterpret_cast<uint64_t *>(cur);
     cur += p1_bytes;
-    h->p2 = reinterpret_cast<float *>(cur);
+    h->p2 = reinterpret_cast<uint64_t *>(cur);
     cur += p2_bytes;
-    h->p3 = reinterpret_cast<float *>(cur);
+    h->p3 = reinterpret_cast<uint64_t *>(cur);
     cur += p3_bytes;
     h->dbg_q = reinterpret_cast<float *>(cur);
     cur += dbg_bytes;
     h->dbg_attn = reinterpret_cast<float *>(cur);
     cur += dbg_bytes;
     h->inv_freq = reinterpret_cast<double *>(cur);
+    cur += freq_bytes;
+    h->dbg_t = reinterpret_cast<unsigned long long *>(cur);
 
     std::vector<double> freq(hd / 2);
     for (size_t i = 0; i < hd / 2; ++i) freq[i] = std::pow((double)c.rope_base, -2.0 * (double)i / (double)hd);
@@ -307,8 +311,8 @@ int cf_status(cf_handle h, void *stream)
     e = hipMemcpy(&flag, h->err, sizeof flag, hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(h, e);
     if (flag) {
-        // a wait gave up: the counters may be inconsistent, start from a clean slate
-        e = hipMemset(h->ws, 0, h->counters_bytes);
+        // a spin gave up: start from a clean slate (launch counter and all stamps)
+        e = hipMemset(h->ws, 0, h->exchange_bytes);
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e != hipSuccess) return hip_fail(h, e);
         return CF_ETIMEOUT;
@@ -318,12 +322,14 @@ int cf_status(cf_handle h, void *stream)
 
 int cf_debug_export(cf_handle h, int32_t what, void *host_dst, size_t bytes, void *stream)
 {
-    if (!h || !host_dst || (what != 0 && what != 1)) return CF_EINVAL;
+    if (!h || !host_dst || what < 0 || what > 2) return CF_EINVAL;
     if (!(h->cfg.flags & CF_FLAG_DEBUG_EXPORT) || h->last_batch < 1) return CF_EINVAL;
-    const size_t want = (size_t)h->last_batch * h->cfg.n_q_heads * h->cfg.head_dim * sizeof(float);
+    const size_t want = what == 2 ? (size_t)h->last_plan[0] * 8 * sizeof(unsigned long long)
+                                  : (size_t)h->last_batch * h->cfg.n_q_heads * h->cfg.head_dim * sizeof(float);
     if (bytes != want) return CF_EINVAL;
+    const void *src = what == 0 ? (const void *)h->dbg_q : what == 1 ? (const void *)h->dbg_attn : (const void *)h->dbg_t;
     hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
-    if (e == hipSuccess) e = hipMemcpy(host_dst, what == 0 ? h->dbg_q : h->dbg_attn, bytes, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(host_dst, src, bytes, hipMemcpyDeviceToHost);
     return e == hipSuccess ? CF_OK : hip_fail(h, e);
 }
 
@@ -332,8 +338,15 @@ int cf_set_tuning(cf_handle h, int32_t workgroups, int32_t k_splits, int32_t kv_
     if (!h || workgroups < 0 || k_splits < 0 || kv_splits < 0 || spin_limit_us < 0) return CF_EINVAL;
     auto pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
     if (workgroups && (workgroups % h->cfg.n_kv_heads || workgroups > 8 * h->num_cu)) return CF_EINVAL;
-    if (k_splits && (!pow2(k_splits) || k_splits > kMaxKS)) return CF_EINVAL;
+    if (k_splits > kMaxKS) return CF_EINVAL;
     if (kv_splits && (!pow2(kv_splits) || kv_splits > cf::kMaxKvSplits)) return CF_EINVAL;
+    if (workgroups != h->tune_w) {
+        // the launch number is derived from a count of finished workgroups: start it afresh
+        hipError_t e = hipDeviceSynchronize();
+        if (e == hipSuccess) e = hipMemset(h->ws, 0, h->exchange_bytes);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) return hip_fail(h, e);
+    }
     h->tune_w = workgroups;
     h->tune_ks = k_splits;
     h->tune_ns = kv_splits;

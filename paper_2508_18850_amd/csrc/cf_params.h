@@ -11,7 +11,6 @@ constexpr int kThreads = 512;              // threads per workgroup (8 wavefront
 constexpr int kWaves = kThreads / 64;
 constexpr int kOutChunk = 512;             // output columns one wavefront covers with one 128-bit load per lane
 constexpr int kP2Stride = 4;               // floats in front of the accumulator in a split-KV partial: m, l, pad, pad
-constexpr int kCounterStride = 32;         // uint32 words between two counters (one 128-byte line each)
 constexpr int kMaxKSplits = 64;
 constexpr int kMaxKvSplits = 64;
 
@@ -20,16 +19,15 @@ struct Params {
     const uint16_t *x, *wqkv, *wo;
     uint16_t *kc, *vc, *out;
     // workspace
-    uint32_t *cnt1;        // [n_kv]  arrivals of projection items per team
-    uint32_t *cnt2;        // [n_kv]  arrivals of attention items per team
-    uint32_t *cnt3;        // [ceil(D/512)] arrivals of output-projection partials per 512-column chunk
-    uint32_t *done;        // workgroups that have finished
-    uint32_t *err;         // set to 1 when a wait gave up
-    float *p1;             // [k_splits][B][Nqkv] partial projections
-    float *p2;             // [B][n_q][kv_splits][head_dim + kP2Stride] split-KV partials
-    float *p3;             // [n_q * row_splits][B][D] per-head partial outputs
+    unsigned long long *done;  // workgroups that have finished, over all launches
+    uint32_t *err;         // set to 1 when a spin gave up
+    // exchange slots: 64-bit {fp32 bits, launch stamp} pairs
+    uint64_t *p1;          // [k_splits][B][Nqkv] partial projections
+    uint64_t *p2;          // [B][n_q][kv_splits][head_dim + kP2Stride] split-KV partials
+    uint64_t *p3;          // [n_q * row_splits][B][D] per-head partial outputs
     const double *inv_freq;// [head_dim/2] RoPE frequencies base^(-2i/d)
     float *dbg_q, *dbg_attn;   // [B][n_q][head_dim] or null
+    unsigned long long *dbg_t; // [W][8] wall-clock stamps at phase boundaries, or null
     int D, nq, nkv, B, pos, max_seq, nqkv;
     int W, TS;             // workgroups, workgroups per team (team = one KV head)
     int KS, RPS;           // projection: splits of the reduction dimension, rows per split
