@@ -89,6 +89,24 @@ int cf_decode_block(cf_handle h, int32_t batch, const void *x, const void *W_qkv
                     void *k_cache, void *v_cache, int32_t pos, void *out, void *stream);
 
 /*
+ * Optional layout for the (static) weights that lets every workgroup stream one
+ * contiguous block instead of a strided column strip; same bytes, same arithmetic.
+ * It is the per-head form of Eq. 1 (W_Qi, W_Ki, W_Vi per head):
+ *   W_qkv_packed [(n_q + 2 n_kv)][d_model][head_dim]   block j = columns [j*head_dim, (j+1)*head_dim) of W_qkv
+ *   W_o_packed   [n_q][ceil(d_model/512)][head_dim][512]  tile (i, c) = rows of head i, columns [512c, 512c+512)
+ *                                                          of W_o, zero-filled past d_model
+ * cf_packed_sizes gives the two buffer sizes in bytes; cf_pack_weights enqueues the
+ * rearrangement on `stream` (source and destination must not overlap);
+ * cf_decode_block_packed is cf_decode_block taking the packed weights.
+ */
+int cf_packed_sizes(cf_handle h, size_t *qkv_bytes, size_t *o_bytes);
+int cf_pack_weights(cf_handle h, const void *W_qkv, const void *W_o, void *W_qkv_packed, void *W_o_packed,
+                    void *stream);
+int cf_decode_block_packed(cf_handle h, int32_t batch, const void *x, const void *W_qkv_packed,
+                           const void *W_o_packed, void *k_cache, void *v_cache, int32_t pos, void *out,
+                           void *stream);
+
+/*
  * Wait for `stream` and report whether any kernel launched through this handle
  * gave up on a cross-workgroup wait (CF_ETIMEOUT) since the last cf_status
  * call.  The fused kernel relies on all its workgroups being resident at once

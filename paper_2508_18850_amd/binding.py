@@ -10,10 +10,11 @@ import ctypes
 import os
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libcfdecode.so")
+_LIB_PATH = os.environ.get("CFDECODE_LIB") or os.path.join(_PKG, "libcfdecode.so")   # override: A/B builds
 _lib = None
 
-EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_status", "cf_debug_export",
+EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_packed", "cf_pack_weights",
+                    "cf_packed_sizes", "cf_status", "cf_debug_export",
                     "cf_set_tuning", "cf_get_plan", "cf_algorithmic_bytes", "cf_strerror", "cf_last_hip_error")
 
 CF_FLAG_DEBUG_EXPORT = 1
@@ -46,6 +47,9 @@ def load_library():
         lib.cf_create.argtypes = [ctypes.POINTER(CfConfig), ctypes.POINTER(vp)]
         lib.cf_destroy.argtypes = [vp]
         lib.cf_decode_block.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp]
+        lib.cf_decode_block_packed.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp]
+        lib.cf_pack_weights.argtypes = [vp, vp, vp, vp, vp, vp]
+        lib.cf_packed_sizes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_size_t)]
         lib.cf_status.argtypes = [vp, vp]
         lib.cf_debug_export.argtypes = [vp, i32, vp, ctypes.c_size_t, vp]
         lib.cf_set_tuning.argtypes = [vp, i32, i32, i32, i32]
@@ -55,7 +59,8 @@ def load_library():
         lib.cf_strerror.argtypes = [ctypes.c_int]
         lib.cf_strerror.restype = ctypes.c_char_p
         lib.cf_last_hip_error.argtypes = [vp]
-        for name in ("cf_create", "cf_destroy", "cf_decode_block", "cf_status", "cf_debug_export",
+        for name in ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_packed", "cf_pack_weights",
+                     "cf_packed_sizes", "cf_status", "cf_debug_export",
                      "cf_set_tuning", "cf_get_plan", "cf_last_hip_error"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
@@ -88,6 +93,20 @@ class DecodeBlock:
 
     def decode_block(self, batch, x, w_qkv, w_o, k_cache, v_cache, pos, out, stream=0):
         rc = self._lib.cf_decode_block(self._h, batch, x, w_qkv, w_o, k_cache, v_cache, pos, out, stream)
+        if rc != 0:
+            self._check(rc)
+
+    def packed_sizes(self):
+        a, b = ctypes.c_size_t(), ctypes.c_size_t()
+        self._check(self._lib.cf_packed_sizes(self._h, ctypes.byref(a), ctypes.byref(b)))
+        return int(a.value), int(b.value)
+
+    def pack_weights(self, w_qkv, w_o, w_qkv_packed, w_o_packed, stream=0):
+        self._check(self._lib.cf_pack_weights(self._h, w_qkv, w_o, w_qkv_packed, w_o_packed, stream))
+
+    def decode_block_packed(self, batch, x, w_qkv_packed, w_o_packed, k_cache, v_cache, pos, out, stream=0):
+        rc = self._lib.cf_decode_block_packed(self._h, batch, x, w_qkv_packed, w_o_packed, k_cache, v_cache, pos,
+                                              out, stream)
         if rc != 0:
             self._check(rc)
 

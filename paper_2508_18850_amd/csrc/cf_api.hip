@@ -77,6 +77,7 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
             if (h->tune_ks > 0 && ks != h->tune_ks) continue;
             const int rps = ceil_div(c.d_model, ks);
             if (rps < 8 && ks > 1) continue;
+            if ((long)(ks - 1) * rps >= c.d_model) continue;   // no empty slice
             const int maxi = bt == 1 ? 4 : (bt <= 4 ? 2 : 1);
             const size_t lds = ((size_t)bt * rps + (size_t)maxi * cf::kWaves * bt * hd) * sizeof(float);
             if (lds > kLdsLimit) continue;
@@ -108,8 +109,12 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
         }
         if (!best) return CF_EINVAL;
         p->NS = best;
-        int tps = ceil_div(ceil_div(pos, best), rows_per_step) * rows_per_step;
-        p->TPS = tps ? tps : rows_per_step;
+        // the member with the last split also sums, rotates, appends and scores the new token:
+        // its split is made shorter by about that much work
+        const int discount = best > 1 ? 64 : 0;
+        int tps = ceil_div(pos + discount, best);
+        if (tps * (best - 1) > pos) tps = ceil_div(pos, best);
+        p->TPS = tps > 0 ? tps : 1;
     }
     // output projection: G heads x NC3 column blocks x RS3 row splits per team
     {
@@ -190,6 +195,14 @@ int cf_create(const cf_config *cfg, cf_handle *out)
         c.max_batch < 1 || c.max_batch > 16 || c.max_seq < 1 || !(c.rope_base > 1.0f))
         return CF_EINVAL;
     if (c.head_dim != 64 && c.head_dim != 128) return CF_EUNSUPPORTED;
+    {
+        // the kernel addresses each tensor with 32-bit byte offsets
+        const unsigned long long lim = 0x7fffffffull;
+        const unsigned long long nqkv = (unsigned long long)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+        if (2ull * c.d_model * nqkv > lim || 2ull * c.n_q_heads * c.head_dim * c.d_model > lim ||
+            2ull * c.max_seq * c.head_dim > lim)
+            return CF_EUNSUPPORTED;
+    }
     const int G = c.n_q_heads / c.n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return CF_EUNSUPPORTED;
 
@@ -220,7 +233,7 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     const size_t p3_bytes = align_up((size_t)c.n_q_heads * 8 * B * c.d_model * sizeof(uint64_t), 256);
     const size_t dbg_bytes = align_up(B * c.n_q_heads * hd * sizeof(float), 256);
     const size_t freq_bytes = align_up(hd / 2 * sizeof(double), 256);
-    const size_t times_bytes = align_up((size_t)8 * h->num_cu * 8 * sizeof(unsigned long long), 256);
+    const size_t times_bytes = align_up((size_t)8 * h->num_cu * cf::kStamps * sizeof(unsigned long long), 256);
     h->exchange_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes;
     h->ws_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes + 2 * dbg_bytes + freq_bytes + times_bytes;
     e = hipMalloc(reinterpret_cast<void **>(&h->ws), h->ws_bytes);
@@ -268,8 +281,8 @@ int cf_destroy(cf_handle h)
     return e == hipSuccess ? CF_OK : CF_EHIP;
 }
 
-int cf_decode_block(cf_handle h, int32_t batch, const void *x, const void *W_qkv, const void *W_o, void *k_cache,
-                    void *v_cache, int32_t pos, void *out, void *stream)
+static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, const void *W_qkv, const void *W_o,
+                       void *k_cache, void *v_cache, int32_t pos, void *out, void *stream)
 {
     if (!h) return CF_EINVAL;
     if (batch < 1 || batch > h->cfg.max_batch || pos < 0 || pos >= h->cfg.max_seq) return CF_EINVAL;
@@ -287,6 +300,7 @@ int cf_decode_block(cf_handle h, int32_t batch, const void *x, const void *W_qkv
     p.out = static_cast<uint16_t *>(out);
     p.B = batch;
     p.pos = pos;
+    p.packed = packed;
     int rc = make_plan(h, batch, pos, &p);
     if (rc != CF_OK) return rc;
     const int bt = batch_tile(batch);
@@ -300,6 +314,38 @@ int cf_decode_block(cf_handle h, int32_t batch, const void *x, const void *W_qkv
     hipError_t e = cf::launch_fused(p, h->cfg.head_dim, h->G, bt, lds, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(h, e);
     return CF_OK;
+}
+
+int cf_decode_block(cf_handle h, int32_t batch, const void *x, const void *W_qkv, const void *W_o, void *k_cache,
+                    void *v_cache, int32_t pos, void *out, void *stream)
+{
+    return decode_impl(h, 0, batch, x, W_qkv, W_o, k_cache, v_cache, pos, out, stream);
+}
+
+int cf_decode_block_packed(cf_handle h, int32_t batch, const void *x, const void *W_qkv_packed,
+                           const void *W_o_packed, void *k_cache, void *v_cache, int32_t pos, void *out, void *stream)
+{
+    return decode_impl(h, 1, batch, x, W_qkv_packed, W_o_packed, k_cache, v_cache, pos, out, stream);
+}
+
+int cf_packed_sizes(cf_handle h, size_t *qkv_bytes, size_t *o_bytes)
+{
+    if (!h || !qkv_bytes || !o_bytes) return CF_EINVAL;
+    *qkv_bytes = (size_t)h->cfg.d_model * h->nqkv * 2;
+    *o_bytes = (size_t)h->cfg.n_q_heads * h->nch * h->cfg.head_dim * cf::kOutChunk * 2;
+    return CF_OK;
+}
+
+int cf_pack_weights(cf_handle h, const void *W_qkv, const void *W_o, void *W_qkv_packed, void *W_o_packed, void *stream)
+{
+    if (!h || !aligned16(W_qkv) || !aligned16(W_o) || !aligned16(W_qkv_packed) || !aligned16(W_o_packed))
+        return CF_EINVAL;
+    if (W_qkv == W_qkv_packed || W_o == W_o_packed) return CF_EINVAL;   // not in place
+    hipError_t e = cf::launch_pack(static_cast<const uint16_t *>(W_qkv), static_cast<const uint16_t *>(W_o),
+                                   static_cast<uint16_t *>(W_qkv_packed), static_cast<uint16_t *>(W_o_packed),
+                                   h->cfg.d_model, h->nqkv, h->cfg.n_q_heads, h->cfg.head_dim,
+                                   static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CF_OK : hip_fail(h, e);
 }
 
 int cf_status(cf_handle h, void *stream)
@@ -324,7 +370,7 @@ int cf_debug_export(cf_handle h, int32_t what, void *host_dst, size_t bytes, voi
 {
     if (!h || !host_dst || what < 0 || what > 2) return CF_EINVAL;
     if (!(h->cfg.flags & CF_FLAG_DEBUG_EXPORT) || h->last_batch < 1) return CF_EINVAL;
-    const size_t want = what == 2 ? (size_t)h->last_plan[0] * 8 * sizeof(unsigned long long)
+    const size_t want = what == 2 ? (size_t)h->last_plan[0] * cf::kStamps * sizeof(unsigned long long)
                                   : (size_t)h->last_batch * h->cfg.n_q_heads * h->cfg.head_dim * sizeof(float);
     if (bytes != want) return CF_EINVAL;
     const void *src = what == 0 ? (const void *)h->dbg_q : what == 1 ? (const void *)h->dbg_attn : (const void *)h->dbg_t;

@@ -42,11 +42,35 @@ constexpr float kNegBig = -1.0e30f;   // stands for "no score yet"; finite so th
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));   // eight fp16 values = one 128-bit load
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-// Streaming 128-bit load of weights / cache rows that are read exactly once.
-__device__ __forceinline__ h8 ld_stream(const uint16_t *p)
-{
-    return __builtin_nontemporal_load(reinterpret_cast<const h8 *>(p));
-}
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// A read-only tensor that is streamed once: raw buffer resource + 128-bit non-temporal loads.
+// The address of a load is base + voff (per lane) + soff (wave-uniform), so no 64-bit
+// address registers are needed per load; a lane with nothing to load passes kNoLoad,
+// which is beyond the buffer's size: the hardware then skips the access and returns zeros.
+constexpr uint32_t kNoLoad = 0x80000000u;
+#ifndef CF_STREAM_GLOBAL
+struct Stream {
+    __amdgpu_buffer_rsrc_t r;
+    __device__ __forceinline__ Stream(const void *base, uint32_t bytes)
+        : r(__builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000)) {}
+    __device__ __forceinline__ h8 ld(uint32_t voff, uint32_t soff) const
+    {
+        return __builtin_bit_cast(h8, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 2));
+    }
+};
+#else
+struct Stream {
+    const char *b;
+    __device__ __forceinline__ Stream(const void *base, uint32_t) : b((const char *)base) {}
+    __device__ __forceinline__ h8 ld(uint32_t voff, uint32_t soff) const
+    {
+        h8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (voff == kNoLoad) return z;
+        return __builtin_nontemporal_load(reinterpret_cast<const h8 *>(b + (size_t)soff + voff));
+    }
+};
+#endif
 
 __device__ __forceinline__ void unpack8(const h8 &u, float (&f)[8])
 {
@@ -72,6 +96,17 @@ __device__ __forceinline__ float row_sum(float v)
     v += dpp_move<0x141>(v);   // row_half_mirror: lane i <-> 7-i within 8 lanes
     if (LPR == 16) v += dpp_move<0x140>(v);   // row_mirror: lane i <-> 15-i within 16 lanes
     return v;
+}
+
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() would also wait for every
+// outstanding global load of the wave (vmcnt(0)), which would drain the loads that are kept in
+// flight across phases; nothing here passes data between the threads of a workgroup through
+// global memory.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 __device__ __forceinline__ float wave_sum(float v)
@@ -143,29 +178,110 @@ __device__ __forceinline__ int qkv_col0(const Params &p, int team, int sel)
 }
 
 // ---------------------------------------------------------------------------
-// Phase 1 (Alg. 3 step 2, split over the reduction dimension): for the selectors
-// sel0, sel0+dsel, ... < sel_end accumulate x[b][r0..r0+nrows) . W[r0.., col0(sel)..+HD)
-// and store the partials into slot ks of the exchange buffer.
+// Phase 1 (Alg. 3 step 2, split over the reduction dimension).  The member owns the
+// row slice ks of W_qkv and, within it, the column blocks ("selectors") sel0, sel0+dsel,
+// ... of the team: query heads first, then key / value.  All (selector, row batch)
+// steps run as one software pipeline: the loads of step k+1 are issued before step k is
+// consumed, also across selectors and across the partial-sum epilogues, and the loads
+// of the NEXT phase (issue_next) are issued before the last step is consumed, so the
+// memory pipe never drains.
 // ---------------------------------------------------------------------------
-template <int HD, int BT>
-__device__ __forceinline__ void p1_stream(const Params &p, const float *xs, const uint16_t *wbase, int nrows, int grp,
-                                          float (&acc)[BT][8])
+template <int HD, int G, int BT, class NextFn>
+__device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member, float *smem, uint32_t *s_stamp,
+                                           NextFn &&issue_next)
 {
-    constexpr int NG = NT / (HD / 8);
+    constexpr int LPR = HD / 8;
+    constexpr int NG = NT / LPR;
     constexpr int U = 8;
+    constexpr int MAXI = BT == 1 ? 4 : (BT <= 4 ? 2 : 1);   // selectors whose wave partials are buffered in LDS
+    const int tid = threadIdx.x, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
+    const int ks = member % p.KS;
+    const int sel0 = member / p.KS, dsel = p.TS / p.KS;
+    const int r0 = ks * p.RPS;
+    const int nrows = min(p.RPS, p.D - r0);                 // > 0: the host never plans an empty slice
     const int iters = (nrows + NG - 1) / NG;
-    auto load = [&](h8(&w)[U], int i0) {
+    const int nb = (iters + U - 1) / U;                     // load batches per selector
+    const int nA = sel0 < G ? (G - sel0 + dsel - 1) / dsel : 0;
+    const int nB = sel0 < 2 ? (2 - sel0 + dsel - 1) / dsel : 0;
+    const int nsteps = (nA + nB) * nb;
+    auto sel_of = [&](int si) { return si < nA ? sel0 + si * dsel : G + sel0 + (si - nA) * dsel; };
+    float *xs = smem;                       // [BT][RPS]
+    float *red = smem + BT * p.RPS;         // [MAXI][NW][BT][HD]
+    const Xbuf x1(p.p1);
+    const Stream W(p.wqkv, (uint32_t)((size_t)p.D * p.nqkv * 2));
+    // row-major [D][Nqkv]: rows are Nqkv*2 bytes apart and a selector starts at column col0;
+    // packed [Nqkv/HD][D][HD]: rows are HD*2 bytes apart and a selector is one contiguous block
+    const uint32_t rowb = p.packed ? (uint32_t)HD * 2 : (uint32_t)p.nqkv * 2;
+    const uint32_t voff0 = (uint32_t)grp * rowb + lig * 16;
+
+    // Workgroups would otherwise walk their (power-of-two spaced) blocks in lockstep and hit the
+    // same memory channels at the same time: every workgroup starts at its own rotation.
+    const int rot = iters > 0 ? (int)((blockIdx.x * 2654435761u >> 16) % (uint32_t)iters) : 0;
+    // step k: selector k / nb, row groups (k % nb) * U + u, rotated by rot within the slice
+    auto row_group = [&](int i) {
+        const int ie = i + rot;
+        return ie >= iters ? ie - iters : ie;
+    };
+    auto load = [&](h8(&w)[U], int k) {
+        const int si = k / nb, i0 = (k - si * nb) * U;
+        const uint32_t col0 = (uint32_t)qkv_col0<HD, G>(p, team, sel_of(si));
+        const uint32_t sblk = (uint32_t)r0 * rowb + (p.packed ? col0 * (uint32_t)p.D * 2 : col0 * 2);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int r = grp + NG * (i0 + u);
-            w[u] = ld_stream(wbase + (size_t)(r < nrows ? r : 0) * p.nqkv);
+            const int ie = row_group(i0 + u);
+            const bool ok = (i0 + u) < iters && (grp + NG * ie) < nrows;
+            w[u] = W.ld(ok ? voff0 : kNoLoad, sblk + (uint32_t)(NG * ie) * rowb);
         }
     };
-    auto consume = [&](const h8(&w)[U], int i0) {
+
+    h8 wa[U], wb[U];
+    if (nsteps > 0) load(wa, 0);                                  // in flight before anything else
+    if (tid == 0) {
+        // launch number = finished workgroups / workgroups per launch + 1.  A workgroup of this launch
+        // that starts late still sees fewer than W finished ones of this launch, hence the same value.
+        const unsigned long long fin = __hip_atomic_load(p.done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_stamp = (uint32_t)(fin / (unsigned long long)p.W + 1ull);
+    }
+    for (int i = tid; i < BT * p.RPS; i += NT) {
+        const int b = i / p.RPS, r = i - b * p.RPS;
+        xs[i] = (b < p.B && r < nrows) ? h2f(p.x[(size_t)b * p.D + r0 + r]) : 0.f;
+    }
+    lds_barrier();
+    const uint32_t stamp = *s_stamp;
+    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 2] = wall_clock64();   // x staged, first batch back
+    if (nsteps > 1) load(wb, 1);
+
+    float acc[BT][8];
+#pragma unroll
+    for (int b = 0; b < BT; ++b)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[b][j] = 0.f;
+    int sels[MAXI];
+    int nbuf = 0;
+    auto flush = [&]() {
+        lds_barrier();
+        for (int e = tid; e < nbuf * BT * HD; e += NT) {
+            const int it = e / (BT * HD), rem = e - it * (BT * HD);
+            const int b = rem / HD, c = rem - b * HD;
+            if (b < p.B) {
+                float sum = 0.f;
+#pragma unroll
+                for (int w8 = 0; w8 < NW; ++w8) sum += red[((it * NW + w8) * BT + b) * HD + c];
+                int sel = sels[0];
+#pragma unroll
+                for (int k = 1; k < MAXI; ++k) sel = (it == k) ? sels[k] : sel;
+                x1.st(((size_t)ks * p.B + b) * p.nqkv + qkv_col0<HD, G>(p, team, sel) + c, sum, stamp);
+            }
+        }
+        lds_barrier();
+        nbuf = 0;
+    };
+    auto consume = [&](const h8(&w)[U], int k) {
+        const int si = k / nb, i0 = (k - si * nb) * U;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int r = grp + NG * (i0 + u);
-            const bool ok = r < nrows;
+            const int r = grp + NG * row_group(i0 + u);
+            const bool ok = (i0 + u) < iters && r < nrows;
             float f[8];
             unpack8(w[u], f);
 #pragma unroll
@@ -175,74 +291,48 @@ __device__ __forceinline__ void p1_stream(const Params &p, const float *xs, cons
                 for (int j = 0; j < 8; ++j) acc[b][j] = fmaf(xv, f[j], acc[b][j]);
             }
         }
-    };
-    h8 wa[U], wb[U];
-    if (iters > 0) load(wa, 0);
-    for (int i0 = 0; i0 < iters; i0 += 2 * U) {
-        if (i0 + U < iters) load(wb, i0 + U);
-        consume(wa, i0);
-        if (i0 + 2 * U < iters) load(wa, i0 + 2 * U);
-        if (i0 + U < iters) consume(wb, i0 + U);
-    }
-}
-
-template <int HD, int G, int BT>
-__device__ void p1_pass(const Params &p, int team, int ks, int sel0, int dsel, int sel_end, uint32_t stamp,
-                        const float *xs, float *red)
-{
-    constexpr int LPR = HD / 8;
-    constexpr int MAXI = BT == 1 ? 4 : (BT <= 4 ? 2 : 1);   // items whose wave partials are buffered in LDS
-    const int tid = threadIdx.x, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
-    const int r0 = ks * p.RPS;
-    const int nrows = min(p.RPS, p.D - r0);
-    const Xbuf x1(p.p1);
-    int sels[MAXI];
-    int nbuf = 0;
-    auto flush = [&]() {
-        __syncthreads();
-        for (int e = tid; e < nbuf * BT * HD; e += NT) {
-            const int it = e / (BT * HD), rem = e - it * (BT * HD);
-            const int b = rem / HD, c = rem - b * HD;
-            if (b < p.B) {
-                float s = 0.f;
+        if (i0 + U >= iters) {
+            // last batch of this selector: row groups of a wavefront by shuffles; the wavefronts
+            // are added in flush(), in a fixed order
 #pragma unroll
-                for (int w8 = 0; w8 < NW; ++w8) s += red[((it * NW + w8) * BT + b) * HD + c];
-                int sel = sels[0];
+            for (int off = LPR; off < 64; off <<= 1)
 #pragma unroll
-                for (int k = 1; k < MAXI; ++k) sel = (it == k) ? sels[k] : sel;
-                x1.st(((size_t)ks * p.B + b) * p.nqkv + qkv_col0<HD, G>(p, team, sel) + c, s, stamp);
+                for (int b = 0; b < BT; ++b)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[b][j] += __shfl_xor(acc[b][j], off);
+            if ((tid & 63) < LPR) {
+#pragma unroll
+                for (int b = 0; b < BT; ++b)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) red[((nbuf * NW + wv) * BT + b) * HD + lig * 8 + j] = acc[b][j];
             }
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[b][j] = 0.f;
+#pragma unroll
+            for (int k2 = 0; k2 < MAXI; ++k2)
+                if (nbuf == k2) sels[k2] = sel_of(si);
+            if (++nbuf == MAXI || si == nA - 1) flush();   // q partials leave as early as possible
         }
-        __syncthreads();
-        nbuf = 0;
     };
-    for (int sel = sel0; sel < sel_end; sel += dsel) {
-        float acc[BT][8];
-#pragma unroll
-        for (int b = 0; b < BT; ++b)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[b][j] = 0.f;
-        const uint16_t *wbase = p.wqkv + (size_t)r0 * p.nqkv + qkv_col0<HD, G>(p, team, sel) + lig * 8;
-        p1_stream<HD, BT>(p, xs, wbase, nrows, grp, acc);
-        // row groups of one wavefront by shuffles; the wavefronts are added in flush(), in a fixed order
-#pragma unroll
-        for (int off = LPR; off < 64; off <<= 1)
-#pragma unroll
-            for (int b = 0; b < BT; ++b)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) acc[b][j] += __shfl_xor(acc[b][j], off);
-        if ((tid & 63) < LPR) {
-#pragma unroll
-            for (int b = 0; b < BT; ++b)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) red[((nbuf * NW + wv) * BT + b) * HD + lig * 8 + j] = acc[b][j];
+
+    // steps k and k+1 are in flight at the top of every iteration; once no step of this phase is
+    // left to issue, the first loads of the next phase go out (before the last steps are consumed)
+    for (int k = 0; k < nsteps; k += 2) {
+        if (k + 2 >= nsteps) issue_next();
+        consume(wa, k);
+        if (p.dbg_t && tid == 0 && k < 6) p.dbg_t[(size_t)blockIdx.x * kStamps + 8 + k] = wall_clock64();
+        if (k + 2 < nsteps) load(wa, k + 2);
+        if (k + 1 < nsteps) {
+            consume(wb, k + 1);
+            if (p.dbg_t && tid == 0 && k + 1 < 6) p.dbg_t[(size_t)blockIdx.x * kStamps + 9 + k] = wall_clock64();
+            if (k + 3 < nsteps) load(wb, k + 3);
         }
-#pragma unroll
-        for (int k = 0; k < MAXI; ++k)
-            if (nbuf == k) sels[k] = sel;
-        if (++nbuf == MAXI) flush();
     }
+    if (nsteps == 0) issue_next();
     if (nbuf) flush();
+    return stamp;
 }
 
 // cos/sin of pos * inv_freq[i] for i < HD/2, angle and range reduction in fp64.
@@ -283,14 +373,100 @@ __device__ void rope_table(const Params &p, float *cs, float *sn)
 
 // ---------------------------------------------------------------------------
 // Phase 2: one (batch row, KV split) of the team's KV head, all G query heads
-// (Alg. 3 steps 3-4; the new token is counted by the last split only)
+// (Alg. 3 steps 3-4; the new token is counted by the last split only).
+// K/V rows are streamed in batches of U rows per row group, two batches in flight.
 // ---------------------------------------------------------------------------
+// The q partials of the team are stored a third of the way into phase 1.  Their loads are put in
+// flight early (before the K/V stream, at the end of phase 1) and checked when q is needed, so the
+// sum costs no round trip in front of the attention loop.  Covers value e = threadIdx.x and the
+// first kEarly k-slices; anything else takes the polling path.
+constexpr int kEarly = 16;
+struct EarlyQ {
+    u32x2 v[kEarly];
+    bool issued = false;
+    template <int HD, int G>
+    __device__ __forceinline__ void issue(const Params &p, int team, int b)
+    {
+        const Xbuf x1(p.p1);
+        const int e = threadIdx.x;
+        if (e < G * HD) {
+            const int sel = e / HD, c = e - sel * HD;
+            const size_t src = (size_t)b * p.nqkv + qkv_col0<HD, G>(p, team, sel) + c;
+#pragma unroll
+            for (int k = 0; k < kEarly; ++k)
+                if (k < p.KS) v[k] = x1.ld(src + (size_t)k * p.B * p.nqkv);
+        }
+        issued = true;
+    }
+    // sum in slice order; false if a slot was not yet stamped or not covered
+    __device__ __forceinline__ bool sum(const Params &p, uint32_t stamp, float &out) const
+    {
+        bool ok = issued && p.KS <= kEarly;
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < kEarly; ++k)
+            if (k < p.KS) {
+                ok &= (v[k].y == stamp);
+                s += __builtin_bit_cast(float, v[k].x);
+            }
+        out = s;
+        return ok;
+    }
+};
+
+template <int G>
+struct P2Cfg {
+    static constexpr int U = G >= 8 ? 2 : 4;   // rows per row group in one batch of loads
+};
+
 template <int HD, int G>
-__device__ void p2_item(const Params &p, int team, int b, int s, uint32_t stamp, bool first, float *smem)
+struct P2Stream {
+    static constexpr int LPR = HD / 8;
+    static constexpr int NG = NT / LPR;
+    static constexpr int U = P2Cfg<G>::U;
+    int t0, t1, iters, grp;
+    uint32_t voff0;
+    size_t head;
+    Stream K, V;
+    // rows >= pos are outside the buffers: they can never be read
+    __device__ __forceinline__ P2Stream(const Params &p, int team, int b, int s)
+        : head(((size_t)b * p.nkv + team) * p.max_seq * HD), K(p.kc + head, (uint32_t)p.pos * HD * 2),
+          V(p.vc + head, (uint32_t)p.pos * HD * 2)
+    {
+        const int lig = threadIdx.x % LPR;
+        grp = threadIdx.x / LPR;
+        t0 = s * p.TPS;
+        t1 = min(t0 + p.TPS, p.pos);
+        iters = t1 > t0 ? (t1 - t0 + NG - 1) / NG : 0;
+        voff0 = (uint32_t)(grp * HD + lig * 8) * 2;
+    }
+    __device__ __forceinline__ void load(h8 (&kr)[U], h8 (&vr)[U], int i0) const
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int tb = t0 + NG * (i0 + u);                 // first row of this step (uniform)
+            const uint32_t voff = (tb + grp) < t1 ? voff0 : kNoLoad;
+            kr[u] = K.ld(voff, (uint32_t)tb * HD * 2);
+            vr[u] = V.ld(voff, (uint32_t)tb * HD * 2);
+        }
+    }
+    // the first two batches do not depend on q: they are put in flight before q is needed
+    __device__ __forceinline__ void prefetch(h8 (&ka)[U], h8 (&va)[U], h8 (&kb)[U], h8 (&vb)[U]) const
+    {
+        if (iters > 0) load(ka, va, 0);
+        if (iters > U) load(kb, vb, U);
+    }
+};
+
+template <int HD, int G, class TailFn>
+__device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s, uint32_t stamp, bool first,
+                                        const P2Stream<HD, G> &st, h8 (&ka)[P2Cfg<G>::U], h8 (&va)[P2Cfg<G>::U],
+                                        h8 (&kb)[P2Cfg<G>::U], h8 (&vb)[P2Cfg<G>::U], const EarlyQ &eq, float *smem,
+                                        TailFn &&issue_next)
 {
     constexpr int LPR = HD / 8;
     constexpr int NG = NT / LPR;
-    constexpr int U = G >= 8 ? 2 : (G >= 4 ? 4 : 8);   // tokens per row group in one batch of loads
+    constexpr int U = P2Cfg<G>::U;
     constexpr int PS = HD + kP2Stride;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
     const bool last = (s == p.NS - 1);
@@ -305,49 +481,34 @@ __device__ void p2_item(const Params &p, int team, int b, int s, uint32_t stamp,
     float *redm = snew + 8;                 // [G][NW]
     float *redl = redm + G * NW;            // [G][NW]
     float *redacc = redl + G * NW;          // [G][NW][HD]
+    const int t0 = st.t0, t1 = st.t1, iters = st.iters;
 
-    const int t0 = s * p.TPS;
-    const int t1 = min(t0 + p.TPS, p.pos);
-    const int iters = t1 > t0 ? (t1 - t0 + NG - 1) / NG : 0;
-    const size_t head = ((size_t)b * p.nkv + team) * p.max_seq * HD;
-    const uint16_t *kbase = p.kc + head + lig * 8;
-    const uint16_t *vbase = p.vc + head + lig * 8;
-    auto load = [&](h8(&kr)[U], h8(&vr)[U], int i0) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int t = t0 + grp + NG * (i0 + u);
-            const size_t off = (size_t)(t < t1 ? t : t0) * HD;
-            kr[u] = ld_stream(kbase + off);
-            vr[u] = ld_stream(vbase + off);
-        }
-    };
-    // ---- the first batch of K/V rows does not depend on q: put it in flight before waiting
-    h8 ka[U], va[U], kb[U], vb[U];
-    if (iters > 0) load(ka, va, 0);
     if (first) rope_table<HD>(p, cs, sn);
     // ---- sum the projection partials of the team (the gather of Alg. 3 step 3): q heads, and for
     //      the last split also the new key and value; then RoPE on q and the key
-    const int nsel = last ? G + 2 : G;
-    for (int e = tid; e < nsel * HD; e += NT) {
+    for (int e = tid; e < G * HD; e += NT) {
         const int sel = e / HD, c = e - sel * HD;
         const size_t src = (size_t)b * p.nqkv + qkv_col0<HD, G>(p, team, sel) + c;
-        qs[e] = ll_sum(p, x1, src, (size_t)p.B * p.nqkv, p.KS, stamp);     // qs, kn, vn are contiguous
+        float v;
+        if (!(first && e == tid && eq.sum(p, stamp, v)))
+            v = ll_sum(p, x1, src, (size_t)p.B * p.nqkv, p.KS, stamp);
+        qs[e] = v;
     }
-    __syncthreads();
-    const int nrot = last ? G + 1 : G;
-    for (int e = tid; e < nrot * (HD / 2); e += NT) {
+    lds_barrier();
+    for (int e = tid; e < G * (HD / 2); e += NT) {
         const int sel = e / (HD / 2), i = e - sel * (HD / 2);
         float *v = qs + sel * HD;
         const float lo = v[i], hi = v[i + HD / 2], c = cs[i], sgn = sn[i];
         v[i] = lo * c - hi * sgn;
         v[i + HD / 2] = hi * c + lo * sgn;
     }
-    __syncthreads();
+    lds_barrier();
     float qf[G][8];
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
         for (int j = 0; j < 8; ++j) qf[g][j] = qs[g * HD + lig * 8 + j] * p.qk_scale_log2e;
+    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 14] = wall_clock64();   // q ready
 
     // ---- online softmax over this split's cached tokens; one row per LPR lanes
     float m[G], l[G], acc[G][8];
@@ -403,12 +564,23 @@ __device__ void p2_item(const Params &p, int team, int b, int s, uint32_t stamp,
                 for (int j = 0; j < 8; ++j) acc[g][j] = fmaf(pr[g][u], vf[j], acc[g][j]);
         }
     };
+    // batches i0 and i0+U are in flight at the top of every iteration; once every batch of this
+    // item has been issued, the first loads of the next phase go out behind them
+    bool next_issued = false;
     for (int i0 = 0; i0 < iters; i0 += 2 * U) {
-        if (i0 + U < iters) load(kb, vb, i0 + U);
         consume(ka, va, i0);
-        if (i0 + 2 * U < iters) load(ka, va, i0 + 2 * U);
-        if (i0 + U < iters) consume(kb, vb, i0 + U);
+        if (i0 + 2 * U < iters) st.load(ka, va, i0 + 2 * U);
+        if (i0 + U < iters) {
+            consume(kb, vb, i0 + U);
+            if (i0 + 3 * U < iters) st.load(kb, vb, i0 + 3 * U);
+        }
+        if (!next_issued && i0 + 4 * U >= iters) {
+            issue_next();
+            next_issued = true;
+        }
     }
+    if (!next_issued) issue_next();
+    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 15] = wall_clock64();   // K/V consumed
     // ---- merge the row groups of a wavefront
 #pragma unroll
     for (int off = LPR; off < 64; off <<= 1) {
@@ -438,8 +610,21 @@ __device__ void p2_item(const Params &p, int team, int b, int s, uint32_t stamp,
         }
     }
     if (last) {
-        // ---- the new token: append its key/value (Sec. 2.1) and score it
-        const size_t row = head + (size_t)p.pos * HD;
+        // ---- the new token: sum its key/value partials (stored at the end of phase 1, long ago by
+        //      now), rotate the key, append both (Sec. 2.1) and score the token
+        for (int e = tid; e < 2 * HD; e += NT) {
+            const int sel = G + e / HD, c = e % HD;
+            const size_t src = (size_t)b * p.nqkv + qkv_col0<HD, G>(p, team, sel) + c;
+            kn[e] = ll_sum(p, x1, src, (size_t)p.B * p.nqkv, p.KS, stamp);      // kn and vn are contiguous
+        }
+        lds_barrier();
+        if (tid < HD / 2) {
+            const float lo = kn[tid], hi = kn[tid + HD / 2], c = cs[tid], sgn = sn[tid];
+            kn[tid] = lo * c - hi * sgn;
+            kn[tid + HD / 2] = hi * c + lo * sgn;
+        }
+        lds_barrier();
+        const size_t row = st.head + (size_t)p.pos * HD;
         if (tid < HD)
             p.kc[row + tid] = f2h(kn[tid]);
         else if (tid < 2 * HD)
@@ -453,7 +638,7 @@ __device__ void p2_item(const Params &p, int team, int b, int s, uint32_t stamp,
         if (p.dbg_q)
             for (int e = tid; e < G * HD; e += NT) p.dbg_q[((size_t)b * p.nq + team * G) * HD + e] = qs[e];
     }
-    __syncthreads();
+    lds_barrier();
     // ---- the wavefronts and the new token -> one partial (m, l, acc) per query head
     for (int e = tid; e < G * HD; e += NT) {
         const int g = e / HD, c = e - g * HD;
@@ -479,14 +664,14 @@ __device__ void p2_item(const Params &p, int team, int b, int s, uint32_t stamp,
         }
         x2.st(dst + kP2Stride + c, A, stamp);
     }
-    __syncthreads();
+    lds_barrier();
 }
 
 // ---------------------------------------------------------------------------
 // Phase 3: merge the split-KV partials of head hq (Alg. 3 steps 5-7), multiply by
 // rows [rs*HD/RS3, (rs+1)*HD/RS3) x columns [c3*CW3, (c3+1)*CW3) of that head's
-// W_o block (step 8), then add the heads once all partials of a chunk are in.
-// The first 512-column chunk of the first item is loaded before the wait.
+// W_o block (step 8) and leave a per-head partial of the output.  The first
+// 512-column chunk is loaded into registers before the attention result is needed.
 // ---------------------------------------------------------------------------
 template <int HD>
 struct OutTile {
@@ -498,26 +683,33 @@ template <int HD>
 __device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs, int ch, OutTile<HD> &t)
 {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    // row-major [nq*HD][D], or packed [nq][ceil(D/512)][HD][512] (one contiguous tile per head and chunk)
+    const Stream Wo(p.wo, p.packed ? (uint32_t)((size_t)p.nq * p.NCH * HD * kOutChunk * 2)
+                                   : (uint32_t)((size_t)p.nq * HD * p.D * 2));
     const int nrows = HD / p.RS3;
     const int cbase = c3 * p.CW3 + ch * kOutChunk;
-    const int col = cbase + lane * 8;
-    const uint16_t *wbase = p.wo + ((size_t)hq * HD + rs * nrows) * p.D + (col < p.D ? col : 0);
+    const uint32_t rowb = p.packed ? (uint32_t)kOutChunk * 2 : (uint32_t)p.D * 2;
+    const uint32_t voff = (cbase + lane * 8) < p.D ? (uint32_t)wv * rowb + lane * 16 : kNoLoad;
+    const uint32_t sbase = p.packed ? (uint32_t)((hq * p.NCH + cbase / kOutChunk) * HD + rs * nrows) * rowb
+                                    : (uint32_t)(hq * HD + rs * nrows) * rowb + (uint32_t)cbase * 2;
     const int iters = nrows / NW;
+    const int rot = (int)((blockIdx.x * 2654435761u >> 16) % (uint32_t)iters);   // see phase 1
 #pragma unroll
     for (int u = 0; u < OutTile<HD>::MAXR; ++u) {
-        const int rr = u < iters ? wv + NW * u : wv;
-        t.w[u] = ld_stream(wbase + (size_t)rr * p.D);
+        const int ue = (u + rot) >= iters ? u + rot - iters : u + rot;
+        t.w[u] = Wo.ld(u < iters ? voff : kNoLoad, sbase + (uint32_t)(NW * ue) * rowb);
     }
 }
 
 template <int HD, int BT>
-__device__ void p3_item(const Params &p, int hq, int c3, int rs, uint32_t stamp, float *smem)
+__device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs, uint32_t stamp, OutTile<HD> &tile,
+                                        bool prefetched, float *smem)
 {
     constexpr int RB = BT < 4 ? BT : 4;
     constexpr int PS = HD + kP2Stride;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     float *as = smem;                 // [BT][HD] merged, normalised attention output of head hq
-    float *red = smem + BT * HD;      // [NW][RB][512]
+    float *red = smem + BT * HD;      // [NW][RB][512]; also the (m, l, a) triples of the merge
     const Xbuf x2(p.p2), x3(p.p3);
 
     const int nrows = HD / p.RS3;
@@ -525,43 +717,77 @@ __device__ void p3_item(const Params &p, int hq, int c3, int rs, uint32_t stamp,
     const int iters = nrows / NW;
     const int slot = hq * p.RS3 + rs;
     const int nchunk = p.CW3 / kOutChunk;
+    const int rot = (int)((blockIdx.x * 2654435761u >> 16) % (uint32_t)iters);   // as in p3_load
 
-    OutTile<HD> tile;
-    p3_load<HD>(p, hq, c3, rs, 0, tile);                 // independent of the attention result
+    if (!prefetched) p3_load<HD>(p, hq, c3, rs, 0, tile);     // independent of the attention result
 
-    for (int e = tid; e < BT * HD; e += NT) {
-        const int b = e / HD, c = e - b * HD;
-        float a = 0.f;
-        if (b < p.B) {
+    // ---- merge of the split-KV partials (Alg. 3 steps 5-7).  Value v = (batch row, column) is
+    //      handled by SG threads, each folding every SG-th split with a running maximum; the SG
+    //      (m, l, a) triples are then folded in split order.  All loads of a thread go out together.
+    const int V = p.B * HD;
+    for (int v0 = 0; v0 < V; v0 += NT) {
+        const int cv = min(NT, V - v0);
+        const int SG = max(1, min(NT / cv, p.NS));
+        const int v = tid % cv, sg = tid / cv;
+        if (sg < SG) {
+            const int b = (v0 + v) / HD, c = (v0 + v) - b * HD;
             const size_t src = ((size_t)b * p.nq + hq) * p.NS * PS;
-            Spin spin;
-            for (;;) {
-                bool ok = true;
-                float M = kNegBig;
-#pragma unroll 8
-                for (int s = 0; s < p.NS; ++s) {
-                    const u32x2 v = x2.ld(src + (size_t)s * PS);
-                    ok &= (v.y == stamp);
-                    M = fmaxf(M, __builtin_bit_cast(float, v.x));
+            float mt = kNegBig, lt = 0.f, at = 0.f;
+            for (int sb = sg; sb < p.NS; sb += 4 * SG) {
+                Spin spin;
+                float mm[4], ll[4], aa[4];
+                for (;;) {
+                    bool ok = true;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int s = sb + k * SG;
+                        const size_t o = src + (size_t)(s < p.NS ? s : sb) * PS;
+                        const u32x2 vm = x2.ld(o), vl = x2.ld(o + 1), va = x2.ld(o + kP2Stride + c);
+                        ok &= (vm.y == stamp) & (vl.y == stamp) & (va.y == stamp);
+                        mm[k] = __builtin_bit_cast(float, vm.x);
+                        ll[k] = __builtin_bit_cast(float, vl.x);
+                        aa[k] = __builtin_bit_cast(float, va.x);
+                    }
+                    if (ok || spin.expired(p)) break;
                 }
-                float L = 0.f, A = 0.f;
-#pragma unroll 8
-                for (int s = 0; s < p.NS; ++s) {
-                    const u32x2 vm = x2.ld(src + (size_t)s * PS), vl = x2.ld(src + (size_t)s * PS + 1),
-                                va = x2.ld(src + (size_t)s * PS + kP2Stride + c);
-                    ok &= (vl.y == stamp) & (va.y == stamp);
-                    const float f = __builtin_amdgcn_exp2f(__builtin_bit_cast(float, vm.x) - M);
-                    L = fmaf(__builtin_bit_cast(float, vl.x), f, L);
-                    A = fmaf(__builtin_bit_cast(float, va.x), f, A);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (sb + k * SG < p.NS) {
+                        const float mn = fmaxf(mt, mm[k]);
+                        const float fa = __builtin_amdgcn_exp2f(mt - mn), fb = __builtin_amdgcn_exp2f(mm[k] - mn);
+                        lt = lt * fa + ll[k] * fb;
+                        at = at * fa + aa[k] * fb;
+                        mt = mn;
+                    }
                 }
-                a = A / L;
-                if (ok || spin.expired(p)) break;
             }
-            if (p.dbg_attn && c3 == 0 && rs == 0) p.dbg_attn[((size_t)b * p.nq + hq) * HD + c] = a;
+            red[(sg * cv + v) * 3 + 0] = mt;
+            red[(sg * cv + v) * 3 + 1] = lt;
+            red[(sg * cv + v) * 3 + 2] = at;
         }
-        as[e] = a;
+        lds_barrier();
+        if (tid < cv) {
+            float mt = kNegBig, lt = 0.f, at = 0.f;
+            for (int k = 0; k < SG; ++k) {
+                const float mk = red[(k * cv + tid) * 3], lk = red[(k * cv + tid) * 3 + 1],
+                            ak = red[(k * cv + tid) * 3 + 2];
+                const float mn = fmaxf(mt, mk);
+                const float fa = __builtin_amdgcn_exp2f(mt - mn), fb = __builtin_amdgcn_exp2f(mk - mn);
+                lt = lt * fa + lk * fb;
+                at = at * fa + ak * fb;
+                mt = mn;
+            }
+            const float a = at / lt;
+            as[v0 + tid] = a;
+            if (p.dbg_attn && c3 == 0 && rs == 0) {
+                const int b = (v0 + tid) / HD, c = (v0 + tid) - b * HD;
+                p.dbg_attn[((size_t)b * p.nq + hq) * HD + c] = a;
+            }
+        }
+        lds_barrier();
     }
-    __syncthreads();
+    for (int e = V + tid; e < BT * HD; e += NT) as[e] = 0.f;
+    lds_barrier();
 
     for (int ch = 0; ch < nchunk; ++ch) {
         const int cbase = c3 * p.CW3 + ch * kOutChunk;
@@ -575,7 +801,7 @@ __device__ void p3_item(const Params &p, int hq, int c3, int rs, uint32_t stamp,
 #pragma unroll
         for (int u = 0; u < OutTile<HD>::MAXR; ++u) {
             if (u < iters) {
-                const int r = rbeg + wv + NW * u;
+                const int r = rbeg + wv + NW * ((u + rot) >= iters ? u + rot - iters : u + rot);
                 float f[8];
                 unpack8(tile.w[u], f);
 #pragma unroll
@@ -593,7 +819,7 @@ __device__ void p3_item(const Params &p, int hq, int c3, int rs, uint32_t stamp,
             for (int b = 0; b < RB; ++b)
 #pragma unroll
                 for (int j = 0; j < 8; ++j) red[(wv * RB + b) * kOutChunk + lane * 8 + j] = acc[bb + b][j];
-            __syncthreads();
+            lds_barrier();
             for (int e = tid; e < RB * kOutChunk; e += NT) {
                 const int b = e / kOutChunk, cc = e - b * kOutChunk;
                 if (bb + b < p.B && cbase + cc < p.D) {
@@ -603,7 +829,7 @@ __device__ void p3_item(const Params &p, int hq, int c3, int rs, uint32_t stamp,
                     x3.st(((size_t)slot * p.B + bb + b) * p.D + cbase + cc, sum, stamp);
                 }
             }
-            __syncthreads();
+            lds_barrier();
         }
     }
 }
@@ -613,7 +839,7 @@ __device__ void p3_item(const Params &p, int hq, int c3, int rs, uint32_t stamp,
 // partials of those columns in slot order (the cross-head reduction that the paper
 // does with atomicAdd), then writes fp16.
 // ---------------------------------------------------------------------------
-__device__ void final_reduce(const Params &p, uint32_t stamp, float *smem)
+__device__ __forceinline__ void final_reduce(const Params &p, uint32_t stamp, float *smem)
 {
     const int tid = threadIdx.x;
     const Xbuf x3(p.p3);
@@ -633,13 +859,13 @@ __device__ void final_reduce(const Params &p, uint32_t stamp, float *smem)
             smem[s0 * cb + v] = ll_sum(p, x3, (size_t)s0 * p.B * p.D + (size_t)b * p.D + c0 + c,
                                        (size_t)spt * p.B * p.D, n, stamp);
         }
-        __syncthreads();
+        lds_barrier();
         if (tid < cb) {
             float sum = 0.f;
             for (int k = 0; k < spt; ++k) sum += smem[k * cb + tid];
             p.out[(size_t)b * p.D + c0 + c] = f2h(sum);
         }
-        __syncthreads();
+        lds_barrier();
     }
 }
 
@@ -648,65 +874,96 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
 {
     extern __shared__ float smem[];
     __shared__ uint32_t s_stamp;
+    constexpr int U2 = P2Cfg<G>::U;
     const int tid = threadIdx.x;
     const int team = blockIdx.x % p.nkv;
     const int member = blockIdx.x / p.nkv;
     auto stamp_t = [&](int k) {
-        if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * 8 + k] = wall_clock64();
+        if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + k] = wall_clock64();
     };
     stamp_t(0);
     if (p.dbg_t && tid == 0)   // where this workgroup runs: XCC id and the HW_ID register (CU, SE ...)
-        p.dbg_t[(size_t)blockIdx.x * 8 + 7] = ((unsigned long long)__builtin_amdgcn_s_getreg(63508) << 32) |
+        p.dbg_t[(size_t)blockIdx.x * kStamps + 7] = ((unsigned long long)__builtin_amdgcn_s_getreg(63508) << 32) |
                                               (unsigned)__builtin_amdgcn_s_getreg(63492);
-    // launch number = finished workgroups / workgroups per launch + 1.  A workgroup of this launch
-    // that starts late still sees fewer than W finished ones of this launch, hence the same value.
-    if (tid == 0) {
-        const unsigned long long fin = __hip_atomic_load(p.done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_stamp = (uint32_t)(fin / (unsigned long long)p.W + 1ull);
-    }
-    __syncthreads();
-    const uint32_t stamp = s_stamp;
 
-    // ---- phase 1: this member's slice ks of the reduction dimension, q selectors first, then k / v
-    {
-        const int ks = member % p.KS;
-        const int sel0 = member / p.KS, dsel = p.TS / p.KS;
-        const int r0 = ks * p.RPS;
-        const int nrows = min(p.RPS, p.D - r0);
-        float *xs = smem;                       // [BT][RPS]
-        float *red = smem + BT * p.RPS;
-        for (int i = tid; i < BT * p.RPS; i += NT) {
-            const int b = i / p.RPS, r = i - b * p.RPS;
-            xs[i] = (b < p.B && r < nrows) ? h2f(p.x[(size_t)b * p.D + r0 + r]) : 0.f;
+    const int n2 = p.B * p.NS;                       // attention items of the team
+    const int n3 = G * p.NC3 * p.RS3;                // output-projection items of the team
+    h8 ka[U2], va[U2], kb[U2], vb[U2];
+    OutTile<HD> tile;
+    P2Stream<HD, G> st2(p, team, member < n2 ? member / p.NS : 0, member < n2 ? member % p.NS : 0);
+
+    // ---- phase 1 (projection); its last step already starts the K/V stream of phase 2
+    EarlyQ eq;
+    const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, &s_stamp, [&]() {
+        if (member < n2) {
+            eq.issue<HD, G>(p, team, member / p.NS);
+            st2.prefetch(ka, va, kb, vb);
         }
-        __syncthreads();
-        p1_pass<HD, G, BT>(p, team, ks, sel0, dsel, G, stamp, xs, red);
-        stamp_t(1);
-        p1_pass<HD, G, BT>(p, team, ks, G + sel0, dsel, G + 2, stamp, xs, red);
-        stamp_t(2);
-    }
-    // ---- phase 2
-    {
-        const int n2 = p.B * p.NS;
-        bool first = true;
-        for (int it = member; it < n2; it += p.TS, first = false)
-            p2_item<HD, G>(p, team, it / p.NS, it % p.NS, stamp, first, smem);
-        stamp_t(3);
-    }
-    // ---- phase 3
-    {
-        const int n3 = G * p.NC3 * p.RS3;
-        for (int it = member; it < n3; it += p.TS) {
-            const int g = it / (p.NC3 * p.RS3), rem = it - g * (p.NC3 * p.RS3);
-            p3_item<HD, BT>(p, team * G + g, rem / p.RS3, rem % p.RS3, stamp, smem);
+    });
+    stamp_t(1);
+    // ---- phase 2 (attention); the last item already starts the W_o stream of phase 3
+    auto p3_args = [&](int it, int &hq, int &c3, int &rs) {
+        const int g = it / (p.NC3 * p.RS3), rem = it - g * (p.NC3 * p.RS3);
+        hq = team * G + g;
+        c3 = rem / p.RS3;
+        rs = rem % p.RS3;
+    };
+    bool tile_ready = false;
+    auto p3_prefetch = [&]() {
+        if (member < n3) {
+            int hq, c3, rs;
+            p3_args(member, hq, c3, rs);
+            p3_load<HD>(p, hq, c3, rs, 0, tile);
+            tile_ready = true;
         }
-        stamp_t(4);
+    };
+    for (int it = member; it < n2; it += p.TS) {
+        const bool first = (it == member), final_item = (it + p.TS >= n2);
+        if (!first) {
+            st2 = P2Stream<HD, G>(p, team, it / p.NS, it % p.NS);
+            st2.prefetch(ka, va, kb, vb);
+        }
+        p2_item<HD, G>(p, team, it / p.NS, it % p.NS, stamp, first, st2, ka, va, kb, vb, eq, smem, [&]() {
+            if (final_item) p3_prefetch();
+        });
     }
-    // ---- phase 4
+    if (member >= n2) p3_prefetch();
+    stamp_t(3);
+    // ---- phase 3 (output projection, per-head partials)
+    for (int it = member; it < n3; it += p.TS) {
+        int hq, c3, rs;
+        p3_args(it, hq, c3, rs);
+        p3_item<HD, BT>(p, hq, c3, rs, stamp, tile, tile_ready && it == member, smem);
+    }
+    stamp_t(4);
+    // ---- phase 4 (sum over heads)
     final_reduce(p, stamp, smem);
     stamp_t(5);
     if (tid == 0) __hip_atomic_fetch_add(p.done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     stamp_t(6);
+}
+
+// One-time rearrangement of the weights into per-head contiguous blocks (16 bytes per thread step).
+__global__ void pack_qkv_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, int D, int nqkv, int hd)
+{
+    const size_t n = (size_t)D * nqkv / 8;
+    const int v_per_row = hd / 8;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t c8 = i % v_per_row, r = (i / v_per_row) % D, cb = i / ((size_t)v_per_row * D);
+        dst[i] = src[(r * nqkv + cb * hd) / 8 + c8];
+    }
+}
+
+__global__ void pack_o_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, int D, int nq, int hd)
+{
+    const int nch = (D + kOutChunk - 1) / kOutChunk;
+    const size_t n = (size_t)nq * nch * hd * (kOutChunk / 8);
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t c8 = i % (kOutChunk / 8), r = (i / (kOutChunk / 8)) % hd;
+        const size_t ch = (i / ((size_t)(kOutChunk / 8) * hd)) % nch, h = i / ((size_t)(kOutChunk / 8) * hd * nch);
+        const size_t col = ch * kOutChunk + c8 * 8;
+        dst[i] = col < (size_t)D ? src[((h * hd + r) * D + col) / 8] : make_uint4(0, 0, 0, 0);
+    }
 }
 
 using KernelFn = void (*)(const Params);
@@ -765,6 +1022,16 @@ hipError_t max_workgroups_per_cu(int hd, int g, int bt, size_t lds_bytes, int *o
         if (e != hipSuccess) return e;
     }
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(out, reinterpret_cast<const void *>(fn), kThreads, lds_bytes);
+}
+
+hipError_t launch_pack(const uint16_t *wqkv, const uint16_t *wo, uint16_t *wqkv_p, uint16_t *wo_p, int D, int nqkv,
+                       int nq, int hd, hipStream_t stream)
+{
+    hipLaunchKernelGGL(pack_qkv_kernel, dim3(2048), dim3(256), 0, stream, reinterpret_cast<const uint4 *>(wqkv),
+                       reinterpret_cast<uint4 *>(wqkv_p), D, nqkv, hd);
+    hipLaunchKernelGGL(pack_o_kernel, dim3(2048), dim3(256), 0, stream, reinterpret_cast<const uint4 *>(wo),
+                       reinterpret_cast<uint4 *>(wo_p), D, nq, hd);
+    return hipGetLastError();
 }
 
 hipError_t launch_fused(const Params &p, int hd, int g, int bt, size_t lds_bytes, hipStream_t stream)

@@ -11,6 +11,7 @@ constexpr int kThreads = 512;              // threads per workgroup (8 wavefront
 constexpr int kWaves = kThreads / 64;
 constexpr int kOutChunk = 512;             // output columns one wavefront covers with one 128-bit load per lane
 constexpr int kP2Stride = 4;               // floats in front of the accumulator in a split-KV partial: m, l, pad, pad
+constexpr int kStamps = 16;                // debug time stamps per workgroup
 constexpr int kMaxKSplits = 64;
 constexpr int kMaxKvSplits = 64;
 
@@ -27,13 +28,14 @@ struct Params {
     uint64_t *p3;          // [n_q * row_splits][B][D] per-head partial outputs
     const double *inv_freq;// [head_dim/2] RoPE frequencies base^(-2i/d)
     float *dbg_q, *dbg_attn;   // [B][n_q][head_dim] or null
-    unsigned long long *dbg_t; // [W][8] wall-clock stamps at phase boundaries, or null
+    unsigned long long *dbg_t; // [W][kStamps] wall-clock stamps at phase boundaries, or null
     int D, nq, nkv, B, pos, max_seq, nqkv;
     int W, TS;             // workgroups, workgroups per team (team = one KV head)
     int KS, RPS;           // projection: splits of the reduction dimension, rows per split
     int NS, TPS;           // attention: splits of the cached sequence, tokens per split
     int NC3, CW3, RS3;     // output projection: column blocks, columns per block, row splits per head
     int NCH;               // number of 512-column chunks of the output
+    int packed;            // weights are in the packed (per-head contiguous) layout of cf_pack_weights
     float qk_scale_log2e;  // log2(e)/sqrt(head_dim)
     long long spin_ticks;  // wait limit in 100 MHz ticks
 };
@@ -45,5 +47,8 @@ hipError_t launch_fused(const Params &p, int head_dim, int group, int batch_tile
 hipError_t max_workgroups_per_cu(int head_dim, int group, int batch_tile, size_t lds_bytes, int *out);
 // LDS floats needed by the three phases for the given plan.
 size_t lds_floats(const Params &p, int head_dim, int group, int batch_tile);
+// Rearrange row-major weights into the packed layout (see cf_pack_weights in the public header).
+hipError_t launch_pack(const uint16_t *wqkv, const uint16_t *wo, uint16_t *wqkv_p, uint16_t *wo_p, int D, int nqkv,
+                       int nq, int head_dim, hipStream_t stream);
 
 }  // namespace cf

@@ -12,19 +12,20 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 
-def run_case(shape, batch, kv_len, seed, use_c=True):
-    _log("full-size %s B=%d L=%d" % (shape.name, batch, kv_len))
+def run_case(shape, batch, kv_len, seed, use_c=True, packed=True):
+    _log("full-size %s B=%d L=%d packed=%s" % (shape.name, batch, kv_len, packed))
     inp = cf_inputs.make_inputs(shape, seed=seed, batch=batch, kv_len=kv_len)
     r = Runner(shape, batch, inp["max_seq"])
-    res = r.run(inp, kv_len, out_fill=float("nan"))
+    res = r.run(inp, kv_len, out_fill=float("nan"), packed=packed)
     _log("plan %s" % r.blk.plan())
     ref = oracle(inp, shape, kv_len, use_c=use_c)
     check(res, ref, inp, kv_len, "%s B=%d L=%d" % (shape.name, batch, kv_len))
     r.blk.close()
 
 
-def test_llama2_7b_kv4096_numpy_oracle():
-    run_case(cf_inputs.SHAPES["llama2_7b"], 1, 4096, seed=1000, use_c=False)
+@pytest.mark.parametrize("packed", [True, False])
+def test_llama2_7b_kv4096_numpy_oracle(packed):
+    run_case(cf_inputs.SHAPES["llama2_7b"], 1, 4096, seed=1000, use_c=False, packed=packed)
 
 
 @pytest.mark.parametrize("kv_len", [1024, 2048, 8192, 16384, 32768])

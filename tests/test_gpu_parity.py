@@ -35,14 +35,25 @@ class Runner:
                                shape.rope_base, debug=debug)
         self.stream = torch.cuda.current_stream().cuda_stream
 
-    def run(self, inp, pos, out_fill=None):
+    def run(self, inp, pos, out_fill=None, packed=False):
         dev = torch.device("cuda:0")
         t = {k: torch.from_numpy(inp[k]).to(dev) for k in ("x", "w_qkv", "w_o", "k_cache", "v_cache")}
         out = torch.empty((self.batch, self.shape.d_model), dtype=torch.float16, device=dev)
         if out_fill is not None:
             out.fill_(out_fill)
-        self.blk.decode_block(self.batch, t["x"].data_ptr(), t["w_qkv"].data_ptr(), t["w_o"].data_ptr(),
-                              t["k_cache"].data_ptr(), t["v_cache"].data_ptr(), pos, out.data_ptr(), self.stream)
+        if packed:
+            nq_bytes, no_bytes = self.blk.packed_sizes()
+            wq_p = torch.full((nq_bytes // 2,), float("nan"), dtype=torch.float16, device=dev)
+            wo_p = torch.full((no_bytes // 2,), float("nan"), dtype=torch.float16, device=dev)
+            self.blk.pack_weights(t["w_qkv"].data_ptr(), t["w_o"].data_ptr(), wq_p.data_ptr(), wo_p.data_ptr(),
+                                  self.stream)
+            self.packed = (wq_p, wo_p)
+            self.blk.decode_block_packed(self.batch, t["x"].data_ptr(), wq_p.data_ptr(), wo_p.data_ptr(),
+                                         t["k_cache"].data_ptr(), t["v_cache"].data_ptr(), pos, out.data_ptr(),
+                                         self.stream)
+        else:
+            self.blk.decode_block(self.batch, t["x"].data_ptr(), t["w_qkv"].data_ptr(), t["w_o"].data_ptr(),
+                                  t["k_cache"].data_ptr(), t["v_cache"].data_ptr(), pos, out.data_ptr(), self.stream)
         self.blk.status(self.stream)
         res = {"out": out.cpu().numpy(), "k_cache": t["k_cache"].cpu().numpy(), "v_cache": t["v_cache"].cpu().numpy()}
         shp = (self.batch, self.shape.n_q_heads, self.shape.head_dim)
@@ -95,13 +106,26 @@ SMALL = cf_inputs.BlockShape("small", 264, 4, 2, 64, 10000.0, 77)
     ("d128_g1_b16", cf_inputs.BlockShape("s", 512, 8, 8, 128, 10000.0, 130), 16, 130),
     ("d64_g8_b5", cf_inputs.BlockShape("s", 256, 8, 1, 64, 10000.0, 45), 5, 45),
 ])
-def test_small_shapes_match_oracle(name, shape, batch, kv_len):
-    _log("case %s B=%d L=%d" % (name, batch, kv_len))
+@pytest.mark.parametrize("packed", [False, True])
+def test_small_shapes_match_oracle(name, shape, batch, kv_len, packed):
+    _log("case %s B=%d L=%d packed=%s" % (name, batch, kv_len, packed))
     inp = cf_inputs.make_inputs(shape, seed=11, batch=batch, kv_len=kv_len)
     r = Runner(shape, batch, inp["max_seq"])
-    res = r.run(inp, kv_len, out_fill=float("nan"))
+    res = r.run(inp, kv_len, out_fill=float("nan"), packed=packed)
     _log("plan %s" % r.blk.plan())
     check(res, oracle(inp, shape, kv_len), inp, kv_len, name)
+    if packed:
+        # the packed buffers are a pure rearrangement of the weights: per-head blocks of W_qkv,
+        # [head][512-column chunk][row][512] tiles of W_o, zero-filled past d_model (bit-exact)
+        D, nq, d = shape.d_model, shape.n_q_heads, shape.head_dim
+        wq_p, wo_p = (a.cpu().numpy().view(np.uint16) for a in r.packed)
+        want_q = inp["w_qkv"].view(np.uint16).reshape(D, shape.n_qkv // d, d).transpose(1, 0, 2)
+        assert np.array_equal(wq_p.reshape(want_q.shape), want_q)
+        nch = (D + 511) // 512
+        padded = np.zeros((nq * d, nch * 512), dtype=np.uint16)
+        padded[:, :D] = inp["w_o"].view(np.uint16)
+        want_o = padded.reshape(nq, d, nch, 512).transpose(0, 2, 1, 3)
+        assert np.array_equal(wo_p.reshape(want_o.shape), want_o)
 
 
 @pytest.mark.parametrize("pos", [0, 1, 2, 31, 32, 33, 255])
