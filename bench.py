@@ -26,7 +26,10 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # keyed by workload name; None = not measured for that workload.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/fused_decode_block_llama2_7b_kv4096_hbm_traffic.md: (99968.7 KiB fetched x 2.0000 + 3119.5 KiB written)
+    "llama2_7b_b1_kv4096": 207930000,
+}
 
 
 def log(*a):
@@ -47,6 +50,9 @@ def parse_args():
     ap.add_argument("--kv-splits", type=int, default=0)
     ap.add_argument("--row-major", action="store_true",
                     help="time cf_decode_block on row-major weights instead of the packed layout")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three 1 GiB device-to-device copies (a kernel of known traffic) before the "
+                         "timed region, for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg")
     return ap.parse_args()
@@ -127,6 +133,13 @@ def main():
     x = torch.randn((B, D), generator=gen, device=dev).half()
     out = torch.empty((B, D), dtype=torch.float16, device=dev)
 
+    if args.calibrate_copy:
+        src = torch.empty(2 ** 28, dtype=torch.float32, device=dev).normal_()      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     stream = torch.cuda.Stream(device=dev)
     ptrs = [(w.data_ptr(), o.data_ptr(), k.data_ptr(), v.data_ptr()) for (w, o, k, v) in layers]
     xp, op = x.data_ptr(), out.data_ptr()

@@ -84,10 +84,13 @@ def check(res, ref, inp, pos, label):
     for key, rtol in (("q_rot", 2e-5), ("attn", 2e-4)):
         e = np.abs(res[key].astype(np.float64) - ref[key]).max()
         assert e <= rtol * np.abs(ref[key]).max() + 1e-6, (key, e)
-    # appended rows: fp16 rounding of the oracle's values (1 ulp slack), all other rows untouched bit for bit
+    # appended rows: fp16 rounding of the oracle's values (1 ulp of fp16 relative slack) on top of the
+    # fp32 accumulation error of a d_model-term dot product (sqrt(n) * 2^-24 * sqrt(n) * rms(term):
+    # about 5e-6 for n = 4096..8192 and these distributions; 2e-5 allowed); all other rows untouched
     for cache, refrow in (("k_cache", ref["k_rot"]), ("v_cache", ref["v_new"])):
         got = res[cache][:, :, pos, :].astype(np.float64)
-        assert np.all(np.abs(got - refrow) <= np.abs(refrow) * 2.0 ** -10 + 2.0 ** -24), cache
+        bad = np.abs(got - refrow) > np.abs(refrow) * 2.0 ** -10 + 2e-5
+        assert not bad.any(), (cache, float(np.abs(got - refrow)[bad].max()))
         before = inp[cache].view(np.uint16).copy()
         after = res[cache].view(np.uint16).copy()
         before[:, :, pos, :] = 0
