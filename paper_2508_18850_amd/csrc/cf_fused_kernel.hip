@@ -119,18 +119,30 @@ __device__ __forceinline__ float wave_sum(float v)
 // Exchange slots (partials handed from one workgroup to another).  A slot is a 64-bit
 // {fp32 bits, stamp} pair written by ONE 8-byte write-through store (agent scope), so a
 // reader sees either the old pair or the new one; the stamp of a launch is its number.
+//
+// Scope.  Slots read by workgroups on any XCD use agent scope (sc1: through to memory).  Slots
+// that only travel inside a team can stay in the team's XCD when all members run on one XCD
+// (`local`): stores go to that XCD's L2 and loads bypass only the per-CU cache (sc0), which
+// makes a hand-over several times faster.  Should the members not share an XCD after all, a
+// reader keeps seeing an old stamp and the bounded spin reports it: data is never wrong.
 struct Xbuf {
     __amdgpu_buffer_rsrc_t r;
-    __device__ __forceinline__ explicit Xbuf(const void *base)
-        : r(__builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0xfffffff8u, 0x00020000)) {}
+    bool local;
+    __device__ __forceinline__ explicit Xbuf(const void *base, bool xcd_local = false)
+        : r(__builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0xfffffff8u, 0x00020000)),
+          local(xcd_local) {}
     __device__ __forceinline__ u32x2 ld(size_t idx) const
     {
+        if (local) return __builtin_amdgcn_raw_buffer_load_b64(r, (unsigned)(idx * 8), 0, 1);
         return __builtin_amdgcn_raw_buffer_load_b64(r, (unsigned)(idx * 8), 0, 16);
     }
     __device__ __forceinline__ void st(size_t idx, float v, uint32_t stamp) const
     {
         u32x2 d = {__builtin_bit_cast(uint32_t, v), stamp};
-        __builtin_amdgcn_raw_buffer_store_b64(d, r, (unsigned)(idx * 8), 0, 16);
+        if (local)
+            __builtin_amdgcn_raw_buffer_store_b64(d, r, (unsigned)(idx * 8), 0, 1);
+        else
+            __builtin_amdgcn_raw_buffer_store_b64(d, r, (unsigned)(idx * 8), 0, 16);
     }
 };
 
@@ -207,7 +219,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     auto sel_of = [&](int si) { return si < nA ? sel0 + si * dsel : G + sel0 + (si - nA) * dsel; };
     float *xs = smem;                       // [BT][RPS]
     float *red = smem + BT * p.RPS;         // [MAXI][NW][BT][HD]
-    const Xbuf x1(p.p1);
+    const Xbuf x1(p.p1, p.xcd_local != 0);
     const Stream W(p.wqkv, (uint32_t)((size_t)p.D * p.nqkv * 2));
     // row-major [D][Nqkv]: rows are Nqkv*2 bytes apart and a selector starts at column col0;
     // packed [Nqkv/HD][D][HD]: rows are HD*2 bytes apart and a selector is one contiguous block
@@ -229,8 +241,13 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int ie = row_group(i0 + u);
-            const bool ok = (i0 + u) < iters && (grp + NG * ie) < nrows;
-            w[u] = W.ld(ok ? voff0 : kNoLoad, sblk + (uint32_t)(NG * ie) * rowb);
+            if (p.map_mode & 1) {     // blocked: every row group walks its own contiguous rows
+                const bool ok = (i0 + u) < iters && (grp * iters + ie) < nrows;
+                w[u] = W.ld(ok ? (uint32_t)(grp * iters) * rowb + lig * 16 : kNoLoad, sblk + (uint32_t)ie * rowb);
+            } else {
+                const bool ok = (i0 + u) < iters && (grp + NG * ie) < nrows;
+                w[u] = W.ld(ok ? voff0 : kNoLoad, sblk + (uint32_t)(NG * ie) * rowb);
+            }
         }
     };
 
@@ -256,7 +273,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     for (int b = 0; b < BT; ++b)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[b][j] = 0.f;
-    int sels[MAXI];
+    int si_first = 0;                       // selector index of the first buffered item
     int nbuf = 0;
     auto flush = [&]() {
         lds_barrier();
@@ -267,10 +284,8 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
                 float sum = 0.f;
 #pragma unroll
                 for (int w8 = 0; w8 < NW; ++w8) sum += red[((it * NW + w8) * BT + b) * HD + c];
-                int sel = sels[0];
-#pragma unroll
-                for (int k = 1; k < MAXI; ++k) sel = (it == k) ? sels[k] : sel;
-                x1.st(((size_t)ks * p.B + b) * p.nqkv + qkv_col0<HD, G>(p, team, sel) + c, sum, stamp);
+                x1.st(((size_t)ks * p.B + b) * p.nqkv + qkv_col0<HD, G>(p, team, sel_of(si_first + it)) + c, sum,
+                      stamp);
             }
         }
         lds_barrier();
@@ -280,7 +295,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
         const int si = k / nb, i0 = (k - si * nb) * U;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int r = grp + NG * row_group(i0 + u);
+            const int r = (p.map_mode & 1) ? grp * iters + row_group(i0 + u) : grp + NG * row_group(i0 + u);
             const bool ok = (i0 + u) < iters && r < nrows;
             float f[8];
             unpack8(w[u], f);
@@ -310,27 +325,28 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
             for (int b = 0; b < BT; ++b)
 #pragma unroll
                 for (int j = 0; j < 8; ++j) acc[b][j] = 0.f;
-#pragma unroll
-            for (int k2 = 0; k2 < MAXI; ++k2)
-                if (nbuf == k2) sels[k2] = sel_of(si);
+            if (nbuf == 0) si_first = si;           // buffered items are consecutive selectors
             if (++nbuf == MAXI || si == nA - 1) flush();   // q partials leave as early as possible
         }
     };
 
     // steps k and k+1 are in flight at the top of every iteration; once no step of this phase is
     // left to issue, the first loads of the next phase go out (before the last steps are consumed)
+    // issue_next(0) goes out before the last two steps are consumed.  (Not more than that: the
+    // partial-sum stores of the final flush queue behind every load issued before them.)
     for (int k = 0; k < nsteps; k += 2) {
-        if (k + 2 >= nsteps) issue_next();
+        const bool last_iter = k + 2 >= nsteps;
+        if (last_iter) issue_next(0);
         consume(wa, k);
         if (p.dbg_t && tid == 0 && k < 6) p.dbg_t[(size_t)blockIdx.x * kStamps + 8 + k] = wall_clock64();
-        if (k + 2 < nsteps) load(wa, k + 2);
+        if (!last_iter) load(wa, k + 2);
         if (k + 1 < nsteps) {
             consume(wb, k + 1);
             if (p.dbg_t && tid == 0 && k + 1 < 6) p.dbg_t[(size_t)blockIdx.x * kStamps + 9 + k] = wall_clock64();
             if (k + 3 < nsteps) load(wb, k + 3);
         }
     }
-    if (nsteps == 0) issue_next();
+    if (nsteps == 0) issue_next(0);
     if (nbuf) flush();
     return stamp;
 }
@@ -380,14 +396,14 @@ __device__ void rope_table(const Params &p, float *cs, float *sn)
 // flight early (before the K/V stream, at the end of phase 1) and checked when q is needed, so the
 // sum costs no round trip in front of the attention loop.  Covers value e = threadIdx.x and the
 // first kEarly k-slices; anything else takes the polling path.
-constexpr int kEarly = 16;
+constexpr int kEarly = 8;
 struct EarlyQ {
     u32x2 v[kEarly];
     bool issued = false;
     template <int HD, int G>
     __device__ __forceinline__ void issue(const Params &p, int team, int b)
     {
-        const Xbuf x1(p.p1);
+        const Xbuf x1(p.p1, p.xcd_local != 0);
         const int e = threadIdx.x;
         if (e < G * HD) {
             const int sel = e / HD, c = e - sel * HD;
@@ -416,7 +432,13 @@ struct EarlyQ {
 
 template <int G>
 struct P2Cfg {
-    static constexpr int U = G >= 8 ? 2 : 4;   // rows per row group in one batch of loads
+    static constexpr int U = G >= 8 ? 2 : 4;    // rows per row group in one batch of loads
+    static constexpr int NB = 2;                // batches in flight
+};
+
+template <int G>
+struct KvBuf {
+    h8 k[P2Cfg<G>::NB][P2Cfg<G>::U], v[P2Cfg<G>::NB][P2Cfg<G>::U];
 };
 
 template <int HD, int G>
@@ -450,27 +472,35 @@ struct P2Stream {
             vr[u] = V.ld(voff, (uint32_t)tb * HD * 2);
         }
     }
-    // the first two batches do not depend on q: they are put in flight before q is needed
-    __device__ __forceinline__ void prefetch(h8 (&ka)[U], h8 (&va)[U], h8 (&kb)[U], h8 (&vb)[U]) const
+    // the first NB batches do not depend on q: they are put in flight before q is needed, in up to
+    // three stages (as registers become free at the end of phase 1)
+    __device__ __forceinline__ void prefetch(KvBuf<G> &buf, int stage) const
     {
-        if (iters > 0) load(ka, va, 0);
-        if (iters > U) load(kb, vb, U);
+        constexpr int NB = P2Cfg<G>::NB;
+        if (stage == 0) {
+            if (iters > 0) load(buf.k[0], buf.v[0], 0);
+            if (iters > U) load(buf.k[1], buf.v[1], U);
+        } else if (NB == 4 && stage == 1) {
+            if (iters > 2 * U) load(buf.k[NB - 2], buf.v[NB - 2], 2 * U);
+        } else if (NB == 4 && stage == 2) {
+            if (iters > 3 * U) load(buf.k[NB - 1], buf.v[NB - 1], 3 * U);
+        }
     }
 };
 
 template <int HD, int G, class TailFn>
 __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s, uint32_t stamp, bool first,
-                                        const P2Stream<HD, G> &st, h8 (&ka)[P2Cfg<G>::U], h8 (&va)[P2Cfg<G>::U],
-                                        h8 (&kb)[P2Cfg<G>::U], h8 (&vb)[P2Cfg<G>::U], const EarlyQ &eq, float *smem,
+                                        const P2Stream<HD, G> &st, KvBuf<G> &buf, const EarlyQ &eq, float *smem,
                                         TailFn &&issue_next)
 {
     constexpr int LPR = HD / 8;
     constexpr int NG = NT / LPR;
     constexpr int U = P2Cfg<G>::U;
+    constexpr int NB = P2Cfg<G>::NB;
     constexpr int PS = HD + kP2Stride;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
     const bool last = (s == p.NS - 1);
-    const Xbuf x1(p.p1), x2(p.p2);
+    const Xbuf x1(p.p1, p.xcd_local != 0), x2(p.p2, p.xcd_local != 0);
 
     float *cs = smem;                       // [HD/2]
     float *sn = cs + HD / 2;                // [HD/2]
@@ -564,22 +594,17 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
                 for (int j = 0; j < 8; ++j) acc[g][j] = fmaf(pr[g][u], vf[j], acc[g][j]);
         }
     };
-    // batches i0 and i0+U are in flight at the top of every iteration; once every batch of this
-    // item has been issued, the first loads of the next phase go out behind them
-    bool next_issued = false;
-    for (int i0 = 0; i0 < iters; i0 += 2 * U) {
-        consume(ka, va, i0);
-        if (i0 + 2 * U < iters) st.load(ka, va, i0 + 2 * U);
-        if (i0 + U < iters) {
-            consume(kb, vb, i0 + U);
-            if (i0 + 3 * U < iters) st.load(kb, vb, i0 + 3 * U);
-        }
-        if (!next_issued && i0 + 4 * U >= iters) {
-            issue_next();
-            next_issued = true;
+    // NB batches are in flight at the top of every iteration.  When all batches of the item are
+    // already out, the first loads of the next phase follow them at once.
+    for (int i0 = 0; i0 < iters; i0 += NB * U) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            if (i0 + j * U < iters) {
+                consume(buf.k[j], buf.v[j], i0 + j * U);
+                if (i0 + (j + NB) * U < iters) st.load(buf.k[j], buf.v[j], i0 + (j + NB) * U);
+            }
         }
     }
-    if (!next_issued) issue_next();
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 15] = wall_clock64();   // K/V consumed
     // ---- merge the row groups of a wavefront
 #pragma unroll
@@ -664,6 +689,9 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
         }
         x2.st(dst + kP2Stride + c, A, stamp);
     }
+    // the partial is on its way to the team; the rest of the next phase's first loads go out
+    // behind it and stream while the team's partials travel
+    issue_next(2);
     lds_barrier();
 }
 
@@ -679,8 +707,9 @@ struct OutTile {
     h8 w[MAXR];
 };
 
+// part: 0 = first half of the rows, 1 = second half, 2 = all
 template <int HD>
-__device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs, int ch, OutTile<HD> &t)
+__device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs, int ch, OutTile<HD> &t, int part = 2)
 {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     // row-major [nq*HD][D], or packed [nq][ceil(D/512)][HD][512] (one contiguous tile per head and chunk)
@@ -696,8 +725,11 @@ __device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs,
     const int rot = (int)((blockIdx.x * 2654435761u >> 16) % (uint32_t)iters);   // see phase 1
 #pragma unroll
     for (int u = 0; u < OutTile<HD>::MAXR; ++u) {
-        const int ue = (u + rot) >= iters ? u + rot - iters : u + rot;
-        t.w[u] = Wo.ld(u < iters ? voff : kNoLoad, sbase + (uint32_t)(NW * ue) * rowb);
+        const bool mine = part == 2 || (part == 0) == (u < OutTile<HD>::MAXR / 2);
+        if (mine) {
+            const int ue = (u + rot) >= iters ? u + rot - iters : u + rot;
+            t.w[u] = Wo.ld(u < iters ? voff : kNoLoad, sbase + (uint32_t)(NW * ue) * rowb);
+        }
     }
 }
 
@@ -710,7 +742,7 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     float *as = smem;                 // [BT][HD] merged, normalised attention output of head hq
     float *red = smem + BT * HD;      // [NW][RB][512]; also the (m, l, a) triples of the merge
-    const Xbuf x2(p.p2), x3(p.p3);
+    const Xbuf x2(p.p2, p.xcd_local != 0), x3(p.p3);
 
     const int nrows = HD / p.RS3;
     const int rbeg = rs * nrows;
@@ -888,18 +920,22 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
 
     const int n2 = p.B * p.NS;                       // attention items of the team
     const int n3 = G * p.NC3 * p.RS3;                // output-projection items of the team
-    h8 ka[U2], va[U2], kb[U2], vb[U2];
+    KvBuf<G> kv;
     OutTile<HD> tile;
     P2Stream<HD, G> st2(p, team, member < n2 ? member / p.NS : 0, member < n2 ? member % p.NS : 0);
 
     // ---- phase 1 (projection); its last step already starts the K/V stream of phase 2
     EarlyQ eq;
-    const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, &s_stamp, [&]() {
+    const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, &s_stamp, [&](int stage) {
         if (member < n2) {
-            eq.issue<HD, G>(p, team, member / p.NS);
-            st2.prefetch(ka, va, kb, vb);
+            if (stage == 0) eq.issue<HD, G>(p, team, member / p.NS);
+            st2.prefetch(kv, stage);
         }
     });
+    if (member < n2) {       // the partial sums of phase 1 are out: deepen the K/V prefetch
+        st2.prefetch(kv, 1);
+        st2.prefetch(kv, 2);
+    }
     stamp_t(1);
     // ---- phase 2 (attention); the last item already starts the W_o stream of phase 3
     auto p3_args = [&](int it, int &hq, int &c3, int &rs) {
@@ -909,11 +945,11 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
         rs = rem % p.RS3;
     };
     bool tile_ready = false;
-    auto p3_prefetch = [&]() {
+    auto p3_prefetch = [&](int part) {
         if (member < n3) {
             int hq, c3, rs;
             p3_args(member, hq, c3, rs);
-            p3_load<HD>(p, hq, c3, rs, 0, tile);
+            p3_load<HD>(p, hq, c3, rs, 0, tile, part);
             tile_ready = true;
         }
     };
@@ -921,13 +957,15 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
         const bool first = (it == member), final_item = (it + p.TS >= n2);
         if (!first) {
             st2 = P2Stream<HD, G>(p, team, it / p.NS, it % p.NS);
-            st2.prefetch(ka, va, kb, vb);
+            st2.prefetch(kv, 0);
+            st2.prefetch(kv, 1);
+            st2.prefetch(kv, 2);
         }
-        p2_item<HD, G>(p, team, it / p.NS, it % p.NS, stamp, first, st2, ka, va, kb, vb, eq, smem, [&]() {
-            if (final_item) p3_prefetch();
+        p2_item<HD, G>(p, team, it / p.NS, it % p.NS, stamp, first, st2, kv, eq, smem, [&](int part) {
+            if (final_item) p3_prefetch(part);
         });
     }
-    if (member >= n2) p3_prefetch();
+    if (member >= n2) p3_prefetch(2);
     stamp_t(3);
     // ---- phase 3 (output projection, per-head partials)
     for (int it = member; it < n3; it += p.TS) {
@@ -964,6 +1002,11 @@ __global__ void pack_o_kernel(const uint4 *__restrict__ src, uint4 *__restrict__
         const size_t col = ch * kOutChunk + c8 * 8;
         dst[i] = col < (size_t)D ? src[((h * hd + r) * D + col) / 8] : make_uint4(0, 0, 0, 0);
     }
+}
+
+__global__ void probe_xcc_kernel(int *xcc)
+{
+    if (threadIdx.x == 0) xcc[blockIdx.x] = (int)(__builtin_amdgcn_s_getreg(63508) & 0xf);   // XCC_ID
 }
 
 using KernelFn = void (*)(const Params);
@@ -1022,6 +1065,19 @@ hipError_t max_workgroups_per_cu(int hd, int g, int bt, size_t lds_bytes, int *o
         if (e != hipSuccess) return e;
     }
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(out, reinterpret_cast<const void *>(fn), kThreads, lds_bytes);
+}
+
+hipError_t probe_xcc(int W, int *host_xcc, hipStream_t stream)
+{
+    int *dev = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&dev), sizeof(int) * (size_t)W);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(probe_xcc_kernel, dim3(W), dim3(kThreads), 0, stream, dev);
+    e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(host_xcc, dev, sizeof(int) * (size_t)W, hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    (void)hipFree(dev);
+    return e;
 }
 
 hipError_t launch_pack(const uint16_t *wqkv, const uint16_t *wo, uint16_t *wqkv_p, uint16_t *wo_p, int D, int nqkv,
