@@ -396,7 +396,7 @@ __device__ void rope_table(const Params &p, float *cs, float *sn)
 // flight early (before the K/V stream, at the end of phase 1) and checked when q is needed, so the
 // sum costs no round trip in front of the attention loop.  Covers value e = threadIdx.x and the
 // first kEarly k-slices; anything else takes the polling path.
-constexpr int kEarly = 8;
+constexpr int kEarly = 16;
 struct EarlyQ {
     u32x2 v[kEarly];
     bool issued = false;
@@ -432,8 +432,9 @@ struct EarlyQ {
 
 template <int G>
 struct P2Cfg {
-    static constexpr int U = G >= 8 ? 2 : 4;    // rows per row group in one batch of loads
-    static constexpr int NB = 2;                // batches in flight
+    static constexpr int U = G >= 4 ? 2 : 4;    // rows per row group in one batch of loads
+    static constexpr int GP = G >= 4 ? 4 : G;   // query heads handled per pass over a batch
+    static constexpr int NB = 2;                // batches in flight (measured: 4 smaller ones spill)
 };
 
 template <int G>
@@ -472,19 +473,12 @@ struct P2Stream {
             vr[u] = V.ld(voff, (uint32_t)tb * HD * 2);
         }
     }
-    // the first NB batches do not depend on q: they are put in flight before q is needed, in up to
-    // three stages (as registers become free at the end of phase 1)
-    __device__ __forceinline__ void prefetch(KvBuf<G> &buf, int stage) const
+    // the first NB batches do not depend on q: they are put in flight before q is needed
+    __device__ __forceinline__ void prefetch(KvBuf<G> &buf) const
     {
-        constexpr int NB = P2Cfg<G>::NB;
-        if (stage == 0) {
-            if (iters > 0) load(buf.k[0], buf.v[0], 0);
-            if (iters > U) load(buf.k[1], buf.v[1], U);
-        } else if (NB == 4 && stage == 1) {
-            if (iters > 2 * U) load(buf.k[NB - 2], buf.v[NB - 2], 2 * U);
-        } else if (NB == 4 && stage == 2) {
-            if (iters > 3 * U) load(buf.k[NB - 1], buf.v[NB - 1], 3 * U);
-        }
+#pragma unroll
+        for (int j = 0; j < P2Cfg<G>::NB; ++j)
+            if (iters > j * U) load(buf.k[j], buf.v[j], j * U);
     }
 };
 
@@ -533,11 +527,19 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
         v[i + HD / 2] = hi * c + lo * sgn;
     }
     lds_barrier();
-    float qf[G][8];
+    // q fragments of this lane's 8 columns, pre-scaled by log2(e)/sqrt(d).  Up to GP heads stay in
+    // registers; wider groups (G > GP) re-read them from LDS for every pass over a batch.
+    constexpr int GP = P2Cfg<G>::GP;
+    float qf[GP][8];
+    if (G > GP) {
+        for (int e = tid; e < G * HD; e += NT) qs[e] *= p.qk_scale_log2e;   // qs now holds the scaled q
+        lds_barrier();
+    } else {
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+        for (int g = 0; g < GP; ++g)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) qf[g][j] = qs[g * HD + lig * 8 + j] * p.qk_scale_log2e;
+            for (int j = 0; j < 8; ++j) qf[g][j] = qs[g * HD + lig * 8 + j] * p.qk_scale_log2e;
+    }
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 14] = wall_clock64();   // q ready
 
     // ---- online softmax over this split's cached tokens; one row per LPR lanes
@@ -550,48 +552,57 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
         for (int j = 0; j < 8; ++j) acc[g][j] = 0.f;
     }
     auto consume = [&](const h8(&kr)[U], const h8(&vr)[U], int i0) {
-        float sc[G][U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float kf[8];
-            unpack8(kr[u], kf);
-            const bool ok = (t0 + grp + NG * (i0 + u)) < t1;
+        for (int g0 = 0; g0 < G; g0 += GP) {
+            if (G > GP) {
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                float d = 0.f;
+                for (int g = 0; g < GP; ++g)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) d = fmaf(qf[g][j], kf[j], d);
-                d = row_sum<LPR>(d);
-                sc[g][u] = ok ? d : kNegBig;
+                    for (int j = 0; j < 8; ++j) qf[g][j] = qs[(g0 + g) * HD + lig * 8 + j];
             }
-        }
-        float pr[G][U];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float mn = m[g];
-#pragma unroll
-            for (int u = 0; u < U; ++u) mn = fmaxf(mn, sc[g][u]);
-            const float scale = __builtin_amdgcn_exp2f(m[g] - mn);
-            m[g] = mn;
-            float ls = l[g] * scale;
+            float sc[GP][U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                float kf[8];
+                unpack8(kr[u], kf);
                 const bool ok = (t0 + grp + NG * (i0 + u)) < t1;
-                pr[g][u] = ok ? __builtin_amdgcn_exp2f(sc[g][u] - mn) : 0.f;
-                ls += pr[g][u];
+#pragma unroll
+                for (int g = 0; g < GP; ++g) {
+                    float d = 0.f;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) d = fmaf(qf[g][j], kf[j], d);
+                    d = row_sum<LPR>(d);
+                    sc[g][u] = ok ? d : kNegBig;
+                }
             }
-            l[g] = ls;
+            float pr[GP][U];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[g][j] *= scale;
-        }
+            for (int g = 0; g < GP; ++g) {
+                float mn = m[g0 + g];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float vf[8];
-            unpack8(vr[u], vf);
+                for (int u = 0; u < U; ++u) mn = fmaxf(mn, sc[g][u]);
+                const float scale = __builtin_amdgcn_exp2f(m[g0 + g] - mn);
+                m[g0 + g] = mn;
+                float ls = l[g0 + g] * scale;
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+                for (int u = 0; u < U; ++u) {
+                    const bool ok = (t0 + grp + NG * (i0 + u)) < t1;
+                    pr[g][u] = ok ? __builtin_amdgcn_exp2f(sc[g][u] - mn) : 0.f;
+                    ls += pr[g][u];
+                }
+                l[g0 + g] = ls;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) acc[g][j] = fmaf(pr[g][u], vf[j], acc[g][j]);
+                for (int j = 0; j < 8; ++j) acc[g0 + g][j] *= scale;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float vf[8];
+                unpack8(vr[u], vf);
+#pragma unroll
+                for (int g = 0; g < GP; ++g)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[g0 + g][j] = fmaf(pr[g][u], vf[j], acc[g0 + g][j]);
+            }
         }
     };
     // NB batches are in flight at the top of every iteration.  When all batches of the item are
@@ -658,10 +669,12 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
             float d = 0.f;
             for (int c = lane; c < HD; c += 64) d = fmaf(qs[g * HD + c], kn[c], d);
             d = wave_sum(d);
-            if (lane == 0) snew[g] = d * p.qk_scale_log2e;
+            if (lane == 0) snew[g] = (G > P2Cfg<G>::GP) ? d : d * p.qk_scale_log2e;   // qs is pre-scaled for wide groups
         }
         if (p.dbg_q)
-            for (int e = tid; e < G * HD; e += NT) p.dbg_q[((size_t)b * p.nq + team * G) * HD + e] = qs[e];
+            for (int e = tid; e < G * HD; e += NT)
+                p.dbg_q[((size_t)b * p.nq + team * G) * HD + e] =
+                    (G > P2Cfg<G>::GP) ? qs[e] / p.qk_scale_log2e : qs[e];
     }
     lds_barrier();
     // ---- the wavefronts and the new token -> one partial (m, l, acc) per query head
@@ -928,14 +941,10 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
     EarlyQ eq;
     const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, &s_stamp, [&](int stage) {
         if (member < n2) {
-            if (stage == 0) eq.issue<HD, G>(p, team, member / p.NS);
-            st2.prefetch(kv, stage);
+            eq.issue<HD, G>(p, team, member / p.NS);
+            st2.prefetch(kv);
         }
     });
-    if (member < n2) {       // the partial sums of phase 1 are out: deepen the K/V prefetch
-        st2.prefetch(kv, 1);
-        st2.prefetch(kv, 2);
-    }
     stamp_t(1);
     // ---- phase 2 (attention); the last item already starts the W_o stream of phase 3
     auto p3_args = [&](int it, int &hq, int &c3, int &rs) {
@@ -957,9 +966,7 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
         const bool first = (it == member), final_item = (it + p.TS >= n2);
         if (!first) {
             st2 = P2Stream<HD, G>(p, team, it / p.NS, it % p.NS);
-            st2.prefetch(kv, 0);
-            st2.prefetch(kv, 1);
-            st2.prefetch(kv, 2);
+            st2.prefetch(kv);
         }
         p2_item<HD, G>(p, team, it / p.NS, it % p.NS, stamp, first, st2, kv, eq, smem, [&](int part) {
             if (final_item) p3_prefetch(part);

@@ -219,3 +219,71 @@ def test_error_paths_do_not_launch():
         DecodeBlock(512, 8, 3, 64, 1, 128, 10000.0)                    # n_q % n_kv != 0
     blk.status()
     blk.close()
+
+
+def _device_case(shape, batch, kv_len, seed):
+    inp = cf_inputs.make_inputs(shape, seed=seed, batch=batch, kv_len=kv_len, poison=False)
+    dev = torch.device("cuda:0")
+    t = {k: torch.from_numpy(inp[k]).to(dev) for k in ("x", "w_qkv", "w_o", "k_cache", "v_cache")}
+    out = torch.empty((batch, shape.d_model), dtype=torch.float16, device=dev)
+    return inp, t, out
+
+
+def test_spin_limit_reports_timeout_and_handle_recovers():
+    """A spin limit far below the time a partner needs makes the bounded waits give up: the kernel
+    still ends, cf_status reports CF_ETIMEOUT, and the next call on the same handle is correct."""
+    from paper_2508_18850_amd import DecodeBlock, CfError
+    shape = cf_inputs.SHAPES["llama2_7b"]
+    L = 1024
+    inp, t, out = _device_case(shape, 1, L, seed=77)
+    blk = DecodeBlock(shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, 1, inp["max_seq"],
+                      shape.rope_base)
+    args = (1, t["x"].data_ptr(), t["w_qkv"].data_ptr(), t["w_o"].data_ptr(), t["k_cache"].data_ptr(),
+            t["v_cache"].data_ptr(), L, out.data_ptr(), 0)
+    blk.set_tuning(0, 0, 0, 1)                    # 1 microsecond
+    _log("launch with a 1 us spin limit")
+    blk.decode_block(*args)
+    with pytest.raises(CfError) as ei:
+        blk.status()
+    assert ei.value.code == -5
+    blk.set_tuning(0, 0, 0, 2000000)              # back to 2 s
+    _log("launch with the normal spin limit")
+    blk.decode_block(*args)
+    blk.status()
+    ref = oracle(inp, shape, L, use_c=True)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.abs(got - ref["out"]).max() <= 1e-2 * np.abs(ref["out"]).max() + 1e-3
+    blk.close()
+
+
+def test_many_launches_are_bitwise_reproducible():
+    """300 launches on one handle with changing positions and batch sizes (launch stamps keep
+    counting, the split plan changes): the same call always gives the same bits."""
+    shape = cf_inputs.BlockShape("s", 1024, 16, 4, 128, 10000.0, 600)
+    inp, t, out = _device_case(shape, 4, 600, seed=5)
+    from paper_2508_18850_amd import DecodeBlock
+    blk = DecodeBlock(shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, 4, inp["max_seq"],
+                      shape.rope_base)
+    k0, v0 = t["k_cache"].clone(), t["v_cache"].clone()
+    first = {}
+    cases = [(1, 600), (4, 37), (2, 599), (4, 600), (3, 0), (1, 1)]
+    for i in range(300):
+        b, pos = cases[i % len(cases)]
+        t["k_cache"].copy_(k0)
+        t["v_cache"].copy_(v0)
+        out.fill_(float("nan"))
+        blk.decode_block(b, t["x"].data_ptr(), t["w_qkv"].data_ptr(), t["w_o"].data_ptr(), t["k_cache"].data_ptr(),
+                         t["v_cache"].data_ptr(), pos, out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        got = out[:b].cpu().numpy().view(np.uint16).copy()
+        if (b, pos) in first:
+            assert np.array_equal(got, first[(b, pos)]), "launch %d differs for batch %d pos %d" % (i, b, pos)
+        else:
+            first[(b, pos)] = got
+    blk.status()
+    for (b, pos), bits in first.items():
+        sub = {k: (inp[k][:b] if k in ("x", "k_cache", "v_cache") else inp[k]) for k in inp if k not in ("shape",)}
+        ref = orc.decode_block(sub["x"], inp["w_qkv"], inp["w_o"], sub["k_cache"], sub["v_cache"], pos,
+                               shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.rope_base)["out"]
+        got = bits.view(np.float16).astype(np.float64)
+        assert np.abs(got - ref).max() <= 1e-2 * np.abs(ref).max() + 1e-3, (b, pos)
+    blk.close()
