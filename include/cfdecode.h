@@ -119,11 +119,12 @@ int cf_status(cf_handle h, void *stream);
  * Copy intermediate vectors of the most recent call to HOST memory (handle must
  * have CF_FLAG_DEBUG_EXPORT).  what = 0: rotated queries [batch, n_q_heads,
  * head_dim]; what = 1: per-head attention outputs a_i, same shape (Alg. 3 step
- * 7 result).  fp32.  what = 2: [workgroups][8] uint64 stamps of the 100 MHz wall
- * clock taken by every workgroup at its phase boundaries (start, projection done,
- * projection of the team visible, attention done, attention of the team visible,
- * output projection done, exit; one unused).  Synchronises `stream`.  `bytes` must
- * equal the tensor size.
+ * 7 result).  fp32.  what = 2: [workgroups][16] uint64 stamps of the 100 MHz wall
+ * clock taken by every workgroup: 0 start, 1 projection done, 2 x staged in LDS,
+ * 3 attention done, 4 output projection done, 5 final reduction done, 6 exit,
+ * 7 hardware id (XCC / CU) instead of a time, 8..13 steps inside the projection,
+ * 14 rotated queries ready, 15 K/V stream consumed.  Synchronises `stream`.
+ * `bytes` must equal the tensor size.
  */
 int cf_debug_export(cf_handle h, int32_t what, void *host_dst, size_t bytes, void *stream);
 
@@ -132,7 +133,8 @@ int cf_debug_export(cf_handle h, int32_t what, void *host_dst, size_t bytes, voi
  * split count of the projection's reduction dimension, split count of the KV
  * sequence, spin limit of the in-kernel waits in microseconds.  Alg. 3's
  * "cluster size" corresponds to workgroups / n_kv_heads.  Returns CF_EINVAL for
- * values the shape cannot use.
+ * values the shape cannot use.  A change of the workgroup count waits for the
+ * device and clears the workspace, so call it between steps, not inside a hot loop.
  */
 int cf_set_tuning(cf_handle h, int32_t workgroups, int32_t k_splits, int32_t kv_splits, int32_t spin_limit_us);
 

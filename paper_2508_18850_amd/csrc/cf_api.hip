@@ -321,7 +321,6 @@ static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, co
     p.B = batch;
     p.pos = pos;
     p.packed = packed;
-    { const char *e = std::getenv("CF_MAP_MODE"); p.map_mode = e ? std::atoi(e) : 0; }
     p.xcd_local = h->xcd_local > 0 ? 1 : 0;
     int rc = make_plan(h, batch, pos, &p);
     if (rc != CF_OK) return rc;

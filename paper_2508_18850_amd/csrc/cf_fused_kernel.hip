@@ -226,47 +226,86 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     const uint32_t rowb = p.packed ? (uint32_t)HD * 2 : (uint32_t)p.nqkv * 2;
     const uint32_t voff0 = (uint32_t)grp * rowb + lig * 16;
 
-    // Workgroups would otherwise walk their (power-of-two spaced) blocks in lockstep and hit the
-    // same memory channels at the same time: every workgroup starts at its own rotation.
-    const int rot = iters > 0 ? (int)((blockIdx.x * 2654435761u >> 16) % (uint32_t)iters) : 0;
-    // step k: selector k / nb, row groups (k % nb) * U + u, rotated by rot within the slice
-    auto row_group = [&](int i) {
-        const int ie = i + rot;
-        return ie >= iters ? ie - iters : ie;
+    // A step is (selector, batch of U row groups).  Steps are loaded and consumed strictly in order,
+    // so each side keeps a cursor that is advanced incrementally: no divisions, and the address
+    // of a load is one per-lane offset plus a wave-uniform offset that grows by a constant.
+    const uint32_t step_b = (uint32_t)NG * rowb;            // bytes between consecutive row groups
+    const bool all_full = nrows == iters * NG && iters % U == 0;   // no ragged tail anywhere
+    struct Cursor {
+        int si, i0;          // selector index, first row group of the batch
+        uint32_t sbase;      // uniform byte offset of that row group's first row
     };
-    auto load = [&](h8(&w)[U], int k) {
-        const int si = k / nb, i0 = (k - si * nb) * U;
+    auto blk_base = [&](int si) {
         const uint32_t col0 = (uint32_t)qkv_col0<HD, G>(p, team, sel_of(si));
-        const uint32_t sblk = (uint32_t)r0 * rowb + (p.packed ? col0 * (uint32_t)p.D * 2 : col0 * 2);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int ie = row_group(i0 + u);
-            if (p.map_mode & 1) {     // blocked: every row group walks its own contiguous rows
-                const bool ok = (i0 + u) < iters && (grp * iters + ie) < nrows;
-                w[u] = W.ld(ok ? (uint32_t)(grp * iters) * rowb + lig * 16 : kNoLoad, sblk + (uint32_t)ie * rowb);
-            } else {
-                const bool ok = (i0 + u) < iters && (grp + NG * ie) < nrows;
-                w[u] = W.ld(ok ? voff0 : kNoLoad, sblk + (uint32_t)(NG * ie) * rowb);
-            }
+        return (uint32_t)r0 * rowb + (p.packed ? col0 * (uint32_t)p.D * 2 : col0 * 2);
+    };
+    auto advance = [&](Cursor &c) {
+        c.i0 += U;
+        c.sbase += (uint32_t)U * step_b;
+        if (c.i0 >= iters) {
+            c.i0 = 0;
+            ++c.si;
+            c.sbase = blk_base(c.si);
         }
     };
+    Cursor lc = {0, 0, nsteps > 0 ? blk_base(0) : 0u};      // next step to load
+    Cursor cc = lc;                                         // next step to consume
+    auto load = [&](h8(&w)[U]) {
+        if (all_full) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) w[u] = W.ld(voff0, lc.sbase + (uint32_t)u * step_b);
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const bool ok = (lc.i0 + u) < iters && (grp + NG * (lc.i0 + u)) < nrows;
+                w[u] = W.ld(ok ? voff0 : kNoLoad, lc.sbase + (uint32_t)u * step_b);
+            }
+        }
+        advance(lc);
+    };
 
+    // Kernel start: the small loads (launch counter, this slice of x) are issued first, then two
+    // batches of weights; loads return in order, so x is staged into LDS while the weights stream.
+    constexpr int XR = BT;                                        // x values per thread kept in registers
+    const bool x_in_regs = BT * p.RPS <= XR * NT;
+    // (all of them unconditional: a load inside a branch would be waited for at the branch's end)
+    // lane 0 of the workgroup reads the launch counter (coherent load; other lanes load nothing)
+    const __amdgpu_buffer_rsrc_t done_rsrc = __builtin_amdgcn_make_buffer_rsrc(p.done, 0, 8, 0x00020000);
+    const u32x2 fin2 = __builtin_amdgcn_raw_buffer_load_b64(done_rsrc, tid == 0 ? 0u : kNoLoad, 0, 16);
+    uint16_t xr[XR];
+    bool xv[XR];
+#pragma unroll
+    for (int q = 0; q < XR; ++q) {
+        const int i = tid + q * NT, b = i / p.RPS, r = i - b * p.RPS;
+        xv[q] = x_in_regs && i < BT * p.RPS && b < p.B && r < nrows;
+        xr[q] = p.x[xv[q] ? (size_t)b * p.D + r0 + r : 0];
+    }
+    __builtin_amdgcn_sched_barrier(0);                            // keep the small loads in front
     h8 wa[U], wb[U];
-    if (nsteps > 0) load(wa, 0);                                  // in flight before anything else
+    if (nsteps > 0) load(wa);
+    if (nsteps > 1) load(wb);
+    __builtin_amdgcn_sched_barrier(0);
     if (tid == 0) {
         // launch number = finished workgroups / workgroups per launch + 1.  A workgroup of this launch
         // that starts late still sees fewer than W finished ones of this launch, hence the same value.
-        const unsigned long long fin = __hip_atomic_load(p.done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long fin = ((unsigned long long)fin2.y << 32) | fin2.x;
         *s_stamp = (uint32_t)(fin / (unsigned long long)p.W + 1ull);
     }
-    for (int i = tid; i < BT * p.RPS; i += NT) {
-        const int b = i / p.RPS, r = i - b * p.RPS;
-        xs[i] = (b < p.B && r < nrows) ? h2f(p.x[(size_t)b * p.D + r0 + r]) : 0.f;
+    if (x_in_regs) {
+#pragma unroll
+        for (int q = 0; q < XR; ++q) {
+            const int i = tid + q * NT;
+            if (i < BT * p.RPS) xs[i] = xv[q] ? h2f(xr[q]) : 0.f;
+        }
+    } else {
+        for (int i = tid; i < BT * p.RPS; i += NT) {
+            const int b = i / p.RPS, r = i - b * p.RPS;
+            xs[i] = (b < p.B && r < nrows) ? h2f(p.x[(size_t)b * p.D + r0 + r]) : 0.f;
+        }
     }
     lds_barrier();
     const uint32_t stamp = *s_stamp;
-    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 2] = wall_clock64();   // x staged, first batch back
-    if (nsteps > 1) load(wb, 1);
+    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 2] = wall_clock64();   // x staged
 
     float acc[BT][8];
 #pragma unroll
@@ -291,12 +330,12 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
         lds_barrier();
         nbuf = 0;
     };
-    auto consume = [&](const h8(&w)[U], int k) {
-        const int si = k / nb, i0 = (k - si * nb) * U;
+    auto consume = [&](const h8(&w)[U]) {
+        const int i0 = cc.i0;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int r = (p.map_mode & 1) ? grp * iters + row_group(i0 + u) : grp + NG * row_group(i0 + u);
-            const bool ok = (i0 + u) < iters && r < nrows;
+            const int r = grp + NG * (i0 + u);
+            const bool ok = all_full || ((i0 + u) < iters && r < nrows);
             float f[8];
             unpack8(w[u], f);
 #pragma unroll
@@ -306,6 +345,10 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
                 for (int j = 0; j < 8; ++j) acc[b][j] = fmaf(xv, f[j], acc[b][j]);
             }
         }
+    };
+    auto finish = [&]() {         // epilogue of the step just consumed, then move the cursor on
+        const int si = cc.si, i0 = cc.i0;
+        advance(cc);
         if (i0 + U >= iters) {
             // last batch of this selector: row groups of a wavefront by shuffles; the wavefronts
             // are added in flush(), in a fixed order
@@ -337,13 +380,15 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     for (int k = 0; k < nsteps; k += 2) {
         const bool last_iter = k + 2 >= nsteps;
         if (last_iter) issue_next(0);
-        consume(wa, k);
+        consume(wa);
         if (p.dbg_t && tid == 0 && k < 6) p.dbg_t[(size_t)blockIdx.x * kStamps + 8 + k] = wall_clock64();
-        if (!last_iter) load(wa, k + 2);
+        if (!last_iter) load(wa);               // the registers are free: reload before any epilogue
+        finish();
         if (k + 1 < nsteps) {
-            consume(wb, k + 1);
+            consume(wb);
             if (p.dbg_t && tid == 0 && k + 1 < 6) p.dbg_t[(size_t)blockIdx.x * kStamps + 9 + k] = wall_clock64();
-            if (k + 3 < nsteps) load(wb, k + 3);
+            if (k + 3 < nsteps) load(wb);
+            finish();
         }
     }
     if (nsteps == 0) issue_next(0);
@@ -434,7 +479,7 @@ template <int G>
 struct P2Cfg {
     static constexpr int U = G >= 4 ? 2 : 4;    // rows per row group in one batch of loads
     static constexpr int GP = G >= 4 ? 4 : G;   // query heads handled per pass over a batch
-    static constexpr int NB = 2;                // batches in flight (measured: 4 smaller ones spill)
+    static constexpr int NB = G <= 2 ? 3 : 2;   // batches in flight (as many as the register budget allows)
 };
 
 template <int G>
@@ -473,19 +518,22 @@ struct P2Stream {
             vr[u] = V.ld(voff, (uint32_t)tb * HD * 2);
         }
     }
-    // the first NB batches do not depend on q: they are put in flight before q is needed
-    __device__ __forceinline__ void prefetch(KvBuf<G> &buf) const
+    // the first NB batches do not depend on q: they are put in flight before q is needed; part 0
+    // (two batches) before the last steps of phase 1, part 1 (the rest) once phase 1 has stored
+    // its partial sums (stores queue behind every load issued before them)
+    __device__ __forceinline__ void prefetch(KvBuf<G> &buf, int part) const
     {
+        constexpr int NB = P2Cfg<G>::NB;
 #pragma unroll
-        for (int j = 0; j < P2Cfg<G>::NB; ++j)
-            if (iters > j * U) load(buf.k[j], buf.v[j], j * U);
+        for (int j = 0; j < NB; ++j)
+            if ((j < 2) == (part == 0) && iters > j * U) load(buf.k[j], buf.v[j], j * U);
     }
 };
 
 template <int HD, int G, class TailFn>
 __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s, uint32_t stamp, bool first,
                                         const P2Stream<HD, G> &st, KvBuf<G> &buf, const EarlyQ &eq, float *smem,
-                                        TailFn &&issue_next)
+                                        const float *rope, TailFn &&issue_next)
 {
     constexpr int LPR = HD / 8;
     constexpr int NG = NT / LPR;
@@ -496,9 +544,9 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
     const bool last = (s == p.NS - 1);
     const Xbuf x1(p.p1, p.xcd_local != 0), x2(p.p2, p.xcd_local != 0);
 
-    float *cs = smem;                       // [HD/2]
-    float *sn = cs + HD / 2;                // [HD/2]
-    float *qs = sn + HD / 2;                // [G][HD]
+    const float *cs = rope;                 // [HD/2] cos, filled at kernel start
+    const float *sn = rope + HD / 2;        // [HD/2] sin
+    float *qs = smem;                       // [G][HD]
     float *kn = qs + G * HD;                // [HD] rotated new key
     float *vn = kn + HD;                    // [HD] new value
     float *snew = vn + HD;                  // [8]  scores of the new token, log2 domain
@@ -507,7 +555,6 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
     float *redacc = redl + G * NW;          // [G][NW][HD]
     const int t0 = st.t0, t1 = st.t1, iters = st.iters;
 
-    if (first) rope_table<HD>(p, cs, sn);
     // ---- sum the projection partials of the team (the gather of Alg. 3 step 3): q heads, and for
     //      the last split also the new key and value; then RoPE on q and the key
     for (int e = tid; e < G * HD; e += NT) {
@@ -735,13 +782,11 @@ __device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs,
     const uint32_t sbase = p.packed ? (uint32_t)((hq * p.NCH + cbase / kOutChunk) * HD + rs * nrows) * rowb
                                     : (uint32_t)(hq * HD + rs * nrows) * rowb + (uint32_t)cbase * 2;
     const int iters = nrows / NW;
-    const int rot = (int)((blockIdx.x * 2654435761u >> 16) % (uint32_t)iters);   // see phase 1
 #pragma unroll
     for (int u = 0; u < OutTile<HD>::MAXR; ++u) {
         const bool mine = part == 2 || (part == 0) == (u < OutTile<HD>::MAXR / 2);
         if (mine) {
-            const int ue = (u + rot) >= iters ? u + rot - iters : u + rot;
-            t.w[u] = Wo.ld(u < iters ? voff : kNoLoad, sbase + (uint32_t)(NW * ue) * rowb);
+            t.w[u] = Wo.ld(u < iters ? voff : kNoLoad, sbase + (uint32_t)(NW * u) * rowb);
         }
     }
 }
@@ -762,7 +807,6 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
     const int iters = nrows / NW;
     const int slot = hq * p.RS3 + rs;
     const int nchunk = p.CW3 / kOutChunk;
-    const int rot = (int)((blockIdx.x * 2654435761u >> 16) % (uint32_t)iters);   // as in p3_load
 
     if (!prefetched) p3_load<HD>(p, hq, c3, rs, 0, tile);     // independent of the attention result
 
@@ -846,7 +890,7 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
 #pragma unroll
         for (int u = 0; u < OutTile<HD>::MAXR; ++u) {
             if (u < iters) {
-                const int r = rbeg + wv + NW * ((u + rot) >= iters ? u + rot - iters : u + rot);
+                const int r = rbeg + wv + NW * u;
                 float f[8];
                 unpack8(tile.w[u], f);
 #pragma unroll
@@ -919,7 +963,7 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
 {
     extern __shared__ float smem[];
     __shared__ uint32_t s_stamp;
-    constexpr int U2 = P2Cfg<G>::U;
+    __shared__ float s_rope[HD];                     // cos / sin of the RoPE angles of this position
     const int tid = threadIdx.x;
     const int team = blockIdx.x % p.nkv;
     const int member = blockIdx.x / p.nkv;
@@ -941,10 +985,14 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
     EarlyQ eq;
     const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, &s_stamp, [&](int stage) {
         if (member < n2) {
-            eq.issue<HD, G>(p, team, member / p.NS);
-            st2.prefetch(kv);
+            st2.prefetch(kv, 0);
         }
+        rope_table<HD>(p, s_rope, s_rope + HD / 2);      // needs nothing but pos; overlaps the stream
     });
+    if (member < n2) {
+        eq.issue<HD, G>(p, team, member / p.NS);    // q partials were stored a third of the way into phase 1
+        st2.prefetch(kv, 1);
+    }
     stamp_t(1);
     // ---- phase 2 (attention); the last item already starts the W_o stream of phase 3
     auto p3_args = [&](int it, int &hq, int &c3, int &rs) {
@@ -966,9 +1014,10 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
         const bool first = (it == member), final_item = (it + p.TS >= n2);
         if (!first) {
             st2 = P2Stream<HD, G>(p, team, it / p.NS, it % p.NS);
-            st2.prefetch(kv);
+            st2.prefetch(kv, 0);
+            st2.prefetch(kv, 1);
         }
-        p2_item<HD, G>(p, team, it / p.NS, it % p.NS, stamp, first, st2, kv, eq, smem, [&](int part) {
+        p2_item<HD, G>(p, team, it / p.NS, it % p.NS, stamp, first, st2, kv, eq, smem, s_rope, [&](int part) {
             if (final_item) p3_prefetch(part);
         });
     }

@@ -36,7 +36,6 @@ struct Params {
     int NC3, CW3, RS3;     // output projection: column blocks, columns per block, row splits per head
     int NCH;               // number of 512-column chunks of the output
     int xcd_local;         // all members of a team run on one XCD: team-internal exchange stays in its L2
-    int map_mode;          // experiment switches for the lane-to-address maps
     int packed;            // weights are in the packed (per-head contiguous) layout of cf_pack_weights
     float qk_scale_log2e;  // log2(e)/sqrt(head_dim)
     long long spin_ticks;  // wait limit in 100 MHz ticks
