@@ -189,6 +189,42 @@ __device__ __forceinline__ int qkv_col0(const Params &p, int team, int sel)
     return (p.nq + p.nkv + team) * HD;
 }
 
+// cos/sin of pos * inv_freq[i] for i < HD/2, angle and range reduction in fp64.
+template <int HD>
+__device__ __forceinline__ void rope_table(int pos, double inv_freq, float *cs, float *sn)
+{
+    const int i = threadIdx.x;
+    if (i < HD / 2) {
+        const double ang = (double)pos * inv_freq;
+        const double k = rint(ang * 0.63661977236758134308);              // 2/pi
+        double r = fma(-k, 1.57079632679489655800e+00, ang);              // pi/2, high part
+        r = fma(-k, 6.12323399573676603587e-17, r);                       // pi/2, low part
+        const double r2 = r * r;                                          // |r| <= pi/4: Taylor series
+        double s = -1.0 / 1307674368000.0;
+        s = fma(s, r2, 1.0 / 6227020800.0);
+        s = fma(s, r2, -1.0 / 39916800.0);
+        s = fma(s, r2, 1.0 / 362880.0);
+        s = fma(s, r2, -1.0 / 5040.0);
+        s = fma(s, r2, 1.0 / 120.0);
+        s = fma(s, r2, -1.0 / 6.0);
+        s = fma(s * r2, r, r);
+        double c = 1.0 / 20922789888000.0;
+        c = fma(c, r2, -1.0 / 87178291200.0);
+        c = fma(c, r2, 1.0 / 479001600.0);
+        c = fma(c, r2, -1.0 / 3628800.0);
+        c = fma(c, r2, 1.0 / 40320.0);
+        c = fma(c, r2, -1.0 / 720.0);
+        c = fma(c, r2, 1.0 / 24.0);
+        c = fma(c, r2, -0.5);
+        c = fma(c, r2, 1.0);
+        const int q = (int)((long long)k & 3);
+        const double sv = (q == 0) ? s : (q == 1) ? c : (q == 2) ? -s : -c;
+        const double cv = (q == 0) ? c : (q == 1) ? -s : (q == 2) ? -c : s;
+        cs[i] = (float)cv;
+        sn[i] = (float)sv;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Phase 1 (Alg. 3 step 2, split over the reduction dimension).  The member owns the
 // row slice ks of W_qkv and, within it, the column blocks ("selectors") sel0, sel0+dsel,
@@ -200,7 +236,7 @@ __device__ __forceinline__ int qkv_col0(const Params &p, int team, int sel)
 // ---------------------------------------------------------------------------
 template <int HD, int G, int BT, class NextFn>
 __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member, float *smem, uint32_t *s_stamp,
-                                           NextFn &&issue_next)
+                                           float *rope, NextFn &&issue_next)
 {
     constexpr int LPR = HD / 8;
     constexpr int NG = NT / LPR;
@@ -230,7 +266,6 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     // so each side keeps a cursor that is advanced incrementally: no divisions, and the address
     // of a load is one per-lane offset plus a wave-uniform offset that grows by a constant.
     const uint32_t step_b = (uint32_t)NG * rowb;            // bytes between consecutive row groups
-    const bool all_full = nrows == iters * NG && iters % U == 0;   // no ragged tail anywhere
     struct Cursor {
         int si, i0;          // selector index, first row group of the batch
         uint32_t sbase;      // uniform byte offset of that row group's first row
@@ -248,20 +283,21 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
             c.sbase = blk_base(c.si);
         }
     };
+    const int nsel = nA + nB;
     Cursor lc = {0, 0, nsteps > 0 ? blk_base(0) : 0u};      // next step to load
     Cursor cc = lc;                                         // next step to consume
-    auto load = [&](h8(&w)[U]) {
-        if (all_full) {
+    // Every call issues exactly U load instructions on one straight-line path, also for a step past
+    // the end (all lanes switched off through their offset).  The compiler derives each wait from
+    // the number of loads issued after the one it needs, taking the smallest over all paths of the
+    // control flow, so a branch around loads would make every later wait drain the queue.
+    const int lim = nrows - grp;                            // row group i is inside the slice iff NG*i < lim
+    auto load = [&](h8(&w)[U], uint32_t voff) {
+        const bool live = lc.si < nsel;
+        const int g0 = live ? NG * lc.i0 : 0x40000000;      // uniform
 #pragma unroll
-            for (int u = 0; u < U; ++u) w[u] = W.ld(voff0, lc.sbase + (uint32_t)u * step_b);
-        } else {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const bool ok = (lc.i0 + u) < iters && (grp + NG * (lc.i0 + u)) < nrows;
-                w[u] = W.ld(ok ? voff0 : kNoLoad, lc.sbase + (uint32_t)u * step_b);
-            }
-        }
-        advance(lc);
+        for (int u = 0; u < U; ++u)
+            w[u] = W.ld((g0 + NG * u) < lim ? voff : kNoLoad, lc.sbase + (uint32_t)u * step_b);
+        if (live) advance(lc);
     };
 
     // Kernel start: the small loads (launch counter, this slice of x) are issued first, then two
@@ -280,10 +316,11 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
         xv[q] = x_in_regs && i < BT * p.RPS && b < p.B && r < nrows;
         xr[q] = p.x[xv[q] ? (size_t)b * p.D + r0 + r : 0];
     }
+    const double inv_freq = p.inv_freq[tid < HD / 2 ? tid : 0];   // for the RoPE table, below
     __builtin_amdgcn_sched_barrier(0);                            // keep the small loads in front
     h8 wa[U], wb[U];
-    if (nsteps > 0) load(wa);
-    if (nsteps > 1) load(wb);
+    load(wa, voff0);
+    load(wb, voff0);
     __builtin_amdgcn_sched_barrier(0);
     if (tid == 0) {
         // launch number = finished workgroups / workgroups per launch + 1.  A workgroup of this launch
@@ -303,6 +340,8 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
             xs[i] = (b < p.B && r < nrows) ? h2f(p.x[(size_t)b * p.D + r0 + r]) : 0.f;
         }
     }
+    // cos / sin of this position while the first weights are still on their way
+    rope_table<HD>(p.pos, inv_freq, rope, rope + HD / 2);
     lds_barrier();
     const uint32_t stamp = *s_stamp;
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 2] = wall_clock64();   // x staged
@@ -334,13 +373,13 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
         const int i0 = cc.i0;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int r = grp + NG * (i0 + u);
-            const bool ok = all_full || ((i0 + u) < iters && r < nrows);
+            // a row past the slice has zero weights (its load was switched off) and any finite x
+            const int r = min(grp + NG * (i0 + u), p.RPS - 1);
             float f[8];
             unpack8(w[u], f);
 #pragma unroll
             for (int b = 0; b < BT; ++b) {
-                const float xv = ok ? xs[b * p.RPS + r] : 0.f;
+                const float xv = xs[b * p.RPS + r];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) acc[b][j] = fmaf(xv, f[j], acc[b][j]);
             }
@@ -348,6 +387,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     };
     auto finish = [&]() {         // epilogue of the step just consumed, then move the cursor on
         const int si = cc.si, i0 = cc.i0;
+        if (si >= nsel) return;                     // padding step: nothing was loaded
         advance(cc);
         if (i0 + U >= iters) {
             // last batch of this selector: row groups of a wavefront by shuffles; the wavefronts
@@ -373,63 +413,41 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
         }
     };
 
-    // steps k and k+1 are in flight at the top of every iteration; once no step of this phase is
-    // left to issue, the first loads of the next phase go out (before the last steps are consumed)
-    // issue_next(0) goes out before the last two steps are consumed.  (Not more than that: the
-    // partial-sum stores of the final flush queue behind every load issued before them.)
-    for (int k = 0; k < nsteps; k += 2) {
-        const bool last_iter = k + 2 >= nsteps;
-        if (last_iter) issue_next(0);
+    // Two steps are in flight at the top of every iteration.  The step count is padded to an even
+    // number >= 2 (a padding step loads nothing and adds zeros), so that the loop body and the
+    // tail are straight-line code with a fixed number of loads.  The scheduling barriers keep the
+    // reload of a register batch behind its last use, so the batch stays in the same registers
+    // (no branch may sit between consume() and the barrier: the multiply-adds would sink past it).
+    const int nsteps2 = max(2, (nsteps + 1) & ~1);
+    // the reload of a register batch must follow its last use, or the compiler keeps old and new
+    // batch in different registers and copies them (after a full drain) at the end of every
+    // iteration: the load offset is made to depend on the accumulators the batch was folded into
+    auto after_consume = [&]() {
+        uint32_t v = voff0;
+#pragma unroll
+        for (int b = 0; b < BT; ++b)
+            asm volatile("" : "+v"(v) : "v"(acc[b][0]), "v"(acc[b][1]), "v"(acc[b][2]), "v"(acc[b][3]),
+                         "v"(acc[b][4]), "v"(acc[b][5]), "v"(acc[b][6]), "v"(acc[b][7]));
+        return v;
+    };
+    for (int k = 0; k + 2 < nsteps2; k += 2) {
         consume(wa);
-        if (p.dbg_t && tid == 0 && k < 6) p.dbg_t[(size_t)blockIdx.x * kStamps + 8 + k] = wall_clock64();
-        if (!last_iter) load(wa);               // the registers are free: reload before any epilogue
+        load(wa, after_consume());
         finish();
-        if (k + 1 < nsteps) {
-            consume(wb);
-            if (p.dbg_t && tid == 0 && k + 1 < 6) p.dbg_t[(size_t)blockIdx.x * kStamps + 9 + k] = wall_clock64();
-            if (k + 3 < nsteps) load(wb);
-            finish();
-        }
+        consume(wb);
+        load(wb, after_consume());
+        finish();
     }
-    if (nsteps == 0) issue_next(0);
+    // tail: no step of this phase is left to issue, so the first loads of the next phase go out
+    // before the last two steps are consumed.  (Not earlier: the partial-sum stores of the final
+    // flush queue behind every load issued before them.)
+    issue_next(0);
+    consume(wa);
+    finish();
+    consume(wb);
+    finish();
     if (nbuf) flush();
     return stamp;
-}
-
-// cos/sin of pos * inv_freq[i] for i < HD/2, angle and range reduction in fp64.
-template <int HD>
-__device__ void rope_table(const Params &p, float *cs, float *sn)
-{
-    const int i = threadIdx.x;
-    if (i < HD / 2) {
-        const double ang = (double)p.pos * p.inv_freq[i];
-        const double k = rint(ang * 0.63661977236758134308);              // 2/pi
-        double r = fma(-k, 1.57079632679489655800e+00, ang);              // pi/2, high part
-        r = fma(-k, 6.12323399573676603587e-17, r);                       // pi/2, low part
-        const double r2 = r * r;                                          // |r| <= pi/4: Taylor series
-        double s = -1.0 / 1307674368000.0;
-        s = fma(s, r2, 1.0 / 6227020800.0);
-        s = fma(s, r2, -1.0 / 39916800.0);
-        s = fma(s, r2, 1.0 / 362880.0);
-        s = fma(s, r2, -1.0 / 5040.0);
-        s = fma(s, r2, 1.0 / 120.0);
-        s = fma(s, r2, -1.0 / 6.0);
-        s = fma(s * r2, r, r);
-        double c = 1.0 / 20922789888000.0;
-        c = fma(c, r2, -1.0 / 87178291200.0);
-        c = fma(c, r2, 1.0 / 479001600.0);
-        c = fma(c, r2, -1.0 / 3628800.0);
-        c = fma(c, r2, 1.0 / 40320.0);
-        c = fma(c, r2, -1.0 / 720.0);
-        c = fma(c, r2, 1.0 / 24.0);
-        c = fma(c, r2, -0.5);
-        c = fma(c, r2, 1.0);
-        const int q = (int)((long long)k & 3);
-        const double sv = (q == 0) ? s : (q == 1) ? c : (q == 2) ? -s : -c;
-        const double cv = (q == 0) ? c : (q == 1) ? -s : (q == 2) ? -c : s;
-        cs[i] = (float)cv;
-        sn[i] = (float)sv;
-    }
 }
 
 // ---------------------------------------------------------------------------
@@ -479,7 +497,7 @@ template <int G>
 struct P2Cfg {
     static constexpr int U = G >= 4 ? 2 : 4;    // rows per row group in one batch of loads
     static constexpr int GP = G >= 4 ? 4 : G;   // query heads handled per pass over a batch
-    static constexpr int NB = G <= 2 ? 3 : 2;   // batches in flight (as many as the register budget allows)
+    static constexpr int NB = 2;                // batches in flight
 };
 
 template <int G>
@@ -496,26 +514,31 @@ struct P2Stream {
     uint32_t voff0;
     size_t head;
     Stream K, V;
-    // rows >= pos are outside the buffers: they can never be read
-    __device__ __forceinline__ P2Stream(const Params &p, int team, int b, int s)
+    // rows >= pos are outside the buffers: they can never be read.  An inactive stream (a workgroup
+    // without an attention item) has an empty row range: its loads are issued with every lane off.
+    __device__ __forceinline__ P2Stream(const Params &p, int team, int b, int s, bool active = true)
         : head(((size_t)b * p.nkv + team) * p.max_seq * HD), K(p.kc + head, (uint32_t)p.pos * HD * 2),
           V(p.vc + head, (uint32_t)p.pos * HD * 2)
     {
         const int lig = threadIdx.x % LPR;
         grp = threadIdx.x / LPR;
-        t0 = s * p.TPS;
-        t1 = min(t0 + p.TPS, p.pos);
+        t0 = active ? s * p.TPS : 0;
+        t1 = active ? min(t0 + p.TPS, p.pos) : 0;
         iters = t1 > t0 ? (t1 - t0 + NG - 1) / NG : 0;
         voff0 = (uint32_t)(grp * HD + lig * 8) * 2;
     }
-    __device__ __forceinline__ void load(h8 (&kr)[U], h8 (&vr)[U], int i0) const
+    // Always 2*U load instructions on a straight-line path (rows past the split: lane switched off),
+    // so that the compiler's wait counts for earlier loads stay exact.
+    __device__ __forceinline__ void load(h8 (&kr)[U], h8 (&vr)[U], int i0, uint32_t voff_on) const
     {
+        const int lim = t1 - t0 - grp;                         // row NG*i + grp is inside the split iff NG*i < lim
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int tb = t0 + NG * (i0 + u);                 // first row of this step (uniform)
-            const uint32_t voff = (tb + grp) < t1 ? voff0 : kNoLoad;
-            kr[u] = K.ld(voff, (uint32_t)tb * HD * 2);
-            vr[u] = V.ld(voff, (uint32_t)tb * HD * 2);
+            const int i = i0 + u;
+            const uint32_t soff = (uint32_t)(t0 + NG * i) * HD * 2;   // first row of this step (uniform)
+            const uint32_t voff = NG * i < lim ? voff_on : kNoLoad;
+            kr[u] = K.ld(voff, soff);
+            vr[u] = V.ld(voff, soff);
         }
     }
     // the first NB batches do not depend on q: they are put in flight before q is needed; part 0
@@ -526,7 +549,7 @@ struct P2Stream {
         constexpr int NB = P2Cfg<G>::NB;
 #pragma unroll
         for (int j = 0; j < NB; ++j)
-            if ((j < 2) == (part == 0) && iters > j * U) load(buf.k[j], buf.v[j], j * U);
+            if ((j < 2) == (part == 0)) load(buf.k[j], buf.v[j], j * U, voff0);
     }
 };
 
@@ -652,18 +675,32 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
             }
         }
     };
-    // NB batches are in flight at the top of every iteration.  When all batches of the item are
-    // already out, the first loads of the next phase follow them at once.
+    // NB batches are in flight at the top of every iteration.  Consume and reload are unconditional
+    // (a batch past the split is all zeros with every row masked, its reload has every lane off), and
+    // the reload offset is made to depend on the state the batch was folded into: the reload then
+    // follows the last use of the registers it overwrites, so no copy and no drain is needed.
+    auto after_consume = [&]() {
+        uint32_t v = st.voff0;
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+            asm volatile("" : "+v"(v) : "v"(acc[g][0]), "v"(acc[g][1]), "v"(acc[g][2]), "v"(acc[g][3]),
+                         "v"(acc[g][4]), "v"(acc[g][5]), "v"(acc[g][6]), "v"(acc[g][7]), "v"(l[g]), "v"(m[g]));
+        return v;
+    };
     for (int i0 = 0; i0 < iters; i0 += NB * U) {
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            if (i0 + j * U < iters) {
-                consume(buf.k[j], buf.v[j], i0 + j * U);
-                if (i0 + (j + NB) * U < iters) st.load(buf.k[j], buf.v[j], i0 + (j + NB) * U);
-            }
+            consume(buf.k[j], buf.v[j], i0 + j * U);
+            st.load(buf.k[j], buf.v[j], i0 + (j + NB) * U, after_consume());
         }
     }
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 15] = wall_clock64();   // K/V consumed
+    // Nothing of this phase is left to load.  Half of the next phase's first tile goes out now and
+    // streams while the partial is merged and stored; the other half follows the stored partial.
+    // (Not all of it now: the vector memory path of a compute unit returns in order, so the stamped
+    // store and the next phase's polls wait for every bulk load issued before them.)  The member with
+    // the last split first polls for the new token's key/value sums, for the same reason.
+    if (!last) issue_next(1);
     // ---- merge the row groups of a wavefront
 #pragma unroll
     for (int off = LPR; off < 64; off <<= 1) {
@@ -692,6 +729,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
             for (int j = 0; j < 8; ++j) redacc[(g * NW + wv) * HD + lig * 8 + j] = acc[g][j];
         }
     }
+    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 8] = wall_clock64();
     if (last) {
         // ---- the new token: sum its key/value partials (stored at the end of phase 1, long ago by
         //      now), rotate the key, append both (Sec. 2.1) and score the token
@@ -700,6 +738,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
             const size_t src = (size_t)b * p.nqkv + qkv_col0<HD, G>(p, team, sel) + c;
             kn[e] = ll_sum(p, x1, src, (size_t)p.B * p.nqkv, p.KS, stamp);      // kn and vn are contiguous
         }
+        issue_next(1);
         lds_barrier();
         if (tid < HD / 2) {
             const float lo = kn[tid], hi = kn[tid + HD / 2], c = cs[tid], sgn = sn[tid];
@@ -724,6 +763,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
                     (G > P2Cfg<G>::GP) ? qs[e] / p.qk_scale_log2e : qs[e];
     }
     lds_barrier();
+    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 9] = wall_clock64();
     // ---- the wavefronts and the new token -> one partial (m, l, acc) per query head
     for (int e = tid; e < G * HD; e += NT) {
         const int g = e / HD, c = e - g * HD;
@@ -749,9 +789,8 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
         }
         x2.st(dst + kP2Stride + c, A, stamp);
     }
-    // the partial is on its way to the team; the rest of the next phase's first loads go out
-    // behind it and stream while the team's partials travel
-    issue_next(2);
+    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 10] = wall_clock64();
+    issue_next(2);       // the rest of the tile, behind the stored partial
     lds_barrier();
 }
 
@@ -767,7 +806,7 @@ struct OutTile {
     h8 w[MAXR];
 };
 
-// part: 0 = first half of the rows, 1 = second half, 2 = all
+// part: 0 = first half of the tile's loads, 1 = second half, 2 = all
 template <int HD>
 __device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs, int ch, OutTile<HD> &t, int part = 2)
 {
@@ -785,9 +824,7 @@ __device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs,
 #pragma unroll
     for (int u = 0; u < OutTile<HD>::MAXR; ++u) {
         const bool mine = part == 2 || (part == 0) == (u < OutTile<HD>::MAXR / 2);
-        if (mine) {
-            t.w[u] = Wo.ld(u < iters ? voff : kNoLoad, sbase + (uint32_t)(NW * u) * rowb);
-        }
+        if (mine) t.w[u] = Wo.ld(u < iters ? voff : kNoLoad, sbase + (uint32_t)(NW * u) * rowb);
     }
 }
 
@@ -810,73 +847,76 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
 
     if (!prefetched) p3_load<HD>(p, hq, c3, rs, 0, tile);     // independent of the attention result
 
-    // ---- merge of the split-KV partials (Alg. 3 steps 5-7).  Value v = (batch row, column) is
-    //      handled by SG threads, each folding every SG-th split with a running maximum; the SG
-    //      (m, l, a) triples are then folded in split order.  All loads of a thread go out together.
-    const int V = p.B * HD;
-    for (int v0 = 0; v0 < V; v0 += NT) {
-        const int cv = min(NT, V - v0);
-        const int SG = max(1, min(NT / cv, p.NS));
-        const int v = tid % cv, sg = tid / cv;
-        if (sg < SG) {
-            const int b = (v0 + v) / HD, c = (v0 + v) - b * HD;
-            const size_t src = ((size_t)b * p.nq + hq) * p.NS * PS;
-            float mt = kNegBig, lt = 0.f, at = 0.f;
-            for (int sb = sg; sb < p.NS; sb += 4 * SG) {
-                Spin spin;
-                float mm[4], ll[4], aa[4];
-                for (;;) {
-                    bool ok = true;
+    {
+        // ---- merge of the split-KV partials (Alg. 3 steps 5-7).  Value v = (batch row, column) is handled by SG threads,
+        //      each folding every SG-th split with a running maximum; the SG (m, l, a) triples are then
+        //      folded in split order.  All loads of a thread go out together.
+        const int V = p.B * HD;
+        for (int v0 = 0; v0 < V; v0 += NT) {
+            const int cv = min(NT, V - v0);
+            const int SG = max(1, min(NT / cv, p.NS));
+            const int v = tid % cv, sg = tid / cv;
+            if (sg < SG) {
+                const int b = (v0 + v) / HD, c = (v0 + v) - b * HD;
+                const size_t src = ((size_t)b * p.nq + hq) * p.NS * PS;
+                float mt = kNegBig, lt = 0.f, at = 0.f;
+                for (int sb = sg; sb < p.NS; sb += 4 * SG) {
+                    Spin spin;
+                    float mm[4], ll[4], aa[4];
+                    for (;;) {
+                        bool ok = true;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const int s = sb + k * SG;
+                            const size_t o = src + (size_t)(s < p.NS ? s : sb) * PS;
+                            const u32x2 vm = x2.ld(o), vl = x2.ld(o + 1), va = x2.ld(o + kP2Stride + c);
+                            ok &= (vm.y == stamp) & (vl.y == stamp) & (va.y == stamp);
+                            mm[k] = __builtin_bit_cast(float, vm.x);
+                            ll[k] = __builtin_bit_cast(float, vl.x);
+                            aa[k] = __builtin_bit_cast(float, va.x);
+                        }
+                        if (ok || spin.expired(p)) break;
+                    }
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
-                        const int s = sb + k * SG;
-                        const size_t o = src + (size_t)(s < p.NS ? s : sb) * PS;
-                        const u32x2 vm = x2.ld(o), vl = x2.ld(o + 1), va = x2.ld(o + kP2Stride + c);
-                        ok &= (vm.y == stamp) & (vl.y == stamp) & (va.y == stamp);
-                        mm[k] = __builtin_bit_cast(float, vm.x);
-                        ll[k] = __builtin_bit_cast(float, vl.x);
-                        aa[k] = __builtin_bit_cast(float, va.x);
-                    }
-                    if (ok || spin.expired(p)) break;
-                }
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    if (sb + k * SG < p.NS) {
-                        const float mn = fmaxf(mt, mm[k]);
-                        const float fa = __builtin_amdgcn_exp2f(mt - mn), fb = __builtin_amdgcn_exp2f(mm[k] - mn);
-                        lt = lt * fa + ll[k] * fb;
-                        at = at * fa + aa[k] * fb;
-                        mt = mn;
+                        if (sb + k * SG < p.NS) {
+                            const float mn = fmaxf(mt, mm[k]);
+                            const float fa = __builtin_amdgcn_exp2f(mt - mn), fb = __builtin_amdgcn_exp2f(mm[k] - mn);
+                            lt = lt * fa + ll[k] * fb;
+                            at = at * fa + aa[k] * fb;
+                            mt = mn;
+                        }
                     }
                 }
+                red[(sg * cv + v) * 3 + 0] = mt;
+                red[(sg * cv + v) * 3 + 1] = lt;
+                red[(sg * cv + v) * 3 + 2] = at;
             }
-            red[(sg * cv + v) * 3 + 0] = mt;
-            red[(sg * cv + v) * 3 + 1] = lt;
-            red[(sg * cv + v) * 3 + 2] = at;
+            lds_barrier();
+            if (tid < cv) {
+                float mt = kNegBig, lt = 0.f, at = 0.f;
+                for (int k = 0; k < SG; ++k) {
+                    const float mk = red[(k * cv + tid) * 3], lk = red[(k * cv + tid) * 3 + 1],
+                                ak = red[(k * cv + tid) * 3 + 2];
+                    const float mn = fmaxf(mt, mk);
+                    const float fa = __builtin_amdgcn_exp2f(mt - mn), fb = __builtin_amdgcn_exp2f(mk - mn);
+                    lt = lt * fa + lk * fb;
+                    at = at * fa + ak * fb;
+                    mt = mn;
+                }
+                const float a = at / lt;
+                as[v0 + tid] = a;
+                if (p.dbg_attn && c3 == 0 && rs == 0) {
+                    const int b = (v0 + tid) / HD, c = (v0 + tid) - b * HD;
+                    p.dbg_attn[((size_t)b * p.nq + hq) * HD + c] = a;
+                }
+            }
+            lds_barrier();
         }
-        lds_barrier();
-        if (tid < cv) {
-            float mt = kNegBig, lt = 0.f, at = 0.f;
-            for (int k = 0; k < SG; ++k) {
-                const float mk = red[(k * cv + tid) * 3], lk = red[(k * cv + tid) * 3 + 1],
-                            ak = red[(k * cv + tid) * 3 + 2];
-                const float mn = fmaxf(mt, mk);
-                const float fa = __builtin_amdgcn_exp2f(mt - mn), fb = __builtin_amdgcn_exp2f(mk - mn);
-                lt = lt * fa + lk * fb;
-                at = at * fa + ak * fb;
-                mt = mn;
-            }
-            const float a = at / lt;
-            as[v0 + tid] = a;
-            if (p.dbg_attn && c3 == 0 && rs == 0) {
-                const int b = (v0 + tid) / HD, c = (v0 + tid) - b * HD;
-                p.dbg_attn[((size_t)b * p.nq + hq) * HD + c] = a;
-            }
-        }
+        for (int e = V + tid; e < BT * HD; e += NT) as[e] = 0.f;
         lds_barrier();
     }
-    for (int e = V + tid; e < BT * HD; e += NT) as[e] = 0.f;
-    lds_barrier();
+    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 11] = wall_clock64();   // attention merged
 
     for (int ch = 0; ch < nchunk; ++ch) {
         const int cbase = c3 * p.CW3 + ch * kOutChunk;
@@ -979,20 +1019,14 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
     const int n3 = G * p.NC3 * p.RS3;                // output-projection items of the team
     KvBuf<G> kv;
     OutTile<HD> tile;
-    P2Stream<HD, G> st2(p, team, member < n2 ? member / p.NS : 0, member < n2 ? member % p.NS : 0);
+    P2Stream<HD, G> st2(p, team, member < n2 ? member / p.NS : 0, member < n2 ? member % p.NS : 0, member < n2);
 
     // ---- phase 1 (projection); its last step already starts the K/V stream of phase 2
     EarlyQ eq;
-    const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, &s_stamp, [&](int stage) {
-        if (member < n2) {
-            st2.prefetch(kv, 0);
-        }
-        rope_table<HD>(p, s_rope, s_rope + HD / 2);      // needs nothing but pos; overlaps the stream
-    });
-    if (member < n2) {
-        eq.issue<HD, G>(p, team, member / p.NS);    // q partials were stored a third of the way into phase 1
-        st2.prefetch(kv, 1);
-    }
+    const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, &s_stamp, s_rope,
+                                             [&](int stage) { st2.prefetch(kv, 0); });
+    if (member < n2) eq.issue<HD, G>(p, team, member / p.NS);   // q partials were stored a third of the way into phase 1
+    st2.prefetch(kv, 1);
     stamp_t(1);
     // ---- phase 2 (attention); the last item already starts the W_o stream of phase 3
     auto p3_args = [&](int it, int &hq, int &c3, int &rs) {
@@ -1017,8 +1051,9 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
             st2.prefetch(kv, 0);
             st2.prefetch(kv, 1);
         }
-        p2_item<HD, G>(p, team, it / p.NS, it % p.NS, stamp, first, st2, kv, eq, smem, s_rope, [&](int part) {
-            if (final_item) p3_prefetch(part);
+        // stage 1: first half of the output-projection tile, stage 2: second half
+        p2_item<HD, G>(p, team, it / p.NS, it % p.NS, stamp, first, st2, kv, eq, smem, s_rope, [&](int stage) {
+            if (final_item) p3_prefetch(stage - 1);
         });
     }
     if (member >= n2) p3_prefetch(2);
