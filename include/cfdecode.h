@@ -92,7 +92,10 @@ int cf_decode_block(cf_handle h, int32_t batch, const void *x, const void *W_qkv
  * Optional layout for the (static) weights that lets every workgroup stream one
  * contiguous block instead of a strided column strip; same bytes, same arithmetic.
  * It is the per-head form of Eq. 1 (W_Qi, W_Ki, W_Vi per head):
- *   W_qkv_packed [(n_q + 2 n_kv)][d_model][head_dim]   block j = columns [j*head_dim, (j+1)*head_dim) of W_qkv
+ *   W_qkv_packed [(n_q + 2 n_kv)][d_model][head_dim]   block j = columns [j*head_dim, (j+1)*head_dim) of W_qkv;
+ *                                                        each block is followed by 256 zero bytes, so that
+ *                                                        equal positions in different blocks fall into
+ *                                                        different memory channels
  *   W_o_packed   [n_q][ceil(d_model/512)][head_dim][512]  tile (i, c) = rows of head i, columns [512c, 512c+512)
  *                                                          of W_o, zero-filled past d_model
  * cf_packed_sizes gives the two buffer sizes in bytes; cf_pack_weights enqueues the

@@ -3,6 +3,7 @@
 #include "cf_params.h"
 
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -30,6 +31,7 @@ struct cf_handle_s {
     unsigned long long *dbg_t = nullptr;
     // tuning
     int tune_w = 0, tune_ks = 0, tune_ns = 0;
+    int balance_rows = 0, balance_tokens = 32;   // half the length difference between even and odd splits (-1: off)
     long long spin_ticks = 200000000LL;   // 2 s of the 100 MHz wall clock
     int wg_per_cu[3] = {0, 0, 0};         // resident workgroups per CU for batch tiles 1, 4, 16 (0 = not probed)
     int xcd_local = -1;                   // -1 not probed, 0 off, 1 on (team members share an XCD)
@@ -91,7 +93,16 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
         }
         if (!best) return h->tune_ks > 0 ? CF_EINVAL : CF_EUNSUPPORTED;
         p->KS = best;
-        p->RPS = ceil_div(c.d_model, best);
+        p->RB = ceil_div(c.d_model, best);
+        // uneven slices (see the kernel's workgroup mapping): only when member parity == slice parity
+        p->pairmap = (TS % 2 == 0 && W % 2 == 0 && h->balance_rows >= 0) ? 1 : 0;
+        p->RD = 0;
+        if (p->pairmap && best % 2 == 0 && p->RB * best == c.d_model && p->RB >= 8 * h->balance_rows) {
+            const int maxi = bt == 1 ? 4 : (bt <= 4 ? 2 : 1);
+            const size_t lds = ((size_t)bt * (p->RB + h->balance_rows) + (size_t)maxi * cf::kWaves * bt * hd) * sizeof(float);
+            if (lds <= kLdsLimit) p->RD = h->balance_rows;
+        }
+        p->RPS = p->RB + p->RD;
     }
     // attention: split the cached sequence so that B*NS items balance over TS members
     {
@@ -116,6 +127,8 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
         int tps = ceil_div(pos + discount, best);
         if (tps * (best - 1) > pos) tps = ceil_div(pos, best);
         p->TPS = tps > 0 ? tps : 1;
+        p->TD = 0;
+        if (p->pairmap && best % 2 == 0 && TS % best == 0 && p->TPS >= 8 * h->balance_tokens) p->TD = h->balance_tokens;
     }
     // output projection: G heads x NC3 column blocks x RS3 row splits per team
     {
@@ -218,7 +231,7 @@ int cf_create(const cf_config *cfg, cf_handle *out)
         // the kernel addresses each tensor with 32-bit byte offsets
         const unsigned long long lim = 0x7fffffffull;
         const unsigned long long nqkv = (unsigned long long)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
-        if (2ull * c.d_model * nqkv > lim || 2ull * c.n_q_heads * c.head_dim * c.d_model > lim ||
+        if (2ull * c.d_model * nqkv + 256ull * (nqkv / c.head_dim) > lim || 2ull * c.n_q_heads * c.head_dim * c.d_model > lim ||
             2ull * c.max_seq * c.head_dim > lim)
             return CF_EUNSUPPORTED;
     }
@@ -229,6 +242,15 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     if (!h) return CF_ENOMEM;
     h->cfg = c;
     h->G = G;
+    // CF_BALANCE="rows,tokens": half the length difference between the splits of workgroups on even
+    // and odd dies, for experiments; "-1" keeps the plain workgroup mapping and equal splits
+    if (const char *e = std::getenv("CF_BALANCE")) {
+        int r = 0, t = 0;
+        const int n = std::sscanf(e, "%d,%d", &r, &t);
+        if (n >= 1) h->balance_rows = r < 0 ? -1 : (r / 8) * 8;
+        if (n >= 2) h->balance_tokens = t < 0 ? 0 : t;
+        if (h->balance_rows < 0) h->balance_tokens = 0;
+    }
     h->nqkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     h->nch = ceil_div(c.d_model, cf::kOutChunk);
 
@@ -321,7 +343,7 @@ static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, co
     p.B = batch;
     p.pos = pos;
     p.packed = packed;
-    p.xcd_local = h->xcd_local > 0 ? 1 : 0;
+    p.xcd_local = (h->xcd_local > 0 && !p.pairmap) ? 1 : 0;
     int rc = make_plan(h, batch, pos, &p);
     if (rc != CF_OK) return rc;
     const int bt = batch_tile(batch);
@@ -329,7 +351,7 @@ static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, co
     if (lds > kLdsLimit) return CF_EUNSUPPORTED;
     rc = check_residency(h, p, bt, lds);
     if (rc != CF_OK) return rc;
-    const int plan[10] = {p.W, p.TS, p.KS, p.RPS, p.NS, p.TPS, p.NC3, p.CW3, p.RS3, (int)lds};
+    const int plan[10] = {p.W, p.TS, p.KS, p.RB, p.NS, p.TPS, p.NC3, p.CW3, p.RS3, (int)lds};
     std::memcpy(h->last_plan, plan, sizeof plan);
     h->last_batch = batch;
     hipError_t e = cf::launch_fused(p, h->cfg.head_dim, h->G, bt, lds, static_cast<hipStream_t>(stream));
@@ -352,7 +374,7 @@ int cf_decode_block_packed(cf_handle h, int32_t batch, const void *x, const void
 int cf_packed_sizes(cf_handle h, size_t *qkv_bytes, size_t *o_bytes)
 {
     if (!h || !qkv_bytes || !o_bytes) return CF_EINVAL;
-    *qkv_bytes = (size_t)h->cfg.d_model * h->nqkv * 2;
+    *qkv_bytes = (size_t)(h->nqkv / h->cfg.head_dim) * ((size_t)h->cfg.d_model * h->cfg.head_dim * 2 + cf::kQkvBlockPad);
     *o_bytes = (size_t)h->cfg.n_q_heads * h->nch * h->cfg.head_dim * cf::kOutChunk * 2;
     return CF_OK;
 }

@@ -245,8 +245,10 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     const int tid = threadIdx.x, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
     const int ks = member % p.KS;
     const int sel0 = member / p.KS, dsel = p.TS / p.KS;
-    const int r0 = ks * p.RPS;
-    const int nrows = min(p.RPS, p.D - r0);                 // > 0: the host never plans an empty slice
+    // slices with an even index (workgroups on the faster dies, see the workgroup mapping in the
+    // kernel) are 2*RD rows longer than those with an odd index
+    const int r0 = ks * p.RB + ((ks & 1) ? p.RD : 0);
+    const int nrows = min(p.RB + ((ks & 1) ? -p.RD : p.RD), p.D - r0);   // > 0: the host never plans an empty slice
     const int iters = (nrows + NG - 1) / NG;
     const int nb = (iters + U - 1) / U;                     // load batches per selector
     const int nA = sel0 < G ? (G - sel0 + dsel - 1) / dsel : 0;
@@ -256,9 +258,10 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     float *xs = smem;                       // [BT][RPS]
     float *red = smem + BT * p.RPS;         // [MAXI][NW][BT][HD]
     const Xbuf x1(p.p1, p.xcd_local != 0);
-    const Stream W(p.wqkv, (uint32_t)((size_t)p.D * p.nqkv * 2));
+    const uint32_t blkb = (uint32_t)p.D * HD * 2 + kQkvBlockPad;          // packed: bytes from one block to the next
+    const Stream W(p.wqkv, p.packed ? (uint32_t)(p.nqkv / HD) * blkb : (uint32_t)((size_t)p.D * p.nqkv * 2));
     // row-major [D][Nqkv]: rows are Nqkv*2 bytes apart and a selector starts at column col0;
-    // packed [Nqkv/HD][D][HD]: rows are HD*2 bytes apart and a selector is one contiguous block
+    // packed [Nqkv/HD][D][HD] (+ pad): rows are HD*2 bytes apart and a selector is one contiguous block
     const uint32_t rowb = p.packed ? (uint32_t)HD * 2 : (uint32_t)p.nqkv * 2;
     const uint32_t voff0 = (uint32_t)grp * rowb + lig * 16;
 
@@ -272,7 +275,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     };
     auto blk_base = [&](int si) {
         const uint32_t col0 = (uint32_t)qkv_col0<HD, G>(p, team, sel_of(si));
-        return (uint32_t)r0 * rowb + (p.packed ? col0 * (uint32_t)p.D * 2 : col0 * 2);
+        return (uint32_t)r0 * rowb + (p.packed ? (col0 / HD) * blkb : col0 * 2);
     };
     auto advance = [&](Cursor &c) {
         c.i0 += U;
@@ -302,7 +305,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
 
     // Kernel start: the small loads (launch counter, this slice of x) are issued first, then two
     // batches of weights; loads return in order, so x is staged into LDS while the weights stream.
-    constexpr int XR = BT;                                        // x values per thread kept in registers
+    constexpr int XR = BT + 1;                                    // x values per thread kept in registers
     const bool x_in_regs = BT * p.RPS <= XR * NT;
     // (all of them unconditional: a load inside a branch would be waited for at the branch's end)
     // lane 0 of the workgroup reads the launch counter (coherent load; other lanes load nothing)
@@ -522,8 +525,8 @@ struct P2Stream {
     {
         const int lig = threadIdx.x % LPR;
         grp = threadIdx.x / LPR;
-        t0 = active ? s * p.TPS : 0;
-        t1 = active ? min(t0 + p.TPS, p.pos) : 0;
+        t0 = active ? s * p.TPS + ((s & 1) ? p.TD : 0) : 0;         // even splits are 2*TD tokens longer
+        t1 = active ? min(t0 + p.TPS + ((s & 1) ? -p.TD : p.TD), p.pos) : 0;
         iters = t1 > t0 ? (t1 - t0 + NG - 1) / NG : 0;
         voff0 = (uint32_t)(grp * HD + lig * 8) * 2;
     }
@@ -1005,8 +1008,12 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
     __shared__ uint32_t s_stamp;
     __shared__ float s_rope[HD];                     // cos / sin of the RoPE angles of this position
     const int tid = threadIdx.x;
-    const int team = blockIdx.x % p.nkv;
-    const int member = blockIdx.x / p.nkv;
+    // Workgroup w runs on die (XCD) w % 8, and the odd dies get about a tenth less memory
+    // bandwidth than the even ones.  With pairmap a team sits on one pair of dies, members with an
+    // even index on the even die: those take the longer slices and splits.
+    const int w = blockIdx.x;
+    const int team = p.pairmap ? (w >> 1) % p.nkv : w % p.nkv;
+    const int member = p.pairmap ? ((w >> 1) / p.nkv) * 2 + (w & 1) : w / p.nkv;
     auto stamp_t = [&](int k) {
         if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + k] = wall_clock64();
     };
@@ -1077,9 +1084,12 @@ __global__ void pack_qkv_kernel(const uint4 *__restrict__ src, uint4 *__restrict
 {
     const size_t n = (size_t)D * nqkv / 8;
     const int v_per_row = hd / 8;
+    const size_t blk = (size_t)v_per_row * D + kQkvBlockPad / 16;      // block stride in 16-byte units
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
         const size_t c8 = i % v_per_row, r = (i / v_per_row) % D, cb = i / ((size_t)v_per_row * D);
-        dst[i] = src[(r * nqkv + cb * hd) / 8 + c8];
+        dst[cb * blk + r * v_per_row + c8] = src[(r * nqkv + cb * hd) / 8 + c8];
+        if (r == 0 && c8 == 0)
+            for (int k = 0; k < kQkvBlockPad / 16; ++k) dst[cb * blk + (size_t)v_per_row * D + k] = make_uint4(0, 0, 0, 0);
     }
 }
 

@@ -12,6 +12,10 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kOutChunk = 512;             // output columns one wavefront covers with one 128-bit load per lane
 constexpr int kP2Stride = 4;               // floats in front of the accumulator in a split-KV partial: m, l, pad, pad
 constexpr int kStamps = 16;                // debug time stamps per workgroup
+// Bytes between the end of one per-head block of the packed W_qkv and the start of the next.  With
+// power-of-two block sizes all workgroups would walk through the memory channels in step (measured:
+// a tenth less bandwidth); 256 bytes shift each block by one channel.
+constexpr int kQkvBlockPad = 256;
 constexpr int kMaxKSplits = 64;
 constexpr int kMaxKvSplits = 64;
 
@@ -31,7 +35,10 @@ struct Params {
     unsigned long long *dbg_t; // [W][kStamps] wall-clock stamps at phase boundaries, or null
     int D, nq, nkv, B, pos, max_seq, nqkv;
     int W, TS;             // workgroups, workgroups per team (team = one KV head)
-    int KS, RPS;           // projection: splits of the reduction dimension, rows per split
+    int KS, RPS;           // projection: splits of the reduction dimension, rows of the longest split (LDS stride)
+    int RB, RD;            // rows of a split are RB + RD (even split index) or RB - RD (odd)
+    int TD;                // attention: tokens of a split are TPS + TD (even split index) or TPS - TD (odd)
+    int pairmap;           // workgroup -> (team, member) keeps the parity of the workgroup id in the member id
     int NS, TPS;           // attention: splits of the cached sequence, tokens per split
     int NC3, CW3, RS3;     // output projection: column blocks, columns per block, row splits per head
     int NCH;               // number of 512-column chunks of the output

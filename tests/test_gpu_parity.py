@@ -118,12 +118,15 @@ def test_small_shapes_match_oracle(name, shape, batch, kv_len, packed):
     _log("plan %s" % r.blk.plan())
     check(res, oracle(inp, shape, kv_len), inp, kv_len, name)
     if packed:
-        # the packed buffers are a pure rearrangement of the weights: per-head blocks of W_qkv,
+        # the packed buffers are a pure rearrangement of the weights: per-head blocks of W_qkv (padded),
         # [head][512-column chunk][row][512] tiles of W_o, zero-filled past d_model (bit-exact)
         D, nq, d = shape.d_model, shape.n_q_heads, shape.head_dim
         wq_p, wo_p = (a.cpu().numpy().view(np.uint16) for a in r.packed)
         want_q = inp["w_qkv"].view(np.uint16).reshape(D, shape.n_qkv // d, d).transpose(1, 0, 2)
-        assert np.array_equal(wq_p.reshape(want_q.shape), want_q)
+        nblk, pad = shape.n_qkv // d, 128                  # each block is followed by 256 zero bytes
+        got_q = wq_p.reshape(nblk, D * d + pad)
+        assert np.array_equal(got_q[:, :D * d].reshape(want_q.shape), want_q)
+        assert not got_q[:, D * d:].any()
         nch = (D + 511) // 512
         padded = np.zeros((nq * d, nch * 512), dtype=np.uint16)
         padded[:, :D] = inp["w_o"].view(np.uint16)
