@@ -152,6 +152,16 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
         p->NC3 = ceil_div(nch * cf::kOutChunk, p->CW3);
     }
     p->NCH = h->nch;
+    p->DSEL = TS / p->KS;
+    auto log2_or_minus1 = [](int v) {
+        for (int k = 0; k < 31; ++k)
+            if ((1 << k) == v) return k;
+        return -1;
+    };
+    p->sh_nkv = log2_or_minus1(c.n_kv_heads);
+    p->sh_ks = log2_or_minus1(p->KS);
+    p->sh_dsel = log2_or_minus1(p->DSEL);
+    p->sh_ns = log2_or_minus1(p->NS);
     return CF_OK;
 }
 
@@ -268,7 +278,8 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     }
 
     const size_t B = (size_t)c.max_batch, hd = (size_t)c.head_dim;
-    h->counters_bytes = 256;   // finished-workgroup counter and error flag
+    // error flag, then one launch counter per workgroup, each in a 128-byte line of its own
+    h->counters_bytes = 256 + (size_t)8 * h->num_cu * cf::kCounterStride * sizeof(unsigned long long);
     const size_t p1_bytes = align_up((size_t)kMaxKS * B * h->nqkv * sizeof(uint64_t), 256);
     const size_t p2_bytes = align_up(B * c.n_q_heads * cf::kMaxKvSplits * (hd + cf::kP2Stride) * sizeof(uint64_t), 256);
     const size_t p3_bytes = align_up((size_t)c.n_q_heads * 8 * B * c.d_model * sizeof(uint64_t), 256);
@@ -283,8 +294,8 @@ int cf_create(const cf_config *cfg, cf_handle *out)
         return e == hipErrorOutOfMemory ? CF_ENOMEM : CF_EHIP;
     }
     char *cur = h->ws;
-    h->done = reinterpret_cast<unsigned long long *>(cur);
     h->err = reinterpret_cast<uint32_t *>(cur + 128);
+    h->done = reinterpret_cast<unsigned long long *>(cur + 256);
     cur += h->counters_bytes;
     h->p1 = reinterpret_cast<uint64_t *>(cur);
     cur += p1_bytes;

@@ -180,6 +180,12 @@ __device__ __forceinline__ float ll_sum(const Params &p, const Xbuf &x, size_t b
     }
 }
 
+// Division by a plan constant: a shift when the host found a power of two (sh >= 0).  Integer division
+// by a run-time value costs some thirty instructions, and a handful of them sat between the start of
+// the kernel and its first weight load.
+__device__ __forceinline__ int qdiv(int n, int d, int sh) { return sh >= 0 ? (n >> sh) : n / d; }
+__device__ __forceinline__ int qmod(int n, int d, int sh) { return sh >= 0 ? (n & (d - 1)) : n % d; }
+
 // First weight column of selector `sel` for a team: sel < G query heads, G = key, G+1 = value.
 template <int HD, int G>
 __device__ __forceinline__ int qkv_col0(const Params &p, int team, int sel)
@@ -234,25 +240,33 @@ __device__ __forceinline__ void rope_table(int pos, double inv_freq, float *cs, 
 // of the NEXT phase (issue_next) are issued before the last step is consumed, so the
 // memory pipe never drains.
 // ---------------------------------------------------------------------------
+// Experiment builds only (-DCF_TRACE_P1, handle created with the debug flag): branch-free time stamps
+// inside phase 1, written by every thread, in place of the detail stamps of the later phases.
+#ifdef CF_TRACE_P1
+#define CF_TRACE_STAMP(k) p.dbg_t[(size_t)blockIdx.x * kStamps + (k)] = wall_clock64()
+#else
+#define CF_TRACE_STAMP(k)
+#endif
+
 template <int HD, int G, int BT, class NextFn>
-__device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member, float *smem, uint32_t *s_stamp,
-                                           float *rope, NextFn &&issue_next)
+__device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member, float *smem,
+                                           float *rope, unsigned long long &launches_out, NextFn &&issue_next)
 {
     constexpr int LPR = HD / 8;
     constexpr int NG = NT / LPR;
     constexpr int U = 8;
     constexpr int MAXI = BT == 1 ? 4 : (BT <= 4 ? 2 : 1);   // selectors whose wave partials are buffered in LDS
     const int tid = threadIdx.x, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
-    const int ks = member % p.KS;
-    const int sel0 = member / p.KS, dsel = p.TS / p.KS;
+    const int ks = qmod(member, p.KS, p.sh_ks);
+    const int sel0 = qdiv(member, p.KS, p.sh_ks), dsel = p.DSEL;
     // slices with an even index (workgroups on the faster dies, see the workgroup mapping in the
     // kernel) are 2*RD rows longer than those with an odd index
     const int r0 = ks * p.RB + ((ks & 1) ? p.RD : 0);
     const int nrows = min(p.RB + ((ks & 1) ? -p.RD : p.RD), p.D - r0);   // > 0: the host never plans an empty slice
     const int iters = (nrows + NG - 1) / NG;
     const int nb = (iters + U - 1) / U;                     // load batches per selector
-    const int nA = sel0 < G ? (G - sel0 + dsel - 1) / dsel : 0;
-    const int nB = sel0 < 2 ? (2 - sel0 + dsel - 1) / dsel : 0;
+    const int nA = sel0 < G ? qdiv(G - sel0 + dsel - 1, dsel, p.sh_dsel) : 0;
+    const int nB = sel0 < 2 ? qdiv(2 - sel0 + dsel - 1, dsel, p.sh_dsel) : 0;
     const int nsteps = (nA + nB) * nb;
     auto sel_of = [&](int si) { return si < nA ? sel0 + si * dsel : G + sel0 + (si - nA) * dsel; };
     float *xs = smem;                       // [BT][RPS]
@@ -303,34 +317,43 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
         if (live) advance(lc);
     };
 
-    // Kernel start: the small loads (launch counter, this slice of x) are issued first, then two
+    CF_TRACE_STAMP(9);      // phase 1 set up
+    // Kernel start: the small loads (this slice of x, the RoPE frequencies) are issued first, then two
     // batches of weights; loads return in order, so x is staged into LDS while the weights stream.
     constexpr int XR = BT + 1;                                    // x values per thread kept in registers
     const bool x_in_regs = BT * p.RPS <= XR * NT;
     // (all of them unconditional: a load inside a branch would be waited for at the branch's end)
-    // lane 0 of the workgroup reads the launch counter (coherent load; other lanes load nothing)
-    const __amdgpu_buffer_rsrc_t done_rsrc = __builtin_amdgcn_make_buffer_rsrc(p.done, 0, 8, 0x00020000);
-    const u32x2 fin2 = __builtin_amdgcn_raw_buffer_load_b64(done_rsrc, tid == 0 ? 0u : kNoLoad, 0, 16);
     uint16_t xr[XR];
     bool xv[XR];
 #pragma unroll
     for (int q = 0; q < XR; ++q) {
-        const int i = tid + q * NT, b = i / p.RPS, r = i - b * p.RPS;
+        const int i = tid + q * NT, b = BT == 1 ? 0 : i / p.RPS, r = i - b * p.RPS;
         xv[q] = x_in_regs && i < BT * p.RPS && b < p.B && r < nrows;
         xr[q] = p.x[xv[q] ? (size_t)b * p.D + r0 + r : 0];
     }
     const double inv_freq = p.inv_freq[tid < HD / 2 ? tid : 0];   // for the RoPE table, below
     __builtin_amdgcn_sched_barrier(0);                            // keep the small loads in front
+    CF_TRACE_STAMP(10);     // small loads issued
     h8 wa[U], wb[U];
     load(wa, voff0);
     load(wb, voff0);
     __builtin_amdgcn_sched_barrier(0);
-    if (tid == 0) {
-        // launch number = finished workgroups / workgroups per launch + 1.  A workgroup of this launch
-        // that starts late still sees fewer than W finished ones of this launch, hence the same value.
-        const unsigned long long fin = ((unsigned long long)fin2.y << 32) | fin2.x;
-        *s_stamp = (uint32_t)(fin / (unsigned long long)p.W + 1ull);
-    }
+    CF_TRACE_STAMP(12);     // first loads issued
+    // Launch number: every workgroup keeps, in a line of its own, the number of launches it has
+    // completed; all workgroups of a launch hold the same count, so count + 1 stamps this launch
+    // without any shared counter.  (One counter for all was read by 256 workgroups at once and
+    // bumped by 256 atomics at the end: both are served one after the other, microseconds in all,
+    // and the read sat at the head of the in-order return queue in front of the weights.)  The
+    // value was written in an earlier launch, so a scalar load through the cache is good enough,
+    // and it does not enter the vector memory queue at all.
+    unsigned long long launches;
+    asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)"
+                 : "=s"(launches)
+                 : "s"(p.done + (size_t)blockIdx.x * kCounterStride)
+                 : "memory");
+    // never 0 (the value of a cleared slot): the low word plus the number of times it has wrapped
+    const unsigned long long cnt = launches + 1ull;
+    const uint32_t stamp = (uint32_t)(cnt + (cnt >> 32));
     if (x_in_regs) {
 #pragma unroll
         for (int q = 0; q < XR; ++q) {
@@ -346,7 +369,6 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     // cos / sin of this position while the first weights are still on their way
     rope_table<HD>(p.pos, inv_freq, rope, rope + HD / 2);
     lds_barrier();
-    const uint32_t stamp = *s_stamp;
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 2] = wall_clock64();   // x staged
 
     float acc[BT][8];
@@ -436,6 +458,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     for (int k = 0; k + 2 < nsteps2; k += 2) {
         consume(wa);
         load(wa, after_consume());
+        CF_TRACE_STAMP(8);
         finish();
         consume(wb);
         load(wb, after_consume());
@@ -450,6 +473,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     consume(wb);
     finish();
     if (nbuf) flush();
+    launches_out = cnt;
     return stamp;
 }
 
@@ -732,7 +756,9 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
             for (int j = 0; j < 8; ++j) redacc[(g * NW + wv) * HD + lig * 8 + j] = acc[g][j];
         }
     }
+#ifndef CF_TRACE_P1
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 8] = wall_clock64();
+#endif
     if (last) {
         // ---- the new token: sum its key/value partials (stored at the end of phase 1, long ago by
         //      now), rotate the key, append both (Sec. 2.1) and score the token
@@ -766,7 +792,9 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
                     (G > P2Cfg<G>::GP) ? qs[e] / p.qk_scale_log2e : qs[e];
     }
     lds_barrier();
+#ifndef CF_TRACE_P1
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 9] = wall_clock64();
+#endif
     // ---- the wavefronts and the new token -> one partial (m, l, acc) per query head
     for (int e = tid; e < G * HD; e += NT) {
         const int g = e / HD, c = e - g * HD;
@@ -792,7 +820,9 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
         }
         x2.st(dst + kP2Stride + c, A, stamp);
     }
+#ifndef CF_TRACE_P1
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 10] = wall_clock64();
+#endif
     issue_next(2);       // the rest of the tile, behind the stored partial
     lds_barrier();
 }
@@ -919,7 +949,9 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
         for (int e = V + tid; e < BT * HD; e += NT) as[e] = 0.f;
         lds_barrier();
     }
+#ifndef CF_TRACE_P1
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 11] = wall_clock64();   // attention merged
+#endif
 
     for (int ch = 0; ch < nchunk; ++ch) {
         const int cbase = c3 * p.CW3 + ch * kOutChunk;
@@ -1005,15 +1037,27 @@ template <int HD, int G, int BT>
 __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
 {
     extern __shared__ float smem[];
-    __shared__ uint32_t s_stamp;
+    {
+        // The compiler loads each kernel argument shortly before its first use: several dependent
+        // round trips to cold memory in a row at the start of every launch.  One word of every 64-byte
+        // line of the argument block is read here, all at once, so the later reads hit the scalar cache.
+        static_assert(sizeof(Params) <= 256, "one load per 64-byte line of the argument block below");
+        auto ka = __builtin_amdgcn_kernarg_segment_ptr();
+        uint32_t t0, t1, t2, t3;
+        asm volatile("s_load_dword %0, %4, 0x0\n\ts_load_dword %1, %4, 0x40\n\ts_load_dword %2, %4, 0x80\n\t"
+                     "s_load_dword %3, %4, 0xc0\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3)
+                     : "s"(ka));
+    }
     __shared__ float s_rope[HD];                     // cos / sin of the RoPE angles of this position
     const int tid = threadIdx.x;
+    CF_TRACE_STAMP(13);     // kernel entry
     // Workgroup w runs on die (XCD) w % 8, and the odd dies get about a tenth less memory
     // bandwidth than the even ones.  With pairmap a team sits on one pair of dies, members with an
     // even index on the even die: those take the longer slices and splits.
     const int w = blockIdx.x;
-    const int team = p.pairmap ? (w >> 1) % p.nkv : w % p.nkv;
-    const int member = p.pairmap ? ((w >> 1) / p.nkv) * 2 + (w & 1) : w / p.nkv;
+    const int team = p.pairmap ? qmod(w >> 1, p.nkv, p.sh_nkv) : qmod(w, p.nkv, p.sh_nkv);
+    const int member = p.pairmap ? qdiv(w >> 1, p.nkv, p.sh_nkv) * 2 + (w & 1) : qdiv(w, p.nkv, p.sh_nkv);
     auto stamp_t = [&](int k) {
         if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + k] = wall_clock64();
     };
@@ -1026,13 +1070,16 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
     const int n3 = G * p.NC3 * p.RS3;                // output-projection items of the team
     KvBuf<G> kv;
     OutTile<HD> tile;
-    P2Stream<HD, G> st2(p, team, member < n2 ? member / p.NS : 0, member < n2 ? member % p.NS : 0, member < n2);
+    P2Stream<HD, G> st2(p, team, member < n2 ? qdiv(member, p.NS, p.sh_ns) : 0, member < n2 ? qmod(member, p.NS, p.sh_ns) : 0,
+                        member < n2);
 
+    CF_TRACE_STAMP(11);     // streams set up
     // ---- phase 1 (projection); its last step already starts the K/V stream of phase 2
     EarlyQ eq;
-    const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, &s_stamp, s_rope,
+    unsigned long long launch_count;
+    const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, s_rope, launch_count,
                                              [&](int stage) { st2.prefetch(kv, 0); });
-    if (member < n2) eq.issue<HD, G>(p, team, member / p.NS);   // q partials were stored a third of the way into phase 1
+    if (member < n2) eq.issue<HD, G>(p, team, qdiv(member, p.NS, p.sh_ns));   // q partials were stored a third of the way into phase 1
     st2.prefetch(kv, 1);
     stamp_t(1);
     // ---- phase 2 (attention); the last item already starts the W_o stream of phase 3
@@ -1054,12 +1101,12 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
     for (int it = member; it < n2; it += p.TS) {
         const bool first = (it == member), final_item = (it + p.TS >= n2);
         if (!first) {
-            st2 = P2Stream<HD, G>(p, team, it / p.NS, it % p.NS);
+            st2 = P2Stream<HD, G>(p, team, qdiv(it, p.NS, p.sh_ns), qmod(it, p.NS, p.sh_ns));
             st2.prefetch(kv, 0);
             st2.prefetch(kv, 1);
         }
         // stage 1: first half of the output-projection tile, stage 2: second half
-        p2_item<HD, G>(p, team, it / p.NS, it % p.NS, stamp, first, st2, kv, eq, smem, s_rope, [&](int stage) {
+        p2_item<HD, G>(p, team, qdiv(it, p.NS, p.sh_ns), qmod(it, p.NS, p.sh_ns), stamp, first, st2, kv, eq, smem, s_rope, [&](int stage) {
             if (final_item) p3_prefetch(stage - 1);
         });
     }
@@ -1075,7 +1122,7 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
     // ---- phase 4 (sum over heads)
     final_reduce(p, stamp, smem);
     stamp_t(5);
-    if (tid == 0) __hip_atomic_fetch_add(p.done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) p.done[(size_t)blockIdx.x * kCounterStride] = launch_count;   // launches completed
     stamp_t(6);
 }
 

@@ -16,6 +16,7 @@ constexpr int kStamps = 16;                // debug time stamps per workgroup
 // power-of-two block sizes all workgroups would walk through the memory channels in step (measured:
 // a tenth less bandwidth); 256 bytes shift each block by one channel.
 constexpr int kQkvBlockPad = 256;
+constexpr int kCounterStride = 16;   // 64-bit words between the launch counters of two workgroups (one 128-byte line each)
 constexpr int kMaxKSplits = 64;
 constexpr int kMaxKvSplits = 64;
 
@@ -24,7 +25,7 @@ struct Params {
     const uint16_t *x, *wqkv, *wo;
     uint16_t *kc, *vc, *out;
     // workspace
-    unsigned long long *done;  // workgroups that have finished, over all launches
+    unsigned long long *done;  // [workgroups][kCounterStride]: launches that workgroup w has completed
     uint32_t *err;         // set to 1 when a spin gave up
     // exchange slots: 64-bit {fp32 bits, launch stamp} pairs
     uint64_t *p1;          // [k_splits][B][Nqkv] partial projections
@@ -38,6 +39,8 @@ struct Params {
     int KS, RPS;           // projection: splits of the reduction dimension, rows of the longest split (LDS stride)
     int RB, RD;            // rows of a split are RB + RD (even split index) or RB - RD (odd)
     int TD;                // attention: tokens of a split are TPS + TD (even split index) or TPS - TD (odd)
+    int DSEL;              // TS / KS: selectors advance by this much from one step of a member to the next
+    int sh_nkv, sh_ks, sh_dsel, sh_ns;   // log2 of nkv, KS, DSEL, NS where that is a power of two, else -1
     int pairmap;           // workgroup -> (team, member) keeps the parity of the workgroup id in the member id
     int NS, TPS;           // attention: splits of the cached sequence, tokens per split
     int NC3, CW3, RS3;     // output projection: column blocks, columns per block, row splits per head
