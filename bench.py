@@ -53,6 +53,7 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 1 GiB device-to-device copies (a kernel of known traffic) before the "
                          "timed region, for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--no-arena", action="store_true", help="one device allocation per tensor instead of one for all layers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg")
     return ap.parse_args()
@@ -110,25 +111,47 @@ def main():
         % (shape.name, B, L, alg_bytes / 2 ** 20, n_layers, n_layers * layer_bytes / 2 ** 30))
 
     gen = torch.Generator(device=dev)
+    # All layers live in ONE device allocation (an arena), as a serving stack would hold its weights and
+    # caches: physically contiguous memory is mapped with large page-table fragments, which keeps the
+    # address-translation caches effective over a multi-GiB working set.  --no-arena allocates per tensor.
+    nq_b, no_b = blk.packed_sizes()
+    wq_elems = D * shape.n_qkv if args.row_major else nq_b // 2
+    wo_elems = nq * d * D if args.row_major else no_b // 2
+    kv_elems = B * nkv * S * d
+    align = 2 ** 20                                              # elements: 2 MiB
+    def up(n):
+        return -(-n // align) * align
+    per_layer = up(wq_elems) + up(wo_elems) + 2 * up(kv_elems)
+    arena = None if args.no_arena else torch.empty((n_layers * per_layer,), dtype=torch.float16, device=dev)
+    def carve(i, off, n, shape_):
+        if arena is None:
+            return torch.empty(shape_, dtype=torch.float16, device=dev)
+        return arena[i * per_layer + off: i * per_layer + off + n].view(shape_)
     layers = []
     for i in range(n_layers):
         gen.manual_seed(1000 + i)
         w_qkv = (torch.randn((D, shape.n_qkv), generator=gen, device=dev) * 0.02).half()
         w_o = (torch.randn((nq * d, D), generator=gen, device=dev) * 0.02).half()
-        kc = torch.zeros((B, nkv, S, d), dtype=torch.float16, device=dev)
-        vc = torch.zeros((B, nkv, S, d), dtype=torch.float16, device=dev)
+        kc = carve(i, up(wq_elems) + up(wo_elems), kv_elems, (B, nkv, S, d))
+        vc = carve(i, up(wq_elems) + up(wo_elems) + up(kv_elems), kv_elems, (B, nkv, S, d))
+        kc.zero_()
+        vc.zero_()
         kc[:, :, :L] = torch.randn((B, nkv, L, d), generator=gen, device=dev).half()
         vc[:, :, :L] = torch.randn((B, nkv, L, d), generator=gen, device=dev).half()
-        if not args.row_major:
+        if args.row_major:
+            wq_t = carve(i, 0, wq_elems, (D, shape.n_qkv))
+            wo_t = carve(i, up(wq_elems), wo_elems, (nq * d, D))
+            wq_t.copy_(w_qkv)
+            wo_t.copy_(w_o)
+        else:
             # weights are static: rearranged once, off the clock, into the library's packed layout
-            nq_b, no_b = blk.packed_sizes()
-            wq_p = torch.empty((nq_b // 2,), dtype=torch.float16, device=dev)
-            wo_p = torch.empty((no_b // 2,), dtype=torch.float16, device=dev)
-            blk.pack_weights(w_qkv.data_ptr(), w_o.data_ptr(), wq_p.data_ptr(), wo_p.data_ptr(),
+            wq_t = carve(i, 0, wq_elems, (wq_elems,))
+            wo_t = carve(i, up(wq_elems), wo_elems, (wo_elems,))
+            blk.pack_weights(w_qkv.data_ptr(), w_o.data_ptr(), wq_t.data_ptr(), wo_t.data_ptr(),
                              torch.cuda.current_stream().cuda_stream)
             torch.cuda.synchronize()
-            w_qkv, w_o = wq_p, wo_p
-        layers.append((w_qkv, w_o, kc, vc))
+        del w_qkv, w_o
+        layers.append((wq_t, wo_t, kc, vc))
     gen.manual_seed(999)
     x = torch.randn((B, D), generator=gen, device=dev).half()
     out = torch.empty((B, D), dtype=torch.float16, device=dev)

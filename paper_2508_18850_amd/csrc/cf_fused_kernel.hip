@@ -318,8 +318,13 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     };
 
     CF_TRACE_STAMP(9);      // phase 1 set up
-    // Kernel start: the small loads (this slice of x, the RoPE frequencies) are issued first, then two
-    // batches of weights; loads return in order, so x is staged into LDS while the weights stream.
+    // Kernel start: the first batch of weights goes out at once, then the small loads (this slice of
+    // x, the RoPE frequencies), then the second batch.  Loads return in order: x arrives right behind
+    // the first batch and is staged into LDS while the second one streams.
+    h8 wa[U], wb[U];
+    load(wa, voff0);
+    __builtin_amdgcn_sched_barrier(0);
+    CF_TRACE_STAMP(10);     // first batch issued
     constexpr int XR = BT + 1;                                    // x values per thread kept in registers
     const bool x_in_regs = BT * p.RPS <= XR * NT;
     // (all of them unconditional: a load inside a branch would be waited for at the branch's end)
@@ -332,10 +337,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
         xr[q] = p.x[xv[q] ? (size_t)b * p.D + r0 + r : 0];
     }
     const double inv_freq = p.inv_freq[tid < HD / 2 ? tid : 0];   // for the RoPE table, below
-    __builtin_amdgcn_sched_barrier(0);                            // keep the small loads in front
-    CF_TRACE_STAMP(10);     // small loads issued
-    h8 wa[U], wb[U];
-    load(wa, voff0);
+    __builtin_amdgcn_sched_barrier(0);
     load(wb, voff0);
     __builtin_amdgcn_sched_barrier(0);
     CF_TRACE_STAMP(12);     // first loads issued
