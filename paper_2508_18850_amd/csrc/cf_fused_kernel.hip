@@ -247,6 +247,11 @@ __device__ __forceinline__ void rope_table(int pos, double inv_freq, float *cs, 
 #else
 #define CF_TRACE_STAMP(k)
 #endif
+#ifdef CF_TRACE_TAIL
+#define CF_TAIL_STAMP(k) p.dbg_t[(size_t)blockIdx.x * kStamps + (k)] = wall_clock64()
+#else
+#define CF_TAIL_STAMP(k)
+#endif
 
 template <int HD, int G, int BT, class NextFn>
 __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member, float *smem,
@@ -758,7 +763,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
             for (int j = 0; j < 8; ++j) redacc[(g * NW + wv) * HD + lig * 8 + j] = acc[g][j];
         }
     }
-#ifndef CF_TRACE_P1
+#if !defined(CF_TRACE_P1) && !defined(CF_TRACE_TAIL)
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 8] = wall_clock64();
 #endif
     if (last) {
@@ -794,7 +799,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
                     (G > P2Cfg<G>::GP) ? qs[e] / p.qk_scale_log2e : qs[e];
     }
     lds_barrier();
-#ifndef CF_TRACE_P1
+#if !defined(CF_TRACE_P1) && !defined(CF_TRACE_TAIL)
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 9] = wall_clock64();
 #endif
     // ---- the wavefronts and the new token -> one partial (m, l, acc) per query head
@@ -822,7 +827,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
         }
         x2.st(dst + kP2Stride + c, A, stamp);
     }
-#ifndef CF_TRACE_P1
+#if !defined(CF_TRACE_P1) && !defined(CF_TRACE_TAIL)
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 10] = wall_clock64();
 #endif
     issue_next(2);       // the rest of the tile, behind the stored partial
@@ -881,6 +886,7 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
     const int nchunk = p.CW3 / kOutChunk;
 
     if (!prefetched) p3_load<HD>(p, hq, c3, rs, 0, tile);     // independent of the attention result
+    CF_TAIL_STAMP(8);       // phase 3 entered
 
     {
         // ---- merge of the split-KV partials (Alg. 3 steps 5-7).  Value v = (batch row, column) is handled by SG threads,
@@ -894,14 +900,15 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
             if (sg < SG) {
                 const int b = (v0 + v) / HD, c = (v0 + v) - b * HD;
                 const size_t src = ((size_t)b * p.nq + hq) * p.NS * PS;
+                constexpr int MC = 4;       // splits polled per round (3 loads each, all in flight together)
                 float mt = kNegBig, lt = 0.f, at = 0.f;
-                for (int sb = sg; sb < p.NS; sb += 4 * SG) {
+                for (int sb = sg; sb < p.NS; sb += MC * SG) {
                     Spin spin;
-                    float mm[4], ll[4], aa[4];
+                    float mm[MC], ll[MC], aa[MC];
                     for (;;) {
                         bool ok = true;
 #pragma unroll
-                        for (int k = 0; k < 4; ++k) {
+                        for (int k = 0; k < MC; ++k) {
                             const int s = sb + k * SG;
                             const size_t o = src + (size_t)(s < p.NS ? s : sb) * PS;
                             const u32x2 vm = x2.ld(o), vl = x2.ld(o + 1), va = x2.ld(o + kP2Stride + c);
@@ -913,7 +920,7 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
                         if (ok || spin.expired(p)) break;
                     }
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
+                    for (int k = 0; k < MC; ++k) {
                         if (sb + k * SG < p.NS) {
                             const float mn = fmaxf(mt, mm[k]);
                             const float fa = __builtin_amdgcn_exp2f(mt - mn), fb = __builtin_amdgcn_exp2f(mm[k] - mn);
@@ -951,10 +958,11 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
         for (int e = V + tid; e < BT * HD; e += NT) as[e] = 0.f;
         lds_barrier();
     }
-#ifndef CF_TRACE_P1
+#if !defined(CF_TRACE_P1) && !defined(CF_TRACE_TAIL)
     if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 11] = wall_clock64();   // attention merged
 #endif
 
+    CF_TAIL_STAMP(9);       // attention merged
     for (int ch = 0; ch < nchunk; ++ch) {
         const int cbase = c3 * p.CW3 + ch * kOutChunk;
         if (cbase >= p.D) break;
@@ -978,6 +986,7 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
                 }
             }
         }
+        CF_TAIL_STAMP(10);  // multiplied
         // wavefronts -> one partial row per batch row, RB batch rows at a time
 #pragma unroll
         for (int bb = 0; bb < BT; bb += RB) {
@@ -995,6 +1004,7 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
                     x3.st(((size_t)slot * p.B + bb + b) * p.D + cbase + cc, sum, stamp);
                 }
             }
+            CF_TAIL_STAMP(11);  // partial stored
             lds_barrier();
         }
     }
@@ -1025,6 +1035,7 @@ __device__ __forceinline__ void final_reduce(const Params &p, uint32_t stamp, fl
             smem[s0 * cb + v] = ll_sum(p, x3, (size_t)s0 * p.B * p.D + (size_t)b * p.D + c0 + c,
                                        (size_t)spt * p.B * p.D, n, stamp);
         }
+        CF_TAIL_STAMP(12);      // head partials arrived
         lds_barrier();
         if (tid < cb) {
             float sum = 0.f;
