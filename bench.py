@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # keyed by workload name; None = not measured for that workload.
 MEASURED_TRAFFIC = {
-    # profiles/fused_decode_block_llama2_7b_kv4096_hbm_traffic.md: (99968.7 KiB fetched x 2.0000 + 3119.5 KiB written)
-    "llama2_7b_b1_kv4096": 207930000,
+    # profiles/fused_decode_block_llama2_7b_kv4096_hbm_traffic.md: (100037.2 KiB fetched x 2.0000 + 2096.0 KiB written)
+    "llama2_7b_b1_kv4096": 207020000,
 }
 
 
