@@ -44,6 +44,7 @@ def parse_args():
     ap.add_argument("--workload", default="llama2_7b", help="shape name from cf_inputs.SHAPES")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--kv-len", type=int, default=None)
+    ap.add_argument("--max-seq", type=int, default=0, help="rows of a KV-cache head slice (0 = kv_len + 1 rounded up to 128)")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffer sets to rotate over (0 = auto)")
     ap.add_argument("--workgroups", type=int, default=0)
     ap.add_argument("--k-splits", type=int, default=0)
@@ -97,7 +98,8 @@ def main():
     shape = cf_inputs.SHAPES[args.workload]
     B = args.batch or shape.batch
     L = args.kv_len if args.kv_len is not None else shape.kv_len
-    S = cf_inputs.default_max_seq(L)
+    S = args.max_seq or cf_inputs.default_max_seq(L)
+    assert S > L, "--max-seq must leave room for the new token"
     dev = torch.device("cuda:0")
     D, nq, nkv, d = shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim
 

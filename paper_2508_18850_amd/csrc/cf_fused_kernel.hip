@@ -972,10 +972,12 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
         for (int b = 0; b < BT; ++b)
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[b][j] = 0.f;
+        if (BT <= 4 && nchunk == 1) {
+            // straight-line code (a branch per row would serialise the LDS reads): a row past the item
+            // has a zero tile entry, its load was switched off, so it may be multiplied by any finite value
 #pragma unroll
-        for (int u = 0; u < OutTile<HD>::MAXR; ++u) {
-            if (u < iters) {
-                const int r = rbeg + wv + NW * u;
+            for (int u = 0; u < OutTile<HD>::MAXR; ++u) {
+                const int r = rbeg + wv + NW * min(u, iters - 1);
                 float f[8];
                 unpack8(tile.w[u], f);
 #pragma unroll
@@ -985,8 +987,24 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
                     for (int j = 0; j < 8; ++j) acc[b][j] = fmaf(av, f[j], acc[b][j]);
                 }
             }
+        } else {
+            // the 16-row batch tile has no registers to spare for reads hoisted across rows; with several
+            // chunks per item the tile was loaded just now, and row-by-row waits overlap its arrival
+#pragma unroll
+            for (int u = 0; u < OutTile<HD>::MAXR; ++u) {
+                if (u < iters) {
+                    const int r = rbeg + wv + NW * u;
+                    float f[8];
+                    unpack8(tile.w[u], f);
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) {
+                        const float av = as[b * HD + r];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) acc[b][j] = fmaf(av, f[j], acc[b][j]);
+                    }
+                }
+            }
         }
-        CF_TAIL_STAMP(10);  // multiplied
         // wavefronts -> one partial row per batch row, RB batch rows at a time
 #pragma unroll
         for (int bb = 0; bb < BT; bb += RB) {
