@@ -125,8 +125,9 @@ int cf_status(cf_handle h, void *stream);
  * 7 result).  fp32.  what = 2: [workgroups][16] uint64 stamps of the 100 MHz wall
  * clock taken by every workgroup: 0 start, 1 projection done, 2 x staged in LDS,
  * 3 attention done, 4 output projection done, 5 final reduction done, 6 exit,
- * 7 hardware id (XCC / CU) instead of a time, 8..13 steps inside the projection,
- * 14 rotated queries ready, 15 K/V stream consumed.  Synchronises `stream`.
+ * 7 hardware id (XCC / CU) instead of a time, 8..11 steps inside the attention tail, 12..13 unused,
+ * 14 rotated queries ready, 15 K/V stream consumed (all zero unless the library was built with
+ * -DCF_STAMPS=1, as libcfdecode_trace.so is).  Synchronises `stream`.
  * `bytes` must equal the tensor size.
  */
 int cf_debug_export(cf_handle h, int32_t what, void *host_dst, size_t bytes, void *stream);

@@ -240,6 +240,12 @@ __device__ __forceinline__ void rope_table(int pos, double inv_freq, float *cs, 
 // of the NEXT phase (issue_next) are issued before the last step is consumed, so the
 // memory pipe never drains.
 // ---------------------------------------------------------------------------
+// Per-phase time stamps (cf_debug_export what = 2) are compiled in only with -DCF_STAMPS=1: the nine
+// `if (debug && thread 0)` blocks cost a quarter of a microsecond per step even when the flag is off.
+#ifndef CF_STAMPS
+#define CF_STAMPS 0
+#endif
+
 // Experiment builds only (-DCF_TRACE_P1, handle created with the debug flag): branch-free time stamps
 // inside phase 1, written by every thread, in place of the detail stamps of the later phases.
 #ifdef CF_TRACE_P1
@@ -376,7 +382,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     // cos / sin of this position while the first weights are still on their way
     rope_table<HD>(p.pos, inv_freq, rope, rope + HD / 2);
     lds_barrier();
-    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 2] = wall_clock64();   // x staged
+    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 2] = wall_clock64();   // x staged
 
     float acc[BT][8];
 #pragma unroll
@@ -644,7 +650,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
 #pragma unroll
             for (int j = 0; j < 8; ++j) qf[g][j] = qs[g * HD + lig * 8 + j] * p.qk_scale_log2e;
     }
-    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 14] = wall_clock64();   // q ready
+    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 14] = wall_clock64();   // q ready
 
     // ---- online softmax over this split's cached tokens; one row per LPR lanes
     float m[G], l[G], acc[G][8];
@@ -728,7 +734,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
             st.load(buf.k[j], buf.v[j], i0 + (j + NB) * U, after_consume());
         }
     }
-    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 15] = wall_clock64();   // K/V consumed
+    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 15] = wall_clock64();   // K/V consumed
     // Nothing of this phase is left to load.  Half of the next phase's first tile goes out now and
     // streams while the partial is merged and stored; the other half follows the stored partial.
     // (Not all of it now: the vector memory path of a compute unit returns in order, so the stamped
@@ -764,7 +770,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
         }
     }
 #if !defined(CF_TRACE_P1) && !defined(CF_TRACE_TAIL)
-    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 8] = wall_clock64();
+    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 8] = wall_clock64();
 #endif
     if (last) {
         // ---- the new token: sum its key/value partials (stored at the end of phase 1, long ago by
@@ -800,7 +806,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
     }
     lds_barrier();
 #if !defined(CF_TRACE_P1) && !defined(CF_TRACE_TAIL)
-    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 9] = wall_clock64();
+    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 9] = wall_clock64();
 #endif
     // ---- the wavefronts and the new token -> one partial (m, l, acc) per query head
     for (int e = tid; e < G * HD; e += NT) {
@@ -828,7 +834,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
         x2.st(dst + kP2Stride + c, A, stamp);
     }
 #if !defined(CF_TRACE_P1) && !defined(CF_TRACE_TAIL)
-    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 10] = wall_clock64();
+    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 10] = wall_clock64();
 #endif
     issue_next(2);       // the rest of the tile, behind the stored partial
     lds_barrier();
@@ -959,7 +965,7 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
         lds_barrier();
     }
 #if !defined(CF_TRACE_P1) && !defined(CF_TRACE_TAIL)
-    if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 11] = wall_clock64();   // attention merged
+    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 11] = wall_clock64();   // attention merged
 #endif
 
     CF_TAIL_STAMP(9);       // attention merged
@@ -1090,10 +1096,10 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
     const int team = p.pairmap ? qmod(w >> 1, p.nkv, p.sh_nkv) : qmod(w, p.nkv, p.sh_nkv);
     const int member = p.pairmap ? qdiv(w >> 1, p.nkv, p.sh_nkv) * 2 + (w & 1) : qdiv(w, p.nkv, p.sh_nkv);
     auto stamp_t = [&](int k) {
-        if (p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + k] = wall_clock64();
+        if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + k] = wall_clock64();
     };
     stamp_t(0);
-    if (p.dbg_t && tid == 0)   // where this workgroup runs: XCC id and the HW_ID register (CU, SE ...)
+    if (CF_STAMPS && p.dbg_t && tid == 0)   // where this workgroup runs: XCC id and the HW_ID register (CU, SE ...)
         p.dbg_t[(size_t)blockIdx.x * kStamps + 7] = ((unsigned long long)__builtin_amdgcn_s_getreg(63508) << 32) |
                                               (unsigned)__builtin_amdgcn_s_getreg(63492);
 
