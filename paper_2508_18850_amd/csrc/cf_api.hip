@@ -34,7 +34,6 @@ struct cf_handle_s {
     int balance_rows = 0, balance_tokens = 32;   // half the length difference between even and odd splits (-1: off)
     long long spin_ticks = 200000000LL;   // 2 s of the 100 MHz wall clock
     int wg_per_cu[3] = {0, 0, 0};         // resident workgroups per CU for batch tiles 1, 4, 16 (0 = not probed)
-    int xcd_local = -1;                   // -1 not probed, 0 off, 1 on (team members share an XCD)
     int last_batch = 0;
     int last_plan[10] = {0};
     int last_hip = 0;
@@ -206,24 +205,6 @@ int check_residency(cf_handle_s *h, const Params &p, int bt, size_t lds_bytes)
     return CF_OK;
 }
 
-// Team-internal exchange through the XCD's L2 (sc0 loads) instead of agent scope.  Off: on MI355X
-// a reader that polls with sc0 loads kept seeing the old stamp (the per-CU cache serves the line),
-// so every launch ran into the spin limit.  CF_XCD_LOCAL=1 turns it on for experiments; it still
-// requires that all workgroups of a team (equal index modulo n_kv_heads) run on one XCD, which
-// is probed with a launch of the same grid.
-void probe_locality(cf_handle_s *h, int W)
-{
-    h->xcd_local = 0;
-    const char *e = std::getenv("CF_XCD_LOCAL");
-    if (!e || !std::atoi(e)) return;
-    std::vector<int> xcc((size_t)W, -1);
-    if (cf::probe_xcc(W, xcc.data(), nullptr) != hipSuccess) return;
-    const int nkv = h->cfg.n_kv_heads;
-    for (int w = nkv; w < W; ++w)
-        if (xcc[w] != xcc[w % nkv]) return;
-    h->xcd_local = 1;
-}
-
 }  // namespace
 
 extern "C" {
@@ -321,7 +302,6 @@ int cf_create(const cf_config *cfg, cf_handle *out)
         delete h;
         return CF_EHIP;
     }
-    probe_locality(h, default_workgroups(h));
     *out = h;
     return CF_OK;
 }
@@ -354,7 +334,6 @@ static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, co
     p.B = batch;
     p.pos = pos;
     p.packed = packed;
-    p.xcd_local = (h->xcd_local > 0 && !p.pairmap) ? 1 : 0;
     int rc = make_plan(h, batch, pos, &p);
     if (rc != CF_OK) return rc;
     const int bt = batch_tile(batch);
@@ -411,9 +390,7 @@ int cf_status(cf_handle h, void *stream)
     e = hipMemcpy(&flag, h->err, sizeof flag, hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(h, e);
     if (flag) {
-        // a spin gave up: start from a clean slate (launch counter and all stamps), and stop relying
-        // on team members sharing an XCD
-        h->xcd_local = 0;
+        // a spin gave up: start from a clean slate (launch counters and all stamps)
         e = hipMemset(h->ws, 0, h->exchange_bytes);
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e != hipSuccess) return hip_fail(h, e);
@@ -443,15 +420,13 @@ int cf_set_tuning(cf_handle h, int32_t workgroups, int32_t k_splits, int32_t kv_
     if (k_splits > kMaxKS) return CF_EINVAL;
     if (kv_splits && (!pow2(kv_splits) || kv_splits > cf::kMaxKvSplits)) return CF_EINVAL;
     if (workgroups != h->tune_w) {
-        // the launch number is derived from a count of finished workgroups: start it afresh
+        // every workgroup counts its own launches; with another grid the counts must start together again
         hipError_t e = hipDeviceSynchronize();
         if (e == hipSuccess) e = hipMemset(h->ws, 0, h->exchange_bytes);
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e != hipSuccess) return hip_fail(h, e);
     }
-    const bool regrid = workgroups != h->tune_w;
     h->tune_w = workgroups;
-    if (regrid && default_workgroups(h) > 0) probe_locality(h, default_workgroups(h));
     h->tune_ks = k_splits;
     h->tune_ns = kv_splits;
     h->wg_per_cu[0] = h->wg_per_cu[1] = h->wg_per_cu[2] = 0;   // LDS size may change: probe residency again

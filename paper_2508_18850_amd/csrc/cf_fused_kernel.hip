@@ -120,29 +120,21 @@ __device__ __forceinline__ float wave_sum(float v)
 // {fp32 bits, stamp} pair written by ONE 8-byte write-through store (agent scope), so a
 // reader sees either the old pair or the new one; the stamp of a launch is its number.
 //
-// Scope.  Slots read by workgroups on any XCD use agent scope (sc1: through to memory).  Slots
-// that only travel inside a team can stay in the team's XCD when all members run on one XCD
-// (`local`): stores go to that XCD's L2 and loads bypass only the per-CU cache (sc0), which
-// makes a hand-over several times faster.  Should the members not share an XCD after all, a
-// reader keeps seeing an old stamp and the bounded spin reports it: data is never wrong.
+// Scope: agent (sc1, through to memory), also for slots that only travel inside a team.  Keeping
+// those in the L2 of the team's die (workgroup-scope loads and stores) was tried: the per-CU cache
+// then serves the polled line and the reader never sees the new stamp.
 struct Xbuf {
     __amdgpu_buffer_rsrc_t r;
-    bool local;
-    __device__ __forceinline__ explicit Xbuf(const void *base, bool xcd_local = false)
-        : r(__builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0xfffffff8u, 0x00020000)),
-          local(xcd_local) {}
+    __device__ __forceinline__ explicit Xbuf(const void *base)
+        : r(__builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0xfffffff8u, 0x00020000)) {}
     __device__ __forceinline__ u32x2 ld(size_t idx) const
     {
-        if (local) return __builtin_amdgcn_raw_buffer_load_b64(r, (unsigned)(idx * 8), 0, 1);
         return __builtin_amdgcn_raw_buffer_load_b64(r, (unsigned)(idx * 8), 0, 16);
     }
     __device__ __forceinline__ void st(size_t idx, float v, uint32_t stamp) const
     {
         u32x2 d = {__builtin_bit_cast(uint32_t, v), stamp};
-        if (local)
-            __builtin_amdgcn_raw_buffer_store_b64(d, r, (unsigned)(idx * 8), 0, 1);
-        else
-            __builtin_amdgcn_raw_buffer_store_b64(d, r, (unsigned)(idx * 8), 0, 16);
+        __builtin_amdgcn_raw_buffer_store_b64(d, r, (unsigned)(idx * 8), 0, 16);
     }
 };
 
@@ -163,18 +155,33 @@ struct Spin {
 };
 
 // Sum of n stamped slots base, base+stride, ... in index order; spins until all are current.
+// Loads go out eight at a time (indices past n repeat the last slot and are ignored) and are consumed
+// only after all eight have been issued: written as one loop, each load was waited for on its own.
 __device__ __forceinline__ float ll_sum(const Params &p, const Xbuf &x, size_t base, size_t stride, int n,
                                         uint32_t stamp)
 {
+    constexpr int C = 8;
     Spin spin;
     for (;;) {
         float s = 0.f;
         bool ok = true;
-#pragma unroll 8
-        for (int k = 0; k < n; ++k) {
-            const u32x2 v = x.ld(base + (size_t)k * stride);
-            ok &= (v.y == stamp);
-            s += __builtin_bit_cast(float, v.x);
+        if (n == 1) {
+            const u32x2 v = x.ld(base);
+            ok = (v.y == stamp);
+            s = __builtin_bit_cast(float, v.x);
+        } else {
+            for (int k0 = 0; k0 < n; k0 += C) {
+                u32x2 v[C];
+#pragma unroll
+                for (int k = 0; k < C; ++k) v[k] = x.ld(base + (size_t)min(k0 + k, n - 1) * stride);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int k = 0; k < C; ++k)
+                    if (k0 + k < n) {
+                        ok &= (v[k].y == stamp);
+                        s += __builtin_bit_cast(float, v[k].x);
+                    }
+            }
         }
         if (ok || spin.expired(p)) return s;
     }
@@ -282,7 +289,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     auto sel_of = [&](int si) { return si < nA ? sel0 + si * dsel : G + sel0 + (si - nA) * dsel; };
     float *xs = smem;                       // [BT][RPS]
     float *red = smem + BT * p.RPS;         // [MAXI][NW][BT][HD]
-    const Xbuf x1(p.p1, p.xcd_local != 0);
+    const Xbuf x1(p.p1);
     const uint32_t blkb = (uint32_t)p.D * HD * 2 + kQkvBlockPad;          // packed: bytes from one block to the next
     const Stream W(p.wqkv, p.packed ? (uint32_t)(p.nqkv / HD) * blkb : (uint32_t)((size_t)p.D * p.nqkv * 2));
     // row-major [D][Nqkv]: rows are Nqkv*2 bytes apart and a selector starts at column col0;
@@ -506,14 +513,18 @@ struct EarlyQ {
     template <int HD, int G>
     __device__ __forceinline__ void issue(const Params &p, int team, int b)
     {
-        const Xbuf x1(p.p1, p.xcd_local != 0);
+        const Xbuf x1(p.p1);
         const int e = threadIdx.x;
         if (e < G * HD) {
             const int sel = e / HD, c = e - sel * HD;
             const size_t src = (size_t)b * p.nqkv + qkv_col0<HD, G>(p, team, sel) + c;
+            // eight loads at a time on a straight-line path (slices past KS repeat the last one)
 #pragma unroll
-            for (int k = 0; k < kEarly; ++k)
-                if (k < p.KS) v[k] = x1.ld(src + (size_t)k * p.B * p.nqkv);
+            for (int k = 0; k < 8; ++k) v[k] = x1.ld(src + (size_t)min(k, p.KS - 1) * p.B * p.nqkv);
+            if (p.KS > 8) {
+#pragma unroll
+                for (int k = 8; k < kEarly; ++k) v[k] = x1.ld(src + (size_t)min(k, p.KS - 1) * p.B * p.nqkv);
+            }
         }
         issued = true;
     }
@@ -605,7 +616,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
     constexpr int PS = HD + kP2Stride;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
     const bool last = (s == p.NS - 1);
-    const Xbuf x1(p.p1, p.xcd_local != 0), x2(p.p2, p.xcd_local != 0);
+    const Xbuf x1(p.p1), x2(p.p2);
 
     const float *cs = rope;                 // [HD/2] cos, filled at kernel start
     const float *sn = rope + HD / 2;        // [HD/2] sin
@@ -883,7 +894,7 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     float *as = smem;                 // [BT][HD] merged, normalised attention output of head hq
     float *red = smem + BT * HD;      // [NW][RB][512]; also the (m, l, a) triples of the merge
-    const Xbuf x2(p.p2, p.xcd_local != 0), x3(p.p3);
+    const Xbuf x2(p.p2), x3(p.p3);
 
     const int nrows = HD / p.RS3;
     const int rbeg = rs * nrows;
@@ -1189,11 +1200,6 @@ __global__ void pack_o_kernel(const uint4 *__restrict__ src, uint4 *__restrict__
     }
 }
 
-__global__ void probe_xcc_kernel(int *xcc)
-{
-    if (threadIdx.x == 0) xcc[blockIdx.x] = (int)(__builtin_amdgcn_s_getreg(63508) & 0xf);   // XCC_ID
-}
-
 using KernelFn = void (*)(const Params);
 
 template <int HD, int G>
@@ -1250,19 +1256,6 @@ hipError_t max_workgroups_per_cu(int hd, int g, int bt, size_t lds_bytes, int *o
         if (e != hipSuccess) return e;
     }
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(out, reinterpret_cast<const void *>(fn), kThreads, lds_bytes);
-}
-
-hipError_t probe_xcc(int W, int *host_xcc, hipStream_t stream)
-{
-    int *dev = nullptr;
-    hipError_t e = hipMalloc(reinterpret_cast<void **>(&dev), sizeof(int) * (size_t)W);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(probe_xcc_kernel, dim3(W), dim3(kThreads), 0, stream, dev);
-    e = hipGetLastError();
-    if (e == hipSuccess) e = hipMemcpyAsync(host_xcc, dev, sizeof(int) * (size_t)W, hipMemcpyDeviceToHost, stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(stream);
-    (void)hipFree(dev);
-    return e;
 }
 
 hipError_t launch_pack(const uint16_t *wqkv, const uint16_t *wo, uint16_t *wqkv_p, uint16_t *wo_p, int D, int nqkv,

@@ -45,7 +45,6 @@ struct Params {
     int NS, TPS;           // attention: splits of the cached sequence, tokens per split
     int NC3, CW3, RS3;     // output projection: column blocks, columns per block, row splits per head
     int NCH;               // number of 512-column chunks of the output
-    int xcd_local;         // all members of a team run on one XCD: team-internal exchange stays in its L2
     int packed;            // weights are in the packed (per-head contiguous) layout of cf_pack_weights
     float qk_scale_log2e;  // log2(e)/sqrt(head_dim)
     long long spin_ticks;  // wait limit in 100 MHz ticks
@@ -59,7 +58,6 @@ hipError_t max_workgroups_per_cu(int head_dim, int group, int batch_tile, size_t
 // LDS floats needed by the three phases for the given plan.
 size_t lds_floats(const Params &p, int head_dim, int group, int batch_tile);
 // XCC id of every workgroup of a W-workgroup launch (host buffer of W ints).
-hipError_t probe_xcc(int W, int *host_xcc, hipStream_t stream);
 // Rearrange row-major weights into the packed layout (see cf_pack_weights in the public header).
 hipError_t launch_pack(const uint16_t *wqkv, const uint16_t *wo, uint16_t *wqkv_p, uint16_t *wo_p, int D, int nqkv,
                        int nq, int head_dim, hipStream_t stream);
