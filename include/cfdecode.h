@@ -122,13 +122,16 @@ int cf_status(cf_handle h, void *stream);
  * Copy intermediate vectors of the most recent call to HOST memory (handle must
  * have CF_FLAG_DEBUG_EXPORT).  what = 0: rotated queries [batch, n_q_heads,
  * head_dim]; what = 1: per-head attention outputs a_i, same shape (Alg. 3 step
- * 7 result).  fp32.  what = 2: [workgroups][16] uint64 stamps of the 100 MHz wall
- * clock taken by every workgroup: 0 start, 1 projection done, 2 x staged in LDS,
- * 3 attention done, 4 output projection done, 5 final reduction done, 6 exit,
- * 7 hardware id (XCC / CU) instead of a time, 8..11 steps inside the attention tail, 12..13 unused,
- * 14 rotated queries ready, 15 K/V stream consumed (all zero unless the library was built with
- * -DCF_STAMPS=1, as libcfdecode_trace.so is).  Synchronises `stream`.
- * `bytes` must equal the tensor size.
+ * 7 result).  fp32.  what = 2: [workgroups][24] uint64 stamps of the 100 MHz wall
+ * clock taken by every workgroup (all zero unless the library was built with
+ * -DCF_STAMPS=1, as libcfdecode_trace.so is): 0 start, 1 projection done, 2 x staged
+ * in LDS, 3 attention done, 4 output projection done, 5 final reduction done, 6 exit,
+ * 7 hardware id (XCC / CU) instead of a time, 8 attention row groups merged,
+ * 9 new token handled, 10 attention partial stored, 11 attention merged, 12 / 21 first /
+ * second weight batch issued, 14 rotated queries ready, 15 K/V stream consumed,
+ * 16 first projection step consumed, 17 output tile multiplied, 18 output partial
+ * stored, 19 head partials arrived, 20 projection set up; others unused.
+ * Synchronises `stream`.  `bytes` must equal the tensor size.
  */
 int cf_debug_export(cf_handle h, int32_t what, void *host_dst, size_t bytes, void *stream);
 

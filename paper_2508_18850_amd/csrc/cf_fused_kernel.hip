@@ -26,11 +26,13 @@
 // Exchange between workgroups needs no counters: every exchanged fp32 value is
 // stored as a 64-bit {value, stamp} pair with one write-through store, the stamp
 // being the launch number; a reader polls the pair until the stamp is current.
-// The launch number is read from a counter of finished workgroups.  All
+// Every workgroup counts the launches it has completed; the count gives the launch number.  All
 // workgroups of the launch must be resident (checked on the host), since
 // readers spin.  Spins are bounded: after spin_ticks a thread sets an error
 // flag and goes on, so the kernel always ends.
 #include "cf_params.h"
+
+#include <type_traits>
 
 namespace cf {
 namespace {
@@ -247,23 +249,21 @@ __device__ __forceinline__ void rope_table(int pos, double inv_freq, float *cs, 
 // of the NEXT phase (issue_next) are issued before the last step is consumed, so the
 // memory pipe never drains.
 // ---------------------------------------------------------------------------
-// Per-phase time stamps (cf_debug_export what = 2) are compiled in only with -DCF_STAMPS=1: the nine
-// `if (debug && thread 0)` blocks cost a quarter of a microsecond per step even when the flag is off.
+// Per-phase time stamps (cf_debug_export what = 2) are compiled in only with -DCF_STAMPS=1: their
+// `if (thread 0)` blocks cost a quarter of a microsecond per step.  A stamp goes to LDS and is copied to
+// memory when the workgroup ends: a store to memory in the first microseconds of a kernel (the first
+// version did that) holds up every load behind it for about 3 us and falsifies what it measures.
 #ifndef CF_STAMPS
 #define CF_STAMPS 0
 #endif
-
-// Experiment builds only (-DCF_TRACE_P1, handle created with the debug flag): branch-free time stamps
-// inside phase 1, written by every thread, in place of the detail stamps of the later phases.
-#ifdef CF_TRACE_P1
-#define CF_TRACE_STAMP(k) p.dbg_t[(size_t)blockIdx.x * kStamps + (k)] = wall_clock64()
+#if CF_STAMPS
+__shared__ unsigned long long s_ts[kStamps];
+#define CF_STAMP(k)                                       \
+    do {                                                  \
+        if (threadIdx.x == 0) s_ts[k] = wall_clock64();   \
+    } while (0)
 #else
-#define CF_TRACE_STAMP(k)
-#endif
-#ifdef CF_TRACE_TAIL
-#define CF_TAIL_STAMP(k) p.dbg_t[(size_t)blockIdx.x * kStamps + (k)] = wall_clock64()
-#else
-#define CF_TAIL_STAMP(k)
+#define CF_STAMP(k)
 #endif
 
 template <int HD, int G, int BT, class NextFn>
@@ -335,14 +335,14 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
         if (live) advance(lc);
     };
 
-    CF_TRACE_STAMP(9);      // phase 1 set up
+    CF_STAMP(20);           // phase 1 set up
     // Kernel start: the first batch of weights goes out at once, then the small loads (this slice of
     // x, the RoPE frequencies), then the second batch.  Loads return in order: x arrives right behind
     // the first batch and is staged into LDS while the second one streams.
     h8 wa[U], wb[U];
     load(wa, voff0);
     __builtin_amdgcn_sched_barrier(0);
-    CF_TRACE_STAMP(10);     // first batch issued
+    CF_STAMP(12);           // first weight batch issued
     constexpr int XR = BT + 1;                                    // x values per thread kept in registers
     const bool x_in_regs = BT * p.RPS <= XR * NT;
     // (all of them unconditional: a load inside a branch would be waited for at the branch's end)
@@ -358,7 +358,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     __builtin_amdgcn_sched_barrier(0);
     load(wb, voff0);
     __builtin_amdgcn_sched_barrier(0);
-    CF_TRACE_STAMP(12);     // first loads issued
+    CF_STAMP(21);           // second weight batch issued
     // Launch number: every workgroup keeps, in a line of its own, the number of launches it has
     // completed; all workgroups of a launch hold the same count, so count + 1 stamps this launch
     // without any shared counter.  (One counter for all was read by 256 workgroups at once and
@@ -389,7 +389,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     // cos / sin of this position while the first weights are still on their way
     rope_table<HD>(p.pos, inv_freq, rope, rope + HD / 2);
     lds_barrier();
-    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 2] = wall_clock64();   // x staged
+    CF_STAMP(2);            // x staged
 
     float acc[BT][8];
 #pragma unroll
@@ -478,7 +478,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     for (int k = 0; k + 2 < nsteps2; k += 2) {
         consume(wa);
         load(wa, after_consume());
-        CF_TRACE_STAMP(8);
+        if (k == 0) CF_STAMP(16);       // first step consumed and reloaded
         finish();
         consume(wb);
         load(wb, after_consume());
@@ -661,7 +661,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
 #pragma unroll
             for (int j = 0; j < 8; ++j) qf[g][j] = qs[g * HD + lig * 8 + j] * p.qk_scale_log2e;
     }
-    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 14] = wall_clock64();   // q ready
+    CF_STAMP(14);           // q ready
 
     // ---- online softmax over this split's cached tokens; one row per LPR lanes
     float m[G], l[G], acc[G][8];
@@ -745,7 +745,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
             st.load(buf.k[j], buf.v[j], i0 + (j + NB) * U, after_consume());
         }
     }
-    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 15] = wall_clock64();   // K/V consumed
+    CF_STAMP(15);           // K/V consumed
     // Nothing of this phase is left to load.  Half of the next phase's first tile goes out now and
     // streams while the partial is merged and stored; the other half follows the stored partial.
     // (Not all of it now: the vector memory path of a compute unit returns in order, so the stamped
@@ -780,9 +780,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
             for (int j = 0; j < 8; ++j) redacc[(g * NW + wv) * HD + lig * 8 + j] = acc[g][j];
         }
     }
-#if !defined(CF_TRACE_P1) && !defined(CF_TRACE_TAIL)
-    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 8] = wall_clock64();
-#endif
+    CF_STAMP(8);            // row groups of the wavefront merged
     if (last) {
         // ---- the new token: sum its key/value partials (stored at the end of phase 1, long ago by
         //      now), rotate the key, append both (Sec. 2.1) and score the token
@@ -816,9 +814,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
                     (G > P2Cfg<G>::GP) ? qs[e] / p.qk_scale_log2e : qs[e];
     }
     lds_barrier();
-#if !defined(CF_TRACE_P1) && !defined(CF_TRACE_TAIL)
-    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 9] = wall_clock64();
-#endif
+    CF_STAMP(9);            // new token handled, wavefronts in step
     // ---- the wavefronts and the new token -> one partial (m, l, acc) per query head
     for (int e = tid; e < G * HD; e += NT) {
         const int g = e / HD, c = e - g * HD;
@@ -844,9 +840,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
         }
         x2.st(dst + kP2Stride + c, A, stamp);
     }
-#if !defined(CF_TRACE_P1) && !defined(CF_TRACE_TAIL)
-    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 10] = wall_clock64();
-#endif
+    CF_STAMP(10);            // partial stored
     issue_next(2);       // the rest of the tile, behind the stored partial
     lds_barrier();
 }
@@ -903,7 +897,6 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
     const int nchunk = p.CW3 / kOutChunk;
 
     if (!prefetched) p3_load<HD>(p, hq, c3, rs, 0, tile);     // independent of the attention result
-    CF_TAIL_STAMP(8);       // phase 3 entered
 
     {
         // ---- merge of the split-KV partials (Alg. 3 steps 5-7).  Value v = (batch row, column) is handled by SG threads,
@@ -975,11 +968,8 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
         for (int e = V + tid; e < BT * HD; e += NT) as[e] = 0.f;
         lds_barrier();
     }
-#if !defined(CF_TRACE_P1) && !defined(CF_TRACE_TAIL)
-    if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + 11] = wall_clock64();   // attention merged
-#endif
+    CF_STAMP(11);           // attention merged
 
-    CF_TAIL_STAMP(9);       // attention merged
     for (int ch = 0; ch < nchunk; ++ch) {
         const int cbase = c3 * p.CW3 + ch * kOutChunk;
         if (cbase >= p.D) break;
@@ -1039,7 +1029,7 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
                     x3.st(((size_t)slot * p.B + bb + b) * p.D + cbase + cc, sum, stamp);
                 }
             }
-            CF_TAIL_STAMP(11);  // partial stored
+            CF_STAMP(18);   // output partial stored
             lds_barrier();
         }
     }
@@ -1070,7 +1060,7 @@ __device__ __forceinline__ void final_reduce(const Params &p, uint32_t stamp, fl
             smem[s0 * cb + v] = ll_sum(p, x3, (size_t)s0 * p.B * p.D + (size_t)b * p.D + c0 + c,
                                        (size_t)spt * p.B * p.D, n, stamp);
         }
-        CF_TAIL_STAMP(12);      // head partials arrived
+        CF_STAMP(19);           // head partials arrived
         lds_barrier();
         if (tid < cb) {
             float sum = 0.f;
@@ -1099,20 +1089,20 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
     }
     __shared__ float s_rope[HD];                     // cos / sin of the RoPE angles of this position
     const int tid = threadIdx.x;
-    CF_TRACE_STAMP(13);     // kernel entry
     // Workgroup w runs on die (XCD) w % 8, and the odd dies get about a tenth less memory
     // bandwidth than the even ones.  With pairmap a team sits on one pair of dies, members with an
     // even index on the even die: those take the longer slices and splits.
     const int w = blockIdx.x;
     const int team = p.pairmap ? qmod(w >> 1, p.nkv, p.sh_nkv) : qmod(w, p.nkv, p.sh_nkv);
     const int member = p.pairmap ? qdiv(w >> 1, p.nkv, p.sh_nkv) * 2 + (w & 1) : qdiv(w, p.nkv, p.sh_nkv);
-    auto stamp_t = [&](int k) {
-        if (CF_STAMPS && p.dbg_t && tid == 0) p.dbg_t[(size_t)blockIdx.x * kStamps + k] = wall_clock64();
-    };
-    stamp_t(0);
-    if (CF_STAMPS && p.dbg_t && tid == 0)   // where this workgroup runs: XCC id and the HW_ID register (CU, SE ...)
-        p.dbg_t[(size_t)blockIdx.x * kStamps + 7] = ((unsigned long long)__builtin_amdgcn_s_getreg(63508) << 32) |
-                                              (unsigned)__builtin_amdgcn_s_getreg(63492);
+#if CF_STAMPS
+    if (tid < kStamps) s_ts[tid] = 0;       // same wavefront as thread 0: ordered before its stamps
+#endif
+    CF_STAMP(0);
+#if CF_STAMPS
+    if (tid == 0)   // where this workgroup runs: XCC id and the HW_ID register (CU, SE ...)
+        s_ts[7] = ((unsigned long long)__builtin_amdgcn_s_getreg(63508) << 32) | (unsigned)__builtin_amdgcn_s_getreg(63492);
+#endif
 
     const int n2 = p.B * p.NS;                       // attention items of the team
     const int n3 = G * p.NC3 * p.RS3;                // output-projection items of the team
@@ -1121,7 +1111,6 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
     P2Stream<HD, G> st2(p, team, member < n2 ? qdiv(member, p.NS, p.sh_ns) : 0, member < n2 ? qmod(member, p.NS, p.sh_ns) : 0,
                         member < n2);
 
-    CF_TRACE_STAMP(11);     // streams set up
     // ---- phase 1 (projection); its last step already starts the K/V stream of phase 2
     EarlyQ eq;
     unsigned long long launch_count;
@@ -1129,7 +1118,7 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
                                              [&](int stage) { st2.prefetch(kv, 0); });
     if (member < n2) eq.issue<HD, G>(p, team, qdiv(member, p.NS, p.sh_ns));   // q partials were stored a third of the way into phase 1
     st2.prefetch(kv, 1);
-    stamp_t(1);
+    CF_STAMP(1);
     // ---- phase 2 (attention); the last item already starts the W_o stream of phase 3
     auto p3_args = [&](int it, int &hq, int &c3, int &rs) {
         const int g = it / (p.NC3 * p.RS3), rem = it - g * (p.NC3 * p.RS3);
@@ -1159,19 +1148,23 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
         });
     }
     if (member >= n2) p3_prefetch(2);
-    stamp_t(3);
+    CF_STAMP(3);
     // ---- phase 3 (output projection, per-head partials)
     for (int it = member; it < n3; it += p.TS) {
         int hq, c3, rs;
         p3_args(it, hq, c3, rs);
         p3_item<HD, BT>(p, hq, c3, rs, stamp, tile, tile_ready && it == member, smem);
     }
-    stamp_t(4);
+    CF_STAMP(4);
     // ---- phase 4 (sum over heads)
     final_reduce(p, stamp, smem);
-    stamp_t(5);
+    CF_STAMP(5);
     if (tid == 0) p.done[(size_t)blockIdx.x * kCounterStride] = launch_count;   // launches completed
-    stamp_t(6);
+#if CF_STAMPS
+    CF_STAMP(6);
+    lds_barrier();
+    if (p.dbg_t && tid < kStamps) p.dbg_t[(size_t)blockIdx.x * kStamps + tid] = s_ts[tid];
+#endif
 }
 
 // One-time rearrangement of the weights into per-head contiguous blocks (16 bytes per thread step).

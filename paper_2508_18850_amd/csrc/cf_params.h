@@ -11,7 +11,7 @@ constexpr int kThreads = 512;              // threads per workgroup (8 wavefront
 constexpr int kWaves = kThreads / 64;
 constexpr int kOutChunk = 512;             // output columns one wavefront covers with one 128-bit load per lane
 constexpr int kP2Stride = 4;               // floats in front of the accumulator in a split-KV partial: m, l, pad, pad
-constexpr int kStamps = 16;                // debug time stamps per workgroup
+constexpr int kStamps = 24;                // debug time stamps per workgroup
 // Bytes between the end of one per-head block of the packed W_qkv and the start of the next.  With
 // power-of-two block sizes all workgroups would walk through the memory channels in step (measured:
 // a tenth less bandwidth); 256 bytes shift each block by one channel.
