@@ -55,6 +55,8 @@ def parse_args():
                     help="also run three 1 GiB device-to-device copies (a kernel of known traffic) before the "
                          "timed region, for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--no-arena", action="store_true", help="one device allocation per tensor instead of one for all layers")
+    ap.add_argument("--reps", type=int, default=1,
+                    help="further timed regions of --steps launches after the first (reported as median / p10 / p90 in\n                    \"repetitions\"; the headline value is always the first region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg")
     return ap.parse_args()
@@ -192,6 +194,16 @@ def main():
         torch.cuda.synchronize()
         blk.status(sh)
         ms_total = ev0.elapsed_time(ev1)
+        rep_us = [ms_total / args.steps * 1e3]
+        for r in range(1, args.reps):
+            ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ea.record(stream)
+            for i in range(args.steps):
+                step(args.warmup + r * args.steps + i)
+            eb.record(stream)
+            torch.cuda.synchronize()
+            rep_us.append(ea.elapsed_time(eb) / args.steps * 1e3)
+        blk.status(sh)
     assert torch.isfinite(out.float()).all(), "non-finite output"
     plan = blk.plan()
 
@@ -211,6 +223,10 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(name),
                      "algorithmic_bytes": alg_bytes, "kernel": "fused_decode_block"},
     }
+    if args.reps > 1:
+        import numpy as np
+        res["repetitions"] = {"n": len(rep_us), "median_us": float(np.median(rep_us)),
+                              "p10_us": float(np.percentile(rep_us, 10)), "p90_us": float(np.percentile(rep_us, 90))}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(shape, B, L, args.cpu_seconds)
     print(json.dumps(res), flush=True)
