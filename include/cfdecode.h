@@ -158,6 +158,44 @@ const char *cf_strerror(int code);
 /* hipError_t of the most recent failing HIP call made through this handle (0 if none). */
 int cf_last_hip_error(cf_handle h);
 
+/* ------------------------------------------------------------------------------------------------
+ * Team collectives: the paper's two cluster-level primitives (Sec. 3.2; ClusterReduce, Alg. 1, and
+ * ClusterGather, Alg. 2) among co-resident workgroups of one kernel, exchanged through stamped slots in
+ * global memory in place of distributed shared memory, and -- for the comparison of the paper's Table 1 --
+ * the same results from two kernels that hand the data over through a buffer in global memory.
+ *
+ * A launch has teams * team_size workgroups ("ranks"); team k consists of ranks k*team_size .. +team_size-1
+ * (team_size = N = 1, 2, 4, 8 or 16, as in the paper).  All pointers are DEVICE pointers to fp32, 4-byte
+ * aligned; the caller owns them.  Calls are asynchronous on `stream`; a handle must not be used from two
+ * streams at once.  All ranks of a launch have to be resident together (one per compute unit): more ranks
+ * than compute units is CF_EUNSUPPORTED.
+ */
+typedef struct cf_team_s *cf_team;
+enum { CF_TEAM_SUM = 0, CF_TEAM_MAX = 1 };
+
+/* max_ranks: most workgroups a launch may have; max_elems: most fp32 values a rank may hold in a reduce,
+ * or receive in a gather (team_size * elems), at most 65536.  Allocates and clears the exchange area
+ * (max_ranks * 4 * max_elems * 8 bytes) and a scratch buffer for the two-kernel versions.  Synchronous. */
+int cf_team_create(int32_t max_ranks, size_t max_elems, cf_team *out);
+int cf_team_destroy(cf_team t);
+
+/* All-reduce (Alg. 1):  in, out [teams][team_size][elems];  out[k][b][:] = op over b' of in[k][b'][:], the same
+ * for every rank b of team k.  fp32; the sum is folded in the order of Alg. 1's rounds (round s adds the
+ * buffer of rank (b - 2^s) mod N as it stands after round s-1), so it is deterministic.  offchip != 0: two
+ * kernels through global memory instead (ranks added in rank order). */
+int cf_team_reduce(cf_team t, int32_t teams, int32_t team_size, int32_t op, const float *in, float *out,
+                   size_t elems, int32_t offchip, void *stream);
+
+/* All-gather (Alg. 2):  in [teams][team_size][elems], out [teams][team_size][team_size][elems];
+ * out[k][b][j][:] = in[k][(b - j) mod N][:]  (segment 0 is the rank's own data, as in Alg. 2). */
+int cf_team_gather(cf_team t, int32_t teams, int32_t team_size, const float *in, float *out, size_t elems,
+                   int32_t offchip, void *stream);
+
+/* Wait for `stream`; CF_ETIMEOUT if a rank gave up waiting for a peer since the last call (the exchange
+ * area is cleared then). */
+int cf_team_status(cf_team t, void *stream);
+int cf_team_set_spin_limit(cf_team t, int32_t spin_limit_us);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,7 +15,9 @@ _lib = None
 
 EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_packed", "cf_pack_weights",
                     "cf_packed_sizes", "cf_status", "cf_debug_export",
-                    "cf_set_tuning", "cf_get_plan", "cf_algorithmic_bytes", "cf_strerror", "cf_last_hip_error")
+                    "cf_set_tuning", "cf_get_plan", "cf_algorithmic_bytes", "cf_strerror", "cf_last_hip_error",
+                    "cf_team_create", "cf_team_destroy", "cf_team_reduce", "cf_team_gather", "cf_team_status",
+                    "cf_team_set_spin_limit")
 
 CF_FLAG_DEBUG_EXPORT = 1
 
@@ -59,6 +61,15 @@ def load_library():
         lib.cf_strerror.argtypes = [ctypes.c_int]
         lib.cf_strerror.restype = ctypes.c_char_p
         lib.cf_last_hip_error.argtypes = [vp]
+        lib.cf_team_create.argtypes = [i32, ctypes.c_size_t, ctypes.POINTER(vp)]
+        lib.cf_team_destroy.argtypes = [vp]
+        lib.cf_team_reduce.argtypes = [vp, i32, i32, i32, vp, vp, ctypes.c_size_t, i32, vp]
+        lib.cf_team_gather.argtypes = [vp, i32, i32, vp, vp, ctypes.c_size_t, i32, vp]
+        lib.cf_team_status.argtypes = [vp, vp]
+        lib.cf_team_set_spin_limit.argtypes = [vp, i32]
+        for name in ("cf_team_create", "cf_team_destroy", "cf_team_reduce", "cf_team_gather", "cf_team_status",
+                     "cf_team_set_spin_limit"):
+            getattr(lib, name).restype = ctypes.c_int
         for name in ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_packed", "cf_pack_weights",
                      "cf_packed_sizes", "cf_status", "cf_debug_export",
                      "cf_set_tuning", "cf_get_plan", "cf_last_hip_error"):
@@ -132,6 +143,51 @@ class DecodeBlock:
     def close(self):
         if self._h:
             self._lib.cf_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+TEAM_SUM, TEAM_MAX = 0, 1
+
+
+class TeamCollectives:
+    """Handle of the team-collective entry points (cf_team_*).  Tensors are raw device addresses of fp32 data."""
+
+    def __init__(self, max_ranks, max_elems):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        self._check(self._lib.cf_team_create(max_ranks, max_elems, ctypes.byref(self._h)))
+
+    def _check(self, rc):
+        if rc != 0:
+            raise CfError(rc, self._lib.cf_strerror(rc).decode())
+
+    def reduce(self, teams, team_size, op, src, dst, elems, offchip=False, stream=0):
+        self._check(self._lib.cf_team_reduce(self._h, teams, team_size, op, src, dst, elems, int(offchip), stream))
+
+    def reduce_rc(self, teams, team_size, op, src, dst, elems, offchip=False, stream=0) -> int:
+        return int(self._lib.cf_team_reduce(self._h, teams, team_size, op, src, dst, elems, int(offchip), stream))
+
+    def gather(self, teams, team_size, src, dst, elems, offchip=False, stream=0):
+        self._check(self._lib.cf_team_gather(self._h, teams, team_size, src, dst, elems, int(offchip), stream))
+
+    def gather_rc(self, teams, team_size, src, dst, elems, offchip=False, stream=0) -> int:
+        return int(self._lib.cf_team_gather(self._h, teams, team_size, src, dst, elems, int(offchip), stream))
+
+    def status(self, stream=0):
+        self._check(self._lib.cf_team_status(self._h, stream))
+
+    def set_spin_limit(self, us):
+        self._check(self._lib.cf_team_set_spin_limit(self._h, us))
+
+    def close(self):
+        if self._h:
+            self._lib.cf_team_destroy(self._h)
             self._h = ctypes.c_void_p()
 
     def __del__(self):

@@ -14,7 +14,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcfdecode.so")
 TRACE_LIB = os.path.join(PKG, "libcfdecode_trace.so")
-SOURCES = ["cf_api.hip", "cf_fused_kernel.hip"]
+SOURCES = ["cf_api.hip", "cf_fused_kernel.hip", "cf_team.hip"]
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -45,7 +45,7 @@ def build(verbose: bool = False) -> str:
         return obj
 
     jobs = [(suffix, defs, src) for (suffix, defs, _) in variants for src in SOURCES]
-    with ThreadPoolExecutor(max_workers=4) as pool:
+    with ThreadPoolExecutor(max_workers=6) as pool:
         objs = list(pool.map(compile_one, jobs))
     for k, (_, _, lib) in enumerate(variants):
         cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs[k * len(SOURCES):(k + 1) * len(SOURCES)]]
