@@ -172,6 +172,18 @@ int cf_last_hip_error(cf_handle h);
  */
 typedef struct cf_team_s *cf_team;
 enum { CF_TEAM_SUM = 0, CF_TEAM_MAX = 1 };
+/* How the ranks exchange their data (argument `mode`):
+ *   CF_TEAM_ROUNDS       one kernel, the paper's schedule: log2(N) rounds, in round s rank b sends to rank
+ *                        (b + 2^s) mod N (Alg. 1, Alg. 2);
+ *   CF_TEAM_TWO_KERNELS  a kernel that writes every rank's buffer to global memory and a second one that reads
+ *                        what each rank needs (the "off-chip" column of Table 1);
+ *   CF_TEAM_DIRECT       one kernel, one hop: every rank posts its buffer once and reads the N - 1 others
+ *                        (the schedule the fused decode kernel uses: a hop through memory costs microseconds,
+ *                        so fewer hops win over fewer bytes for small buffers);
+ *   CF_TEAM_TWO_HOPS     reduce only: one kernel, two hops, fewest bytes: rank b folds slice b of the buffer
+ *                        from the others' posts, posts the result and reads the other slices from their owners
+ *                        (a rank receives 2 (N-1)/N * elems values, against (N-1) * elems in one hop). */
+enum { CF_TEAM_ROUNDS = 0, CF_TEAM_TWO_KERNELS = 1, CF_TEAM_DIRECT = 2, CF_TEAM_TWO_HOPS = 3 };
 
 /* max_ranks: most workgroups a launch may have; max_elems: most fp32 values a rank may hold in a reduce,
  * or receive in a gather (team_size * elems), at most 65536.  Allocates and clears the exchange area
@@ -181,15 +193,15 @@ int cf_team_destroy(cf_team t);
 
 /* All-reduce (Alg. 1):  in, out [teams][team_size][elems];  out[k][b][:] = op over b' of in[k][b'][:], the same
  * for every rank b of team k.  fp32; the sum is folded in the order of Alg. 1's rounds (round s adds the
- * buffer of rank (b - 2^s) mod N as it stands after round s-1), so it is deterministic.  offchip != 0: two
- * kernels through global memory instead (ranks added in rank order). */
+ * buffer of rank (b - 2^s) mod N as it stands after round s-1), so it is deterministic.  The other modes
+ * add the ranks in rank order (all ranks of a team then hold the same bits). */
 int cf_team_reduce(cf_team t, int32_t teams, int32_t team_size, int32_t op, const float *in, float *out,
-                   size_t elems, int32_t offchip, void *stream);
+                   size_t elems, int32_t mode, void *stream);
 
 /* All-gather (Alg. 2):  in [teams][team_size][elems], out [teams][team_size][team_size][elems];
  * out[k][b][j][:] = in[k][(b - j) mod N][:]  (segment 0 is the rank's own data, as in Alg. 2). */
 int cf_team_gather(cf_team t, int32_t teams, int32_t team_size, const float *in, float *out, size_t elems,
-                   int32_t offchip, void *stream);
+                   int32_t mode, void *stream);
 
 /* Wait for `stream`; CF_ETIMEOUT if a rank gave up waiting for a peer since the last call (the exchange
  * area is cleared then). */

@@ -153,6 +153,7 @@ class DecodeBlock:
 
 
 TEAM_SUM, TEAM_MAX = 0, 1
+TEAM_ROUNDS, TEAM_TWO_KERNELS, TEAM_DIRECT, TEAM_TWO_HOPS = 0, 1, 2, 3     # how the ranks exchange their data (argument `mode`)
 
 
 class TeamCollectives:
@@ -167,17 +168,17 @@ class TeamCollectives:
         if rc != 0:
             raise CfError(rc, self._lib.cf_strerror(rc).decode())
 
-    def reduce(self, teams, team_size, op, src, dst, elems, offchip=False, stream=0):
-        self._check(self._lib.cf_team_reduce(self._h, teams, team_size, op, src, dst, elems, int(offchip), stream))
+    def reduce(self, teams, team_size, op, src, dst, elems, mode=TEAM_ROUNDS, stream=0):
+        self._check(self._lib.cf_team_reduce(self._h, teams, team_size, op, src, dst, elems, int(mode), stream))
 
-    def reduce_rc(self, teams, team_size, op, src, dst, elems, offchip=False, stream=0) -> int:
-        return int(self._lib.cf_team_reduce(self._h, teams, team_size, op, src, dst, elems, int(offchip), stream))
+    def reduce_rc(self, teams, team_size, op, src, dst, elems, mode=TEAM_ROUNDS, stream=0) -> int:
+        return int(self._lib.cf_team_reduce(self._h, teams, team_size, op, src, dst, elems, int(mode), stream))
 
-    def gather(self, teams, team_size, src, dst, elems, offchip=False, stream=0):
-        self._check(self._lib.cf_team_gather(self._h, teams, team_size, src, dst, elems, int(offchip), stream))
+    def gather(self, teams, team_size, src, dst, elems, mode=TEAM_ROUNDS, stream=0):
+        self._check(self._lib.cf_team_gather(self._h, teams, team_size, src, dst, elems, int(mode), stream))
 
-    def gather_rc(self, teams, team_size, src, dst, elems, offchip=False, stream=0) -> int:
-        return int(self._lib.cf_team_gather(self._h, teams, team_size, src, dst, elems, int(offchip), stream))
+    def gather_rc(self, teams, team_size, src, dst, elems, mode=TEAM_ROUNDS, stream=0) -> int:
+        return int(self._lib.cf_team_gather(self._h, teams, team_size, src, dst, elems, int(mode), stream))
 
     def status(self, stream=0):
         self._check(self._lib.cf_team_status(self._h, stream))

@@ -1,6 +1,6 @@
 // Team collectives behind the C ABI (cf_team_* in include/cfdecode.h): kernels that run the paper's
 // ClusterReduce / ClusterGather schedules (Alg. 1, Alg. 2) among co-resident workgroups through stamped
-// exchange slots, and the two-kernel versions that go through a scratch buffer in global memory instead
+// exchange slots, one-hop versions of the same collectives, and the two-kernel versions that go through a scratch buffer in global memory instead
 // (the "off-chip" column of the paper's Table 1).
 #include "../../include/cfdecode.h"
 #include "cf_team_device.h"
@@ -12,6 +12,7 @@ namespace {
 
 using cf::team::kThreads;
 constexpr int kCounterStride = 16;      // 64-bit words between the launch counters of two workgroups
+constexpr size_t kMaxElems = 65536;     // largest buffer of one rank (values)
 
 struct TeamArgs {
     const float *in;
@@ -37,7 +38,8 @@ __device__ __forceinline__ uint32_t launch_stamp(const TeamArgs &a, unsigned lon
     return (uint32_t)(cnt + (cnt >> 32));
 }
 
-template <int E, int OP>
+// E values per thread and chunk; the buffer is worked through chunk by chunk
+template <int E, int OP, bool DIRECT>
 __global__ void __launch_bounds__(kThreads) team_reduce_kernel(const TeamArgs a)
 {
     const int w = blockIdx.x, team = w / a.N, b = w % a.N, tid = threadIdx.x;
@@ -45,64 +47,107 @@ __global__ void __launch_bounds__(kThreads) team_reduce_kernel(const TeamArgs a)
     const cf::team::Exchange x = {a.slots, a.cap, launch_stamp(a, cnt), a.err, a.spin_ticks};
     const float *src = a.in + (size_t)w * a.count;
     float *dst = a.out + (size_t)w * a.count;
-    float d[E];
+    for (size_t first = 0; first < a.count; first += (size_t)kThreads * E) {
+        float d[E];
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const size_t i = tid + (size_t)kThreads * e;
-        d[e] = i < a.count ? src[i] : 0.f;
-    }
-    cf::team::reduce<E, OP>(x, team * a.N, a.N, b, a.count, d);
+        for (int e = 0; e < E; ++e) {
+            const size_t i = first + tid + (size_t)kThreads * e;
+            d[e] = i < a.count ? src[i] : 0.f;
+        }
+        if (DIRECT)
+            cf::team::reduce_direct<E, OP>(x, team * a.N, a.N, b, first, a.count, d);
+        else
+            cf::team::reduce<E, OP>(x, team * a.N, a.N, b, first, a.count, d);
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const size_t i = tid + (size_t)kThreads * e;
-        if (i < a.count) dst[i] = d[e];
+        for (int e = 0; e < E; ++e) {
+            const size_t i = first + tid + (size_t)kThreads * e;
+            if (i < a.count) dst[i] = d[e];
+        }
     }
     if (tid == 0) a.counters[(size_t)w * kCounterStride] = cnt;
 }
 
+template <int OP>
+__global__ void __launch_bounds__(kThreads) team_reduce_two_hops_kernel(const TeamArgs a)
+{
+    const int w = blockIdx.x, team = w / a.N, b = w % a.N;
+    unsigned long long cnt;
+    const cf::team::Exchange x = {a.slots, a.cap, launch_stamp(a, cnt), a.err, a.spin_ticks};
+    const float *src = a.in + (size_t)w * a.count;
+    float *dst = a.out + (size_t)w * a.count;
+    cf::team::reduce_two_hops<OP>(x, team * a.N, a.N, b, a.count, [&](size_t i) { return src[i]; },
+                                  [&](size_t i, float v) { dst[i] = v; });
+    if (threadIdx.x == 0) a.counters[(size_t)w * kCounterStride] = cnt;
+}
+
 // count = values of one segment; a rank's output has N segments
-template <int E>
+template <bool DIRECT>
 __global__ void __launch_bounds__(kThreads) team_gather_kernel(const TeamArgs a)
 {
-    const int w = blockIdx.x, team = w / a.N, b = w % a.N, tid = threadIdx.x;
+    const int w = blockIdx.x, team = w / a.N, b = w % a.N;
     unsigned long long cnt;
     const cf::team::Exchange x = {a.slots, a.cap, launch_stamp(a, cnt), a.err, a.spin_ticks};
     const float *src = a.in + (size_t)w * a.count;
     float *dst = a.out + (size_t)w * a.count * a.N;
-    float g[E];
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const size_t i = tid + (size_t)kThreads * e;
-        g[e] = i < a.count ? src[i] : 0.f;
-    }
-    cf::team::gather<E>(x, team * a.N, a.N, b, a.count, g);
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const size_t i = tid + (size_t)kThreads * e;
-        if (i < a.count * a.N) dst[i] = g[e];
-    }
-    if (tid == 0) a.counters[(size_t)w * kCounterStride] = cnt;
+    auto own = [&](size_t i) { return src[i]; };
+    auto use = [&](size_t p, float v) { dst[p] = v; };
+    if (DIRECT)
+        cf::team::gather_direct(x, team * a.N, a.N, b, a.count, own, use);
+    else
+        cf::team::gather(x, team * a.N, a.N, b, a.count, own, use);
+    if (threadIdx.x == 0) a.counters[(size_t)w * kCounterStride] = cnt;
 }
 
 // ---- the two-kernel versions: every rank writes its buffer to global memory, the kernel boundary is the
 //      synchronisation, then every rank reads what it needs
+// (eight independent loads per thread and step, so that these kernels are bound by bandwidth and not by
+// one load latency per value)
+constexpr int kU = 8;
+
 __global__ void __launch_bounds__(kThreads) team_stage_kernel(const TeamArgs a)
 {
     const size_t w = blockIdx.x;
-    for (size_t i = threadIdx.x; i < a.count; i += kThreads) a.scratch[w * a.count + i] = a.in[w * a.count + i];
+    for (size_t i0 = threadIdx.x; i0 < a.count; i0 += (size_t)kThreads * kU) {
+        float v[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const size_t i = i0 + (size_t)kThreads * u;
+            v[u] = i < a.count ? a.in[w * a.count + i] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const size_t i = i0 + (size_t)kThreads * u;
+            if (i < a.count) a.scratch[w * a.count + i] = v[u];
+        }
+    }
 }
 
 template <int OP>
 __global__ void __launch_bounds__(kThreads) team_reduce_offchip_kernel(const TeamArgs a)
 {
     const int w = blockIdx.x, team = w / a.N;
-    for (size_t i = threadIdx.x; i < a.count; i += kThreads) {
-        float v = a.scratch[(size_t)team * a.N * a.count + i];
-        for (int r = 1; r < a.N; ++r) {
-            const float o = a.scratch[((size_t)team * a.N + r) * a.count + i];
-            v = OP == cf::team::kSum ? v + o : fmaxf(v, o);
+    for (size_t i0 = threadIdx.x; i0 < a.count; i0 += (size_t)kThreads * kU) {
+        float v[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const size_t i = i0 + (size_t)kThreads * u;
+            v[u] = i < a.count ? a.scratch[(size_t)team * a.N * a.count + i] : 0.f;
         }
-        a.out[(size_t)w * a.count + i] = v;
+        for (int r = 1; r < a.N; ++r) {
+            float o[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const size_t i = i0 + (size_t)kThreads * u;
+                o[u] = i < a.count ? a.scratch[((size_t)team * a.N + r) * a.count + i] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u) v[u] = OP == cf::team::kSum ? v[u] + o[u] : fmaxf(v[u], o[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const size_t i = i0 + (size_t)kThreads * u;
+            if (i < a.count) a.out[(size_t)w * a.count + i] = v[u];
+        }
     }
 }
 
@@ -111,51 +156,43 @@ __global__ void __launch_bounds__(kThreads) team_gather_offchip_kernel(const Tea
     const int w = blockIdx.x, team = w / a.N, b = w % a.N;
     for (int j = 0; j < a.N; ++j) {
         const int r = (b - j + a.N) % a.N;
-        for (size_t i = threadIdx.x; i < a.count; i += kThreads)
-            a.out[((size_t)w * a.N + j) * a.count + i] = a.scratch[((size_t)team * a.N + r) * a.count + i];
+        for (size_t i0 = threadIdx.x; i0 < a.count; i0 += (size_t)kThreads * kU) {
+            float v[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const size_t i = i0 + (size_t)kThreads * u;
+                v[u] = i < a.count ? a.scratch[((size_t)team * a.N + r) * a.count + i] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const size_t i = i0 + (size_t)kThreads * u;
+                if (i < a.count) a.out[((size_t)w * a.N + j) * a.count + i] = v[u];
+            }
+        }
     }
 }
 
 using Kernel = void (*)(const TeamArgs);
 
-template <int OP>
+template <int OP, bool DIRECT>
 Kernel pick_reduce(int e)
 {
     switch (e) {
-    case 1: return team_reduce_kernel<1, OP>;
-    case 2: return team_reduce_kernel<2, OP>;
-    case 4: return team_reduce_kernel<4, OP>;
-    case 8: return team_reduce_kernel<8, OP>;
-    case 16: return team_reduce_kernel<16, OP>;
-    case 32: return team_reduce_kernel<32, OP>;
-    case 64: return team_reduce_kernel<64, OP>;
-    case 128: return team_reduce_kernel<128, OP>;
+    case 1: return team_reduce_kernel<1, OP, DIRECT>;
+    case 2: return team_reduce_kernel<2, OP, DIRECT>;
+    case 4: return team_reduce_kernel<4, OP, DIRECT>;
+    case 8: return team_reduce_kernel<8, OP, DIRECT>;
     }
-    return nullptr;
+    return team_reduce_kernel<16, OP, DIRECT>;
 }
 
-Kernel pick_gather(int e)
-{
-    switch (e) {
-    case 1: return team_gather_kernel<1>;
-    case 2: return team_gather_kernel<2>;
-    case 4: return team_gather_kernel<4>;
-    case 8: return team_gather_kernel<8>;
-    case 16: return team_gather_kernel<16>;
-    case 32: return team_gather_kernel<32>;
-    case 64: return team_gather_kernel<64>;
-    case 128: return team_gather_kernel<128>;
-    }
-    return nullptr;
-}
-
-// values per thread, rounded up to a compiled variant; 0 if too many
+// values per thread and chunk: enough for the whole buffer in one chunk up to 16
 int values_per_thread(size_t values)
 {
     const size_t need = (values + kThreads - 1) / kThreads;
-    for (int e = 1; e <= 128; e *= 2)
+    for (int e = 1; e < 16; e *= 2)
         if ((size_t)e >= need) return e;
-    return 0;
+    return 16;
 }
 
 }  // namespace
@@ -185,8 +222,10 @@ int fail(cf_team t, hipError_t e)
 
 bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
-int check_call(cf_team t, int32_t teams, int32_t team_size, const void *in, const void *out, size_t elems)
+int check_call(cf_team t, int32_t teams, int32_t team_size, const void *in, const void *out, size_t elems, int32_t mode)
 {
+    if (mode != CF_TEAM_ROUNDS && mode != CF_TEAM_TWO_KERNELS && mode != CF_TEAM_DIRECT && mode != CF_TEAM_TWO_HOPS)
+        return CF_EINVAL;
     if (!t || !in || !out || teams < 1 || !pow2(team_size) || team_size > 16 || elems < 1) return CF_EINVAL;
     if ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 3u) return CF_EINVAL;
     if ((long)teams * team_size > t->max_ranks) return CF_EINVAL;
@@ -230,7 +269,7 @@ extern "C" {
 
 int cf_team_create(int32_t max_ranks, size_t max_elems, cf_team *out)
 {
-    if (!out || max_ranks < 1 || max_elems < 1 || max_elems > (size_t)kThreads * 128) return CF_EINVAL;
+    if (!out || max_ranks < 1 || max_elems < 1 || max_elems > kMaxElems) return CF_EINVAL;
     *out = nullptr;
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -280,16 +319,16 @@ int cf_team_destroy(cf_team t)
 }
 
 int cf_team_reduce(cf_team t, int32_t teams, int32_t team_size, int32_t op, const float *in, float *out, size_t elems,
-                   int32_t offchip, void *stream)
+                   int32_t mode, void *stream)
 {
-    int rc = check_call(t, teams, team_size, in, out, elems);
+    int rc = check_call(t, teams, team_size, in, out, elems, mode);
     if (rc != CF_OK) return rc;
     if ((op != CF_TEAM_SUM && op != CF_TEAM_MAX) || elems > t->cap) return CF_EINVAL;
-    if (!offchip && (rc = same_grid(t, teams * team_size)) != CF_OK) return rc;
+    if (mode != CF_TEAM_TWO_KERNELS && (rc = same_grid(t, teams * team_size)) != CF_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const TeamArgs a = make_args(t, in, out, elems, team_size);
     const dim3 grid(teams * team_size), block(kThreads);
-    if (offchip) {
+    if (mode == CF_TEAM_TWO_KERNELS) {
         hipLaunchKernelGGL(team_stage_kernel, grid, block, 0, s, a);
         if (op == CF_TEAM_SUM)
             hipLaunchKernelGGL(team_reduce_offchip_kernel<cf::team::kSum>, grid, block, 0, s, a);
@@ -297,8 +336,13 @@ int cf_team_reduce(cf_team t, int32_t teams, int32_t team_size, int32_t op, cons
             hipLaunchKernelGGL(team_reduce_offchip_kernel<cf::team::kMax>, grid, block, 0, s, a);
     } else {
         const int e = values_per_thread(elems);
-        Kernel k = op == CF_TEAM_SUM ? pick_reduce<cf::team::kSum>(e) : pick_reduce<cf::team::kMax>(e);
-        if (!k) return CF_EUNSUPPORTED;
+        Kernel k;
+        if (mode == CF_TEAM_TWO_HOPS)
+            k = op == CF_TEAM_SUM ? team_reduce_two_hops_kernel<cf::team::kSum> : team_reduce_two_hops_kernel<cf::team::kMax>;
+        else if (mode == CF_TEAM_DIRECT)
+            k = op == CF_TEAM_SUM ? pick_reduce<cf::team::kSum, true>(e) : pick_reduce<cf::team::kMax, true>(e);
+        else
+            k = op == CF_TEAM_SUM ? pick_reduce<cf::team::kSum, false>(e) : pick_reduce<cf::team::kMax, false>(e);
         hipLaunchKernelGGL(k, grid, block, 0, s, a);
     }
     hipError_t e = hipGetLastError();
@@ -306,22 +350,22 @@ int cf_team_reduce(cf_team t, int32_t teams, int32_t team_size, int32_t op, cons
 }
 
 int cf_team_gather(cf_team t, int32_t teams, int32_t team_size, const float *in, float *out, size_t elems,
-                   int32_t offchip, void *stream)
+                   int32_t mode, void *stream)
 {
-    int rc = check_call(t, teams, team_size, in, out, elems);
+    int rc = check_call(t, teams, team_size, in, out, elems, mode);
     if (rc != CF_OK) return rc;
-    if (elems * (size_t)team_size > t->cap) return CF_EINVAL;
-    if (!offchip && (rc = same_grid(t, teams * team_size)) != CF_OK) return rc;
+    if (elems * (size_t)team_size > t->cap || mode == CF_TEAM_TWO_HOPS) return CF_EINVAL;
+    if (mode != CF_TEAM_TWO_KERNELS && (rc = same_grid(t, teams * team_size)) != CF_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const TeamArgs a = make_args(t, in, out, elems, team_size);
     const dim3 grid(teams * team_size), block(kThreads);
-    if (offchip) {
+    if (mode == CF_TEAM_TWO_KERNELS) {
         hipLaunchKernelGGL(team_stage_kernel, grid, block, 0, s, a);
         hipLaunchKernelGGL(team_gather_offchip_kernel, grid, block, 0, s, a);
+    } else if (mode == CF_TEAM_DIRECT) {
+        hipLaunchKernelGGL(team_gather_kernel<true>, grid, block, 0, s, a);
     } else {
-        Kernel k = pick_gather(values_per_thread(elems * (size_t)team_size));
-        if (!k) return CF_EUNSUPPORTED;
-        hipLaunchKernelGGL(k, grid, block, 0, s, a);
+        hipLaunchKernelGGL(team_gather_kernel<false>, grid, block, 0, s, a);
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? CF_OK : fail(t, e);

@@ -1,10 +1,11 @@
 """Parity of the team collectives (cf_team_reduce / cf_team_gather) with the CPU simulation of the paper's
-Alg. 1 / Alg. 2 (oracle/cluster_collectives.py), through the C ABI, for both the in-kernel exchange and the
-two-kernel version.
+Alg. 1 / Alg. 2 (oracle/cluster_collectives.py), through the C ABI, for every way of exchanging the data:
+the paper's rounds inside one kernel, one hop or (reduce) two hops inside one kernel, and two kernels.
 
 Bar: the gather and the max-reduce move or select values, so they are bit-exact.  The sum-reduce is fp32 and
-follows Alg. 1's order of additions, which the oracle executes in fp64: each result is a sum of N <= 16 values
-of magnitude <= ~4, so |err| <= N * 2^-24 * sum|x| is the bound used (a few 1e-6).
+adds in Alg. 1's order (rounds) or in rank order (the other two modes); the oracle executes Alg. 1 in fp64: each
+result is a sum of N <= 16 values of magnitude <= ~4, and |err| <= N * 2^-24 * sum|x| (a few 1e-6) bounds the
+rounding of any order of fp32 additions.
 """
 import sys
 
@@ -15,7 +16,10 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 from oracle import cluster_collectives as oc                      # noqa: E402
-from paper_2508_18850_amd import TeamCollectives, TEAM_SUM, TEAM_MAX   # noqa: E402
+from paper_2508_18850_amd import (TeamCollectives, TEAM_SUM, TEAM_MAX, TEAM_ROUNDS, TEAM_TWO_KERNELS,   # noqa: E402
+                                  TEAM_DIRECT, TEAM_TWO_HOPS)
+
+MODES = [TEAM_ROUNDS, TEAM_TWO_KERNELS, TEAM_DIRECT]
 
 
 def _log(msg):
@@ -33,10 +37,10 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("offchip", [False, True])
+@pytest.mark.parametrize("mode", MODES + [TEAM_TWO_HOPS])
 @pytest.mark.parametrize("teams,n,elems", CASES)
-def test_reduce_matches_alg1(teams, n, elems, offchip):
-    _log("reduce teams=%d N=%d elems=%d offchip=%s" % (teams, n, elems, offchip))
+def test_reduce_matches_alg1(teams, n, elems, mode):
+    _log("reduce teams=%d N=%d elems=%d mode=%d" % (teams, n, elems, mode))
     tc = TeamCollectives(256, 65536)
     host = _data(teams, n, elems, seed=elems + n)
     src = torch.from_numpy(host).cuda()
@@ -44,8 +48,8 @@ def test_reduce_matches_alg1(teams, n, elems, offchip):
         dst = torch.full_like(src, float("nan"))
         st = torch.cuda.current_stream().cuda_stream
         # two calls in a row: the second must not be confused by the first one's slots
-        tc.reduce(teams, n, op, src.data_ptr(), dst.data_ptr(), elems, offchip, st)
-        tc.reduce(teams, n, op, src.data_ptr(), dst.data_ptr(), elems, offchip, st)
+        tc.reduce(teams, n, op, src.data_ptr(), dst.data_ptr(), elems, mode, st)
+        tc.reduce(teams, n, op, src.data_ptr(), dst.data_ptr(), elems, mode, st)
         tc.status(st)
         got = dst.cpu().numpy()
         for k in range(teams):
@@ -57,23 +61,25 @@ def test_reduce_matches_alg1(teams, n, elems, offchip):
                 else:
                     tol = n * 2.0 ** -24 * np.abs(host[k]).sum(axis=0) + 1e-30
                     assert np.all(np.abs(got[k, b].astype(np.float64) - want[b]) <= tol)
-        # every rank of a team ends with the same bits (Alg. 1 is symmetric in the ranks only for max;
-        # for the sum each rank adds in its own order, so equality is checked against the oracle only)
+        # adding in rank order, every rank of a team ends with the same bits (in Alg. 1's order each rank
+        # adds in an order of its own)
+        if mode != TEAM_ROUNDS:
+            assert np.array_equal(got, np.broadcast_to(got[:, :1], got.shape))
     tc.close()
 
 
-@pytest.mark.parametrize("offchip", [False, True])
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("teams,n,elems", [(1, 1, 5), (3, 2, 1), (2, 4, 513), (4, 8, 8192), (2, 16, 1000), (16, 16, 4096),
                                            (32, 8, 8192), (1, 16, 4096)])
-def test_gather_matches_alg2(teams, n, elems, offchip):
-    _log("gather teams=%d N=%d elems=%d offchip=%s" % (teams, n, elems, offchip))
+def test_gather_matches_alg2(teams, n, elems, mode):
+    _log("gather teams=%d N=%d elems=%d mode=%d" % (teams, n, elems, mode))
     tc = TeamCollectives(256, 65536)
     host = _data(teams, n, elems, seed=7 * elems + n)
     src = torch.from_numpy(host).cuda()
     dst = torch.full((teams, n, n, elems), float("nan"), dtype=torch.float32, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
-    tc.gather(teams, n, src.data_ptr(), dst.data_ptr(), elems, offchip, st)
-    tc.gather(teams, n, src.data_ptr(), dst.data_ptr(), elems, offchip, st)
+    tc.gather(teams, n, src.data_ptr(), dst.data_ptr(), elems, mode, st)
+    tc.gather(teams, n, src.data_ptr(), dst.data_ptr(), elems, mode, st)
     tc.status(st)
     got = dst.cpu().numpy()
     for k in range(teams):
@@ -95,6 +101,8 @@ def test_bad_arguments_are_refused():
     assert tc.reduce_rc(16, 8, TEAM_SUM, p, p, 16) == -1         # more ranks than the handle's capacity
     assert tc.reduce_rc(1, 8, TEAM_SUM, 0, p, 16) == -1          # null pointer
     assert tc.gather_rc(1, 8, p, p, 256) == -1                   # gathered buffer larger than the capacity
+    assert tc.reduce_rc(1, 8, TEAM_SUM, p, p, 16, 4) == -1       # unknown mode
+    assert tc.gather_rc(1, 8, p, p, 16, TEAM_TWO_HOPS) == -1     # a mode of the reduce only
     tc.close()
     big = TeamCollectives(1024, 16)
     assert big.reduce_rc(64, 8, TEAM_SUM, p, p, 16) == -2        # more workgroups than compute units: not resident
