@@ -71,3 +71,26 @@ def decode_block(x, w_qkv, w_o, k_cache, v_cache, pos, n_q_heads, n_kv_heads, he
     if rc != 0:
         raise ValueError("cfo_decode_block rejected its arguments")
     return {"out": out, "q_rot": q_rot, "k_rot": k_rot, "v_new": v_new, "attn": attn}
+
+
+def decode_layer(x, gamma, eps, w_qkv, w_o, k_cache, v_cache, pos, n_q_heads, n_kv_heads, head_dim, rope_base):
+    """Same contract as oracle.decode_block.decode_layer; inputs must be fp16 arrays."""
+    lib = _load()
+    B, D = x.shape
+    nq, nkv, d = int(n_q_heads), int(n_kv_heads), int(head_dim)
+    max_seq = k_cache.shape[2]
+    assert gamma.shape == (D,)
+    assert w_qkv.shape == (D, (nq + 2 * nkv) * d) and w_o.shape == (nq * d, D)
+    assert k_cache.shape == (B, nkv, max_seq, d) and v_cache.shape == k_cache.shape
+    kx, kg = _u16(x), _u16(gamma)
+    keep = [_u16(a) for a in (w_qkv, w_o, k_cache, v_cache)]
+    out = np.empty((B, D)); q_rot = np.empty((B, nq, d)); k_rot = np.empty((B, nkv, d))
+    v_new = np.empty((B, nkv, d)); attn = np.empty((B, nq, d))
+    f64p = ctypes.POINTER(ctypes.c_double)
+    lib.cfo_decode_layer.restype = ctypes.c_int
+    rc = lib.cfo_decode_layer(kx[1], kg[1], ctypes.c_double(float(eps)), *[k[1] for k in keep], B, D, nq, nkv, d, max_seq,
+                              int(pos), ctypes.c_double(float(rope_base)),
+                              *[a.ctypes.data_as(f64p) for a in (out, q_rot, k_rot, v_new, attn)])
+    if rc != 0:
+        raise ValueError("cfo_decode_layer rejected its arguments")
+    return {"out": out, "q_rot": q_rot, "k_rot": k_rot, "v_new": v_new, "attn": attn}

@@ -26,6 +26,9 @@ RoPE identity/norm/relative-position/one-hot closed forms, uniform-softmax
 closed form for x = 0, empty-cache case reducing to two matrix products,
 hand-computed two-key example fixing the 1/sqrt(d) scale, convexity and
 permutation invariance, GQA-vs-replicated-MHA, batch-row independence.
+rms_norm / decode_layer (tests/test_oracle_layer.py): constant-row closed form, unit mean square,
+scale invariance at eps = 0, a library routine (torch rms_norm in fp64), W_o = 0 leaves x, an input
+of unit mean square with gamma = 1 reduces to x + decode_block(x).
 """
 from __future__ import annotations
 
@@ -110,6 +113,31 @@ def decode_block(x, w_qkv, w_o, k_cache, v_cache, pos, n_q_heads, n_kv_heads,
                 attn[b, i] = w @ V
     out = attn.reshape(B, nq * d) @ np.asarray(w_o).astype(np.float64)
     return {"out": out, "q_rot": q_rot, "k_rot": k_rot, "v_new": v_new, "attn": attn}
+
+
+def rms_norm(x, gamma, eps):
+    """RMSNorm of every row of x [B, D]:  x / sqrt(mean(x^2) + eps) * gamma, in fp64, nothing rounded.
+
+    The paper does not define it (it leaves RMSNorm to other libraries, end of Sec. 3); this is the
+    pre-normalisation of the Llama-family layers whose shapes the paper measures.
+    """
+    x = np.asarray(x).astype(np.float64)
+    g = np.asarray(gamma).astype(np.float64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + float(eps)) * g
+
+
+def decode_layer(x, gamma, eps, w_qkv, w_o, k_cache, v_cache, pos, n_q_heads, n_kv_heads,
+                 head_dim, rope_base):
+    """The attention half of a pre-norm decoder layer:  out = x + block(rms_norm(x)).
+
+    Same arguments and result as decode_block, plus gamma [D] and eps; `out` includes the residual.
+    The normalised activations enter the block unrounded.
+    """
+    r = decode_block(rms_norm(x, gamma, eps), w_qkv, w_o, k_cache, v_cache, pos, n_q_heads, n_kv_heads,
+                     head_dim, rope_base)
+    r["out"] = r["out"] + np.asarray(x).astype(np.float64)
+    return r
 
 
 def attention_weights(q_rot_i, K):

@@ -93,23 +93,19 @@ static void rope_inplace(double *v, int d, int pos, double base)
 }
 
 /*
- * x [B,D], w_qkv [D,(nq+2nkv)d], w_o [nq d, D], caches [B,nkv,max_seq,d] (fp16 bits).
- * Outputs (double, caller-allocated): out [B,D], q_rot [B,nq,d], k_rot [B,nkv,d],
- * v_new [B,nkv,d], attn [B,nq,d].  The caches are not modified.  Returns 0, or -1
- * on a bad argument or allocation failure.
+ * The block for an input given as doubles: xd [B,D] (not modified); everything else as in
+ * cfo_decode_block below.
  */
-int cfo_decode_block(const uint16_t *x, const uint16_t *w_qkv, const uint16_t *w_o,
-                     const uint16_t *k_cache, const uint16_t *v_cache,
-                     int B, int D, int nq, int nkv, int d, int max_seq, int pos, double rope_base,
-                     double *out, double *q_rot, double *k_rot, double *v_new, double *attn)
+int cfo_decode_block_real(const double *xd, const uint16_t *w_qkv, const uint16_t *w_o,
+                          const uint16_t *k_cache, const uint16_t *v_cache,
+                          int B, int D, int nq, int nkv, int d, int max_seq, int pos, double rope_base,
+                          double *out, double *q_rot, double *k_rot, double *v_new, double *attn)
 {
     if (B < 1 || D < 1 || nq < 1 || nkv < 1 || nq % nkv || d < 2 || (d & 1) || pos < 0 || pos >= max_seq)
         return -1;
     int G = nq / nkv, nqkv = (nq + 2 * nkv) * d;
-    double *xd = (double *)malloc(sizeof(double) * (size_t)B * D);
     double *y = (double *)malloc(sizeof(double) * (size_t)B * nqkv);
-    if (!xd || !y) { free(xd); free(y); return -1; }
-    for (size_t i = 0; i < (size_t)B * D; ++i) xd[i] = half_to_double(x[i]);
+    if (!y) return -1;
 
     matvec(xd, w_qkv, B, D, nqkv, y);
     for (int b = 0; b < B; ++b) {
@@ -161,7 +157,60 @@ int cfo_decode_block(const uint16_t *x, const uint16_t *w_qkv, const uint16_t *w
         free(s);
     }
     if (!fail) matvec(attn, w_o, B, nq * d, D, out);
-    free(xd);
     free(y);
     return fail ? -1 : 0;
+}
+
+/*
+ * x [B,D], w_qkv [D,(nq+2nkv)d], w_o [nq d, D], caches [B,nkv,max_seq,d] (fp16 bits).
+ * Outputs (double, caller-allocated): out [B,D], q_rot [B,nq,d], k_rot [B,nkv,d],
+ * v_new [B,nkv,d], attn [B,nq,d].  The caches are not modified.  Returns 0, or -1
+ * on a bad argument or allocation failure.
+ */
+int cfo_decode_block(const uint16_t *x, const uint16_t *w_qkv, const uint16_t *w_o,
+                     const uint16_t *k_cache, const uint16_t *v_cache,
+                     int B, int D, int nq, int nkv, int d, int max_seq, int pos, double rope_base,
+                     double *out, double *q_rot, double *k_rot, double *v_new, double *attn)
+{
+    if (B < 1 || D < 1) return -1;
+    double *xd = (double *)malloc(sizeof(double) * (size_t)B * D);
+    if (!xd) return -1;
+    for (size_t i = 0; i < (size_t)B * D; ++i) xd[i] = half_to_double(x[i]);
+    int rc = cfo_decode_block_real(xd, w_qkv, w_o, k_cache, v_cache, B, D, nq, nkv, d, max_seq, pos, rope_base,
+                                   out, q_rot, k_rot, v_new, attn);
+    free(xd);
+    return rc;
+}
+
+/*
+ * The decoder layer around the block: pre-normalisation and residual connection of a Llama-style
+ * layer (the paper leaves RMSNorm to other libraries, end of Sec. 3; the block is Eq. 1):
+ *   n_b   = x_b / sqrt(mean_j(x_bj^2) + eps) * gamma      (RMSNorm, all in double, nothing rounded)
+ *   out_b = x_b + block(n_b)
+ * gamma [D] fp16 bits.  Other arguments and outputs as above.
+ */
+int cfo_decode_layer(const uint16_t *x, const uint16_t *gamma, double eps, const uint16_t *w_qkv, const uint16_t *w_o,
+                     const uint16_t *k_cache, const uint16_t *v_cache,
+                     int B, int D, int nq, int nkv, int d, int max_seq, int pos, double rope_base,
+                     double *out, double *q_rot, double *k_rot, double *v_new, double *attn)
+{
+    if (B < 1 || D < 1) return -1;
+    double *n = (double *)malloc(sizeof(double) * (size_t)B * D);
+    if (!n) return -1;
+    for (int b = 0; b < B; ++b) {
+        double ss = 0.0;
+        for (int j = 0; j < D; ++j) {
+            double v = half_to_double(x[(size_t)b * D + j]);
+            ss += v * v;
+        }
+        double r = 1.0 / sqrt(ss / (double)D + eps);
+        for (int j = 0; j < D; ++j)
+            n[(size_t)b * D + j] = half_to_double(x[(size_t)b * D + j]) * r * half_to_double(gamma[j]);
+    }
+    int rc = cfo_decode_block_real(n, w_qkv, w_o, k_cache, v_cache, B, D, nq, nkv, d, max_seq, pos, rope_base,
+                                   out, q_rot, k_rot, v_new, attn);
+    if (rc == 0)
+        for (size_t i = 0; i < (size_t)B * D; ++i) out[i] += half_to_double(x[i]);
+    free(n);
+    return rc;
 }
