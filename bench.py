@@ -57,6 +57,9 @@ def parse_args():
     ap.add_argument("--no-arena", action="store_true", help="one device allocation per tensor instead of one for all layers")
     ap.add_argument("--reps", type=int, default=1,
                     help="further timed regions of --steps launches after the first (reported as median / p10 / p90 in\n                    \"repetitions\"; the headline value is always the first region)")
+    ap.add_argument("--layer", action="store_true",
+                    help="time cf_decode_layer (RMSNorm in front of the block and the residual added, in the same kernel) "
+                         "instead of the bare block; out then is a second buffer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg")
     return ap.parse_args()
@@ -176,6 +179,12 @@ def main():
         sh = stream.cuda_stream
 
         decode = blk.decode_block if args.row_major else blk.decode_block_packed
+        if args.layer:
+            gamma = (1.0 + 0.25 * torch.randn((D,), generator=gen, device=dev)).half()
+            gp = gamma.data_ptr()
+
+            def decode(B_, xp_, w, o, k, v, L_, op_, sh_):
+                blk.decode_layer(B_, xp_, gp, 1e-5, True, not args.row_major, w, o, k, v, L_, op_, sh_)
 
         def step(i):
             w, o, k, v = ptrs[i % n_layers]
@@ -218,6 +227,7 @@ def main():
         "config": {"workload": name, "d_model": D, "n_q_heads": nq, "n_kv_heads": nkv, "head_dim": d,
                    "batch": B, "kv_len": L, "layers_rotated": n_layers,
                    "weight_layout": "row-major" if args.row_major else "packed (per-head blocks, one-time rearrangement)",
+                   "fused_steps": "rmsnorm + block + residual" if args.layer else "block",
                    "plan": plan},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(name),

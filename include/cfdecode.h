@@ -110,6 +110,24 @@ int cf_decode_block_packed(cf_handle h, int32_t batch, const void *x, const void
                            void *stream);
 
 /*
+ * The steps of a pre-norm decoder layer that sit directly around the block, in the same single kernel
+ * (the paper fuses the block of Eq. 1 and leaves RMSNorm to other libraries, end of Sec. 3):
+ *
+ *   n_b   = x_b / sqrt(mean_j(x_bj^2) + eps) * norm_weight        (norm_weight != NULL; else n_b = x_b)
+ *   out_b = block(n_b)  [+ x_b  when residual != 0]
+ *
+ * with block() and all other arguments as in cf_decode_block (packed == 0) or cf_decode_block_packed
+ * (packed != 0).  norm_weight: DEVICE [d_model] fp16, 16-byte aligned, read.  The mean square is taken in
+ * fp32 from the fp16 values of x and the normalised row enters the projection unrounded.  `out` must not
+ * overlap `x` (other workgroups may still be reading x when the first results are written).
+ * Errors as for cf_decode_block; in addition CF_EINVAL for eps < 0 or not finite, CF_EUNSUPPORTED for a
+ * norm_weight with d_model > 8192.
+ */
+int cf_decode_layer(cf_handle h, int32_t batch, const void *x, const void *norm_weight, float eps, int32_t residual,
+                    int32_t packed, const void *W_qkv, const void *W_o, void *k_cache, void *v_cache, int32_t pos,
+                    void *out, void *stream);
+
+/*
  * Wait for `stream` and report whether any kernel launched through this handle
  * gave up on a cross-workgroup wait (CF_ETIMEOUT) since the last cf_status
  * call.  The fused kernel relies on all its workgroups being resident at once

@@ -32,6 +32,8 @@ def build(verbose: bool = False) -> str:
     os.makedirs(obj_dir, exist_ok=True)
     hipcc = _hipcc()
     variants = (("", ["-DCF_STAMPS=0"], LIB), ("_trace", ["-DCF_STAMPS=1"], TRACE_LIB))
+    # (object suffix, extra definitions, source): the fused kernel is compiled a second time with -DCF_LAYER=1
+    units = [("", [], src) for src in SOURCES] + [("_layer", ["-DCF_LAYER=1"], "cf_fused_kernel.hip")]
 
     def compile_one(job):
         suffix, defs, src = job
@@ -44,11 +46,11 @@ def build(verbose: bool = False) -> str:
             print(res.stderr)
         return obj
 
-    jobs = [(suffix, defs, src) for (suffix, defs, _) in variants for src in SOURCES]
-    with ThreadPoolExecutor(max_workers=6) as pool:
+    jobs = [(usuf + suffix, defs + udefs, src) for (suffix, defs, _) in variants for (usuf, udefs, src) in units]
+    with ThreadPoolExecutor(max_workers=8) as pool:
         objs = list(pool.map(compile_one, jobs))
     for k, (_, _, lib) in enumerate(variants):
-        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs[k * len(SOURCES):(k + 1) * len(SOURCES)]]
+        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs[k * len(units):(k + 1) * len(units)]]
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0:
             raise RuntimeError("link failed:\n" + res.stderr)

@@ -33,7 +33,8 @@ struct cf_handle_s {
     int tune_w = 0, tune_ks = 0, tune_ns = 0;
     int balance_rows = 0, balance_tokens = 32;   // half the length difference between even and odd splits (-1: off)
     long long spin_ticks = 200000000LL;   // 2 s of the 100 MHz wall clock
-    int wg_per_cu[3] = {0, 0, 0};         // resident workgroups per CU for batch tiles 1, 4, 16 (0 = not probed)
+    int wg_per_cu[6] = {0, 0, 0, 0, 0, 0};   // resident workgroups per CU for batch tiles 1, 4, 16 of the block kernel,
+                                          // then of the layer kernel (0 = not probed)
     int last_batch = 0;
     int last_plan[10] = {0};
     int last_hip = 0;
@@ -194,10 +195,11 @@ int hip_fail(cf_handle_s *h, hipError_t e)
 // Check (once per batch tile) that the whole grid can be resident at the same time.
 int check_residency(cf_handle_s *h, const Params &p, int bt, size_t lds_bytes)
 {
-    int &slot = h->wg_per_cu[tile_index(bt)];
+    const bool layer = cf::wants_layer_kernel(p);
+    int &slot = h->wg_per_cu[tile_index(bt) + (layer ? 3 : 0)];
     if (slot == 0) {
         int n = 0;
-        hipError_t e = cf::max_workgroups_per_cu(h->cfg.head_dim, h->G, bt, lds_bytes, &n);
+        hipError_t e = cf::max_workgroups_per_cu(h->cfg.head_dim, h->G, bt, lds_bytes, layer, &n);
         if (e != hipSuccess) return hip_fail(h, e);
         slot = n > 0 ? n : -1;
     }
@@ -315,9 +317,12 @@ int cf_destroy(cf_handle h)
 }
 
 static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, const void *W_qkv, const void *W_o,
-                       void *k_cache, void *v_cache, int32_t pos, void *out, void *stream)
+                       void *k_cache, void *v_cache, int32_t pos, void *out, void *stream,
+                       const void *norm_weight = nullptr, float eps = 0.f, int residual = 0)
 {
     if (!h) return CF_EINVAL;
+    if ((norm_weight && !aligned16(norm_weight)) || !(eps >= 0.f) || !std::isfinite(eps)) return CF_EINVAL;
+    if (norm_weight && h->cfg.d_model > 8 * 2 * cf::kThreads) return CF_EUNSUPPORTED;        // the kernel squares a row with two loads per thread
     if (batch < 1 || batch > h->cfg.max_batch || pos < 0 || pos >= h->cfg.max_seq) return CF_EINVAL;
     if (!aligned16(x) || !aligned16(W_qkv) || !aligned16(W_o) || !aligned16(k_cache) || !aligned16(v_cache) ||
         !aligned16(out))
@@ -331,6 +336,9 @@ static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, co
     p.kc = static_cast<uint16_t *>(k_cache);
     p.vc = static_cast<uint16_t *>(v_cache);
     p.out = static_cast<uint16_t *>(out);
+    p.gamma = static_cast<const uint16_t *>(norm_weight);
+    p.eps = eps;
+    p.residual = residual != 0;
     p.B = batch;
     p.pos = pos;
     p.packed = packed;
@@ -359,6 +367,15 @@ int cf_decode_block_packed(cf_handle h, int32_t batch, const void *x, const void
                            const void *W_o_packed, void *k_cache, void *v_cache, int32_t pos, void *out, void *stream)
 {
     return decode_impl(h, 1, batch, x, W_qkv_packed, W_o_packed, k_cache, v_cache, pos, out, stream);
+}
+
+int cf_decode_layer(cf_handle h, int32_t batch, const void *x, const void *norm_weight, float eps, int32_t residual,
+                    int32_t packed, const void *W_qkv, const void *W_o, void *k_cache, void *v_cache, int32_t pos,
+                    void *out, void *stream)
+{
+    if (residual && x == out) return CF_EINVAL;
+    return decode_impl(h, packed != 0, batch, x, W_qkv, W_o, k_cache, v_cache, pos, out, stream, norm_weight, eps,
+                       residual);
 }
 
 int cf_packed_sizes(cf_handle h, size_t *qkv_bytes, size_t *o_bytes)
@@ -429,7 +446,7 @@ int cf_set_tuning(cf_handle h, int32_t workgroups, int32_t k_splits, int32_t kv_
     h->tune_w = workgroups;
     h->tune_ks = k_splits;
     h->tune_ns = kv_splits;
-    h->wg_per_cu[0] = h->wg_per_cu[1] = h->wg_per_cu[2] = 0;   // LDS size may change: probe residency again
+    for (int &v : h->wg_per_cu) v = 0;   // LDS size may change: probe residency again
     if (spin_limit_us) h->spin_ticks = (long long)spin_limit_us * 100;
     return CF_OK;
 }

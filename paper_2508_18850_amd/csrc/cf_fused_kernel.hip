@@ -256,6 +256,17 @@ __device__ __forceinline__ void rope_table(int pos, double inv_freq, float *cs, 
 #ifndef CF_STAMPS
 #define CF_STAMPS 0
 #endif
+// CF_LAYER=1 compiles the kernel with the RMSNorm prologue and the residual epilogue (fused_decode_layer);
+// without it none of that code is in the kernel (fused_decode_block).
+#ifndef CF_LAYER
+#define CF_LAYER 0
+#endif
+#if CF_LAYER
+#define CF_KERNEL fused_decode_layer
+#else
+#define CF_KERNEL fused_decode_block
+#endif
+constexpr bool kLayer = CF_LAYER != 0;
 #if CF_STAMPS
 __shared__ unsigned long long s_ts[kStamps];
 #define CF_STAMP(k)                                       \
@@ -354,11 +365,73 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
         xv[q] = x_in_regs && i < BT * p.RPS && b < p.B && r < nrows;
         xr[q] = p.x[xv[q] ? (size_t)b * p.D + r0 + r : 0];
     }
+    // RMSNorm in front of the projection (when a weight vector is given): the projection is linear, so the
+    // weights gamma go into the staged slice of x and the factor 1/sqrt(mean(x^2) + eps) of a row goes into
+    // the partial sums when they are stored.  Every workgroup takes the mean square from the whole row
+    // (D*2 bytes: one or two 16-byte loads per thread, issued here with the other small loads).
+    const bool norm = kLayer && p.gamma != nullptr;
+    const uint16_t *gsrc = norm ? p.gamma : p.x;                  // any readable address when there is no weight
+    uint16_t gr[XR];
+#pragma unroll
+    for (int q = 0; q < XR; ++q) gr[q] = 0;
+    if (norm) {             // (a wait behind this branch counts the loads of the path without it: nothing drains)
+#pragma unroll
+        for (int q = 0; q < XR; ++q) {
+            const int i = tid + q * NT, b = BT == 1 ? 0 : i / p.RPS, r = i - b * p.RPS;
+            gr[q] = gsrc[xv[q] ? r0 + r : 0];
+        }
+    }
+    float *nrm = red + MAXI * NW * BT * HD;                       // [NW][BT] sums of squares, one per wavefront and row
+    constexpr int RG = BT < 4 ? BT : 4;                           // rows whose loads are in flight together
+    const int d8 = p.D >> 3;                                      // 16-byte pieces of a row
+    const uint4 *x4 = reinterpret_cast<const uint4 *>(p.x);
+    uint4 xq[RG][2];                                              // rows b0 .. b0 + RG - 1; needs D <= 2 * 8 * NT
+    bool ok[RG][2];
+    auto load_rows = [&](int b0) {
+#pragma unroll
+        for (int r = 0; r < RG; ++r)
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int c = tid + k * NT;
+                ok[r][k] = norm && b0 + r < p.B && c < d8;
+                xq[r][k] = x4[ok[r][k] ? (size_t)(b0 + r) * d8 + c : 0];
+            }
+    };
+    auto square_rows = [&](int b0) {
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            float ss = 0.f;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                float f[8];
+                unpack8(__builtin_bit_cast(h8, xq[r][k]), f);
+                float t = 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) t = fmaf(f[j], f[j], t);
+                ss += ok[r][k] ? t : 0.f;
+            }
+            ss = wave_sum(ss);
+            if ((tid & 63) == 0 && b0 + r < BT) nrm[wv * BT + b0 + r] = ss;
+        }
+    };
+#pragma unroll
+    for (int r = 0; r < RG; ++r)
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            xq[r][k] = uint4{0u, 0u, 0u, 0u};
+            ok[r][k] = false;
+        }
+    if (BT <= 4 && norm) load_rows(0);
     const double inv_freq = p.inv_freq[tid < HD / 2 ? tid : 0];   // for the RoPE table, below
     __builtin_amdgcn_sched_barrier(0);
     load(wb, voff0);
     __builtin_amdgcn_sched_barrier(0);
     CF_STAMP(21);           // second weight batch issued
+    if (BT > 4 && norm)     // large batches: four rows at a time, each group waits for its loads
+        for (int b0 = 0; b0 < p.B; b0 += RG) {
+            load_rows(b0);
+            square_rows(b0);
+        }
     // Launch number: every workgroup keeps, in a line of its own, the number of launches it has
     // completed; all workgroups of a launch hold the same count, so count + 1 stamps this launch
     // without any shared counter.  (One counter for all was read by 256 workgroups at once and
@@ -378,14 +451,16 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
 #pragma unroll
         for (int q = 0; q < XR; ++q) {
             const int i = tid + q * NT;
-            if (i < BT * p.RPS) xs[i] = xv[q] ? h2f(xr[q]) : 0.f;
+            if (i < BT * p.RPS) xs[i] = xv[q] ? h2f(xr[q]) * (norm ? h2f(gr[q]) : 1.f) : 0.f;
         }
     } else {
         for (int i = tid; i < BT * p.RPS; i += NT) {
             const int b = i / p.RPS, r = i - b * p.RPS;
-            xs[i] = (b < p.B && r < nrows) ? h2f(p.x[(size_t)b * p.D + r0 + r]) : 0.f;
+            const bool in = b < p.B && r < nrows;
+            xs[i] = in ? h2f(p.x[(size_t)b * p.D + r0 + r]) * (norm ? h2f(gsrc[r0 + r]) : 1.f) : 0.f;
         }
     }
+    if (BT <= 4 && norm) square_rows(0);
     // cos / sin of this position while the first weights are still on their way
     rope_table<HD>(p.pos, inv_freq, rope, rope + HD / 2);
     lds_barrier();
@@ -404,9 +479,14 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
             const int it = e / (BT * HD), rem = e - it * (BT * HD);
             const int b = rem / HD, c = rem - b * HD;
             if (b < p.B) {
-                float sum = 0.f;
+                float sum = 0.f, ss = 0.f;
 #pragma unroll
                 for (int w8 = 0; w8 < NW; ++w8) sum += red[((it * NW + w8) * BT + b) * HD + c];
+                if (norm) {
+#pragma unroll
+                    for (int w8 = 0; w8 < NW; ++w8) ss += nrm[w8 * BT + b];
+                    sum *= 1.0f / sqrtf(ss / (float)p.D + p.eps);
+                }
                 x1.st(((size_t)ks * p.B + b) * p.nqkv + qkv_col0<HD, G>(p, team, sel_of(si_first + it)) + c, sum,
                       stamp);
             }
@@ -1040,6 +1120,21 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
 // partials of those columns in slot order (the cross-head reduction that the paper
 // does with atomicAdd), then writes fp16.
 // ---------------------------------------------------------------------------
+// The residual input of output value v0 + threadIdx.x of this workgroup (0 when there is none).
+__device__ __forceinline__ uint16_t residual_input(const Params &p, int v0)
+{
+    const int cpw = (p.D + p.W - 1) / p.W;
+    const int c0 = blockIdx.x * cpw;
+    const int ncol = min(cpw, p.D - c0);
+    const int i = v0 + (int)threadIdx.x;
+    uint16_t r = 0;
+    if (kLayer && p.residual && ncol > 0 && i < ncol * p.B) {
+        const int b = i / ncol, c = i - b * ncol;
+        r = p.x[(size_t)b * p.D + c0 + c];
+    }
+    return r;
+}
+
 __device__ __forceinline__ void final_reduce(const Params &p, uint32_t stamp, float *smem)
 {
     const int tid = threadIdx.x;
@@ -1055,6 +1150,10 @@ __device__ __forceinline__ void final_reduce(const Params &p, uint32_t stamp, fl
         const int spt = min(NT / cb, nslots);        // slots read in parallel
         const int v = tid % cb, s0 = tid / cb;
         const int b = (v0 + v) / ncol, c = (v0 + v) - b * ncol;
+        // the residual input of the value this thread writes below (threads tid < cb have v == tid), on its
+        // way while the partials are polled.  (Fetching it before phase 3 was tried: a load inside a branch
+        // there makes every later wait for the output-projection tile drain the queue.)
+        const uint16_t xres = residual_input(p, v0);
         if (s0 < spt) {
             const int n = (nslots - s0 + spt - 1) / spt;
             smem[s0 * cb + v] = ll_sum(p, x3, (size_t)s0 * p.B * p.D + (size_t)b * p.D + c0 + c,
@@ -1063,7 +1162,7 @@ __device__ __forceinline__ void final_reduce(const Params &p, uint32_t stamp, fl
         CF_STAMP(19);           // head partials arrived
         lds_barrier();
         if (tid < cb) {
-            float sum = 0.f;
+            float sum = kLayer && p.residual ? h2f(xres) : 0.f;
             for (int k = 0; k < spt; ++k) sum += smem[k * cb + tid];
             p.out[(size_t)b * p.D + c0 + c] = f2h(sum);
         }
@@ -1072,7 +1171,7 @@ __device__ __forceinline__ void final_reduce(const Params &p, uint32_t stamp, fl
 }
 
 template <int HD, int G, int BT>
-__global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
+__global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
 {
     extern __shared__ float smem[];
     {
@@ -1167,6 +1266,7 @@ __global__ void __launch_bounds__(NT) fused_decode_block(const Params p)
 #endif
 }
 
+#if !CF_LAYER
 // One-time rearrangement of the weights into per-head contiguous blocks (16 bytes per thread step).
 __global__ void pack_qkv_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, int D, int nqkv, int hd)
 {
@@ -1193,15 +1293,17 @@ __global__ void pack_o_kernel(const uint4 *__restrict__ src, uint4 *__restrict__
     }
 }
 
+#endif  // !CF_LAYER
+
 using KernelFn = void (*)(const Params);
 
 template <int HD, int G>
 KernelFn pick_bt(int bt)
 {
     switch (bt) {
-    case 1: return fused_decode_block<HD, G, 1>;
-    case 4: return fused_decode_block<HD, G, 4>;
-    case 16: return fused_decode_block<HD, G, 16>;
+    case 1: return CF_KERNEL<HD, G, 1>;
+    case 4: return CF_KERNEL<HD, G, 4>;
+    case 16: return CF_KERNEL<HD, G, 16>;
     default: return nullptr;
     }
 }
@@ -1227,20 +1329,8 @@ KernelFn pick(int hd, int g, int bt)
 
 }  // namespace
 
-size_t lds_floats(const Params &p, int hd, int g, int bt)
+static hipError_t occupancy_of(KernelFn fn, size_t lds_bytes, int *out)
 {
-    const size_t rb = bt < 4 ? bt : 4;
-    const size_t maxi = bt == 1 ? 4 : (bt <= 4 ? 2 : 1);
-    const size_t f1 = (size_t)bt * p.RPS + maxi * kWaves * bt * hd;
-    const size_t f2 = (size_t)hd + (size_t)(g + 2) * hd + 8 + 2 * (size_t)g * kWaves + (size_t)g * kWaves * hd;
-    const size_t f3 = (size_t)bt * hd + (size_t)kWaves * rb * kOutChunk;
-    size_t f = f1 > f2 ? f1 : f2;
-    return f > f3 ? f : f3;
-}
-
-hipError_t max_workgroups_per_cu(int hd, int g, int bt, size_t lds_bytes, int *out)
-{
-    KernelFn fn = pick(hd, g, bt);
     *out = 0;
     if (!fn) return hipSuccess;
     if (lds_bytes > 48 * 1024) {
@@ -1249,6 +1339,44 @@ hipError_t max_workgroups_per_cu(int hd, int g, int bt, size_t lds_bytes, int *o
         if (e != hipSuccess) return e;
     }
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(out, reinterpret_cast<const void *>(fn), kThreads, lds_bytes);
+}
+
+static hipError_t launch_of(KernelFn fn, const Params &p, size_t lds_bytes, hipStream_t stream)
+{
+    if (!fn) return hipErrorInvalidDeviceFunction;
+    hipLaunchKernelGGL(fn, dim3(p.W), dim3(kThreads), lds_bytes, stream, p);
+    return hipGetLastError();
+}
+
+#if CF_LAYER
+
+hipError_t max_workgroups_per_cu_layer(int hd, int g, int bt, size_t lds_bytes, int *out)
+{
+    return occupancy_of(pick(hd, g, bt), lds_bytes, out);
+}
+
+hipError_t launch_fused_layer(const Params &p, int hd, int g, int bt, size_t lds_bytes, hipStream_t stream)
+{
+    return launch_of(pick(hd, g, bt), p, lds_bytes, stream);
+}
+
+#else
+
+size_t lds_floats(const Params &p, int hd, int g, int bt)
+{
+    const size_t rb = bt < 4 ? bt : 4;
+    const size_t maxi = bt == 1 ? 4 : (bt <= 4 ? 2 : 1);
+    const size_t f1 = (size_t)bt * p.RPS + maxi * kWaves * bt * hd + (size_t)kWaves * bt;
+    const size_t f2 = (size_t)hd + (size_t)(g + 2) * hd + 8 + 2 * (size_t)g * kWaves + (size_t)g * kWaves * hd;
+    const size_t f3 = (size_t)bt * hd + (size_t)kWaves * rb * kOutChunk;
+    size_t f = f1 > f2 ? f1 : f2;
+    return f > f3 ? f : f3;
+}
+
+hipError_t max_workgroups_per_cu(int hd, int g, int bt, size_t lds_bytes, bool layer, int *out)
+{
+    if (layer) return max_workgroups_per_cu_layer(hd, g, bt, lds_bytes, out);
+    return occupancy_of(pick(hd, g, bt), lds_bytes, out);
 }
 
 hipError_t launch_pack(const uint16_t *wqkv, const uint16_t *wo, uint16_t *wqkv_p, uint16_t *wo_p, int D, int nqkv,
@@ -1263,10 +1391,10 @@ hipError_t launch_pack(const uint16_t *wqkv, const uint16_t *wo, uint16_t *wqkv_
 
 hipError_t launch_fused(const Params &p, int hd, int g, int bt, size_t lds_bytes, hipStream_t stream)
 {
-    KernelFn fn = pick(hd, g, bt);
-    if (!fn) return hipErrorInvalidDeviceFunction;
-    hipLaunchKernelGGL(fn, dim3(p.W), dim3(kThreads), lds_bytes, stream, p);
-    return hipGetLastError();
+    if (wants_layer_kernel(p)) return launch_fused_layer(p, hd, g, bt, lds_bytes, stream);
+    return launch_of(pick(hd, g, bt), p, lds_bytes, stream);
 }
+
+#endif  // CF_LAYER
 
 }  // namespace cf

@@ -23,6 +23,7 @@ constexpr int kMaxKvSplits = 64;
 // Everything the fused kernel needs, passed by value.
 struct Params {
     const uint16_t *x, *wqkv, *wo;
+    const uint16_t *gamma;     // [D] RMSNorm weight applied to x in front of the projection, or null: x is used as it is
     uint16_t *kc, *vc, *out;
     // workspace
     unsigned long long *done;  // [workgroups][kCounterStride]: launches that workgroup w has completed
@@ -47,14 +48,24 @@ struct Params {
     int NCH;               // number of 512-column chunks of the output
     int packed;            // weights are in the packed (per-head contiguous) layout of cf_pack_weights
     float qk_scale_log2e;  // log2(e)/sqrt(head_dim)
+    float eps;             // RMSNorm: added to the mean square
+    int residual;          // out = x + block output
     long long spin_ticks;  // wait limit in 100 MHz ticks
 };
 
+// The kernel exists twice: the block alone, and the block with the RMSNorm prologue and the residual epilogue
+// (a translation unit of its own, compiled from the same source with -DCF_LAYER=1, so that the block kernel
+// carries none of that code).
+inline bool wants_layer_kernel(const Params &p) { return p.gamma != nullptr || p.residual != 0; }
 // Launch the variant for (head_dim, group size, batch tile).  Returns a hipError_t.
 hipError_t launch_fused(const Params &p, int head_dim, int group, int batch_tile, size_t lds_bytes,
                         hipStream_t stream);
 // Workgroups of that variant that fit on one CU with `lds_bytes` of LDS each (0 = variant missing).
-hipError_t max_workgroups_per_cu(int head_dim, int group, int batch_tile, size_t lds_bytes, int *out);
+hipError_t max_workgroups_per_cu(int head_dim, int group, int batch_tile, size_t lds_bytes, bool layer, int *out);
+// the same two for the layer kernel (defined by the -DCF_LAYER=1 translation unit; called by the two above)
+hipError_t launch_fused_layer(const Params &p, int head_dim, int group, int batch_tile, size_t lds_bytes,
+                              hipStream_t stream);
+hipError_t max_workgroups_per_cu_layer(int head_dim, int group, int batch_tile, size_t lds_bytes, int *out);
 // LDS floats needed by the three phases for the given plan.
 size_t lds_floats(const Params &p, int head_dim, int group, int batch_tile);
 // XCC id of every workgroup of a W-workgroup launch (host buffer of W ints).
