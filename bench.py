@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # keyed by workload name; None = not measured for that workload.
 MEASURED_TRAFFIC = {
-    # profiles/fused_decode_block_llama2_7b_kv4096_hbm_traffic.md: (100037.2 KiB fetched x 2.0000 + 2096.0 KiB written)
-    "llama2_7b_b1_kv4096": 207020000,
+    # profiles/fused_decode_block_llama2_7b_kv4096_hbm_traffic.md: (100079.5 KiB fetched x 2.0000 + 2088.0 KiB written)
+    "llama2_7b_b1_kv4096": 207100000,
 }
 
 
@@ -230,8 +230,9 @@ def main():
                    "fused_steps": "rmsnorm + block + residual" if args.layer else "block",
                    "plan": plan},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(name),
-                     "algorithmic_bytes": alg_bytes, "kernel": "fused_decode_block"},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if args.layer else MEASURED_TRAFFIC.get(name),
+                     "algorithmic_bytes": alg_bytes,
+                     "kernel": "fused_decode_layer" if args.layer else "fused_decode_block"},
     }
     if args.reps > 1:
         import numpy as np
