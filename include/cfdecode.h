@@ -128,6 +128,21 @@ int cf_decode_layer(cf_handle h, int32_t batch, const void *x, const void *norm_
                     void *out, void *stream);
 
 /*
+ * cf_decode_layer for a batch whose rows have different lengths (continuous batching): row b has row_pos[b]
+ * cached tokens; its query and new key are rotated for position row_pos[b], it attends to its rows
+ * 0 .. row_pos[b] and its new key / value go to row row_pos[b] of its cache slice.  Rows of a batch are
+ * independent in Eq. 1, so this is the block applied row by row with each row's own position.
+ *   row_pos  DEVICE [batch] int32, 4-byte aligned, read by the kernel (it may be written by earlier work on
+ *            `stream`); 0 <= row_pos[b] <= max_pos.  Entries outside that range are clamped into it.
+ *   max_pos  HOST value, an upper bound of the entries, 0 <= max_pos < max_seq: the work is split as for a batch
+ *            with max_pos cached tokens in every row (shorter rows leave their last splits empty).
+ * norm_weight may be NULL and residual 0: then this is the bare block with per-row positions.
+ */
+int cf_decode_layer_rows(cf_handle h, int32_t batch, const void *x, const void *norm_weight, float eps,
+                         int32_t residual, int32_t packed, const void *W_qkv, const void *W_o, void *k_cache,
+                         void *v_cache, const int32_t *row_pos, int32_t max_pos, void *out, void *stream);
+
+/*
  * Wait for `stream` and report whether any kernel launched through this handle
  * gave up on a cross-workgroup wait (CF_ETIMEOUT) since the last cf_status
  * call.  The fused kernel relies on all its workgroups being resident at once

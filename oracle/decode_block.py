@@ -140,6 +140,31 @@ def decode_layer(x, gamma, eps, w_qkv, w_o, k_cache, v_cache, pos, n_q_heads, n_
     return r
 
 
+def decode_rows(x, gamma, eps, w_qkv, w_o, k_cache, v_cache, row_pos, n_q_heads, n_kv_heads,
+                head_dim, rope_base, layer_fn=None, block_fn=None):
+    """A batch whose rows have positions of their own (row b has row_pos[b] cached tokens).
+
+    The rows of a batch do not interact anywhere in Eq. 1, so this is, by definition, the one-row computation
+    applied to every row with that row's position: decode_layer when gamma is given (its `out` then includes
+    the residual), else decode_block.  layer_fn / block_fn let a caller substitute another implementation of
+    those two functions with the same contract (the C oracle).
+    """
+    layer_fn = layer_fn or decode_layer
+    block_fn = block_fn or decode_block
+    x = np.asarray(x)
+    res = None
+    for b in range(x.shape[0]):
+        tail = (w_qkv, w_o, k_cache[b:b + 1], v_cache[b:b + 1], int(row_pos[b]), n_q_heads, n_kv_heads,
+                head_dim, rope_base)
+        r = layer_fn(x[b:b + 1], gamma, eps, *tail) if gamma is not None else block_fn(x[b:b + 1], *tail)
+        if res is None:
+            res = {k: [v] for k, v in r.items()}
+        else:
+            for k, v in r.items():
+                res[k].append(v)
+    return {k: np.concatenate(v, axis=0) for k, v in res.items()}
+
+
 def attention_weights(q_rot_i, K):
     """Softmax weights of one query head over the rows of K (Eq. 1), exposed so
     that tests can check that they are non-negative and sum to one."""

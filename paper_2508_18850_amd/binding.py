@@ -13,7 +13,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("CFDECODE_LIB") or os.path.join(_PKG, "libcfdecode.so")   # override: A/B builds
 _lib = None
 
-EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_packed", "cf_decode_layer", "cf_pack_weights",
+EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_packed", "cf_decode_layer", "cf_decode_layer_rows",
+                    "cf_pack_weights",
                     "cf_packed_sizes", "cf_status", "cf_debug_export",
                     "cf_set_tuning", "cf_get_plan", "cf_algorithmic_bytes", "cf_strerror", "cf_last_hip_error",
                     "cf_team_create", "cf_team_destroy", "cf_team_reduce", "cf_team_gather", "cf_team_status",
@@ -51,6 +52,7 @@ def load_library():
         lib.cf_decode_block.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp]
         lib.cf_decode_block_packed.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp]
         lib.cf_decode_layer.argtypes = [vp, i32, vp, vp, ctypes.c_float, i32, i32, vp, vp, vp, vp, i32, vp, vp]
+        lib.cf_decode_layer_rows.argtypes = [vp, i32, vp, vp, ctypes.c_float, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp]
         lib.cf_pack_weights.argtypes = [vp, vp, vp, vp, vp, vp]
         lib.cf_packed_sizes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_size_t)]
         lib.cf_status.argtypes = [vp, vp]
@@ -71,7 +73,8 @@ def load_library():
         for name in ("cf_team_create", "cf_team_destroy", "cf_team_reduce", "cf_team_gather", "cf_team_status",
                      "cf_team_set_spin_limit"):
             getattr(lib, name).restype = ctypes.c_int
-        for name in ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_packed", "cf_decode_layer", "cf_pack_weights",
+        for name in ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_packed", "cf_decode_layer", "cf_decode_layer_rows",
+                    "cf_pack_weights",
                      "cf_packed_sizes", "cf_status", "cf_debug_export",
                      "cf_set_tuning", "cf_get_plan", "cf_last_hip_error"):
             getattr(lib, name).restype = ctypes.c_int
@@ -127,6 +130,18 @@ class DecodeBlock:
                                        k_cache, v_cache, pos, out, stream)
         if rc != 0:
             self._check(rc)
+
+    def decode_layer_rows(self, batch, x, norm_weight, eps, residual, packed, w_qkv, w_o, k_cache, v_cache, row_pos,
+                          max_pos, out, stream=0):
+        rc = self._lib.cf_decode_layer_rows(self._h, batch, x, norm_weight, eps, int(residual), int(packed), w_qkv, w_o,
+                                            k_cache, v_cache, row_pos, max_pos, out, stream)
+        if rc != 0:
+            self._check(rc)
+
+    def decode_layer_rows_rc(self, batch, x, norm_weight, eps, residual, packed, w_qkv, w_o, k_cache, v_cache, row_pos,
+                             max_pos, out, stream=0) -> int:
+        return int(self._lib.cf_decode_layer_rows(self._h, batch, x, norm_weight, eps, int(residual), int(packed), w_qkv,
+                                                  w_o, k_cache, v_cache, row_pos, max_pos, out, stream))
 
     def decode_layer_rc(self, batch, x, norm_weight, eps, residual, packed, w_qkv, w_o, k_cache, v_cache, pos, out,
                         stream=0) -> int:

@@ -318,9 +318,11 @@ int cf_destroy(cf_handle h)
 
 static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, const void *W_qkv, const void *W_o,
                        void *k_cache, void *v_cache, int32_t pos, void *out, void *stream,
-                       const void *norm_weight = nullptr, float eps = 0.f, int residual = 0)
+                       const void *norm_weight = nullptr, float eps = 0.f, int residual = 0,
+                       const int32_t *row_pos = nullptr)
 {
     if (!h) return CF_EINVAL;
+    if (reinterpret_cast<uintptr_t>(row_pos) & 3u) return CF_EINVAL;
     if ((norm_weight && !aligned16(norm_weight)) || !(eps >= 0.f) || !std::isfinite(eps)) return CF_EINVAL;
     if (norm_weight && h->cfg.d_model > 8 * 2 * cf::kThreads) return CF_EUNSUPPORTED;        // the kernel squares a row with two loads per thread
     if (batch < 1 || batch > h->cfg.max_batch || pos < 0 || pos >= h->cfg.max_seq) return CF_EINVAL;
@@ -339,6 +341,7 @@ static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, co
     p.gamma = static_cast<const uint16_t *>(norm_weight);
     p.eps = eps;
     p.residual = residual != 0;
+    p.row_pos = row_pos;
     p.B = batch;
     p.pos = pos;
     p.packed = packed;
@@ -376,6 +379,15 @@ int cf_decode_layer(cf_handle h, int32_t batch, const void *x, const void *norm_
     if (residual && x == out) return CF_EINVAL;
     return decode_impl(h, packed != 0, batch, x, W_qkv, W_o, k_cache, v_cache, pos, out, stream, norm_weight, eps,
                        residual);
+}
+
+int cf_decode_layer_rows(cf_handle h, int32_t batch, const void *x, const void *norm_weight, float eps, int32_t residual,
+                         int32_t packed, const void *W_qkv, const void *W_o, void *k_cache, void *v_cache,
+                         const int32_t *row_pos, int32_t max_pos, void *out, void *stream)
+{
+    if (!row_pos || (residual && x == out)) return CF_EINVAL;
+    return decode_impl(h, packed != 0, batch, x, W_qkv, W_o, k_cache, v_cache, max_pos, out, stream, norm_weight, eps,
+                       residual, row_pos);
 }
 
 int cf_packed_sizes(cf_handle h, size_t *qkv_bytes, size_t *o_bytes)

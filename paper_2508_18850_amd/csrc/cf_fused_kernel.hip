@@ -37,6 +37,17 @@
 namespace cf {
 namespace {
 
+// CF_LAYER=1 compiles the kernel with the RMSNorm prologue, the residual epilogue and per-row positions
+// (fused_decode_layer); without it none of that code is in the kernel (fused_decode_block).
+#ifndef CF_LAYER
+#define CF_LAYER 0
+#endif
+#if CF_LAYER
+#define CF_KERNEL fused_decode_layer
+#else
+#define CF_KERNEL fused_decode_block
+#endif
+constexpr bool kLayer = CF_LAYER != 0;
 constexpr int NT = kThreads;
 constexpr int NW = kWaves;
 constexpr float kNegBig = -1.0e30f;   // stands for "no score yet"; finite so that differences never give NaN
@@ -196,6 +207,14 @@ __device__ __forceinline__ int qdiv(int n, int d, int sh) { return sh >= 0 ? (n 
 __device__ __forceinline__ int qmod(int n, int d, int sh) { return sh >= 0 ? (n & (d - 1)) : n % d; }
 
 // First weight column of selector `sel` for a team: sel < G query heads, G = key, G+1 = value.
+// Tokens cached for batch row b == index of the row's new token (b is uniform over the workgroup).
+// Values outside 0 .. pos are clamped, so that a bad entry cannot make the kernel leave its buffers.
+__device__ __forceinline__ int row_pos(const Params &p, int b)
+{
+    if (kLayer && p.row_pos) return min(max(__builtin_amdgcn_readfirstlane(p.row_pos[b]), 0), p.pos);
+    return p.pos;
+}
+
 template <int HD, int G>
 __device__ __forceinline__ int qkv_col0(const Params &p, int team, int sel)
 {
@@ -256,17 +275,6 @@ __device__ __forceinline__ void rope_table(int pos, double inv_freq, float *cs, 
 #ifndef CF_STAMPS
 #define CF_STAMPS 0
 #endif
-// CF_LAYER=1 compiles the kernel with the RMSNorm prologue and the residual epilogue (fused_decode_layer);
-// without it none of that code is in the kernel (fused_decode_block).
-#ifndef CF_LAYER
-#define CF_LAYER 0
-#endif
-#if CF_LAYER
-#define CF_KERNEL fused_decode_layer
-#else
-#define CF_KERNEL fused_decode_block
-#endif
-constexpr bool kLayer = CF_LAYER != 0;
 #if CF_STAMPS
 __shared__ unsigned long long s_ts[kStamps];
 #define CF_STAMP(k)                                       \
@@ -279,7 +287,8 @@ __shared__ unsigned long long s_ts[kStamps];
 
 template <int HD, int G, int BT, class NextFn>
 __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member, float *smem,
-                                           float *rope, unsigned long long &launches_out, NextFn &&issue_next)
+                                           float *rope, int rope_pos, unsigned long long &launches_out,
+                                           NextFn &&issue_next)
 {
     constexpr int LPR = HD / 8;
     constexpr int NG = NT / LPR;
@@ -462,7 +471,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     }
     if (BT <= 4 && norm) square_rows(0);
     // cos / sin of this position while the first weights are still on their way
-    rope_table<HD>(p.pos, inv_freq, rope, rope + HD / 2);
+    rope_table<HD>(rope_pos, inv_freq, rope, rope + HD / 2);
     lds_barrier();
     CF_STAMP(2);            // x staged
 
@@ -641,20 +650,22 @@ struct P2Stream {
     static constexpr int LPR = HD / 8;
     static constexpr int NG = NT / LPR;
     static constexpr int U = P2Cfg<G>::U;
-    int t0, t1, iters, grp;
+    int t0, t1, iters, grp, pos;
     uint32_t voff0;
     size_t head;
     Stream K, V;
-    // rows >= pos are outside the buffers: they can never be read.  An inactive stream (a workgroup
-    // without an attention item) has an empty row range: its loads are issued with every lane off.
-    __device__ __forceinline__ P2Stream(const Params &p, int team, int b, int s, bool active = true)
-        : head(((size_t)b * p.nkv + team) * p.max_seq * HD), K(p.kc + head, (uint32_t)p.pos * HD * 2),
-          V(p.vc + head, (uint32_t)p.pos * HD * 2)
+    // `pos_b`: tokens cached for this batch row.  Rows >= pos_b are outside the buffers: they can never be
+    // read.  An inactive stream (a workgroup without an attention item) has an empty row range: its
+    // loads are issued with every lane off.  A row shorter than the longest one of the batch uses the
+    // same split boundaries: its splits past pos_b are empty.
+    __device__ __forceinline__ P2Stream(const Params &p, int team, int b, int s, int pos_b, bool active = true)
+        : pos(pos_b), head(((size_t)b * p.nkv + team) * p.max_seq * HD), K(p.kc + head, (uint32_t)pos_b * HD * 2),
+          V(p.vc + head, (uint32_t)pos_b * HD * 2)
     {
         const int lig = threadIdx.x % LPR;
         grp = threadIdx.x / LPR;
         t0 = active ? s * p.TPS + ((s & 1) ? p.TD : 0) : 0;         // even splits are 2*TD tokens longer
-        t1 = active ? min(t0 + p.TPS + ((s & 1) ? -p.TD : p.TD), p.pos) : 0;
+        t1 = active ? min(t0 + p.TPS + ((s & 1) ? -p.TD : p.TD), pos_b) : 0;
         iters = t1 > t0 ? (t1 - t0 + NG - 1) / NG : 0;
         voff0 = (uint32_t)(grp * HD + lig * 8) * 2;
     }
@@ -877,7 +888,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
             kn[tid + HD / 2] = hi * c + lo * sgn;
         }
         lds_barrier();
-        const size_t row = st.head + (size_t)p.pos * HD;
+        const size_t row = st.head + (size_t)st.pos * HD;
         if (tid < HD)
             p.kc[row + tid] = f2h(kn[tid]);
         else if (tid < 2 * HD)
@@ -1178,12 +1189,12 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
         // The compiler loads each kernel argument shortly before its first use: several dependent
         // round trips to cold memory in a row at the start of every launch.  One word of every 64-byte
         // line of the argument block is read here, all at once, so the later reads hit the scalar cache.
-        static_assert(sizeof(Params) <= 256, "one load per 64-byte line of the argument block below");
+        static_assert(sizeof(Params) > 256 && sizeof(Params) <= 320, "one load per 64-byte line of the argument block below");
         auto ka = __builtin_amdgcn_kernarg_segment_ptr();
-        uint32_t t0, t1, t2, t3;
-        asm volatile("s_load_dword %0, %4, 0x0\n\ts_load_dword %1, %4, 0x40\n\ts_load_dword %2, %4, 0x80\n\t"
-                     "s_load_dword %3, %4, 0xc0\n\ts_waitcnt lgkmcnt(0)"
-                     : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3)
+        uint32_t t0, t1, t2, t3, t4;
+        asm volatile("s_load_dword %0, %5, 0x0\n\ts_load_dword %1, %5, 0x40\n\ts_load_dword %2, %5, 0x80\n\t"
+                     "s_load_dword %3, %5, 0xc0\n\ts_load_dword %4, %5, 0x100\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4)
                      : "s"(ka));
     }
     __shared__ float s_rope[HD];                     // cos / sin of the RoPE angles of this position
@@ -1207,13 +1218,15 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
     const int n3 = G * p.NC3 * p.RS3;                // output-projection items of the team
     KvBuf<G> kv;
     OutTile<HD> tile;
-    P2Stream<HD, G> st2(p, team, member < n2 ? qdiv(member, p.NS, p.sh_ns) : 0, member < n2 ? qmod(member, p.NS, p.sh_ns) : 0,
-                        member < n2);
+    const int b_first = member < n2 ? qdiv(member, p.NS, p.sh_ns) : 0;     // batch row of the first attention item
+    const int pos_first = row_pos(p, b_first);
+    P2Stream<HD, G> st2(p, team, b_first, member < n2 ? qmod(member, p.NS, p.sh_ns) : 0, pos_first, member < n2);
+    int rope_row = b_first;                          // the row whose position the RoPE table in LDS holds
 
     // ---- phase 1 (projection); its last step already starts the K/V stream of phase 2
     EarlyQ eq;
     unsigned long long launch_count;
-    const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, s_rope, launch_count,
+    const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, s_rope, pos_first, launch_count,
                                              [&](int stage) { st2.prefetch(kv, 0); });
     if (member < n2) eq.issue<HD, G>(p, team, qdiv(member, p.NS, p.sh_ns));   // q partials were stored a third of the way into phase 1
     st2.prefetch(kv, 1);
@@ -1237,9 +1250,16 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
     for (int it = member; it < n2; it += p.TS) {
         const bool first = (it == member), final_item = (it + p.TS >= n2);
         if (!first) {
-            st2 = P2Stream<HD, G>(p, team, qdiv(it, p.NS, p.sh_ns), qmod(it, p.NS, p.sh_ns));
+            const int b_it = qdiv(it, p.NS, p.sh_ns);
+            st2 = P2Stream<HD, G>(p, team, b_it, qmod(it, p.NS, p.sh_ns), row_pos(p, b_it));
             st2.prefetch(kv, 0);
             st2.prefetch(kv, 1);
+            if (kLayer && p.row_pos && b_it != rope_row) {
+                // another row, another position: new RoPE table (all reads of the old one lie before the
+                // barriers that end the previous item; the barrier in front of the rotation orders the new one)
+                rope_table<HD>(st2.pos, p.inv_freq[tid < HD / 2 ? tid : 0], s_rope, s_rope + HD / 2);
+                rope_row = b_it;
+            }
         }
         // stage 1: first half of the output-projection tile, stage 2: second half
         p2_item<HD, G>(p, team, qdiv(it, p.NS, p.sh_ns), qmod(it, p.NS, p.sh_ns), stamp, first, st2, kv, eq, smem, s_rope, [&](int stage) {

@@ -23,6 +23,7 @@ constexpr int kMaxKvSplits = 64;
 // Everything the fused kernel needs, passed by value.
 struct Params {
     const uint16_t *x, *wqkv, *wo;
+    const int32_t *row_pos;    // [B] tokens cached for each batch row (at most pos), or null: pos for every row
     const uint16_t *gamma;     // [D] RMSNorm weight applied to x in front of the projection, or null: x is used as it is
     uint16_t *kc, *vc, *out;
     // workspace
@@ -53,10 +54,11 @@ struct Params {
     long long spin_ticks;  // wait limit in 100 MHz ticks
 };
 
-// The kernel exists twice: the block alone, and the block with the RMSNorm prologue and the residual epilogue
+// The kernel exists twice: the block alone, and the block with the RMSNorm prologue, the residual epilogue
+// and per-row positions
 // (a translation unit of its own, compiled from the same source with -DCF_LAYER=1, so that the block kernel
 // carries none of that code).
-inline bool wants_layer_kernel(const Params &p) { return p.gamma != nullptr || p.residual != 0; }
+inline bool wants_layer_kernel(const Params &p) { return p.gamma != nullptr || p.residual != 0 || p.row_pos != nullptr; }
 // Launch the variant for (head_dim, group size, batch tile).  Returns a hipError_t.
 hipError_t launch_fused(const Params &p, int head_dim, int group, int batch_tile, size_t lds_bytes,
                         hipStream_t stream);

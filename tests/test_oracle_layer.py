@@ -99,3 +99,29 @@ def test_c_oracle_layer_matches_numpy_oracle(shape):
     c = c_oracle.decode_layer(x, gamma, 1e-5, w_qkv, w_o, kc, vc, L, nq, nkv, d, 10000.0)
     for key in ("out", "q_rot", "k_rot", "v_new", "attn"):
         assert np.allclose(a[key], c[key], rtol=1e-11, atol=1e-11), key
+
+
+def test_rows_with_equal_positions_are_the_batched_call_and_rows_permute():
+    B, D, nq, nkv, d, L = 3, 32, 4, 2, 8, 6
+    x, gamma, w_qkv, w_o, kc, vc = rand_case(B, D, nq, nkv, d, L)
+    whole = orc.decode_layer(x, gamma, 1e-5, w_qkv, w_o, kc, vc, L, nq, nkv, d, 10000.0)
+    rows = orc.decode_rows(x, gamma, 1e-5, w_qkv, w_o, kc, vc, [L] * B, nq, nkv, d, 10000.0)
+    for key in whole:
+        assert np.allclose(whole[key], rows[key], rtol=1e-13, atol=1e-13), key
+    # rows with positions of their own: each row is the one-row call at its position, wherever it sits in the batch
+    pos = [2, 6, 0]
+    mixed = orc.decode_rows(x, gamma, 1e-5, w_qkv, w_o, kc, vc, pos, nq, nkv, d, 10000.0)
+    perm = [2, 0, 1]
+    again = orc.decode_rows(x[perm], gamma, 1e-5, w_qkv, w_o, kc[perm], vc[perm], [pos[i] for i in perm], nq, nkv, d,
+                            10000.0)
+    for key in mixed:
+        assert np.array_equal(mixed[key][perm], again[key]), key
+    # a row at position 0 attends to its own new token only: out = x + v_new W_o (per KV group) for that row
+    b = 2
+    v = mixed["v_new"][b]                                   # [nkv, d]
+    concat = np.concatenate([v[i // (nq // nkv)] for i in range(nq)])
+    assert np.allclose(mixed["out"][b], x[b].astype(np.float64) + concat @ w_o.astype(np.float64), rtol=1e-12, atol=1e-12)
+    # without gamma it is the bare block per row
+    plain = orc.decode_rows(x, None, 0.0, w_qkv, w_o, kc, vc, pos, nq, nkv, d, 10000.0)
+    one = orc.decode_block(x[1:2], w_qkv, w_o, kc[1:2], vc[1:2], pos[1], nq, nkv, d, 10000.0)
+    assert np.array_equal(plain["out"][1:2], one["out"])
