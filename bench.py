@@ -60,6 +60,9 @@ def parse_args():
     ap.add_argument("--layer", action="store_true",
                     help="time cf_decode_layer (RMSNorm in front of the block and the residual added, in the same kernel) "
                          "instead of the bare block; out then is a second buffer")
+    ap.add_argument("--ragged", action="store_true",
+                    help="rows of different lengths (cf_decode_layer_rows): row b caches a seeded length between kv_len/4 "
+                         "and kv_len, the first row kv_len; the algorithmic bytes count each row's own length")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg")
     return ap.parse_args()
@@ -112,6 +115,13 @@ def main():
     if args.workgroups or args.k_splits or args.kv_splits:
         blk.set_tuning(args.workgroups, args.k_splits, args.kv_splits, 0)
     alg_bytes = algorithmic_bytes(blk.cfg, B, L)
+    row_pos = None
+    if args.ragged:
+        import numpy as np
+        rng = np.random.Generator(np.random.PCG64(7))
+        row_pos = [L] + [int(v) for v in rng.integers(L // 4, L + 1, size=B - 1)]
+        # every row reads its own number of cached K/V rows: replace B * L rows by the sum of the lengths
+        alg_bytes = algorithmic_bytes(blk.cfg, B, 0) + sum(row_pos) * 2 * nkv * d * 2
     layer_bytes = 2 * (D * shape.n_qkv + nq * d * D + 2 * B * nkv * S * d)
     n_layers = args.layers or max(8, -(-3 * 2 ** 30 // layer_bytes))       # >= 3 GiB of distinct buffers
     log("workload %s B=%d L=%d: %.1f MiB algorithmic bytes/step, %d layers (%.2f GiB resident)"
@@ -186,6 +196,14 @@ def main():
             def decode(B_, xp_, w, o, k, v, L_, op_, sh_):
                 blk.decode_layer(B_, xp_, gp, 1e-5, True, not args.row_major, w, o, k, v, L_, op_, sh_)
 
+        if args.ragged:
+            rp = torch.tensor(row_pos, dtype=torch.int32, device=dev)
+            rpp = rp.data_ptr()
+            gp2 = gp if args.layer else 0
+
+            def decode(B_, xp_, w, o, k, v, L_, op_, sh_):
+                blk.decode_layer_rows(B_, xp_, gp2, 1e-5, args.layer, not args.row_major, w, o, k, v, rpp, L_, op_, sh_)
+
         def step(i):
             w, o, k, v = ptrs[i % n_layers]
             decode(B, xp, w, o, k, v, L, op, sh)
@@ -228,11 +246,12 @@ def main():
                    "batch": B, "kv_len": L, "layers_rotated": n_layers,
                    "weight_layout": "row-major" if args.row_major else "packed (per-head blocks, one-time rearrangement)",
                    "fused_steps": "rmsnorm + block + residual" if args.layer else "block",
+                   "row_lengths": row_pos if args.ragged else "all kv_len",
                    "plan": plan},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if args.layer else MEASURED_TRAFFIC.get(name),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.layer or args.ragged) else MEASURED_TRAFFIC.get(name),
                      "algorithmic_bytes": alg_bytes,
-                     "kernel": "fused_decode_layer" if args.layer else "fused_decode_block"},
+                     "kernel": "fused_decode_layer" if (args.layer or args.ragged) else "fused_decode_block"},
     }
     if args.reps > 1:
         import numpy as np

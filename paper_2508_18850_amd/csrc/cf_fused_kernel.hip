@@ -32,6 +32,7 @@
 // flag and goes on, so the kernel always ends.
 #include "cf_params.h"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace cf {
@@ -223,41 +224,45 @@ __device__ __forceinline__ int qkv_col0(const Params &p, int team, int sel)
     return (p.nq + p.nkv + team) * HD;
 }
 
-// cos/sin of pos * inv_freq[i] for i < HD/2, angle and range reduction in fp64.
-template <int HD>
-__device__ __forceinline__ void rope_table(int pos, double inv_freq, float *cs, float *sn)
+// cos and sin of pos * inv_freq, angle and range reduction in fp64.
+__device__ __forceinline__ void rope_cos_sin(int pos, double inv_freq, float &cos_out, float &sin_out)
 {
-    const int i = threadIdx.x;
-    if (i < HD / 2) {
-        const double ang = (double)pos * inv_freq;
-        const double k = rint(ang * 0.63661977236758134308);              // 2/pi
-        double r = fma(-k, 1.57079632679489655800e+00, ang);              // pi/2, high part
-        r = fma(-k, 6.12323399573676603587e-17, r);                       // pi/2, low part
-        const double r2 = r * r;                                          // |r| <= pi/4: Taylor series
-        double s = -1.0 / 1307674368000.0;
-        s = fma(s, r2, 1.0 / 6227020800.0);
-        s = fma(s, r2, -1.0 / 39916800.0);
-        s = fma(s, r2, 1.0 / 362880.0);
-        s = fma(s, r2, -1.0 / 5040.0);
-        s = fma(s, r2, 1.0 / 120.0);
-        s = fma(s, r2, -1.0 / 6.0);
-        s = fma(s * r2, r, r);
-        double c = 1.0 / 20922789888000.0;
-        c = fma(c, r2, -1.0 / 87178291200.0);
-        c = fma(c, r2, 1.0 / 479001600.0);
-        c = fma(c, r2, -1.0 / 3628800.0);
-        c = fma(c, r2, 1.0 / 40320.0);
-        c = fma(c, r2, -1.0 / 720.0);
-        c = fma(c, r2, 1.0 / 24.0);
-        c = fma(c, r2, -0.5);
-        c = fma(c, r2, 1.0);
-        const int q = (int)((long long)k & 3);
-        const double sv = (q == 0) ? s : (q == 1) ? c : (q == 2) ? -s : -c;
-        const double cv = (q == 0) ? c : (q == 1) ? -s : (q == 2) ? -c : s;
-        cs[i] = (float)cv;
-        sn[i] = (float)sv;
-    }
+    const double ang = (double)pos * inv_freq;
+    const double k = rint(ang * 0.63661977236758134308);              // 2/pi
+    double r = fma(-k, 1.57079632679489655800e+00, ang);              // pi/2, high part
+    r = fma(-k, 6.12323399573676603587e-17, r);                       // pi/2, low part
+    const double r2 = r * r;                                          // |r| <= pi/4: Taylor series
+    double s = -1.0 / 1307674368000.0;
+    s = fma(s, r2, 1.0 / 6227020800.0);
+    s = fma(s, r2, -1.0 / 39916800.0);
+    s = fma(s, r2, 1.0 / 362880.0);
+    s = fma(s, r2, -1.0 / 5040.0);
+    s = fma(s, r2, 1.0 / 120.0);
+    s = fma(s, r2, -1.0 / 6.0);
+    s = fma(s * r2, r, r);
+    double c = 1.0 / 20922789888000.0;
+    c = fma(c, r2, -1.0 / 87178291200.0);
+    c = fma(c, r2, 1.0 / 479001600.0);
+    c = fma(c, r2, -1.0 / 3628800.0);
+    c = fma(c, r2, 1.0 / 40320.0);
+    c = fma(c, r2, -1.0 / 720.0);
+    c = fma(c, r2, 1.0 / 24.0);
+    c = fma(c, r2, -0.5);
+    c = fma(c, r2, 1.0);
+    const int q = (int)((long long)k & 3);
+    const double sv = (q == 0) ? s : (q == 1) ? c : (q == 2) ? -s : -c;
+    const double cv = (q == 0) ? c : (q == 1) ? -s : (q == 2) ? -c : s;
+    cos_out = (float)cv;
+    sin_out = (float)sv;
 }
+
+// The RoPE tables in LDS: [rows][HD] floats, per row HD/2 cosines then HD/2 sines of that row's position.
+// One row (the common position) unless the rows of the batch have positions of their own.
+template <int HD, int BT>
+struct RopeRows {
+    static constexpr int ROWS = kLayer ? BT : 1;                      // rows the LDS array has room for
+    static constexpr int NE = (ROWS * (HD / 2) + NT - 1) / NT;        // table entries per thread
+};
 
 // ---------------------------------------------------------------------------
 // Phase 1 (Alg. 3 step 2, split over the reduction dimension).  The member owns the
@@ -287,8 +292,7 @@ __shared__ unsigned long long s_ts[kStamps];
 
 template <int HD, int G, int BT, class NextFn>
 __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member, float *smem,
-                                           float *rope, int rope_pos, unsigned long long &launches_out,
-                                           NextFn &&issue_next)
+                                           float *rope, unsigned long long &launches_out, NextFn &&issue_next)
 {
     constexpr int LPR = HD / 8;
     constexpr int NG = NT / LPR;
@@ -431,7 +435,18 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
             ok[r][k] = false;
         }
     if (BT <= 4 && norm) load_rows(0);
-    const double inv_freq = p.inv_freq[tid < HD / 2 ? tid : 0];   // for the RoPE table, below
+    // for the RoPE tables, below: the frequency and the position of every table entry of this thread
+    constexpr int NE = RopeRows<HD, BT>::NE;
+    const bool own_pos = kLayer && p.row_pos != nullptr;
+    const int32_t *psrc = own_pos ? p.row_pos : reinterpret_cast<const int32_t *>(p.inv_freq);   // any readable address
+    double inv_freq[NE];
+    int epos[NE];
+#pragma unroll
+    for (int k = 0; k < NE; ++k) {
+        const int e = tid + k * NT, eb = e / (HD / 2);
+        inv_freq[k] = p.inv_freq[e % (HD / 2)];
+        epos[k] = psrc[own_pos && eb < p.B ? eb : 0];
+    }
     __builtin_amdgcn_sched_barrier(0);
     load(wb, voff0);
     __builtin_amdgcn_sched_barrier(0);
@@ -471,7 +486,14 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     }
     if (BT <= 4 && norm) square_rows(0);
     // cos / sin of this position while the first weights are still on their way
-    rope_table<HD>(rope_pos, inv_freq, rope, rope + HD / 2);
+#pragma unroll
+    for (int k = 0; k < NE; ++k) {
+        const int e = tid + k * NT, eb = e / (HD / 2), i = e % (HD / 2);
+        if (eb < (own_pos ? p.B : 1)) {
+            const int pos_e = own_pos ? min(max(epos[k], 0), p.pos) : p.pos;
+            rope_cos_sin(pos_e, inv_freq[k], rope[eb * HD + i], rope[eb * HD + HD / 2 + i]);
+        }
+    }
     lds_barrier();
     CF_STAMP(2);            // x staged
 
@@ -1197,7 +1219,7 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
                      : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4)
                      : "s"(ka));
     }
-    __shared__ float s_rope[HD];                     // cos / sin of the RoPE angles of this position
+    __shared__ float s_rope[RopeRows<HD, BT>::ROWS * HD];    // cos / sin of the RoPE angles, per row if the rows differ
     const int tid = threadIdx.x;
     // Workgroup w runs on die (XCD) w % 8, and the odd dies get about a tenth less memory
     // bandwidth than the even ones.  With pairmap a team sits on one pair of dies, members with an
@@ -1220,14 +1242,20 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
     OutTile<HD> tile;
     const int b_first = member < n2 ? qdiv(member, p.NS, p.sh_ns) : 0;     // batch row of the first attention item
     const int pos_first = row_pos(p, b_first);
-    P2Stream<HD, G> st2(p, team, b_first, member < n2 ? qmod(member, p.NS, p.sh_ns) : 0, pos_first, member < n2);
-    int rope_row = b_first;                          // the row whose position the RoPE table in LDS holds
+    const int s_first = member < n2 ? qmod(member, p.NS, p.sh_ns) : 0;
+    // (with positions per row the stream is set up only where phase 1 first needs it: the position comes from
+    // memory, and waiting for it here would hold up the first weight loads)
+    const bool own_pos = kLayer && p.row_pos != nullptr;
+    P2Stream<HD, G> st2(p, team, b_first, s_first, own_pos ? 0 : p.pos, member < n2 && !own_pos);
 
     // ---- phase 1 (projection); its last step already starts the K/V stream of phase 2
     EarlyQ eq;
     unsigned long long launch_count;
-    const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, s_rope, pos_first, launch_count,
-                                             [&](int stage) { st2.prefetch(kv, 0); });
+    const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, s_rope, launch_count,
+                                             [&](int stage) {
+                                                 if (own_pos) st2 = P2Stream<HD, G>(p, team, b_first, s_first, pos_first, member < n2);
+                                                 st2.prefetch(kv, 0);
+                                             });
     if (member < n2) eq.issue<HD, G>(p, team, qdiv(member, p.NS, p.sh_ns));   // q partials were stored a third of the way into phase 1
     st2.prefetch(kv, 1);
     CF_STAMP(1);
@@ -1254,15 +1282,10 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
             st2 = P2Stream<HD, G>(p, team, b_it, qmod(it, p.NS, p.sh_ns), row_pos(p, b_it));
             st2.prefetch(kv, 0);
             st2.prefetch(kv, 1);
-            if (kLayer && p.row_pos && b_it != rope_row) {
-                // another row, another position: new RoPE table (all reads of the old one lie before the
-                // barriers that end the previous item; the barrier in front of the rotation orders the new one)
-                rope_table<HD>(st2.pos, p.inv_freq[tid < HD / 2 ? tid : 0], s_rope, s_rope + HD / 2);
-                rope_row = b_it;
-            }
         }
         // stage 1: first half of the output-projection tile, stage 2: second half
-        p2_item<HD, G>(p, team, qdiv(it, p.NS, p.sh_ns), qmod(it, p.NS, p.sh_ns), stamp, first, st2, kv, eq, smem, s_rope, [&](int stage) {
+        p2_item<HD, G>(p, team, qdiv(it, p.NS, p.sh_ns), qmod(it, p.NS, p.sh_ns), stamp, first, st2, kv, eq, smem,
+                       s_rope + (kLayer && p.row_pos ? qdiv(it, p.NS, p.sh_ns) * HD : 0), [&](int stage) {
             if (final_item) p3_prefetch(stage - 1);
         });
     }
@@ -1381,6 +1404,17 @@ hipError_t launch_fused_layer(const Params &p, int hd, int g, int bt, size_t lds
 }
 
 #else
+
+bool wants_layer_kernel(const Params &p)
+{
+    // CF_FORCE_LAYER_KERNEL=1 (read once): the layer kernel also for calls that need none of its steps, to
+    // compare the two builds on the same work
+    static const bool force = [] {
+        const char *e = getenv("CF_FORCE_LAYER_KERNEL");
+        return e && *e == '1';
+    }();
+    return force || p.gamma != nullptr || p.residual != 0 || p.row_pos != nullptr;
+}
 
 size_t lds_floats(const Params &p, int hd, int g, int bt)
 {

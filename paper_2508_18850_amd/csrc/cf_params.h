@@ -58,7 +58,7 @@ struct Params {
 // and per-row positions
 // (a translation unit of its own, compiled from the same source with -DCF_LAYER=1, so that the block kernel
 // carries none of that code).
-inline bool wants_layer_kernel(const Params &p) { return p.gamma != nullptr || p.residual != 0 || p.row_pos != nullptr; }
+bool wants_layer_kernel(const Params &p);
 // Launch the variant for (head_dim, group size, batch tile).  Returns a hipError_t.
 hipError_t launch_fused(const Params &p, int head_dim, int group, int batch_tile, size_t lds_bytes,
                         hipStream_t stream);
