@@ -60,6 +60,9 @@ def parse_args():
     ap.add_argument("--layer", action="store_true",
                     help="time cf_decode_layer (RMSNorm in front of the block and the residual added, in the same kernel) "
                          "instead of the bare block; out then is a second buffer")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one pass over the rotating layers in a HIP graph and time replays of it instead of "
+                         "stream launches (steps is rounded down to a multiple of the layer count)")
     ap.add_argument("--ragged", action="store_true",
                     help="rows of different lengths (cf_decode_layer_rows): row b caches a seeded length between kv_len/4 "
                          "and kv_len, the first row kv_len; the algorithmic bytes count each row's own length")
@@ -211,12 +214,32 @@ def main():
         for i in range(args.warmup):
             step(i)
         blk.status(sh)
+        if args.graph:
+            # one pass over the layers becomes one graph launch; a timed "step" still is one kernel
+            args.steps = max(1, args.steps // n_layers) * n_layers
+            graph = torch.cuda.CUDAGraph()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=stream):
+                csh = torch.cuda.current_stream().cuda_stream
+                for i in range(n_layers):
+                    w, o, k, v = ptrs[i]
+                    decode(B, xp, w, o, k, v, L, op, csh)
+            n_replays = args.steps // n_layers
+            graph.replay()
+            torch.cuda.synchronize()
+
+            def timed_region(first_step):
+                for _ in range(n_replays):
+                    graph.replay()
+        else:
+            def timed_region(first_step):
+                for i in range(args.steps):
+                    step(first_step + i)
         # timed region: exactly `steps` launches between two events on the launch stream
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         ev0.record(stream)
-        for i in range(args.steps):
-            step(args.warmup + i)
+        timed_region(args.warmup)
         ev1.record(stream)
         torch.cuda.synchronize()
         blk.status(sh)
@@ -225,8 +248,7 @@ def main():
         for r in range(1, args.reps):
             ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             ea.record(stream)
-            for i in range(args.steps):
-                step(args.warmup + r * args.steps + i)
+            timed_region(args.warmup + r * args.steps)
             eb.record(stream)
             torch.cuda.synchronize()
             rep_us.append(ea.elapsed_time(eb) / args.steps * 1e3)
@@ -245,6 +267,7 @@ def main():
         "config": {"workload": name, "d_model": D, "n_q_heads": nq, "n_kv_heads": nkv, "head_dim": d,
                    "batch": B, "kv_len": L, "layers_rotated": n_layers,
                    "weight_layout": "row-major" if args.row_major else "packed (per-head blocks, one-time rearrangement)",
+                   "launch": "graph replay of one pass over the layers" if args.graph else "stream launches",
                    "fused_steps": "rmsnorm + block + residual" if args.layer else "block",
                    "row_lengths": row_pos if args.ragged else "all kv_len",
                    "plan": plan},
