@@ -183,7 +183,7 @@ void fill_static(const cf_handle_s *h, Params *p)
     p->max_seq = c.max_seq;
     p->nqkv = h->nqkv;
     p->qk_scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)c.head_dim));
-    p->spin_ticks = h->spin_ticks;
+    p->spin_ticks = (uint32_t)(h->spin_ticks > 0xffffffffLL ? 0xffffffffLL : h->spin_ticks);
 }
 
 int hip_fail(cf_handle_s *h, hipError_t e)
@@ -340,11 +340,10 @@ static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, co
     p.out = static_cast<uint16_t *>(out);
     p.gamma = static_cast<const uint16_t *>(norm_weight);
     p.eps = eps;
-    p.residual = residual != 0;
     p.row_pos = row_pos;
     p.B = batch;
     p.pos = pos;
-    p.packed = packed;
+    p.flags = (packed ? cf::kFlagPacked : 0) | (residual ? cf::kFlagResidual : 0);
     int rc = make_plan(h, batch, pos, &p);
     if (rc != CF_OK) return rc;
     const int bt = batch_tile(batch);

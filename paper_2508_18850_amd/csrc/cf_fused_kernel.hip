@@ -160,7 +160,7 @@ struct Spin {
         __builtin_amdgcn_s_sleep(1);
         const long long now = wall_clock64();
         if (t0 == 0) t0 = now;
-        if (now - t0 > p.spin_ticks) {
+        if (now - t0 > (long long)p.spin_ticks) {
             __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return true;
         }
@@ -315,10 +315,10 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     float *red = smem + BT * p.RPS;         // [MAXI][NW][BT][HD]
     const Xbuf x1(p.p1);
     const uint32_t blkb = (uint32_t)p.D * HD * 2 + kQkvBlockPad;          // packed: bytes from one block to the next
-    const Stream W(p.wqkv, p.packed ? (uint32_t)(p.nqkv / HD) * blkb : (uint32_t)((size_t)p.D * p.nqkv * 2));
+    const Stream W(p.wqkv, (p.flags & kFlagPacked) ? (uint32_t)(p.nqkv / HD) * blkb : (uint32_t)((size_t)p.D * p.nqkv * 2));
     // row-major [D][Nqkv]: rows are Nqkv*2 bytes apart and a selector starts at column col0;
     // packed [Nqkv/HD][D][HD] (+ pad): rows are HD*2 bytes apart and a selector is one contiguous block
-    const uint32_t rowb = p.packed ? (uint32_t)HD * 2 : (uint32_t)p.nqkv * 2;
+    const uint32_t rowb = (p.flags & kFlagPacked) ? (uint32_t)HD * 2 : (uint32_t)p.nqkv * 2;
     const uint32_t voff0 = (uint32_t)grp * rowb + lig * 16;
 
     // A step is (selector, batch of U row groups).  Steps are loaded and consumed strictly in order,
@@ -331,7 +331,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     };
     auto blk_base = [&](int si) {
         const uint32_t col0 = (uint32_t)qkv_col0<HD, G>(p, team, sel_of(si));
-        return (uint32_t)r0 * rowb + (p.packed ? (col0 / HD) * blkb : col0 * 2);
+        return (uint32_t)r0 * rowb + ((p.flags & kFlagPacked) ? (col0 / HD) * blkb : col0 * 2);
     };
     auto advance = [&](Cursor &c) {
         c.i0 += U;
@@ -444,7 +444,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
 #pragma unroll
     for (int k = 0; k < NE; ++k) {
         const int e = tid + k * NT, eb = e / (HD / 2);
-        inv_freq[k] = p.inv_freq[e % (HD / 2)];
+        inv_freq[k] = p.inv_freq[kLayer ? e % (HD / 2) : (e < HD / 2 ? e : 0)];
         epos[k] = psrc[own_pos && eb < p.B ? eb : 0];
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -565,7 +565,9 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
 #pragma unroll
                 for (int j = 0; j < 8; ++j) acc[b][j] = 0.f;
             if (nbuf == 0) si_first = si;           // buffered items are consecutive selectors
-            if (++nbuf == MAXI || si == nA - 1) flush();   // q partials leave as early as possible
+            // (flushing as soon as the q heads are done, so that q leaves early, was measured: the two extra
+            // barriers in the middle of the stream cost more than the early q gains)
+            if (++nbuf == MAXI) flush();
         }
     };
 
@@ -613,10 +615,10 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
 // (Alg. 3 steps 3-4; the new token is counted by the last split only).
 // K/V rows are streamed in batches of U rows per row group, two batches in flight.
 // ---------------------------------------------------------------------------
-// The q partials of the team are stored a third of the way into phase 1.  Their loads are put in
-// flight early (before the K/V stream, at the end of phase 1) and checked when q is needed, so the
-// sum costs no round trip in front of the attention loop.  Covers value e = threadIdx.x and the
-// first kEarly k-slices; anything else takes the polling path.
+// The loads of the team's q partials are put in flight right behind this workgroup's own partial sums
+// (at the end of phase 1, before the second part of the K/V prefetch) and checked when q is needed:
+// where the other members were no later than this one, the sum costs no further round trip.  Covers
+// value e = threadIdx.x and the first kEarly k-slices; anything else takes the polling path.
 constexpr int kEarly = 16;
 struct EarlyQ {
     u32x2 v[kEarly];
@@ -976,13 +978,13 @@ __device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs,
 {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     // row-major [nq*HD][D], or packed [nq][ceil(D/512)][HD][512] (one contiguous tile per head and chunk)
-    const Stream Wo(p.wo, p.packed ? (uint32_t)((size_t)p.nq * p.NCH * HD * kOutChunk * 2)
+    const Stream Wo(p.wo, (p.flags & kFlagPacked) ? (uint32_t)((size_t)p.nq * p.NCH * HD * kOutChunk * 2)
                                    : (uint32_t)((size_t)p.nq * HD * p.D * 2));
     const int nrows = HD / p.RS3;
     const int cbase = c3 * p.CW3 + ch * kOutChunk;
-    const uint32_t rowb = p.packed ? (uint32_t)kOutChunk * 2 : (uint32_t)p.D * 2;
+    const uint32_t rowb = (p.flags & kFlagPacked) ? (uint32_t)kOutChunk * 2 : (uint32_t)p.D * 2;
     const uint32_t voff = (cbase + lane * 8) < p.D ? (uint32_t)wv * rowb + lane * 16 : kNoLoad;
-    const uint32_t sbase = p.packed ? (uint32_t)((hq * p.NCH + cbase / kOutChunk) * HD + rs * nrows) * rowb
+    const uint32_t sbase = (p.flags & kFlagPacked) ? (uint32_t)((hq * p.NCH + cbase / kOutChunk) * HD + rs * nrows) * rowb
                                     : (uint32_t)(hq * HD + rs * nrows) * rowb + (uint32_t)cbase * 2;
     const int iters = nrows / NW;
 #pragma unroll
@@ -1161,7 +1163,7 @@ __device__ __forceinline__ uint16_t residual_input(const Params &p, int v0)
     const int ncol = min(cpw, p.D - c0);
     const int i = v0 + (int)threadIdx.x;
     uint16_t r = 0;
-    if (kLayer && p.residual && ncol > 0 && i < ncol * p.B) {
+    if (kLayer && (p.flags & kFlagResidual) && ncol > 0 && i < ncol * p.B) {
         const int b = i / ncol, c = i - b * ncol;
         r = p.x[(size_t)b * p.D + c0 + c];
     }
@@ -1195,7 +1197,7 @@ __device__ __forceinline__ void final_reduce(const Params &p, uint32_t stamp, fl
         CF_STAMP(19);           // head partials arrived
         lds_barrier();
         if (tid < cb) {
-            float sum = kLayer && p.residual ? h2f(xres) : 0.f;
+            float sum = kLayer && (p.flags & kFlagResidual) ? h2f(xres) : 0.f;
             for (int k = 0; k < spt; ++k) sum += smem[k * cb + tid];
             p.out[(size_t)b * p.D + c0 + c] = f2h(sum);
         }
@@ -1211,12 +1213,12 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
         // The compiler loads each kernel argument shortly before its first use: several dependent
         // round trips to cold memory in a row at the start of every launch.  One word of every 64-byte
         // line of the argument block is read here, all at once, so the later reads hit the scalar cache.
-        static_assert(sizeof(Params) > 256 && sizeof(Params) <= 320, "one load per 64-byte line of the argument block below");
+        static_assert(sizeof(Params) <= 256, "one load per 64-byte line of the argument block below");
         auto ka = __builtin_amdgcn_kernarg_segment_ptr();
-        uint32_t t0, t1, t2, t3, t4;
-        asm volatile("s_load_dword %0, %5, 0x0\n\ts_load_dword %1, %5, 0x40\n\ts_load_dword %2, %5, 0x80\n\t"
-                     "s_load_dword %3, %5, 0xc0\n\ts_load_dword %4, %5, 0x100\n\ts_waitcnt lgkmcnt(0)"
-                     : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4)
+        uint32_t t0, t1, t2, t3;
+        asm volatile("s_load_dword %0, %4, 0x0\n\ts_load_dword %1, %4, 0x40\n\ts_load_dword %2, %4, 0x80\n\t"
+                     "s_load_dword %3, %4, 0xc0\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3)
                      : "s"(ka));
     }
     __shared__ float s_rope[RopeRows<HD, BT>::ROWS * HD];    // cos / sin of the RoPE angles, per row if the rows differ
@@ -1256,7 +1258,7 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
                                                  if (own_pos) st2 = P2Stream<HD, G>(p, team, b_first, s_first, pos_first, member < n2);
                                                  st2.prefetch(kv, 0);
                                              });
-    if (member < n2) eq.issue<HD, G>(p, team, qdiv(member, p.NS, p.sh_ns));   // q partials were stored a third of the way into phase 1
+    if (member < n2) eq.issue<HD, G>(p, team, qdiv(member, p.NS, p.sh_ns));   // a first look at the team's q partials
     st2.prefetch(kv, 1);
     CF_STAMP(1);
     // ---- phase 2 (attention); the last item already starts the W_o stream of phase 3
@@ -1413,7 +1415,7 @@ bool wants_layer_kernel(const Params &p)
         const char *e = getenv("CF_FORCE_LAYER_KERNEL");
         return e && *e == '1';
     }();
-    return force || p.gamma != nullptr || p.residual != 0 || p.row_pos != nullptr;
+    return force || p.gamma != nullptr || (p.flags & kFlagResidual) != 0 || p.row_pos != nullptr;
 }
 
 size_t lds_floats(const Params &p, int hd, int g, int bt)

@@ -20,7 +20,10 @@ constexpr int kCounterStride = 16;   // 64-bit words between the launch counters
 constexpr int kMaxKSplits = 64;
 constexpr int kMaxKvSplits = 64;
 
-// Everything the fused kernel needs, passed by value.
+constexpr int kFlagPacked = 1;     // weights are in the packed (per-head contiguous) layout of cf_pack_weights
+constexpr int kFlagResidual = 2;   // out = x + block output
+
+// Everything the fused kernel needs, passed by value (256 bytes: four 64-byte lines, fetched together at kernel start).
 struct Params {
     const uint16_t *x, *wqkv, *wo;
     const int32_t *row_pos;    // [B] tokens cached for each batch row (at most pos), or null: pos for every row
@@ -47,11 +50,10 @@ struct Params {
     int NS, TPS;           // attention: splits of the cached sequence, tokens per split
     int NC3, CW3, RS3;     // output projection: column blocks, columns per block, row splits per head
     int NCH;               // number of 512-column chunks of the output
-    int packed;            // weights are in the packed (per-head contiguous) layout of cf_pack_weights
+    int flags;             // kFlagPacked, kFlagResidual
     float qk_scale_log2e;  // log2(e)/sqrt(head_dim)
     float eps;             // RMSNorm: added to the mean square
-    int residual;          // out = x + block output
-    long long spin_ticks;  // wait limit in 100 MHz ticks
+    uint32_t spin_ticks;   // wait limit in 100 MHz ticks (at most 42 s)
 };
 
 // The kernel exists twice: the block alone, and the block with the RMSNorm prologue, the residual epilogue
