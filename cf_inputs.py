@@ -79,3 +79,50 @@ def make_inputs(shape: BlockShape, seed: int, batch: int | None = None, kv_len: 
         v_cache[:, :, :L, :] = normal((B, nkv, L, d), 1.0)
     return {"x": x, "w_qkv": w_qkv, "w_o": w_o, "k_cache": k_cache, "v_cache": v_cache,
             "pos": L, "batch": B, "max_seq": S, "shape": shape}
+
+
+# ---------------------------------------------------------------------------------------------------
+# Multi-Head Latent Attention block (weight-absorbed form), DeepSeek-V2-Lite-shaped
+# ---------------------------------------------------------------------------------------------------
+
+@dataclass(frozen=True)
+class MlaShape:
+    name: str
+    d_model: int
+    n_heads: int
+    nope_dim: int
+    rope_dim: int
+    kv_lora_rank: int
+    v_head_dim: int
+    rope_base: float
+    kv_len: int
+    batch: int = 1
+
+
+MLA_SHAPES = {
+    # the model the paper measures its fused MLA block on (hidden 2048, 16 heads, 128 + 64 query dimensions,
+    # latent rank 512, value dimension 128); sequence length as in the paper's sweeps
+    "deepseek_v2_lite": MlaShape("deepseek_v2_lite", 2048, 16, 128, 64, 512, 128, 10000.0, 4096),
+}
+
+
+def make_mla_inputs(shape: MlaShape, seed: int, batch: int | None = None, kv_len: int | None = None,
+                    poison: bool = True) -> dict:
+    """Seeded fp16 inputs of one MLA layer: unit-variance activations and cached rows, weights scaled by
+    1/sqrt(fan-in) so that every intermediate stays of order one."""
+    B = shape.batch if batch is None else int(batch)
+    Lk = shape.kv_len if kv_len is None else int(kv_len)
+    S = default_max_seq(Lk)
+    rng = np.random.Generator(np.random.PCG64(seed))
+
+    def normal(shp, std):
+        return (rng.standard_normal(size=shp, dtype=np.float32) * np.float32(std)).astype(np.float16)
+
+    D, nh, n, r, l, v = shape.d_model, shape.n_heads, shape.nope_dim, shape.rope_dim, shape.kv_lora_rank, shape.v_head_dim
+    cache = np.full((B, S, l + r), np.float16(np.nan) if poison else np.float16(0.0), dtype=np.float16)
+    if Lk > 0:
+        cache[:, :Lk] = normal((B, Lk, l + r), 1.0)
+    return {"x": normal((B, D), 1.0), "w_q": normal((D, nh * (n + r)), D ** -0.5), "w_kv": normal((D, l + r), D ** -0.5),
+            "w_up": normal((nh, n, l), n ** -0.5), "w_down": normal((nh, l, v), l ** -0.5),
+            "w_o": normal((nh * v, D), (nh * v) ** -0.5), "kv_cache": cache, "pos": Lk, "batch": B, "max_seq": S,
+            "shape": shape}

@@ -241,6 +241,42 @@ int cf_team_gather(cf_team t, int32_t teams, int32_t team_size, const float *in,
 int cf_team_status(cf_team t, void *stream);
 int cf_team_set_spin_limit(cf_team t, int32_t spin_limit_us);
 
+/* ------------------------------------------------------------------------------------------------
+ * Fused decode step of a Multi-Head Latent Attention block in its weight-absorbed form (paper Appendix B:
+ * Q = Hidden W_Q W_Up, K = Hidden W_K, V = K[:kv_lora_rank]; Alg. 4), one kernel:
+ *
+ *   q_i = x W_Q[:, head i] -> (q_nope_i [nope_dim] | q_rope_i [rope_dim]);   kv_new = x W_KV -> (c_new | k_rope_new)
+ *   q_rope_i, k_rope_new <- RoPE at position pos (pairs (d, d + rope_dim/2), angle pos * rope_base^(-2d/rope_dim))
+ *   kv_cache[b, pos, :] = fp16(c_new | k_rope_new)                            one latent row shared by all heads
+ *   q_lat_i = q_nope_i W_Up[i];   s_i = ((q_lat_i | q_rope_i) . K^T) / sqrt(nope_dim + rope_dim)  over rows 0..pos
+ *   z_i = softmax(s_i) . K[:, :kv_lora_rank];   a_i = z_i W_Down[i];   out = concat_i(a_i) W_O
+ *
+ * All pointers are DEVICE pointers to fp16 (IEEE binary16), 16-byte aligned, row-major; the caller owns them:
+ *   x [batch, d_model]; W_q [d_model, n_heads * (nope_dim + rope_dim)] (per head: nope part, rope part);
+ *   W_kv [d_model, kv_lora_rank + rope_dim]; W_up [n_heads, nope_dim, kv_lora_rank];
+ *   W_down [n_heads, kv_lora_rank, v_head_dim]; W_o [n_heads * v_head_dim, d_model];
+ *   kv_cache [batch, max_seq, kv_lora_rank + rope_dim]: rows < pos read, row pos written; out [batch, d_model].
+ * Storage fp16, accumulation fp32.  Asynchronous on `stream`; no allocation, no host synchronisation.
+ * This first kernel is written for kv_lora_rank 512, rope_dim 64, n_heads <= 16 (16 workgroups per head, all
+ * resident), batch <= 4, v_head_dim a multiple of 16 up to 128, d_model a multiple of 32 up to 8192 and at most
+ * 128 * n_heads: cf_mla_create returns CF_EUNSUPPORTED otherwise.  cf_mla_status is cf_status for this handle.
+ */
+typedef struct cf_mla_config {
+    int32_t d_model, n_heads, nope_dim, rope_dim, kv_lora_rank, v_head_dim;
+    int32_t max_batch, max_seq;
+    float rope_base;
+} cf_mla_config;
+typedef struct cf_mla_s *cf_mla;
+
+int cf_mla_create(const cf_mla_config *cfg, cf_mla *out);
+int cf_mla_destroy(cf_mla t);
+int cf_mla_decode(cf_mla t, int32_t batch, const void *x, const void *W_q, const void *W_kv, const void *W_up,
+                  const void *W_down, const void *W_o, void *kv_cache, int32_t pos, void *out, void *stream);
+int cf_mla_status(cf_mla t, void *stream);
+int cf_mla_set_spin_limit(cf_mla t, int32_t spin_limit_us);
+/* Algorithmic HBM bytes of one call (all weights + cached rows + appended rows + x + out). */
+int64_t cf_mla_algorithmic_bytes(const cf_mla_config *cfg, int32_t batch, int32_t pos);
+
 #ifdef __cplusplus
 }
 #endif

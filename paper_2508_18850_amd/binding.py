@@ -18,7 +18,9 @@ EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_blo
                     "cf_packed_sizes", "cf_status", "cf_debug_export",
                     "cf_set_tuning", "cf_get_plan", "cf_algorithmic_bytes", "cf_strerror", "cf_last_hip_error",
                     "cf_team_create", "cf_team_destroy", "cf_team_reduce", "cf_team_gather", "cf_team_status",
-                    "cf_team_set_spin_limit")
+                    "cf_team_set_spin_limit",
+                    "cf_mla_create", "cf_mla_destroy", "cf_mla_decode", "cf_mla_status", "cf_mla_set_spin_limit",
+                    "cf_mla_algorithmic_bytes")
 
 CF_FLAG_DEBUG_EXPORT = 1
 
@@ -27,6 +29,12 @@ class CfConfig(ctypes.Structure):
     _fields_ = [("d_model", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("max_batch", ctypes.c_int32), ("max_seq", ctypes.c_int32),
                 ("rope_base", ctypes.c_float), ("flags", ctypes.c_int32)]
+
+
+class MlaConfig(ctypes.Structure):
+    _fields_ = [("d_model", ctypes.c_int32), ("n_heads", ctypes.c_int32), ("nope_dim", ctypes.c_int32),
+                ("rope_dim", ctypes.c_int32), ("kv_lora_rank", ctypes.c_int32), ("v_head_dim", ctypes.c_int32),
+                ("max_batch", ctypes.c_int32), ("max_seq", ctypes.c_int32), ("rope_base", ctypes.c_float)]
 
 
 class CfError(RuntimeError):
@@ -70,8 +78,17 @@ def load_library():
         lib.cf_team_gather.argtypes = [vp, i32, i32, vp, vp, ctypes.c_size_t, i32, vp]
         lib.cf_team_status.argtypes = [vp, vp]
         lib.cf_team_set_spin_limit.argtypes = [vp, i32]
+        lib.cf_mla_create.argtypes = [ctypes.POINTER(MlaConfig), ctypes.POINTER(vp)]
+        lib.cf_mla_destroy.argtypes = [vp]
+        lib.cf_mla_decode.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
+        lib.cf_mla_status.argtypes = [vp, vp]
+        lib.cf_mla_set_spin_limit.argtypes = [vp, i32]
+        lib.cf_mla_algorithmic_bytes.argtypes = [ctypes.POINTER(MlaConfig), i32, i32]
+        lib.cf_mla_algorithmic_bytes.restype = ctypes.c_int64
         for name in ("cf_team_create", "cf_team_destroy", "cf_team_reduce", "cf_team_gather", "cf_team_status",
-                     "cf_team_set_spin_limit"):
+                     "cf_team_set_spin_limit",
+                    "cf_mla_create", "cf_mla_destroy", "cf_mla_decode", "cf_mla_status", "cf_mla_set_spin_limit",
+                    "cf_mla_algorithmic_bytes"):
             getattr(lib, name).restype = ctypes.c_int
         for name in ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_packed", "cf_decode_layer", "cf_decode_layer_rows",
                     "cf_pack_weights",
@@ -216,6 +233,45 @@ class TeamCollectives:
     def close(self):
         if self._h:
             self._lib.cf_team_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class MlaBlock:
+    """Handle of the fused MLA decode block (cf_mla_*).  Tensors are raw device addresses of fp16 data."""
+
+    def __init__(self, d_model, n_heads, nope_dim, rope_dim, kv_lora_rank, v_head_dim, max_batch, max_seq, rope_base):
+        self._lib = load_library()
+        self.cfg = MlaConfig(d_model, n_heads, nope_dim, rope_dim, kv_lora_rank, v_head_dim, max_batch, max_seq, rope_base)
+        self._h = ctypes.c_void_p()
+        self._check(self._lib.cf_mla_create(ctypes.byref(self.cfg), ctypes.byref(self._h)))
+
+    def _check(self, rc):
+        if rc != 0:
+            raise CfError(rc, self._lib.cf_strerror(rc).decode())
+
+    def decode(self, batch, x, w_q, w_kv, w_up, w_down, w_o, kv_cache, pos, out, stream=0):
+        rc = self._lib.cf_mla_decode(self._h, batch, x, w_q, w_kv, w_up, w_down, w_o, kv_cache, pos, out, stream)
+        if rc != 0:
+            self._check(rc)
+
+    def decode_rc(self, batch, x, w_q, w_kv, w_up, w_down, w_o, kv_cache, pos, out, stream=0) -> int:
+        return int(self._lib.cf_mla_decode(self._h, batch, x, w_q, w_kv, w_up, w_down, w_o, kv_cache, pos, out, stream))
+
+    def status(self, stream=0):
+        self._check(self._lib.cf_mla_status(self._h, stream))
+
+    def algorithmic_bytes(self, batch, pos) -> int:
+        return int(self._lib.cf_mla_algorithmic_bytes(ctypes.byref(self.cfg), batch, pos))
+
+    def close(self):
+        if self._h:
+            self._lib.cf_mla_destroy(self._h)
             self._h = ctypes.c_void_p()
 
     def __del__(self):

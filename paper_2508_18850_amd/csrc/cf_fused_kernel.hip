@@ -31,6 +31,7 @@
 // readers spin.  Spins are bounded: after spin_ticks a thread sets an error
 // flag and goes on, so the kernel always ends.
 #include "cf_params.h"
+#include "cf_rope_device.h"
 
 #include <cstdlib>
 #include <type_traits>
@@ -222,38 +223,6 @@ __device__ __forceinline__ int qkv_col0(const Params &p, int team, int sel)
     if (sel < G) return (team * G + sel) * HD;
     if (sel == G) return (p.nq + team) * HD;
     return (p.nq + p.nkv + team) * HD;
-}
-
-// cos and sin of pos * inv_freq, angle and range reduction in fp64.
-__device__ __forceinline__ void rope_cos_sin(int pos, double inv_freq, float &cos_out, float &sin_out)
-{
-    const double ang = (double)pos * inv_freq;
-    const double k = rint(ang * 0.63661977236758134308);              // 2/pi
-    double r = fma(-k, 1.57079632679489655800e+00, ang);              // pi/2, high part
-    r = fma(-k, 6.12323399573676603587e-17, r);                       // pi/2, low part
-    const double r2 = r * r;                                          // |r| <= pi/4: Taylor series
-    double s = -1.0 / 1307674368000.0;
-    s = fma(s, r2, 1.0 / 6227020800.0);
-    s = fma(s, r2, -1.0 / 39916800.0);
-    s = fma(s, r2, 1.0 / 362880.0);
-    s = fma(s, r2, -1.0 / 5040.0);
-    s = fma(s, r2, 1.0 / 120.0);
-    s = fma(s, r2, -1.0 / 6.0);
-    s = fma(s * r2, r, r);
-    double c = 1.0 / 20922789888000.0;
-    c = fma(c, r2, -1.0 / 87178291200.0);
-    c = fma(c, r2, 1.0 / 479001600.0);
-    c = fma(c, r2, -1.0 / 3628800.0);
-    c = fma(c, r2, 1.0 / 40320.0);
-    c = fma(c, r2, -1.0 / 720.0);
-    c = fma(c, r2, 1.0 / 24.0);
-    c = fma(c, r2, -0.5);
-    c = fma(c, r2, 1.0);
-    const int q = (int)((long long)k & 3);
-    const double sv = (q == 0) ? s : (q == 1) ? c : (q == 2) ? -s : -c;
-    const double cv = (q == 0) ? c : (q == 1) ? -s : (q == 2) ? -c : s;
-    cos_out = (float)cv;
-    sin_out = (float)sv;
 }
 
 // The RoPE tables in LDS: [rows][HD] floats, per row HD/2 cosines then HD/2 sines of that row's position.

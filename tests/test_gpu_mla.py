@@ -1,0 +1,123 @@
+"""GPU parity of the fused MLA decode block (cf_mla_decode) with the CPU oracle (oracle/mla_block.py), through
+the C ABI.
+
+Tolerance on the block output, as for the other block: max|err| <= 1e-2 * max|ref| + 1e-3 (fp16 storage, fp32
+accumulation), plus relative RMS < 5e-3; the appended cache row within one fp16 ulp plus the fp32 accumulation error
+of a d_model-term dot product; every other cache row bit-identical.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import cf_inputs
+from oracle import mla_block as orc
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def _log(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def run(shape, inp, pos):
+    from paper_2508_18850_amd import MlaBlock
+    dev = torch.device("cuda:0")
+    B = inp["batch"]
+    blk = MlaBlock(shape.d_model, shape.n_heads, shape.nope_dim, shape.rope_dim, shape.kv_lora_rank, shape.v_head_dim,
+                   B, inp["max_seq"], shape.rope_base)
+    st = torch.cuda.current_stream().cuda_stream
+    t = {k: torch.from_numpy(inp[k]).to(dev) for k in ("x", "w_q", "w_kv", "w_up", "w_down", "w_o", "kv_cache")}
+    out = torch.full((B, shape.d_model), float("nan"), dtype=torch.float16, device=dev)
+    for _ in range(2):          # two calls in a row: the second must not be confused by the first one's slots
+        blk.decode(B, t["x"].data_ptr(), t["w_q"].data_ptr(), t["w_kv"].data_ptr(), t["w_up"].data_ptr(),
+                   t["w_down"].data_ptr(), t["w_o"].data_ptr(), t["kv_cache"].data_ptr(), pos, out.data_ptr(), st)
+    blk.status(st)
+    res = {"out": out.cpu().numpy(), "kv_cache": t["kv_cache"].cpu().numpy()}
+    blk.close()
+    return res
+
+
+def check(res, ref, inp, pos, label):
+    out = res["out"].astype(np.float64)
+    mref = np.abs(ref["out"]).max()
+    err = np.abs(out - ref["out"]).max()
+    rel_rms = np.sqrt(np.mean((out - ref["out"]) ** 2) / np.mean(ref["out"] ** 2))
+    _log("%s: max|err| %.3e tol %.3e max|ref| %.3e rel-rms %.2e" % (label, err, 1e-2 * mref + 1e-3, mref, rel_rms))
+    assert np.isfinite(out).all()
+    assert err <= 1e-2 * mref + 1e-3
+    assert rel_rms < 5e-3
+    got = res["kv_cache"][:, pos].astype(np.float64)
+    bad = np.abs(got - ref["kv_new"]) > np.abs(ref["kv_new"]) * 2.0 ** -10 + 2e-5
+    assert not bad.any(), float(np.abs(got - ref["kv_new"])[bad].max())
+    before, after = inp["kv_cache"].view(np.uint16).copy(), res["kv_cache"].view(np.uint16).copy()
+    before[:, pos] = 0
+    after[:, pos] = 0
+    assert np.array_equal(before, after), "cache rows other than pos were modified"
+
+
+def oracle(shape, inp, pos):
+    return orc.mla_decode_block(inp["x"], inp["w_q"], inp["w_kv"], inp["w_up"], inp["w_down"], inp["w_o"],
+                                inp["kv_cache"], pos, shape.n_heads, shape.nope_dim, shape.rope_dim, shape.kv_lora_rank,
+                                shape.v_head_dim, shape.rope_base)
+
+
+CASES = [
+    # name, shape, batch, cached tokens
+    ("one_head", cf_inputs.MlaShape("s", 96, 1, 16, 64, 512, 32, 10000.0, 0), 1, 17),
+    ("two_heads_b3", cf_inputs.MlaShape("s", 64, 2, 32, 64, 512, 16, 10000.0, 0), 3, 37),
+    ("wide_b4", cf_inputs.MlaShape("s", 512, 16, 128, 64, 512, 128, 500000.0, 0), 4, 300),
+    ("five_heads_b2", cf_inputs.MlaShape("s", 320, 5, 48, 64, 512, 64, 10000.0, 0), 2, 129),
+]
+
+
+@pytest.mark.parametrize("name,shape,batch,kv_len", CASES)
+def test_small_shapes_match_oracle(name, shape, batch, kv_len):
+    _log("mla case %s B=%d L=%d" % (name, batch, kv_len))
+    inp = cf_inputs.make_mla_inputs(shape, seed=61, batch=batch, kv_len=kv_len)
+    check(run(shape, inp, kv_len), oracle(shape, inp, kv_len), inp, kv_len, name)
+
+
+@pytest.mark.parametrize("pos", [0, 1, 15, 16, 17, 127, 128])
+def test_edge_positions(pos):
+    """Empty cache, fewer tokens than members of a team, the boundaries of the token split."""
+    shape = cf_inputs.MlaShape("s", 128, 2, 32, 64, 512, 32, 10000.0, 0)
+    inp = cf_inputs.make_mla_inputs(shape, seed=62 + pos, batch=2, kv_len=pos)
+    check(run(shape, inp, pos), oracle(shape, inp, pos), inp, pos, "pos %d" % pos)
+
+
+def test_planted_row_is_selected():
+    """A cached row that matches head 0's absorbed query dominates its softmax, wherever it sits in the token split."""
+    shape = cf_inputs.MlaShape("s", 128, 2, 32, 64, 512, 32, 10000.0, 0)
+    for where in (0, 63, 199):
+        inp = cf_inputs.make_mla_inputs(shape, seed=70, batch=1, kv_len=200)
+        ref0 = oracle(shape, inp, 200)
+        target = np.concatenate([ref0["q_lat"][0, 0], ref0["q_rope"][0, 0]])
+        inp["kv_cache"][0, where] = (target * 80.0 / np.linalg.norm(target)).astype(np.float16)
+        check(run(shape, inp, 200), oracle(shape, inp, 200), inp, 200, "planted at %d" % where)
+
+
+def test_full_size_deepseek_v2_lite_shape():
+    shape = cf_inputs.MLA_SHAPES["deepseek_v2_lite"]
+    inp = cf_inputs.make_mla_inputs(shape, seed=1000)
+    check(run(shape, inp, shape.kv_len), oracle(shape, inp, shape.kv_len), inp, shape.kv_len, shape.name)
+
+
+def test_unsupported_shapes_and_bad_arguments_are_refused():
+    from paper_2508_18850_amd import MlaBlock, CfError
+    with pytest.raises(CfError) as e:
+        MlaBlock(2048, 16, 128, 64, 256, 128, 1, 64, 10000.0)          # kv_lora_rank the kernel is not written for
+    assert e.value.code == -2
+    with pytest.raises(CfError) as e:
+        MlaBlock(2048, 32, 128, 64, 512, 128, 1, 64, 10000.0)          # more heads than teams fit
+    assert e.value.code == -2
+    blk = MlaBlock(128, 2, 32, 64, 512, 32, 2, 64, 10000.0)
+    a = torch.zeros(1 << 20, dtype=torch.float16, device="cuda")
+    p = a.data_ptr()
+    assert blk.decode_rc(3, p, p, p, p, p, p, p, 5, p) == -1           # batch above max_batch
+    assert blk.decode_rc(1, p, p, p, p, p, p, p, 64, p) == -1          # pos outside the cache
+    assert blk.decode_rc(1, p + 2, p, p, p, p, p, p, 5, p) == -1       # misaligned pointer
+    assert blk.decode_rc(1, 0, p, p, p, p, p, p, 5, p) == -1           # null pointer
+    blk.close()
