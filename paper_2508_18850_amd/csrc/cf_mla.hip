@@ -3,18 +3,19 @@
 //
 // Alg. 4 runs one cluster per head and moves data between its blocks with three ClusterGathers and three
 // ClusterReduces.  Here a head is a team of 16 co-resident workgroups and every hand-over is one hop through
-// stamped {value, stamp} slots in global memory (cf_team_device.h), five hops in all:
+// stamped {value, stamp} slots in global memory (cf_team_device.h), five hops in all; every weight matrix is read
+// in contiguous rows:
 //
 //   A  projections        [q | kv_new] = x [W_Q | W_KV]           16 row slices x 16 column blocks, partial sums
 //   B  up-projection      q_lat_i = q_nope_i W_Up[i]              member j: 1/16 of the kv_lora_rank columns
 //   C  attention          partial softmax over 1/16 of the tokens  (m, l, acc[kv_lora_rank]) per member;
 //                         the last member appends the new row and counts the new token
-//   D1 merge              member j merges 1/16 of the latent dimensions of the 16 partials
-//   D2 down-projection    a_i = z_i W_Down[i]                      member j: 1/16 of the value columns
-//   E  output projection  out = concat(a) W_O                      every workgroup: 1/W of the output columns
+//   D  merge + down-proj. member j merges 1/16 of the latent dimensions of the 16 partials and multiplies them
+//                         by the same rows of W_Down[i]: a partial of a_i per member (summed by the reader)
+//   E1 output projection  rows of W_O of head i, 1/16 of the output columns per member: a partial of out per head
+//   E2 sum over heads     every workgroup: 1/W of the output columns (the paper's atomicAdd)
 //
-// This is a first, correctness-first version: weights are read with plain (narrow) loads, nothing is prefetched
-// across the hops.  All waits are bounded (CF_ETIMEOUT), all workgroups have to be resident at once.
+// A first version: nothing is prefetched across the hops yet.  All waits are bounded (CF_ETIMEOUT), all workgroups have to be resident at once.
 #include "../../include/cfdecode.h"
 #include "cf_rope_device.h"
 #include "cf_team_device.h"
@@ -48,9 +49,9 @@ struct MlaArgs {
     uint64_t *slots;
     unsigned long long *counters;
     uint32_t *err;
-    size_t x1, x2, x3, x4, x5;      // first slot of each exchange area
+    size_t x1, x2, x3, x5, x6;      // first slot of each exchange area
     int D, nh, n, v, B, pos, max_seq, W;
-    int cq, ckv;                    // columns of W_Q / W_KV per column block
+    int cq, ckv;                    // 16-byte pieces (8 columns) of W_Q / W_KV per column block
     float scale_log2e;              // log2(e) / sqrt(nope_dim + rope_dim)
     double log2_base;
     long long spin_ticks;
@@ -89,7 +90,30 @@ __device__ __forceinline__ float take_sum(const Exchange &x, __amdgpu_buffer_rsr
     return s;
 }
 
+// The stamped value at idx (one poll per try).
+__device__ __forceinline__ float take1(const Exchange &x, __amdgpu_buffer_rsrc_t r, size_t idx)
+{
+    long long t0 = 0;
+    for (;;) {
+        const pair_t q = cf::team::peek(r, idx);
+        if (q.y == x.stamp) return __builtin_bit_cast(float, q.x);
+        if (cf::team::gave_up(x, t0)) return 0.f;
+    }
+}
+
 __device__ __forceinline__ void lds_sync() { __syncthreads(); }
+
+// Stage time stamps of every workgroup, only in builds with -DCF_STAMPS=1 (the profiling library).
+#ifndef CF_STAMPS
+#define CF_STAMPS 0
+#endif
+#if CF_STAMPS
+constexpr int kMlaStamps = 16;
+__device__ unsigned long long g_mla_ts[256 * kMlaStamps];
+#define MLA_STAMP(k) do { if (threadIdx.x == 0) s_ts[k] = wall_clock64(); } while (0)
+#else
+#define MLA_STAMP(k)
+#endif
 
 __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
 {
@@ -100,6 +124,11 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, w = blockIdx.x;
     const int head = w / TS, j = w % TS;
     const int B = a.B, nr = a.n + R, CQq = a.nh * nr, CQ = CQq + L + R;
+#if CF_STAMPS
+    __shared__ unsigned long long s_ts[kMlaStamps];
+    if (tid < kMlaStamps) s_ts[tid] = 0;
+#endif
+    MLA_STAMP(0);
 
     unsigned long long launches;
     asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)"
@@ -111,39 +140,68 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     const __amdgpu_buffer_rsrc_t r = cf::team::slots_rsrc(x);
 
     // ---- A: partial projections.  Work item (kb, cb): rows [kb*RK, +RK) of x, column block cb of W_Q and of W_KV.
-    const int RK = a.D / KS, ncols = a.cq + a.ckv;
+    //      A thread owns one 16-byte piece (8 columns) of the block and every 16th row of the slice: lanes run
+    //      along the columns, so a row of the block is one contiguous read; the two row groups of a wavefront
+    //      are added by a shuffle, the eight wavefronts through LDS.
+    const int RK = a.D / KS;
+    const int qv = CQq / 8, kvv = (L + R) / 8;                        // 16-byte pieces of a row of W_Q / W_KV
     for (int item = w; item < KS * 16; item += a.W) {
         const int kb = item / 16, cb = item % 16;
         lds_sync();
-        for (int i = tid; i < B * RK; i += NT) s_a[i] = h2f(a.x[(size_t)(i / RK) * a.D + kb * RK + i % RK]);
+        for (int i = tid; i < B * RK; i += NT) s_b[i] = h2f(a.x[(size_t)(i / RK) * a.D + kb * RK + i % RK]);
         lds_sync();
-        const int c = tid % MAXCOLS, half = tid / MAXCOLS;           // two halves of the rows per column
-        const bool isq = c < a.cq;
-        const int col = isq ? cb * a.cq + c : cb * a.ckv + (c - a.cq);
-        const bool live = c < ncols && col < (isq ? CQq : L + R);
-        const uint16_t *wp = isq ? a.wq + col : a.wkv + col;
-        const size_t ld = isq ? CQq : L + R;
-        float acc[MAXB] = {0.f, 0.f, 0.f, 0.f};
-        if (live) {
-            const int r0 = half * (RK / 2), r1 = half ? RK : RK / 2;
-            for (int rr = r0; rr < r1; ++rr) {
-                const float wgt = h2f(wp[(size_t)(kb * RK + rr) * ld]);
+        const int pv = tid % 32, g = tid / 32;                        // piece of the block, row group 0..15
+        const bool isq = pv < a.cq;
+        const int piece = isq ? cb * a.cq + pv : cb * a.ckv + (pv - a.cq);
+        const bool live = pv < a.cq + a.ckv && piece < (isq ? qv : kvv);
+        const h8 *wp = reinterpret_cast<const h8 *>(isq ? a.wq : a.wkv) + piece;
+        const size_t ld = isq ? qv : kvv;                             // row stride in pieces
+        float acc[MAXB][8];
 #pragma unroll
-                for (int b = 0; b < MAXB; ++b)
-                    if (b < B) acc[b] = fmaf(s_a[b * RK + rr], wgt, acc[b]);
+        for (int b = 0; b < MAXB; ++b)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[b][c] = 0.f;
+        for (int r0 = g; r0 < RK; r0 += 16 * 8) {                      // eight rows of this thread in flight
+            h8 wr[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int rr = r0 + 16 * k;
+                wr[k] = (live && rr < RK) ? wp[(size_t)(kb * RK + rr) * ld] : h8{0, 0, 0, 0, 0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int rr = min(r0 + 16 * k, RK - 1);
+#pragma unroll
+                for (int b = 0; b < MAXB; ++b) {
+                    const float xv = b < B ? s_b[b * RK + rr] : 0.f;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) acc[b][c] = fmaf(xv, (float)wr[k][c], acc[b][c]);
+                }
             }
         }
 #pragma unroll
-        for (int b = 0; b < MAXB; ++b) s_b[(b * 2 + half) * MAXCOLS + c] = acc[b];
+        for (int b = 0; b < MAXB; ++b)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                acc[b][c] += __shfl_xor(acc[b][c], 32);
+                if (lane < 32 && b < B) s_a[(wv * MAXB + b) * MAXCOLS + pv * 8 + c] = acc[b][c];
+            }
         lds_sync();
-        if (half == 0 && live) {
-            const int gcol = isq ? col : CQq + col;
-            for (int b = 0; b < B; ++b)
-                cf::team::put(r, a.x1 + ((size_t)kb * B + b) * CQ + gcol,
-                              s_b[(b * 2) * MAXCOLS + c] + s_b[(b * 2 + 1) * MAXCOLS + c], x.stamp);
+        for (int i = tid; i < B * MAXCOLS; i += NT) {
+            const int b = i / MAXCOLS, cc = i % MAXCOLS, p2 = cc / 8;
+            const bool q2 = p2 < a.cq;
+            const int piece2 = q2 ? cb * a.cq + p2 : cb * a.ckv + (p2 - a.cq);
+            if (p2 < a.cq + a.ckv && piece2 < (q2 ? qv : kvv)) {
+                float sum = 0.f;
+#pragma unroll
+                for (int w8 = 0; w8 < NW; ++w8) sum += s_a[(w8 * MAXB + b) * MAXCOLS + cc];
+                const int gcol = (q2 ? 0 : CQq) + piece2 * 8 + cc % 8;
+                cf::team::put(r, a.x1 + ((size_t)kb * B + b) * CQ + gcol, sum, x.stamp);
+            }
         }
     }
 
+    MLA_STAMP(1);           // A done
     // ---- B: up-projection of head `head`, columns [LJ*j, +LJ) of the latent dimension
     constexpr int LJ = L / TS;                                        // 32
     lds_sync();
@@ -152,26 +210,44 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         s_a[i] = take_sum(x, r, a.x1 + (size_t)b * CQ + head * nr + c, (size_t)B * CQ, KS);
     }
     lds_sync();
+    MLA_STAMP(2);           // q_nope arrived
     {
-        const int c = tid % LJ, g = tid / LJ;                         // 16 row groups
-        float acc[MAXB] = {0.f, 0.f, 0.f, 0.f};
-        for (int row = g; row < a.n; row += NT / LJ) {
-            const float wgt = h2f(a.wup[((size_t)head * a.n + row) * L + LJ * j + c]);
+        // W_Up[head] rows x this member's 32 columns: four 16-byte pieces per row, one (row, piece) per thread
+        // and pass; lanes with the same piece are added by shuffles, the wavefronts through LDS
+        const int pc = tid % 4, row0 = tid / 4;
+        float acc[MAXB][8];
 #pragma unroll
-            for (int b = 0; b < MAXB; ++b)
-                if (b < B) acc[b] = fmaf(s_a[b * a.n + row], wgt, acc[b]);
+        for (int b = 0; b < MAXB; ++b)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[b][c] = 0.f;
+        for (int row = row0; row < a.n; row += NT / 4) {
+            const h8 wr = *reinterpret_cast<const h8 *>(a.wup + ((size_t)head * a.n + row) * L + LJ * j + pc * 8);
+#pragma unroll
+            for (int b = 0; b < MAXB; ++b) {
+                const float qv2 = b < B ? s_a[b * a.n + row] : 0.f;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) acc[b][c] = fmaf(qv2, (float)wr[c], acc[b][c]);
+            }
         }
 #pragma unroll
-        for (int b = 0; b < MAXB; ++b) s_b[(b * (NT / LJ) + g) * LJ + c] = acc[b];
+        for (int b = 0; b < MAXB; ++b)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                float t = acc[b][c];
+#pragma unroll
+                for (int off = 4; off < 64; off <<= 1) t += __shfl_xor(t, off);
+                if (lane < 4) s_b[(wv * MAXB + b) * LJ + pc * 8 + c] = t;
+            }
         lds_sync();
         if (tid < LJ * B) {
             const int b = tid / LJ, cc = tid % LJ;
-            float s = 0.f;
-            for (int g2 = 0; g2 < NT / LJ; ++g2) s += s_b[(b * (NT / LJ) + g2) * LJ + cc];
-            cf::team::put(r, a.x2 + ((size_t)b * a.nh + head) * L + LJ * j + cc, s, x.stamp);
+            float sum = 0.f;
+            for (int w8 = 0; w8 < NW; ++w8) sum += s_b[(w8 * MAXB + b) * LJ + cc];
+            cf::team::put(r, a.x2 + ((size_t)b * a.nh + head) * L + LJ * j + cc, sum, x.stamp);
         }
     }
 
+    MLA_STAMP(3);           // B done
     // ---- C: attention over the tokens [t0, t1) of this member; the last member also takes the new token
     lds_sync();
     const bool last = j == TS - 1;
@@ -180,7 +256,7 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     // s_a: [B][L + R] the query in the latent space and its rotated rotary part; s_b: [B][L + R] the new row
     for (int i = tid; i < B * L; i += NT) {
         const int b = i / L, d = i % L;
-        s_a[b * (L + R) + d] = take_sum(x, r, a.x2 + ((size_t)b * a.nh + head) * L + d, 0, 1);
+        s_a[b * (L + R) + d] = take1(x, r, a.x2 + ((size_t)b * a.nh + head) * L + d);
     }
     for (int i = tid; i < B * R; i += NT) {
         const int b = i / R, d = i % R;
@@ -211,6 +287,7 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         }
     }
     lds_sync();
+    MLA_STAMP(4);           // query arrived and rotated
     if (last)                                                         // append (Sec. 2.1): row pos of every sequence
         for (int i = tid; i < B * (L + R); i += NT) {
             const int b = i / (L + R), d = i % (L + R);
@@ -226,29 +303,60 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         }
         float m = kNegBig, lsum = 0.f, acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         const uint16_t *rows = a.cache + (size_t)b * a.max_seq * (L + R);
-        for (int t = t0 + wv; t < t1; t += NW * 4) {                   // four rows of this wavefront in flight
-            h8 kl[4], kr[4];
+        // Four rows of this wavefront per batch, two batches in flight: the next batch is requested before the
+        // current one is used.  Rows past the split are read from its last row (finite data) and count for nothing.
+        constexpr int UR = 4;
+        h8 kl[2][UR], kr[2][UR];
+        auto request = [&](int buf, int t) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < UR; ++u) {
                 const int tt = min(t + u * NW, t1 - 1);
-                kl[u] = *reinterpret_cast<const h8 *>(rows + (size_t)tt * (L + R) + lane * 8);
-                kr[u] = *reinterpret_cast<const h8 *>(rows + (size_t)tt * (L + R) + L + (lane & (R / 8 - 1)) * 8);
+                kl[buf][u] = *reinterpret_cast<const h8 *>(rows + (size_t)tt * (L + R) + lane * 8);
+                kr[buf][u] = *reinterpret_cast<const h8 *>(rows + (size_t)tt * (L + R) + L + (lane & (R / 8 - 1)) * 8);
+            }
+        };
+        auto use = [&](int buf, int t) {
+            float d[UR];
+#pragma unroll
+            for (int u = 0; u < UR; ++u) {
+                float dd = 0.f;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) dd = fmaf(ql[k], (float)kl[buf][u][k], dd);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) dd = fmaf(qr[k], (float)kr[buf][u][k], dd);
+                d[u] = dd;
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                float d = 0.f;
+            for (int off = 32; off > 0; off >>= 1)
 #pragma unroll
-                for (int k = 0; k < 8; ++k) d = fmaf(ql[k], (float)kl[u][k], d);
+                for (int u = 0; u < UR; ++u) d[u] += __shfl_xor(d[u], off);
+            float mn = m;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) d = fmaf(qr[k], (float)kr[u][k], d);
-                d = wave_sum(d);
-                if (t + u * NW < t1) {                                  // uniform over the wavefront
-                    const float mn = fmaxf(m, d), f = __builtin_amdgcn_exp2f(m - mn), pw = __builtin_amdgcn_exp2f(d - mn);
-                    m = mn;
-                    lsum = lsum * f + pw;
+            for (int u = 0; u < UR; ++u) {
+                d[u] = (t + u * NW < t1) ? d[u] : kNegBig;
+                mn = fmaxf(mn, d[u]);
+            }
+            const float f = __builtin_amdgcn_exp2f(m - mn);
+            m = mn;
+            lsum *= f;
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) acc[k] = fmaf(pw, (float)kl[u][k], acc[k] * f);
-                }
+            for (int k = 0; k < 8; ++k) acc[k] *= f;
+#pragma unroll
+            for (int u = 0; u < UR; ++u) {
+                const float pw = (t + u * NW < t1) ? __builtin_amdgcn_exp2f(d[u] - mn) : 0.f;
+                lsum += pw;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) acc[k] = fmaf(pw, (float)kl[buf][u][k], acc[k]);
+            }
+        };
+        if (t1 > t0) {                                                 // uniform over the workgroup
+            constexpr int step = NW * UR;
+            request(0, t0 + wv);
+            for (int t = t0 + wv; t < t1; t += 2 * step) {
+                request(1, t + step);
+                use(0, t);
+                request(0, t + 2 * step);
+                use(1, t + step);
             }
         }
         lds_sync();
@@ -293,105 +401,161 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         }
     }
 
-    // ---- D1: merge latent dimensions [LJ*j, +LJ) of the team's partials (online softmax, Alg. 4 steps 8-10)
+    MLA_STAMP(5);           // C done
+    // ---- D: merge latent dimensions [LJ*j, +LJ) of the team's partials (online softmax, Alg. 4 steps 8-10) and
+    //      multiply them by the same rows of W_Down[head]: a partial of a_head per member, no hop in between
+    lds_sync();
     if (tid < LJ * B) {
         const int b = tid / LJ, d = LJ * j + tid % LJ;
         const size_t src = a.x3 + ((size_t)b * a.nh + head) * TS * (L + 2);
-        float ms[TS], ls[TS], as[TS];
+        pair_t qm[TS], ql2[TS], qa[TS];
+        long long tw = 0;
+        for (;;) {                                                     // all 48 polls of this thread in one go
 #pragma unroll
-        for (int s = 0; s < TS; ++s) ms[s] = take_sum(x, r, src + (size_t)s * (L + 2), 0, 1);
+            for (int s2 = 0; s2 < TS; ++s2) {
+                qm[s2] = cf::team::peek(r, src + (size_t)s2 * (L + 2));
+                ql2[s2] = cf::team::peek(r, src + (size_t)s2 * (L + 2) + 1);
+                qa[s2] = cf::team::peek(r, src + (size_t)s2 * (L + 2) + 2 + d);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            bool ok = true;
 #pragma unroll
-        for (int s = 0; s < TS; ++s) ls[s] = take_sum(x, r, src + (size_t)s * (L + 2) + 1, 0, 1);
-#pragma unroll
-        for (int s = 0; s < TS; ++s) as[s] = take_sum(x, r, src + (size_t)s * (L + 2) + 2 + d, 0, 1);
+            for (int s2 = 0; s2 < TS; ++s2) ok &= (qm[s2].y == x.stamp) & (ql2[s2].y == x.stamp) & (qa[s2].y == x.stamp);
+            if (ok || cf::team::gave_up(x, tw)) break;
+        }
         float M = kNegBig;
 #pragma unroll
-        for (int s = 0; s < TS; ++s) M = fmaxf(M, ms[s]);
+        for (int s2 = 0; s2 < TS; ++s2) M = fmaxf(M, __builtin_bit_cast(float, qm[s2].x));
         float Ls = 0.f, A = 0.f;
 #pragma unroll
-        for (int s = 0; s < TS; ++s) {
-            const float f = __builtin_amdgcn_exp2f(ms[s] - M);
-            Ls = fmaf(ls[s], f, Ls);
-            A = fmaf(as[s], f, A);
+        for (int s2 = 0; s2 < TS; ++s2) {
+            const float f = __builtin_amdgcn_exp2f(__builtin_bit_cast(float, qm[s2].x) - M);
+            Ls = fmaf(__builtin_bit_cast(float, ql2[s2].x), f, Ls);
+            A = fmaf(__builtin_bit_cast(float, qa[s2].x), f, A);
         }
-        cf::team::put(r, a.x4 + ((size_t)b * a.nh + head) * L + d, A / Ls, x.stamp);
+        s_b[b * LJ + tid % LJ] = A / Ls;                               // z[b][LJ*j + ...]
     }
-
-    // ---- D2: down-projection, value columns [VJ*j, +VJ) of this head
-    const int VJ = a.v / TS;                                           // <= 8
     lds_sync();
-    for (int i = tid; i < B * L; i += NT)
-        s_a[i] = take_sum(x, r, a.x4 + ((size_t)(i / L) * a.nh + head) * L + i % L, 0, 1);
-    lds_sync();
+    MLA_STAMP(6);           // z slice merged
     {
-        float part[MAXB][8];
+        // rows [LJ*j, +LJ) of W_Down[head], all v columns: one contiguous block; thread = (row, 16-byte piece)
+        const int pcs = a.v / 8;                                        // <= 16
+        const int pc = tid % 16, row = tid / 16;                        // 32 rows
+        float acc[MAXB][8];
 #pragma unroll
         for (int b = 0; b < MAXB; ++b)
 #pragma unroll
-            for (int c = 0; c < 8; ++c) part[b][c] = 0.f;
-        const uint16_t *wrow = a.wdown + ((size_t)head * L + tid) * a.v + VJ * j;      // row tid of W_Down[head]
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            const float wgt = c < VJ ? h2f(wrow[c]) : 0.f;
+            for (int c = 0; c < 8; ++c) acc[b][c] = 0.f;
+        if (pc < pcs) {
+            const h8 wr = *reinterpret_cast<const h8 *>(a.wdown + ((size_t)head * L + LJ * j + row) * a.v + pc * 8);
 #pragma unroll
             for (int b = 0; b < MAXB; ++b)
-                if (b < B) part[b][c] = s_a[b * L + tid] * wgt;
+                if (b < B) {
+                    const float zv = s_b[b * LJ + row];
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) acc[b][c] = zv * (float)wr[c];
+                }
         }
 #pragma unroll
         for (int b = 0; b < MAXB; ++b)
+            if (b < B) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                const float s = wave_sum(part[b][c]);
-                if (lane == 0) s_red[(wv * MAXB + b) * 8 + c] = s;
+                for (int c = 0; c < 8; ++c) {
+                    float t = acc[b][c];
+                    t += __shfl_xor(t, 16);
+                    t += __shfl_xor(t, 32);
+                    if (lane < 16) s_red[(wv * MAXB + b) * 128 + pc * 8 + c] = t;
+                }
             }
         lds_sync();
-        if (tid < B * VJ) {
-            const int b = tid / VJ, c = tid % VJ;
-            float s = 0.f;
-            for (int w8 = 0; w8 < NW; ++w8) s += s_red[(w8 * MAXB + b) * 8 + c];
-            cf::team::put(r, a.x5 + (size_t)b * a.nh * a.v + head * a.v + VJ * j + c, s, x.stamp);
+        for (int i = tid; i < B * a.v; i += NT) {
+            const int b = i / a.v, c = i % a.v;
+            float sum = 0.f;
+#pragma unroll
+            for (int w8 = 0; w8 < NW; ++w8) sum += s_red[(w8 * MAXB + b) * 128 + c];
+            cf::team::put(r, a.x5 + (((size_t)b * a.nh + head) * TS + j) * a.v + c, sum, x.stamp);
         }
     }
+    MLA_STAMP(7);           // D done
 
-    // ---- E: output projection, columns [CW*w, +CW) of the output
-    const int HV = a.nh * a.v, CW = (a.D + a.W - 1) / a.W;             // CW <= 8
+    // ---- E1: rows of W_O that belong to this head, column block j of the output: a partial of out per head
     lds_sync();
-    for (int i = tid; i < B * HV; i += NT) s_a[i] = take_sum(x, r, a.x5 + i, 0, 1);
+    for (int i = tid; i < B * a.v; i += NT) {
+        const int b = i / a.v, c = i % a.v;
+        s_b[i] = take_sum(x, r, a.x5 + ((size_t)b * a.nh + head) * TS * a.v + c, (size_t)a.v, TS);
+    }
     lds_sync();
+    MLA_STAMP(8);           // a_head arrived
     {
-        float part[MAXB][8];
+        const int dp = a.D / 8, pcs = (dp + TS - 1) / TS;               // 16-byte pieces of an output row; per member
+        const int pc = tid % 16, rg = tid / 16;                         // 32 row groups
+        for (int p0 = 0; p0 < pcs; p0 += 16) {
+            const int piece = j * pcs + p0 + pc;
+            const bool live = p0 + pc < pcs && piece < dp;
+            float acc[MAXB][8];
 #pragma unroll
-        for (int b = 0; b < MAXB; ++b)
+            for (int b = 0; b < MAXB; ++b)
 #pragma unroll
-            for (int c = 0; c < 8; ++c) part[b][c] = 0.f;
-        const int c0 = CW * w;
-        for (int row = tid; row < HV; row += NT) {
+                for (int c = 0; c < 8; ++c) acc[b][c] = 0.f;
+            h8 wr[4];                                                   // v <= 128: at most four rows per thread
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                const float wgt = (c < CW && c0 + c < a.D) ? h2f(a.wo[(size_t)row * a.D + c0 + c]) : 0.f;
+            for (int k = 0; k < 4; ++k) {
+                const int row = rg + 32 * k;
+                wr[k] = (live && row < a.v) ? *reinterpret_cast<const h8 *>(a.wo + ((size_t)head * a.v + row) * a.D + piece * 8)
+                                            : h8{0, 0, 0, 0, 0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int row = min(rg + 32 * k, a.v - 1);
 #pragma unroll
                 for (int b = 0; b < MAXB; ++b)
-                    if (b < B) part[b][c] = fmaf(s_a[b * HV + row], wgt, part[b][c]);
+                    if (b < B) {
+                        const float av = s_b[b * a.v + row];
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) acc[b][c] = fmaf(av, (float)wr[k][c], acc[b][c]);
+                    }
+            }
+            lds_sync();
+#pragma unroll
+            for (int b = 0; b < MAXB; ++b)
+                if (b < B) {
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) {
+                        float t = acc[b][c];
+                        t += __shfl_xor(t, 16);
+                        t += __shfl_xor(t, 32);
+                        if (lane < 16) s_red[(wv * MAXB + b) * 128 + pc * 8 + c] = t;
+                    }
+                }
+            lds_sync();
+            for (int i = tid; i < B * 128; i += NT) {
+                const int b = i / 128, cc = i % 128, piece2 = j * pcs + p0 + cc / 8;
+                if (p0 + cc / 8 < pcs && piece2 < dp) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int w8 = 0; w8 < NW; ++w8) sum += s_red[(w8 * MAXB + b) * 128 + cc];
+                    cf::team::put(r, a.x6 + ((size_t)b * a.nh + head) * a.D + piece2 * 8 + cc % 8, sum, x.stamp);
+                }
             }
         }
-#pragma unroll
-        for (int b = 0; b < MAXB; ++b)
-#pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                const float s = wave_sum(part[b][c]);
-                if (lane == 0) s_red[(wv * MAXB + b) * 8 + c] = s;
-            }
-        lds_sync();
+    }
+    MLA_STAMP(10);          // E1 done
+
+    // ---- E2: sum over the heads (what the paper does with atomicAdd), columns [CW*w, +CW) of the output
+    {
+        const int CW = (a.D + a.W - 1) / a.W;
         if (tid < B * CW) {
-            const int b = tid / CW, c = tid % CW;
-            if (c0 + c < a.D) {
-                float s = 0.f;
-                for (int w8 = 0; w8 < NW; ++w8) s += s_red[(w8 * MAXB + b) * 8 + c];
-                a.out[(size_t)b * a.D + c0 + c] = f2h(s);
-            }
+            const int b = tid / CW, col = CW * w + tid % CW;
+            if (col < a.D)
+                a.out[(size_t)b * a.D + col] = f2h(take_sum(x, r, a.x6 + (size_t)b * a.nh * a.D + col, (size_t)a.D, a.nh));
         }
     }
     if (tid == 0) a.counters[(size_t)w * kCounterStride] = cnt;
+    MLA_STAMP(9);
+#if CF_STAMPS
+    lds_sync();
+    if (tid < kMlaStamps && w < 256) g_mla_ts[w * kMlaStamps + tid] = s_ts[tid];
+#endif
 }
 
 }  // namespace
@@ -404,7 +568,7 @@ struct cf_mla_s {
     uint64_t *slots = nullptr;
     unsigned long long *counters = nullptr;
     uint32_t *err = nullptr;
-    size_t x1 = 0, x2 = 0, x3 = 0, x4 = 0, x5 = 0;
+    size_t x1 = 0, x2 = 0, x3 = 0, x5 = 0, x6 = 0;
     long long spin_ticks = 200000000LL;
     int last_hip = 0;
 };
@@ -422,10 +586,10 @@ int cf_mla_create(const cf_mla_config *cfg, cf_mla *out)
     // what this first kernel is written for
     const int W = c.n_heads * TS;
     const int CQq = c.n_heads * (c.nope_dim + R);
-    const int cq = (CQq + 15) / 16, ckv = (L + R + 15) / 16;
+    const int cq = (CQq / 8 + 15) / 16, ckv = ((L + R) / 8 + 15) / 16;     // 16-byte pieces per column block
     if (c.kv_lora_rank != L || c.rope_dim != R || c.max_batch > MAXB || c.d_model % (2 * KS) || c.d_model / KS > NT ||
-        c.v_head_dim % TS || c.v_head_dim / TS > 8 || c.n_heads * c.v_head_dim > MAXA || cq + ckv > MAXCOLS ||
-        c.nope_dim > L || c.d_model > 8 * W)
+        c.v_head_dim % 8 || c.v_head_dim > 128 || cq + ckv > 32 || c.nope_dim % 8 ||
+        c.nope_dim > L || c.d_model > 8 * W || c.d_model % 8)
         return CF_EUNSUPPORTED;
     int dev = 0;
     hipDeviceProp_t prop;
@@ -443,9 +607,9 @@ int cf_mla_create(const cf_mla_config *cfg, cf_mla *out)
     t->x1 = 0;
     t->x2 = t->x1 + (size_t)KS * B * CQ;
     t->x3 = t->x2 + B * c.n_heads * L;
-    t->x4 = t->x3 + B * c.n_heads * TS * (L + 2);
-    t->x5 = t->x4 + B * c.n_heads * L;
-    const size_t nslots = t->x5 + B * c.n_heads * c.v_head_dim;
+    t->x5 = t->x3 + B * c.n_heads * TS * (L + 2);
+    t->x6 = t->x5 + B * c.n_heads * TS * c.v_head_dim;
+    const size_t nslots = t->x6 + B * c.n_heads * c.d_model;
     const size_t head = 256 + (size_t)W * kCounterStride * sizeof(unsigned long long);
     const size_t head_al = (head + 255) / 256 * 256;
     t->ws_bytes = head_al + nslots * sizeof(uint64_t);
@@ -499,11 +663,11 @@ int cf_mla_decode(cf_mla t, int32_t batch, const void *x, const void *W_q, const
     a.counters = t->counters;
     a.err = t->err;
     // the exchange areas are laid out for max_batch; a smaller batch uses the front of each
-    a.x1 = t->x1, a.x2 = t->x2, a.x3 = t->x3, a.x4 = t->x4, a.x5 = t->x5;
+    a.x1 = t->x1, a.x2 = t->x2, a.x3 = t->x3, a.x5 = t->x5, a.x6 = t->x6;
     a.D = c.d_model, a.nh = c.n_heads, a.n = c.nope_dim, a.v = c.v_head_dim, a.B = batch, a.pos = pos;
     a.max_seq = c.max_seq, a.W = t->W;
-    a.cq = (c.n_heads * (c.nope_dim + R) + 15) / 16;
-    a.ckv = (L + R + 15) / 16;
+    a.cq = (c.n_heads * (c.nope_dim + R) / 8 + 15) / 16;
+    a.ckv = ((L + R) / 8 + 15) / 16;
     a.scale_log2e = 1.4426950408889634f / std::sqrt((float)(c.nope_dim + R));
     a.log2_base = std::log2((double)c.rope_base);
     a.spin_ticks = t->spin_ticks;
@@ -533,6 +697,16 @@ int cf_mla_status(cf_mla t, void *stream)
     }
     return CF_OK;
 }
+
+#if CF_STAMPS
+// profiling library only: the stage stamps of the last launch (host buffer of 256 * 16 64-bit words)
+int cf_mla_trace_read(void *host_dst)
+{
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(g_mla_ts), sizeof(unsigned long long) * 256 * kMlaStamps);
+    return e == hipSuccess ? CF_OK : CF_EHIP;
+}
+#endif
 
 int cf_mla_set_spin_limit(cf_mla t, int32_t spin_limit_us)
 {
