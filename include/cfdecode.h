@@ -258,8 +258,8 @@ int cf_team_set_spin_limit(cf_team t, int32_t spin_limit_us);
  *   kv_cache [batch, max_seq, kv_lora_rank + rope_dim]: rows < pos read, row pos written; out [batch, d_model].
  * Storage fp16, accumulation fp32.  Asynchronous on `stream`; no allocation, no host synchronisation.
  * This first kernel is written for kv_lora_rank 512, rope_dim 64, n_heads <= 16 (16 workgroups per head, all
- * resident), batch <= 4, v_head_dim a multiple of 16 up to 128, d_model a multiple of 32 up to 8192 and at most
- * 128 * n_heads: cf_mla_create returns CF_EUNSUPPORTED otherwise.  cf_mla_status is cf_status for this handle.
+ * resident), batch <= 4, nope_dim a multiple of 8 up to 128, v_head_dim a multiple of 8 up to 128, d_model a
+ * multiple of 32, at most 8192 and at most 128 * n_heads: cf_mla_create returns CF_EUNSUPPORTED otherwise.  cf_mla_status is cf_status for this handle.
  */
 typedef struct cf_mla_config {
     int32_t d_model, n_heads, nope_dim, rope_dim, kv_lora_rank, v_head_dim;

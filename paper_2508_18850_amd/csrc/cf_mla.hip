@@ -147,9 +147,6 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     const int qv = CQq / 8, kvv = (L + R) / 8;                        // 16-byte pieces of a row of W_Q / W_KV
     for (int item = w; item < KS * 16; item += a.W) {
         const int kb = item / 16, cb = item % 16;
-        lds_sync();
-        for (int i = tid; i < B * RK; i += NT) s_b[i] = h2f(a.x[(size_t)(i / RK) * a.D + kb * RK + i % RK]);
-        lds_sync();
         const int pv = tid % 32, g = tid / 32;                        // piece of the block, row group 0..15
         const bool isq = pv < a.cq;
         const int piece = isq ? cb * a.cq + pv : cb * a.ckv + (pv - a.cq);
@@ -161,13 +158,20 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         for (int b = 0; b < MAXB; ++b)
 #pragma unroll
             for (int c = 0; c < 8; ++c) acc[b][c] = 0.f;
-        for (int r0 = g; r0 < RK; r0 += 16 * 8) {                      // eight rows of this thread in flight
-            h8 wr[8];
+        h8 wr[8];                                                      // eight rows of this thread in flight
+        auto request = [&](int r0) {
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int rr = r0 + 16 * k;
                 wr[k] = (live && rr < RK) ? wp[(size_t)(kb * RK + rr) * ld] : h8{0, 0, 0, 0, 0, 0, 0, 0};
             }
+        };
+        request(g);                                                    // the first weights go out before the slice of x
+        lds_sync();                                                    // (all threads, whatever their row group)
+        for (int i = tid; i < B * RK; i += NT) s_b[i] = h2f(a.x[(size_t)(i / RK) * a.D + kb * RK + i % RK]);
+        lds_sync();
+        for (int r0 = g; r0 < RK; r0 += 16 * 8) {
+            if (r0 != g) request(r0);
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int rr = min(r0 + 16 * k, RK - 1);
@@ -204,6 +208,10 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     MLA_STAMP(1);           // A done
     // ---- B: up-projection of head `head`, columns [LJ*j, +LJ) of the latent dimension
     constexpr int LJ = L / TS;                                        // 32
+    // (the weights of a stage do not depend on what the stage waits for: they are requested first)
+    const int pcB = tid % 4, rowB = tid / 4;                          // nope_dim <= 128: one (row, piece) per thread
+    const h8 wupr = rowB < a.n ? *reinterpret_cast<const h8 *>(a.wup + ((size_t)head * a.n + rowB) * L + LJ * j + pcB * 8)
+                               : h8{0, 0, 0, 0, 0, 0, 0, 0};
     lds_sync();
     for (int i = tid; i < B * a.n; i += NT) {
         const int b = i / a.n, c = i % a.n;
@@ -212,31 +220,19 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     lds_sync();
     MLA_STAMP(2);           // q_nope arrived
     {
-        // W_Up[head] rows x this member's 32 columns: four 16-byte pieces per row, one (row, piece) per thread
-        // and pass; lanes with the same piece are added by shuffles, the wavefronts through LDS
-        const int pc = tid % 4, row0 = tid / 4;
-        float acc[MAXB][8];
+        // W_Up[head] rows x this member's 32 columns: four 16-byte pieces per row; lanes with the same piece are
+        // added by shuffles, the wavefronts through LDS
 #pragma unroll
         for (int b = 0; b < MAXB; ++b)
+            if (b < B) {
+                const float qv2 = rowB < a.n ? s_a[b * a.n + rowB] : 0.f;
 #pragma unroll
-            for (int c = 0; c < 8; ++c) acc[b][c] = 0.f;
-        for (int row = row0; row < a.n; row += NT / 4) {
-            const h8 wr = *reinterpret_cast<const h8 *>(a.wup + ((size_t)head * a.n + row) * L + LJ * j + pc * 8);
+                for (int c = 0; c < 8; ++c) {
+                    float t = qv2 * (float)wupr[c];
 #pragma unroll
-            for (int b = 0; b < MAXB; ++b) {
-                const float qv2 = b < B ? s_a[b * a.n + row] : 0.f;
-#pragma unroll
-                for (int c = 0; c < 8; ++c) acc[b][c] = fmaf(qv2, (float)wr[c], acc[b][c]);
-            }
-        }
-#pragma unroll
-        for (int b = 0; b < MAXB; ++b)
-#pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                float t = acc[b][c];
-#pragma unroll
-                for (int off = 4; off < 64; off <<= 1) t += __shfl_xor(t, off);
-                if (lane < 4) s_b[(wv * MAXB + b) * LJ + pc * 8 + c] = t;
+                    for (int off = 4; off < 64; off <<= 1) t += __shfl_xor(t, off);
+                    if (lane < 4) s_b[(wv * MAXB + b) * LJ + pcB * 8 + c] = t;
+                }
             }
         lds_sync();
         if (tid < LJ * B) {
@@ -304,7 +300,7 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         float m = kNegBig, lsum = 0.f, acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         const uint16_t *rows = a.cache + (size_t)b * a.max_seq * (L + R);
         // Four rows of this wavefront per batch, two batches in flight: the next batch is requested before the
-        // current one is used.  Rows past the split are read from its last row (finite data) and count for nothing.
+        // current one is used (deeper pipelines and larger batches were measured: both are slower).  Rows past the split are read from its last row (finite data) and count for nothing.
         constexpr int UR = 4;
         h8 kl[2][UR], kr[2][UR];
         auto request = [&](int buf, int t) {
@@ -404,6 +400,9 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     MLA_STAMP(5);           // C done
     // ---- D: merge latent dimensions [LJ*j, +LJ) of the team's partials (online softmax, Alg. 4 steps 8-10) and
     //      multiply them by the same rows of W_Down[head]: a partial of a_head per member, no hop in between
+    const int pcsD = a.v / 8, pcD = tid % 16, rowD = tid / 16;        // thread = (row of the slice, 16-byte piece)
+    const h8 wdr = pcD < pcsD ? *reinterpret_cast<const h8 *>(a.wdown + ((size_t)head * L + LJ * j + rowD) * a.v + pcD * 8)
+                              : h8{0, 0, 0, 0, 0, 0, 0, 0};
     lds_sync();
     if (tid < LJ * B) {
         const int b = tid / LJ, d = LJ * j + tid % LJ;
@@ -438,33 +437,17 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     lds_sync();
     MLA_STAMP(6);           // z slice merged
     {
-        // rows [LJ*j, +LJ) of W_Down[head], all v columns: one contiguous block; thread = (row, 16-byte piece)
-        const int pcs = a.v / 8;                                        // <= 16
-        const int pc = tid % 16, row = tid / 16;                        // 32 rows
-        float acc[MAXB][8];
-#pragma unroll
-        for (int b = 0; b < MAXB; ++b)
-#pragma unroll
-            for (int c = 0; c < 8; ++c) acc[b][c] = 0.f;
-        if (pc < pcs) {
-            const h8 wr = *reinterpret_cast<const h8 *>(a.wdown + ((size_t)head * L + LJ * j + row) * a.v + pc * 8);
-#pragma unroll
-            for (int b = 0; b < MAXB; ++b)
-                if (b < B) {
-                    const float zv = s_b[b * LJ + row];
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) acc[b][c] = zv * (float)wr[c];
-                }
-        }
+        // rows [LJ*j, +LJ) of W_Down[head], all v columns: one contiguous block (requested above)
 #pragma unroll
         for (int b = 0; b < MAXB; ++b)
             if (b < B) {
+                const float zv = s_b[b * LJ + rowD];
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
-                    float t = acc[b][c];
+                    float t = zv * (float)wdr[c];
                     t += __shfl_xor(t, 16);
                     t += __shfl_xor(t, 32);
-                    if (lane < 16) s_red[(wv * MAXB + b) * 128 + pc * 8 + c] = t;
+                    if (lane < 16) s_red[(wv * MAXB + b) * 128 + pcD * 8 + c] = t;
                 }
             }
         lds_sync();
@@ -479,6 +462,20 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     MLA_STAMP(7);           // D done
 
     // ---- E1: rows of W_O that belong to this head, column block j of the output: a partial of out per head
+    const int dpE = a.D / 8, pcsE = (dpE + TS - 1) / TS;                // 16-byte pieces of an output row; per member
+    const int pcE = tid % 16, rgE = tid / 16;                         // 32 row groups
+    auto wo_rows = [&](int p0, h8 (&wr)[4]) {                          // v <= 128: at most four rows per thread
+        const int piece = j * pcsE + p0 + pcE;
+        const bool live = p0 + pcE < pcsE && piece < dpE;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int row = rgE + 32 * k;
+            wr[k] = (live && row < a.v) ? *reinterpret_cast<const h8 *>(a.wo + ((size_t)head * a.v + row) * a.D + piece * 8)
+                                        : h8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+    };
+    h8 wor[4];
+    wo_rows(0, wor);
     lds_sync();
     for (int i = tid; i < B * a.v; i += NT) {
         const int b = i / a.v, c = i % a.v;
@@ -486,56 +483,44 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     }
     lds_sync();
     MLA_STAMP(8);           // a_head arrived
-    {
-        const int dp = a.D / 8, pcs = (dp + TS - 1) / TS;               // 16-byte pieces of an output row; per member
-        const int pc = tid % 16, rg = tid / 16;                         // 32 row groups
-        for (int p0 = 0; p0 < pcs; p0 += 16) {
-            const int piece = j * pcs + p0 + pc;
-            const bool live = p0 + pc < pcs && piece < dp;
-            float acc[MAXB][8];
+    for (int p0 = 0; p0 < pcsE; p0 += 16) {
+        if (p0 > 0) wo_rows(p0, wor);
+        float acc[MAXB][8];
 #pragma unroll
-            for (int b = 0; b < MAXB; ++b)
+        for (int b = 0; b < MAXB; ++b)
 #pragma unroll
-                for (int c = 0; c < 8; ++c) acc[b][c] = 0.f;
-            h8 wr[4];                                                   // v <= 128: at most four rows per thread
+            for (int c = 0; c < 8; ++c) acc[b][c] = 0.f;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int row = rg + 32 * k;
-                wr[k] = (live && row < a.v) ? *reinterpret_cast<const h8 *>(a.wo + ((size_t)head * a.v + row) * a.D + piece * 8)
-                                            : h8{0, 0, 0, 0, 0, 0, 0, 0};
-            }
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int row = min(rg + 32 * k, a.v - 1);
-#pragma unroll
-                for (int b = 0; b < MAXB; ++b)
-                    if (b < B) {
-                        const float av = s_b[b * a.v + row];
-#pragma unroll
-                        for (int c = 0; c < 8; ++c) acc[b][c] = fmaf(av, (float)wr[k][c], acc[b][c]);
-                    }
-            }
-            lds_sync();
+        for (int k = 0; k < 4; ++k) {
+            const int row = min(rgE + 32 * k, a.v - 1);
 #pragma unroll
             for (int b = 0; b < MAXB; ++b)
                 if (b < B) {
+                    const float av = s_b[b * a.v + row];
 #pragma unroll
-                    for (int c = 0; c < 8; ++c) {
-                        float t = acc[b][c];
-                        t += __shfl_xor(t, 16);
-                        t += __shfl_xor(t, 32);
-                        if (lane < 16) s_red[(wv * MAXB + b) * 128 + pc * 8 + c] = t;
-                    }
+                    for (int c = 0; c < 8; ++c) acc[b][c] = fmaf(av, (float)wor[k][c], acc[b][c]);
                 }
-            lds_sync();
-            for (int i = tid; i < B * 128; i += NT) {
-                const int b = i / 128, cc = i % 128, piece2 = j * pcs + p0 + cc / 8;
-                if (p0 + cc / 8 < pcs && piece2 < dp) {
-                    float sum = 0.f;
+        }
+        lds_sync();
 #pragma unroll
-                    for (int w8 = 0; w8 < NW; ++w8) sum += s_red[(w8 * MAXB + b) * 128 + cc];
-                    cf::team::put(r, a.x6 + ((size_t)b * a.nh + head) * a.D + piece2 * 8 + cc % 8, sum, x.stamp);
+        for (int b = 0; b < MAXB; ++b)
+            if (b < B) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    float t = acc[b][c];
+                    t += __shfl_xor(t, 16);
+                    t += __shfl_xor(t, 32);
+                    if (lane < 16) s_red[(wv * MAXB + b) * 128 + pcE * 8 + c] = t;
                 }
+            }
+        lds_sync();
+        for (int i = tid; i < B * 128; i += NT) {
+            const int b = i / 128, cc = i % 128, piece2 = j * pcsE + p0 + cc / 8;
+            if (p0 + cc / 8 < pcsE && piece2 < dpE) {
+                float sum = 0.f;
+#pragma unroll
+                for (int w8 = 0; w8 < NW; ++w8) sum += s_red[(w8 * MAXB + b) * 128 + cc];
+                cf::team::put(r, a.x6 + ((size_t)b * a.nh + head) * a.D + piece2 * 8 + cc % 8, sum, x.stamp);
             }
         }
     }
@@ -589,7 +574,7 @@ int cf_mla_create(const cf_mla_config *cfg, cf_mla *out)
     const int cq = (CQq / 8 + 15) / 16, ckv = ((L + R) / 8 + 15) / 16;     // 16-byte pieces per column block
     if (c.kv_lora_rank != L || c.rope_dim != R || c.max_batch > MAXB || c.d_model % (2 * KS) || c.d_model / KS > NT ||
         c.v_head_dim % 8 || c.v_head_dim > 128 || cq + ckv > 32 || c.nope_dim % 8 ||
-        c.nope_dim > L || c.d_model > 8 * W || c.d_model % 8)
+        c.nope_dim > 128 || c.d_model > 8 * W || c.d_model % 8)
         return CF_EUNSUPPORTED;
     int dev = 0;
     hipDeviceProp_t prop;
