@@ -183,12 +183,16 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
                 }
             }
         }
+        // (all shuffles of a row first, then the stores: a store between two shuffles makes each one wait for the last)
 #pragma unroll
         for (int b = 0; b < MAXB; ++b)
+            if (b < B) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                acc[b][c] += __shfl_xor(acc[b][c], 32);
-                if (lane < 32 && b < B) s_a[(wv * MAXB + b) * MAXCOLS + pv * 8 + c] = acc[b][c];
+                for (int c = 0; c < 8; ++c) acc[b][c] += __shfl_xor(acc[b][c], 32);
+                if (lane < 32) {
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) s_a[(wv * MAXB + b) * MAXCOLS + pv * 8 + c] = acc[b][c];
+                }
             }
         lds_sync();
         for (int i = tid; i < B * MAXCOLS; i += NT) {
@@ -226,12 +230,16 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         for (int b = 0; b < MAXB; ++b)
             if (b < B) {
                 const float qv2 = rowB < a.n ? s_a[b * a.n + rowB] : 0.f;
+                float t[8];
 #pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    float t = qv2 * (float)wupr[c];
+                for (int c = 0; c < 8; ++c) t[c] = qv2 * (float)wupr[c];
 #pragma unroll
-                    for (int off = 4; off < 64; off <<= 1) t += __shfl_xor(t, off);
-                    if (lane < 4) s_b[(wv * MAXB + b) * LJ + pcB * 8 + c] = t;
+                for (int off = 4; off < 64; off <<= 1)
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) t[c] += __shfl_xor(t[c], off);
+                if (lane < 4) {
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) s_b[(wv * MAXB + b) * LJ + pcB * 8 + c] = t[c];
                 }
             }
         lds_sync();
@@ -442,12 +450,16 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         for (int b = 0; b < MAXB; ++b)
             if (b < B) {
                 const float zv = s_b[b * LJ + rowD];
+                float t[8];
 #pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    float t = zv * (float)wdr[c];
-                    t += __shfl_xor(t, 16);
-                    t += __shfl_xor(t, 32);
-                    if (lane < 16) s_red[(wv * MAXB + b) * 128 + pcD * 8 + c] = t;
+                for (int c = 0; c < 8; ++c) t[c] = zv * (float)wdr[c];
+#pragma unroll
+                for (int c = 0; c < 8; ++c) t[c] += __shfl_xor(t[c], 16);
+#pragma unroll
+                for (int c = 0; c < 8; ++c) t[c] += __shfl_xor(t[c], 32);
+                if (lane < 16) {
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) s_red[(wv * MAXB + b) * 128 + pcD * 8 + c] = t[c];
                 }
             }
         lds_sync();
@@ -506,11 +518,12 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         for (int b = 0; b < MAXB; ++b)
             if (b < B) {
 #pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    float t = acc[b][c];
-                    t += __shfl_xor(t, 16);
-                    t += __shfl_xor(t, 32);
-                    if (lane < 16) s_red[(wv * MAXB + b) * 128 + pcE * 8 + c] = t;
+                for (int c = 0; c < 8; ++c) acc[b][c] += __shfl_xor(acc[b][c], 16);
+#pragma unroll
+                for (int c = 0; c < 8; ++c) acc[b][c] += __shfl_xor(acc[b][c], 32);
+                if (lane < 16) {
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) s_red[(wv * MAXB + b) * 128 + pcE * 8 + c] = acc[b][c];
                 }
             }
         lds_sync();
