@@ -42,6 +42,7 @@ constexpr int kCounterStride = 16;
 constexpr float kNegBig = -1.0e30f;
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 
 struct MlaArgs {
     const uint16_t *x, *wq, *wkv, *wup, *wdown, *wo;
@@ -60,11 +61,26 @@ struct MlaArgs {
 __device__ __forceinline__ float h2f(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
 __device__ __forceinline__ uint16_t f2h(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over the wavefront, the same value in every lane: four data-parallel-primitive steps inside each row of
+// 16 lanes, then the four row totals are read out as scalars (no trip through the LDS crossbar).
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    return v;
+    v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);   // row_half_mirror
+    v += dpp_move<0x140>(v);   // row_mirror
+    const int i = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 48));
+    return (r0 + r1) + (r2 + r3);
 }
 
 // Sum of the n stamped values at idx, idx + stride, ... (in that order); polls go out eight at a time.
@@ -299,41 +315,51 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         }
     for (int b = 0; b < B; ++b) {
         const float *q = s_a + b * (L + R);
-        float ql[8], qr[8];
+        // latent part: lane owns 8 of the 512 dimensions of every row.  Rotary part: the 4 x 64 rotary values of a
+        // batch of four rows are spread over the wavefront, lane -> (row lane / 16, 4 dimensions from 4 * (lane % 16)).
+        float ql[8], qr[8], qr4[4];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             ql[k] = q[lane * 8 + k] * a.scale_log2e;
-            qr[k] = lane < R / 8 ? q[L + lane * 8 + k] * a.scale_log2e : 0.f;
+            qr[k] = lane < R / 8 ? q[L + lane * 8 + k] * a.scale_log2e : 0.f;      // for the new token, below
         }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) qr4[k] = q[L + (lane & 15) * 4 + k] * a.scale_log2e;
         float m = kNegBig, lsum = 0.f, acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         const uint16_t *rows = a.cache + (size_t)b * a.max_seq * (L + R);
         // Four rows of this wavefront per batch, two batches in flight: the next batch is requested before the
         // current one is used (deeper pipelines and larger batches were measured: both are slower).  Rows past the split are read from its last row (finite data) and count for nothing.
         constexpr int UR = 4;
-        h8 kl[2][UR], kr[2][UR];
+        h8 kl[2][UR];
+        h4 kr[2];
         auto request = [&](int buf, int t) {
 #pragma unroll
             for (int u = 0; u < UR; ++u) {
                 const int tt = min(t + u * NW, t1 - 1);
                 kl[buf][u] = *reinterpret_cast<const h8 *>(rows + (size_t)tt * (L + R) + lane * 8);
-                kr[buf][u] = *reinterpret_cast<const h8 *>(rows + (size_t)tt * (L + R) + L + (lane & (R / 8 - 1)) * 8);
             }
+            const int tr = min(t + (lane >> 4) * NW, t1 - 1);
+            kr[buf] = *reinterpret_cast<const h4 *>(rows + (size_t)tr * (L + R) + L + (lane & 15) * 4);
         };
         auto use = [&](int buf, int t) {
-            float d[UR];
+            float kf[UR][8], d[UR];
 #pragma unroll
             for (int u = 0; u < UR; ++u) {
                 float dd = 0.f;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) dd = fmaf(ql[k], (float)kl[buf][u][k], dd);
-#pragma unroll
-                for (int k = 0; k < 8; ++k) dd = fmaf(qr[k], (float)kr[buf][u][k], dd);
+                for (int k = 0; k < 8; ++k) {
+                    kf[u][k] = (float)kl[buf][u][k];
+                    dd = fmaf(ql[k], kf[u][k], dd);
+                }
                 d[u] = dd;
             }
+            float rp = 0.f;
 #pragma unroll
-            for (int off = 32; off > 0; off >>= 1)
+            for (int k = 0; k < 4; ++k) rp = fmaf(qr4[k], (float)kr[buf][k], rp);
 #pragma unroll
-                for (int u = 0; u < UR; ++u) d[u] += __shfl_xor(d[u], off);
+            for (int u = 0; u < UR; ++u) d[u] += (lane >> 4) == u ? rp : 0.f;
+#pragma unroll
+            for (int u = 0; u < UR; ++u) d[u] = wave_sum(d[u]);
             float mn = m;
 #pragma unroll
             for (int u = 0; u < UR; ++u) {
@@ -350,7 +376,7 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
                 const float pw = (t + u * NW < t1) ? __builtin_amdgcn_exp2f(d[u] - mn) : 0.f;
                 lsum += pw;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) acc[k] = fmaf(pw, (float)kl[buf][u][k], acc[k]);
+                for (int k = 0; k < 8; ++k) acc[k] = fmaf(pw, kf[u][k], acc[k]);
             }
         };
         if (t1 > t0) {                                                 // uniform over the workgroup
