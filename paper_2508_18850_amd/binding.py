@@ -269,6 +269,9 @@ class MlaBlock:
     def algorithmic_bytes(self, batch, pos) -> int:
         return int(self._lib.cf_mla_algorithmic_bytes(ctypes.byref(self.cfg), batch, pos))
 
+    def set_spin_limit(self, us):
+        self._check(self._lib.cf_mla_set_spin_limit(self._h, us))
+
     def close(self):
         if self._h:
             self._lib.cf_mla_destroy(self._h)
