@@ -83,24 +83,26 @@ __device__ __forceinline__ float wave_sum(float v)
     return (r0 + r1) + (r2 + r3);
 }
 
-// Sum of the n stamped values at idx, idx + stride, ... (in that order); polls go out eight at a time.
+// Sum of the n stamped values at idx, idx + stride, ... (in that order); polls go out sixteen at a time (the
+// teams and the row slices have 16 members: one round trip).
 __device__ __forceinline__ float take_sum(const Exchange &x, __amdgpu_buffer_rsrc_t r, size_t idx, size_t stride, int n)
 {
+    constexpr int NP = 16;
     float s = 0.f;
-    for (int k0 = 0; k0 < n; k0 += 8) {
-        pair_t q[8];
+    for (int k0 = 0; k0 < n; k0 += NP) {
+        pair_t q[NP];
         long long t0 = 0;
         for (;;) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) q[k] = cf::team::peek(r, idx + (size_t)min(k0 + k, n - 1) * stride);
+            for (int k = 0; k < NP; ++k) q[k] = cf::team::peek(r, idx + (size_t)min(k0 + k, n - 1) * stride);
             __builtin_amdgcn_sched_barrier(0);
             bool ok = true;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) ok &= q[k].y == x.stamp;
+            for (int k = 0; k < NP; ++k) ok &= q[k].y == x.stamp;
             if (ok || cf::team::gave_up(x, t0)) break;
         }
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
+        for (int k = 0; k < NP; ++k)
             if (k0 + k < n) s += __builtin_bit_cast(float, q[k].x);
     }
     return s;
@@ -273,10 +275,12 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     const bool last = j == TS - 1;
     const int tps = (a.pos + TS - 1) / TS;
     const int t0 = min(j * tps, a.pos), t1 = min(t0 + tps, a.pos);
-    // s_a: [B][L + R] the query in the latent space and its rotated rotary part; s_b: [B][L + R] the new row
-    for (int i = tid; i < B * L; i += NT) {
-        const int b = i / L, d = i % L;
-        s_a[b * (L + R) + d] = take1(x, r, a.x2 + ((size_t)b * a.nh + head) * L + d);
+    // s_a: [B][L + R] the query in the latent space and its rotated rotary part; s_b: [B][L + R] the new row.
+    // First what has been there since stage A (the rotary part of the query, the new row) and the angles, last the
+    // latent query, which the other members of the team are still producing.
+    if (tid < R / 2) {
+        const double inv_freq = exp2(-2.0 * (double)tid / (double)R * a.log2_base);
+        cf::rope_cos_sin(a.pos, inv_freq, s_small[tid], s_small[R / 2 + tid]);
     }
     for (int i = tid; i < B * R; i += NT) {
         const int b = i / R, d = i % R;
@@ -287,9 +291,9 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
             const int b = i / (L + R), d = i % (L + R);
             s_b[i] = take_sum(x, r, a.x1 + (size_t)b * CQ + CQq + d, (size_t)B * CQ, KS);
         }
-    if (tid < R / 2) {
-        const double inv_freq = exp2(-2.0 * (double)tid / (double)R * a.log2_base);
-        cf::rope_cos_sin(a.pos, inv_freq, s_small[tid], s_small[R / 2 + tid]);
+    for (int i = tid; i < B * L; i += NT) {
+        const int b = i / L, d = i % L;
+        s_a[b * (L + R) + d] = take1(x, r, a.x2 + ((size_t)b * a.nh + head) * L + d);
     }
     lds_sync();
     for (int i = tid; i < B * (R / 2); i += NT) {                     // RoPE on the rotary parts (pairs d, d + R/2)
