@@ -39,6 +39,8 @@ constexpr int MAXB = 4;             // largest batch
 constexpr int MAXCOLS = 256;        // projection columns per column block
 constexpr int MAXA = 2048;          // n_heads * v_head_dim
 constexpr int kCounterStride = 16;
+constexpr int NPART = NW * 4;       // attention partials of a workgroup: four row groups per wavefront
+constexpr size_t kDynLds = (size_t)NPART * (L + 2) * sizeof(float);
 constexpr float kNegBig = -1.0e30f;
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -138,6 +140,7 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     __shared__ float s_a[MAXB * MAXA];                  // stage buffers, reused from stage to stage
     __shared__ float s_b[MAXB * (L + R)];
     __shared__ float s_red[NW * (L + 2)];
+    extern __shared__ float s_part[];                   // [NPART][L + 2] attention partials of the row groups (dynamic)
     __shared__ float s_small[R + MAXB];                 // cos, sin of the rotary angles; score of the new token per row
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, w = blockIdx.x;
     const int head = w / TS, j = w % TS;
@@ -319,107 +322,131 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         }
     for (int b = 0; b < B; ++b) {
         const float *q = s_a + b * (L + R);
-        // latent part: lane owns 8 of the 512 dimensions of every row.  Rotary part: the 4 x 64 rotary values of a
-        // batch of four rows are spread over the wavefront, lane -> (row lane / 16, 4 dimensions from 4 * (lane % 16)).
-        float ql[8], qr[8], qr4[4];
+        // A row of the cache is handled by 16 lanes (a wavefront takes four rows at a time): lane li of a row group
+        // owns the latent dimensions 128 k + 8 li .. + 8 (k < 4) and the rotary dimensions 4 li .. + 4, so a row's
+        // score needs only the four in-row steps of a cross-lane sum and one exponential serves 36 multiply-adds.
+        const int li = lane & 15, rg = lane >> 4;
+        float ql[4][8], qr4[4];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            ql[k] = q[lane * 8 + k] * a.scale_log2e;
-            qr[k] = lane < R / 8 ? q[L + lane * 8 + k] * a.scale_log2e : 0.f;      // for the new token, below
-        }
+        for (int k = 0; k < 4; ++k)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) qr4[k] = q[L + (lane & 15) * 4 + k] * a.scale_log2e;
-        float m = kNegBig, lsum = 0.f, acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int c = 0; c < 8; ++c) ql[k][c] = q[128 * k + 8 * li + c] * a.scale_log2e;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) qr4[c] = q[L + 4 * li + c] * a.scale_log2e;
+        float m = kNegBig, lsum = 0.f, acc[4][8];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[k][c] = 0.f;
         const uint16_t *rows = a.cache + (size_t)b * a.max_seq * (L + R);
-        // Four rows of this wavefront per batch, two batches in flight: the next batch is requested before the
-        // current one is used (deeper pipelines and larger batches were measured: both are slower).  Rows past the split are read from its last row (finite data) and count for nothing.
-        constexpr int UR = 4;
-        h8 kl[2][UR];
-        h4 kr[2];
+        // Two rows per row group and batch, two batches in flight.  Rows past the split are read from its last row
+        // (finite data) and count for nothing.
+        constexpr int UR = 4, RPB = NW * 4;                            // rows of the workgroup per sub-batch
+        h8 kl[2][UR][4];
+        h4 kr[2][UR];
+        const int myrow = wv * 4 + rg;
         auto request = [&](int buf, int t) {
 #pragma unroll
             for (int u = 0; u < UR; ++u) {
-                const int tt = min(t + u * NW, t1 - 1);
-                kl[buf][u] = *reinterpret_cast<const h8 *>(rows + (size_t)tt * (L + R) + lane * 8);
+                const uint16_t *row = rows + (size_t)min(t + myrow + u * RPB, t1 - 1) * (L + R);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) kl[buf][u][k] = *reinterpret_cast<const h8 *>(row + 128 * k + 8 * li);
+                kr[buf][u] = *reinterpret_cast<const h4 *>(row + L + 4 * li);
             }
-            const int tr = min(t + (lane >> 4) * NW, t1 - 1);
-            kr[buf] = *reinterpret_cast<const h4 *>(rows + (size_t)tr * (L + R) + L + (lane & 15) * 4);
         };
         auto use = [&](int buf, int t) {
-            float kf[UR][8], d[UR];
+            float d[UR];
 #pragma unroll
             for (int u = 0; u < UR; ++u) {
                 float dd = 0.f;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    kf[u][k] = (float)kl[buf][u][k];
-                    dd = fmaf(ql[k], kf[u][k], dd);
-                }
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) dd = fmaf(ql[k][c], (float)kl[buf][u][k][c], dd);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) dd = fmaf(qr4[c], (float)kr[buf][u][c], dd);
                 d[u] = dd;
             }
-            float rp = 0.f;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) rp = fmaf(qr4[k], (float)kr[buf][k], rp);
-#pragma unroll
-            for (int u = 0; u < UR; ++u) d[u] += (lane >> 4) == u ? rp : 0.f;
-#pragma unroll
-            for (int u = 0; u < UR; ++u) d[u] = wave_sum(d[u]);
+            for (int u = 0; u < UR; ++u) {                             // sum over the 16 lanes of the row
+                d[u] += dpp_move<0xB1>(d[u]);
+                d[u] += dpp_move<0x4E>(d[u]);
+                d[u] += dpp_move<0x141>(d[u]);
+                d[u] += dpp_move<0x140>(d[u]);
+            }
             float mn = m;
 #pragma unroll
             for (int u = 0; u < UR; ++u) {
-                d[u] = (t + u * NW < t1) ? d[u] : kNegBig;
+                d[u] = (t + myrow + u * RPB < t1) ? d[u] : kNegBig;
                 mn = fmaxf(mn, d[u]);
             }
             const float f = __builtin_amdgcn_exp2f(m - mn);
             m = mn;
             lsum *= f;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) acc[k] *= f;
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int c = 0; c < 8; ++c) acc[k][c] *= f;
 #pragma unroll
             for (int u = 0; u < UR; ++u) {
-                const float pw = (t + u * NW < t1) ? __builtin_amdgcn_exp2f(d[u] - mn) : 0.f;
+                const float pw = (t + myrow + u * RPB < t1) ? __builtin_amdgcn_exp2f(d[u] - mn) : 0.f;
                 lsum += pw;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) acc[k] = fmaf(pw, kf[u][k], acc[k]);
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) acc[k][c] = fmaf(pw, (float)kl[buf][u][k][c], acc[k][c]);
             }
         };
         if (t1 > t0) {                                                 // uniform over the workgroup
-            constexpr int step = NW * UR;
-            request(0, t0 + wv);
-            for (int t = t0 + wv; t < t1; t += 2 * step) {
+            constexpr int step = RPB * UR;
+            request(0, t0);
+            for (int t = t0; t < t1; t += 2 * step) {
                 request(1, t + step);
                 use(0, t);
                 request(0, t + 2 * step);
                 use(1, t + step);
             }
         }
+        MLA_STAMP(11);          // rows consumed
+        // every row group of every wavefront leaves its (m, l, acc) in LDS: 32 partials, folded below
         lds_sync();
-        if (lane == 0) {
-            s_red[wv * (L + 2)] = m;
-            s_red[wv * (L + 2) + 1] = lsum;
-        }
+        {
+            float *part = s_part + (wv * 4 + rg) * (L + 2);
+            if (li == 0) {
+                part[0] = m;
+                part[1] = lsum;
+            }
 #pragma unroll
-        for (int k = 0; k < 8; ++k) s_red[wv * (L + 2) + 2 + lane * 8 + k] = acc[k];
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int c = 0; c < 8; ++c) part[2 + 128 * k + 8 * li + c] = acc[k][c];
+        }
+        MLA_STAMP(12);          // row groups merged
         if (last && wv == 0) {                                        // score of the new token (its row is not rounded)
             const float *kn = s_b + b * (L + R);
             float d = 0.f;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) d = fmaf(ql[k], kn[lane * 8 + k], d);
+            for (int k = 0; k < 4; ++k)
 #pragma unroll
-            for (int k = 0; k < 8; ++k) d = fmaf(qr[k], kn[L + (lane & (R / 8 - 1)) * 8 + k], d);
-            d = wave_sum(d);
+                for (int c = 0; c < 8; ++c) d = fmaf(ql[k][c], kn[128 * k + 8 * li + c], d);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) d = fmaf(qr4[c], kn[L + 4 * li + c], d);
+            d += dpp_move<0xB1>(d);
+            d += dpp_move<0x4E>(d);
+            d += dpp_move<0x141>(d);
+            d += dpp_move<0x140>(d);
             if (lane == 0) s_small[R + b] = d;
         }
         lds_sync();
         {
             const int d = tid;                                         // one latent dimension per thread
             float M = last ? s_small[R + b] : kNegBig;
-            for (int w8 = 0; w8 < NW; ++w8) M = fmaxf(M, s_red[w8 * (L + 2)]);
+            for (int w8 = 0; w8 < NPART; ++w8) M = fmaxf(M, s_part[w8 * (L + 2)]);
             float Ls = 0.f, A = 0.f;
-            for (int w8 = 0; w8 < NW; ++w8) {
-                const float f = __builtin_amdgcn_exp2f(s_red[w8 * (L + 2)] - M);
-                Ls = fmaf(s_red[w8 * (L + 2) + 1], f, Ls);
-                A = fmaf(s_red[w8 * (L + 2) + 2 + d], f, A);
+            for (int w8 = 0; w8 < NPART; ++w8) {
+                const float f = __builtin_amdgcn_exp2f(s_part[w8 * (L + 2)] - M);
+                Ls = fmaf(s_part[w8 * (L + 2) + 1], f, Ls);
+                A = fmaf(s_part[w8 * (L + 2) + 2 + d], f, A);
             }
             if (last) {
                 const float f = __builtin_amdgcn_exp2f(s_small[R + b] - M);
@@ -624,7 +651,9 @@ int cf_mla_create(const cf_mla_config *cfg, cf_mla *out)
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return CF_EHIP;
     if (W > prop.multiProcessorCount) return CF_EUNSUPPORTED;        // all workgroups resident, one per compute unit
     int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fused_mla_decode), NT, 0) !=
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(fused_mla_decode), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)kDynLds) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fused_mla_decode), NT, kDynLds) !=
             hipSuccess || per_cu < 1)
         return CF_EUNSUPPORTED;
     cf_mla t = new (std::nothrow) cf_mla_s();
@@ -699,7 +728,7 @@ int cf_mla_decode(cf_mla t, int32_t batch, const void *x, const void *W_q, const
     a.scale_log2e = 1.4426950408889634f / std::sqrt((float)(c.nope_dim + R));
     a.log2_base = std::log2((double)c.rope_base);
     a.spin_ticks = t->spin_ticks;
-    hipLaunchKernelGGL(fused_mla_decode, dim3(t->W), dim3(NT), 0, static_cast<hipStream_t>(stream), a);
+    hipLaunchKernelGGL(fused_mla_decode, dim3(t->W), dim3(NT), kDynLds, static_cast<hipStream_t>(stream), a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         t->last_hip = (int)e;
