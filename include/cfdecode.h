@@ -171,7 +171,8 @@ int cf_debug_export(cf_handle h, int32_t what, void *host_dst, size_t bytes, voi
 /*
  * Tuning knobs (all optional; 0 keeps the default): workgroups per launch,
  * split count of the projection's reduction dimension, split count of the KV
- * sequence, spin limit of the in-kernel waits in microseconds.  Alg. 3's
+ * sequence, spin limit of the in-kernel waits in microseconds (-1: every wait gives up at its first
+ * unsuccessful look, which makes any launch report CF_ETIMEOUT: for tests of the error path).  Alg. 3's
  * "cluster size" corresponds to workgroups / n_kv_heads.  Returns CF_EINVAL for
  * values the shape cannot use.  A change of the workgroup count waits for the
  * device and clears the workspace, so call it between steps, not inside a hot loop.
@@ -239,6 +240,8 @@ int cf_team_gather(cf_team t, int32_t teams, int32_t team_size, const float *in,
 /* Wait for `stream`; CF_ETIMEOUT if a rank gave up waiting for a peer since the last call (the exchange
  * area is cleared then). */
 int cf_team_status(cf_team t, void *stream);
+/* Limit of the in-kernel waits in microseconds; 0: every wait gives up at its first unsuccessful look (any launch then
+ * reports CF_ETIMEOUT: for tests of the error path). */
 int cf_team_set_spin_limit(cf_team t, int32_t spin_limit_us);
 
 /* ------------------------------------------------------------------------------------------------
@@ -273,7 +276,7 @@ int cf_mla_destroy(cf_mla t);
 int cf_mla_decode(cf_mla t, int32_t batch, const void *x, const void *W_q, const void *W_kv, const void *W_up,
                   const void *W_down, const void *W_o, void *kv_cache, int32_t pos, void *out, void *stream);
 int cf_mla_status(cf_mla t, void *stream);
-int cf_mla_set_spin_limit(cf_mla t, int32_t spin_limit_us);
+int cf_mla_set_spin_limit(cf_mla t, int32_t spin_limit_us);   /* as cf_team_set_spin_limit */
 /* Algorithmic HBM bytes of one call (all weights + cached rows + appended rows + x + out). */
 int64_t cf_mla_algorithmic_bytes(const cf_mla_config *cfg, int32_t batch, int32_t pos);
 

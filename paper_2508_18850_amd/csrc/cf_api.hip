@@ -442,7 +442,7 @@ int cf_debug_export(cf_handle h, int32_t what, void *host_dst, size_t bytes, voi
 
 int cf_set_tuning(cf_handle h, int32_t workgroups, int32_t k_splits, int32_t kv_splits, int32_t spin_limit_us)
 {
-    if (!h || workgroups < 0 || k_splits < 0 || kv_splits < 0 || spin_limit_us < 0) return CF_EINVAL;
+    if (!h || workgroups < 0 || k_splits < 0 || kv_splits < 0 || spin_limit_us < -1) return CF_EINVAL;
     auto pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
     if (workgroups && (workgroups % h->cfg.n_kv_heads || workgroups > 8 * h->num_cu)) return CF_EINVAL;
     if (k_splits > kMaxKS) return CF_EINVAL;
@@ -458,7 +458,7 @@ int cf_set_tuning(cf_handle h, int32_t workgroups, int32_t k_splits, int32_t kv_
     h->tune_ks = k_splits;
     h->tune_ns = kv_splits;
     for (int &v : h->wg_per_cu) v = 0;   // LDS size may change: probe residency again
-    if (spin_limit_us) h->spin_ticks = (long long)spin_limit_us * 100;
+    if (spin_limit_us) h->spin_ticks = spin_limit_us < 0 ? 0 : (long long)spin_limit_us * 100;
     return CF_OK;
 }
 

@@ -161,7 +161,7 @@ struct Spin {
         __builtin_amdgcn_s_sleep(1);
         const long long now = wall_clock64();
         if (t0 == 0) t0 = now;
-        if (now - t0 > (long long)p.spin_ticks) {
+        if (now - t0 >= (long long)p.spin_ticks) {            // a limit of 0 gives up at the first failed look
             __hip_atomic_store(p.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return true;
         }

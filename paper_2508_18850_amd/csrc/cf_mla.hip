@@ -767,7 +767,7 @@ int cf_mla_trace_read(void *host_dst)
 
 int cf_mla_set_spin_limit(cf_mla t, int32_t spin_limit_us)
 {
-    if (!t || spin_limit_us < 1) return CF_EINVAL;
+    if (!t || spin_limit_us < 0) return CF_EINVAL;
     t->spin_ticks = (long long)spin_limit_us * 100;
     return CF_OK;
 }

@@ -390,7 +390,7 @@ int cf_team_status(cf_team t, void *stream)
 
 int cf_team_set_spin_limit(cf_team t, int32_t spin_limit_us)
 {
-    if (!t || spin_limit_us < 1) return CF_EINVAL;
+    if (!t || spin_limit_us < 0) return CF_EINVAL;
     t->spin_ticks = (long long)spin_limit_us * 100;
     return CF_OK;
 }

@@ -39,7 +39,7 @@ struct Exchange {
     size_t cap;          // pairs per inbox
     uint32_t stamp;      // stamp of this launch, never 0
     uint32_t *err;       // set to 1 when a wait gave up
-    long long spin_ticks;    // give up after this many ticks of the 100 MHz wall clock
+    long long spin_ticks;    // give up after this many ticks of the 100 MHz wall clock (0: at the first failed look)
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t slots_rsrc(const Exchange &x)
@@ -64,7 +64,7 @@ __device__ __forceinline__ bool gave_up(const Exchange &x, long long &t0)
     __builtin_amdgcn_s_sleep(1);
     const long long now = wall_clock64();
     if (t0 == 0) t0 = now;
-    if (now - t0 > x.spin_ticks) {
+    if (now - t0 >= x.spin_ticks) {                 // a limit of 0 gives up at the first failed look
         __hip_atomic_store(x.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return true;
     }

@@ -233,7 +233,7 @@ def _device_case(shape, batch, kv_len, seed):
 
 
 def test_spin_limit_reports_timeout_and_handle_recovers():
-    """A spin limit far below the time a partner needs makes the bounded waits give up: the kernel
+    """A spin limit of zero makes the bounded waits give up at their first unsuccessful look: the kernel
     still ends, cf_status reports CF_ETIMEOUT, and the next call on the same handle is correct."""
     from paper_2508_18850_amd import DecodeBlock, CfError
     shape = cf_inputs.SHAPES["llama2_7b"]
@@ -243,8 +243,8 @@ def test_spin_limit_reports_timeout_and_handle_recovers():
                       shape.rope_base)
     args = (1, t["x"].data_ptr(), t["w_qkv"].data_ptr(), t["w_o"].data_ptr(), t["k_cache"].data_ptr(),
             t["v_cache"].data_ptr(), L, out.data_ptr(), 0)
-    blk.set_tuning(0, 0, 0, 1)                    # 1 microsecond
-    _log("launch with a 1 us spin limit")
+    blk.set_tuning(0, 0, 0, -1)                   # give up at the first failed look
+    _log("launch with a zero spin limit")
     blk.decode_block(*args)
     with pytest.raises(CfError) as ei:
         blk.status()
