@@ -15,7 +15,8 @@
 //   E1 output projection  rows of W_O of head i, 1/16 of the output columns per member: a partial of out per head
 //   E2 sum over heads     every workgroup: 1/W of the output columns (the paper's atomicAdd)
 //
-// A first version: nothing is prefetched across the hops yet.  All waits are bounded (CF_ETIMEOUT), all workgroups have to be resident at once.
+// Each stage requests its weights before it waits for its input.  All waits are bounded (CF_ETIMEOUT), all
+// workgroups have to be resident at once.
 #include "../../include/cfdecode.h"
 #include "cf_rope_device.h"
 #include "cf_team_device.h"
@@ -33,11 +34,11 @@ constexpr int NT = 512;             // threads per workgroup
 constexpr int NW = NT / 64;
 constexpr int TS = 16;              // workgroups per head (team)
 constexpr int KS = 16;              // row slices of the projections
-constexpr int L = 512;              // kv_lora_rank the lane mapping is written for: 64 lanes x 8 values
-constexpr int R = 64;               // rope_dim: 8 lanes x 8 values
+constexpr int L = 512;              // kv_lora_rank the lane mapping is written for: 16 lanes x 32 values per cached row
+constexpr int R = 64;               // rope_dim: 16 lanes x 4 values
 constexpr int MAXB = 4;             // largest batch
 constexpr int MAXCOLS = 256;        // projection columns per column block
-constexpr int MAXA = 2048;          // n_heads * v_head_dim
+constexpr int MAXA = 2048;          // floats of the largest stage buffer per batch row
 constexpr int kCounterStride = 16;
 constexpr int NPART = NW * 4;       // attention partials of a workgroup: four row groups per wavefront
 constexpr size_t kDynLds = (size_t)NPART * (L + 2) * sizeof(float);
