@@ -708,9 +708,16 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
     float *kn = qs + G * HD;                // [HD] rotated new key
     float *vn = kn + HD;                    // [HD] new value
     float *snew = vn + HD;                  // [8]  scores of the new token, log2 domain
-    float *redm = snew + 8;                 // [G][NW]
-    float *redl = redm + G * NW;            // [G][NW]
-    float *redacc = redl + G * NW;          // [G][NW][HD]
+    // Partials that are folded through LDS: one per wavefront (its row groups merged by shuffles first), or, for
+    // groups of 8 heads, one per row group: there the shuffle merge of 10 values per head and step runs on
+    // spilled registers and costs more than the larger fold (measured: 70B shape 111 -> 105 us; with 4 heads
+    // per group the shuffle merge is the faster one, 32.1 against 35.1 us).
+    constexpr int RGW = 64 / LPR;                               // row groups of a wavefront
+    constexpr bool kFoldRowGroups = G >= 8;
+    constexpr int NPART = kFoldRowGroups ? NW * RGW : NW;
+    float *redm = snew + 8;                 // [G][NPART]
+    float *redl = redm + G * NPART;         // [G][NPART]
+    float *redacc = redl + G * NPART;       // [G][NPART][HD]
     const int t0 = st.t0, t1 = st.t1, iters = st.iters;
 
     // ---- sum the projection partials of the team (the gather of Alg. 3 step 3): q heads, and for
@@ -836,32 +843,46 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
     // store and the next phase's polls wait for every bulk load issued before them.)  The member with
     // the last split first polls for the new token's key/value sums, for the same reason.
     if (!last) issue_next(1);
-    // ---- merge the row groups of a wavefront
-#pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) {
+    if (kFoldRowGroups) {
+        // ---- every row group leaves its partial in LDS
+        const int part = wv * RGW + (lane / LPR);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const float mo = __shfl_xor(m[g], off), lo = __shfl_xor(l[g], off);
-            const float mn = fmaxf(m[g], mo);
-            const float sa = __builtin_amdgcn_exp2f(m[g] - mn), sb = __builtin_amdgcn_exp2f(mo - mn);
-            l[g] = l[g] * sa + lo * sb;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float ao = __shfl_xor(acc[g][j], off);
-                acc[g][j] = acc[g][j] * sa + ao * sb;
+            if (lig == 0) {
+                redm[g * NPART + part] = m[g];
+                redl[g * NPART + part] = l[g];
             }
-            m[g] = mn;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) redacc[(g * NPART + part) * HD + lig * 8 + j] = acc[g][j];
         }
-    }
-    if (lane < LPR) {
+    } else {
+        // ---- merge the row groups of a wavefront
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            if (lane == 0) {
-                redm[g * NW + wv] = m[g];
-                redl[g * NW + wv] = l[g];
+        for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float mo = __shfl_xor(m[g], off), lo = __shfl_xor(l[g], off);
+                const float mn = fmaxf(m[g], mo);
+                const float sa = __builtin_amdgcn_exp2f(m[g] - mn), sb = __builtin_amdgcn_exp2f(mo - mn);
+                l[g] = l[g] * sa + lo * sb;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float ao = __shfl_xor(acc[g][j], off);
+                    acc[g][j] = acc[g][j] * sa + ao * sb;
+                }
+                m[g] = mn;
             }
+        }
+        if (lane < LPR) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) redacc[(g * NW + wv) * HD + lig * 8 + j] = acc[g][j];
+            for (int g = 0; g < G; ++g) {
+                if (lane == 0) {
+                    redm[g * NPART + wv] = m[g];
+                    redl[g * NPART + wv] = l[g];
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) redacc[(g * NPART + wv) * HD + lig * 8 + j] = acc[g][j];
+            }
         }
     }
     CF_STAMP(8);            // row groups of the wavefront merged
@@ -904,13 +925,13 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
         const int g = e / HD, c = e - g * HD;
         float M = last ? snew[g] : kNegBig;
 #pragma unroll
-        for (int w8 = 0; w8 < NW; ++w8) M = fmaxf(M, redm[g * NW + w8]);
+        for (int w8 = 0; w8 < NPART; ++w8) M = fmaxf(M, redm[g * NPART + w8]);
         float L = 0.f, A = 0.f;
 #pragma unroll
-        for (int w8 = 0; w8 < NW; ++w8) {
-            const float f = __builtin_amdgcn_exp2f(redm[g * NW + w8] - M);
-            L = fmaf(redl[g * NW + w8], f, L);
-            A = fmaf(redacc[(g * NW + w8) * HD + c], f, A);
+        for (int w8 = 0; w8 < NPART; ++w8) {
+            const float f = __builtin_amdgcn_exp2f(redm[g * NPART + w8] - M);
+            L = fmaf(redl[g * NPART + w8], f, L);
+            A = fmaf(redacc[(g * NPART + w8) * HD + c], f, A);
         }
         if (last) {
             const float f = __builtin_amdgcn_exp2f(snew[g] - M);
@@ -1392,7 +1413,8 @@ size_t lds_floats(const Params &p, int hd, int g, int bt)
     const size_t rb = bt < 4 ? bt : 4;
     const size_t maxi = bt == 1 ? 4 : (bt <= 4 ? 2 : 1);
     const size_t f1 = (size_t)bt * p.RPS + maxi * kWaves * bt * hd + (size_t)kWaves * bt;
-    const size_t f2 = (size_t)hd + (size_t)(g + 2) * hd + 8 + 2 * (size_t)g * kWaves + (size_t)g * kWaves * hd;
+    const size_t npart = g >= 8 ? (size_t)kWaves * (64 / (hd / 8)) : kWaves;      // attention partials folded through LDS
+    const size_t f2 = (size_t)hd + (size_t)(g + 2) * hd + 8 + 2 * (size_t)g * npart + (size_t)g * npart * hd;
     const size_t f3 = (size_t)bt * hd + (size_t)kWaves * rb * kOutChunk;
     size_t f = f1 > f2 ? f1 : f2;
     return f > f3 ? f : f3;
