@@ -266,8 +266,9 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     constexpr int LPR = HD / 8;
     constexpr int NG = NT / LPR;
     // loads per thread and batch: the 16-row batch tile keeps 128 accumulators per thread, and anything above two
-    // loads per batch spills (measured on the 8B shape, batch 16: 202 us with 8, 181 with 4, 177 with 2)
-    constexpr int U = BT > 4 ? 2 : 8;
+    // loads per batch spills (measured on the 8B shape, batch 16: 202 us with 8, 181 with 4, 177 with 2, 182 with 1);
+    // the 4-row tile is best with 4 (8B shape, batch 4: 55.1 us with 8, 53.6 with 4, 53.7 with 2)
+    constexpr int U = BT > 4 ? 2 : (BT == 4 ? 4 : 8);
     constexpr int MAXI = BT == 1 ? 4 : (BT <= 4 ? 2 : 1);   // selectors whose wave partials are buffered in LDS
     const int tid = threadIdx.x, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
     const int ks = qmod(member, p.KS, p.sh_ks);
