@@ -280,6 +280,37 @@ int cf_mla_set_spin_limit(cf_mla t, int32_t spin_limit_us);   /* as cf_team_set_
 /* Algorithmic HBM bytes of one call (all weights + cached rows + appended rows + x + out). */
 int64_t cf_mla_algorithmic_bytes(const cf_mla_config *cfg, int32_t batch, int32_t pos);
 
+/* ------------------------------------------------------------------------------------------------
+ * The SplitHead dataflow (paper Appendix B, Alg. 5) of the decode step of cf_decode_block: the same operation on
+ * the same tensors, with the work divided the other way, as the ablation the paper measures against its
+ * SplitToken dataflow (Alg. 3).  A head is a team of `team_size` workgroups (Alg. 5's cluster of N blocks) that
+ * split the head dimension in the projection, the attention and the output projection; the partial scores of all
+ * tokens and the partial output projection are summed over the team (Alg. 5's two ClusterReduce), the heads are
+ * summed with atomicAdd.  One kernel per call.
+ *
+ * cf_splithead_create: cfg as for cf_create.  Written for batch 1 (max_batch == 1), n_kv_heads == n_q_heads,
+ *   head_dim 64 or 128, team_size 2, 4 or 8 with head_dim % (16 * team_size) == 0, n_q_heads * team_size not above
+ *   the number of compute units, and (d_model + max_seq + 64) * 4 bytes of LDS at most 150 KiB (the scores of all
+ *   tokens stay on chip): CF_EUNSUPPORTED otherwise.  Allocates and clears the exchange workspace; synchronous.
+ * cf_splithead_pack: one-time rearrangement of W_qkv [d_model, 3 * n_q_heads * head_dim] (as for cf_decode_block)
+ *   into W_qkv_members (same size, caller-owned, must not overlap), where the columns of every team member are
+ *   contiguous: [head][member][d_model][q lo | q hi | k lo | k hi | v lo | v hi], each part head_dim / (2 *
+ *   team_size) values, "lo" the member's dimensions below head_dim / 2 and "hi" their RoPE partners.  Asynchronous.
+ * cf_splithead_decode: x [1, d_model], W_o, k_cache, v_cache [1, n_heads, max_seq, head_dim], pos and out [1,
+ *   d_model] as for cf_decode_block (rows < pos read, row pos written).  Asynchronous on `stream`, no allocation.
+ *   The stamp of a launch is counted on the host, so a captured launch must not be replayed.  The order of the
+ *   atomic additions, and with it the last bits of the result, is not fixed.
+ * cf_splithead_status / cf_splithead_set_spin_limit: as cf_team_status / cf_team_set_spin_limit.
+ */
+typedef struct cf_splithead_s *cf_splithead;
+int cf_splithead_create(const cf_config *cfg, int32_t team_size, cf_splithead *out);
+int cf_splithead_destroy(cf_splithead t);
+int cf_splithead_pack(cf_splithead t, const void *W_qkv, void *W_qkv_members, void *stream);
+int cf_splithead_decode(cf_splithead t, const void *x, const void *W_qkv_members, const void *W_o, void *k_cache,
+                        void *v_cache, int32_t pos, void *out, void *stream);
+int cf_splithead_status(cf_splithead t, void *stream);
+int cf_splithead_set_spin_limit(cf_splithead t, int32_t spin_limit_us);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,9 @@ EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_blo
                     "cf_team_create", "cf_team_destroy", "cf_team_reduce", "cf_team_gather", "cf_team_status",
                     "cf_team_set_spin_limit",
                     "cf_mla_create", "cf_mla_destroy", "cf_mla_decode", "cf_mla_status", "cf_mla_set_spin_limit",
-                    "cf_mla_algorithmic_bytes")
+                    "cf_mla_algorithmic_bytes",
+                    "cf_splithead_create", "cf_splithead_destroy", "cf_splithead_pack", "cf_splithead_decode",
+                    "cf_splithead_status", "cf_splithead_set_spin_limit")
 
 CF_FLAG_DEBUG_EXPORT = 1
 
@@ -85,6 +87,15 @@ def load_library():
         lib.cf_mla_set_spin_limit.argtypes = [vp, i32]
         lib.cf_mla_algorithmic_bytes.argtypes = [ctypes.POINTER(MlaConfig), i32, i32]
         lib.cf_mla_algorithmic_bytes.restype = ctypes.c_int64
+        lib.cf_splithead_create.argtypes = [ctypes.POINTER(CfConfig), i32, ctypes.POINTER(vp)]
+        lib.cf_splithead_destroy.argtypes = [vp]
+        lib.cf_splithead_pack.argtypes = [vp, vp, vp, vp]
+        lib.cf_splithead_decode.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp]
+        lib.cf_splithead_status.argtypes = [vp, vp]
+        lib.cf_splithead_set_spin_limit.argtypes = [vp, i32]
+        for name in ("cf_splithead_create", "cf_splithead_destroy", "cf_splithead_pack", "cf_splithead_decode",
+                     "cf_splithead_status", "cf_splithead_set_spin_limit"):
+            getattr(lib, name).restype = ctypes.c_int
         for name in ("cf_team_create", "cf_team_destroy", "cf_team_reduce", "cf_team_gather", "cf_team_status",
                      "cf_team_set_spin_limit",
                     "cf_mla_create", "cf_mla_destroy", "cf_mla_decode", "cf_mla_status", "cf_mla_set_spin_limit",
@@ -275,6 +286,50 @@ class MlaBlock:
     def close(self):
         if self._h:
             self._lib.cf_mla_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class SplitHeadBlock:
+    """Handle of the SplitHead variant of the decode block (cf_splithead_*): batch 1, one KV head per query head.
+    Tensors are raw device addresses of fp16 data."""
+
+    def __init__(self, d_model, n_heads, head_dim, max_seq, rope_base, team_size):
+        self._lib = load_library()
+        self.cfg = CfConfig(d_model, n_heads, n_heads, head_dim, 1, max_seq, rope_base, 0)
+        self.team_size = int(team_size)
+        self._h = ctypes.c_void_p()
+        self._check(self._lib.cf_splithead_create(ctypes.byref(self.cfg), self.team_size, ctypes.byref(self._h)))
+
+    def _check(self, rc):
+        if rc != 0:
+            raise CfError(rc, self._lib.cf_strerror(rc).decode())
+
+    def pack(self, w_qkv, w_qkv_members, stream=0):
+        self._check(self._lib.cf_splithead_pack(self._h, w_qkv, w_qkv_members, stream))
+
+    def decode(self, x, w_qkv_members, w_o, k_cache, v_cache, pos, out, stream=0):
+        rc = self._lib.cf_splithead_decode(self._h, x, w_qkv_members, w_o, k_cache, v_cache, pos, out, stream)
+        if rc != 0:
+            self._check(rc)
+
+    def decode_rc(self, x, w_qkv_members, w_o, k_cache, v_cache, pos, out, stream=0) -> int:
+        return int(self._lib.cf_splithead_decode(self._h, x, w_qkv_members, w_o, k_cache, v_cache, pos, out, stream))
+
+    def status(self, stream=0):
+        self._check(self._lib.cf_splithead_status(self._h, stream))
+
+    def set_spin_limit(self, us):
+        self._check(self._lib.cf_splithead_set_spin_limit(self._h, us))
+
+    def close(self):
+        if self._h:
+            self._lib.cf_splithead_destroy(self._h)
             self._h = ctypes.c_void_p()
 
     def __del__(self):
