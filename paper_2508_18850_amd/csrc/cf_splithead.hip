@@ -325,23 +325,24 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
 #pragma unroll
             for (int e = 0; e < E; ++e) {
                 const int i = first + tid + NT * e;
-                if (i < hi) (void)__hip_atomic_fetch_add(a.acc + i, d[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (i < hi) {
+                    // the returned value is waited for: the addition has been performed where all workgroups see it
+                    const float before = __hip_atomic_fetch_add(a.acc + i, d[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    asm volatile("" ::"v"(before));
+                }
             }
         }
     }
 
-    // ---- 7: the last head to add its slice b finishes it
-    __threadfence();
+    // ---- 7: the last head to add its slice b finishes it.  No fence: every addition above has returned before the
+    // barrier, the counter is incremented after it, and the sums are fetched with an atomic exchange (which also
+    // clears them), so nothing here depends on what a cache of this XCD holds.
     __syncthreads();
-    if (tid == 0) s_flag = __hip_atomic_fetch_add(a.arrive + b, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) s_flag = __hip_atomic_fetch_add(a.arrive + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (s_flag == (uint32_t)a.nh - 1u) {
-        __threadfence();
-        for (int i = lo + tid; i < hi; i += NT) {
-            const float v = __hip_atomic_load(a.acc + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            a.out[i] = f2h(v);
-            __hip_atomic_store(a.acc + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        for (int i = lo + tid; i < hi; i += NT)
+            a.out[i] = f2h(__hip_atomic_exchange(a.acc + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         if (tid == 0) __hip_atomic_store(a.arrive + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
