@@ -1,6 +1,8 @@
 """GPU parity of the SplitHead variant (cf_splithead_decode; paper Appendix B, Alg. 5) with the CPU oracle of the
 decode block, through the C ABI.  Alg. 5 computes the same block as Alg. 3 with the work divided along the head
-dimension, so the oracle is the same one (oracle/decode_block.py, its C twin for the large shape).
+dimension, so the oracle is the same one (oracle/decode_block.py, its C twin for the large shape); that Alg. 5, taken
+step by step, is that function is pinned on the CPU (oracle/splithead_block.py, tests/test_oracle_splithead.py), and one
+case here compares with that execution directly.
 
 Bar, as for the other kernel: max|err| <= 1e-2 * max|ref| + 1e-3 on the output (fp16 storage, fp32 accumulation;
 the order of the atomic additions over the heads is not fixed, which stays far inside this), relative RMS < 5e-3;
@@ -97,6 +99,17 @@ def test_small_shapes_match_oracle(name, shape, team, kv_len):
     _log("splithead case %s N=%d L=%d" % (name, team, kv_len))
     inp = cf_inputs.make_inputs(shape, seed=71, batch=1, kv_len=kv_len)
     check(run(shape, inp, kv_len, team), oracle(inp, shape, kv_len), inp, kv_len, name)
+
+
+def test_matches_the_block_by_block_execution_of_alg5():
+    """The same bar against the oracle that takes Alg. 5's steps block by block (oracle/splithead_block.py)."""
+    from oracle import splithead_block as sh
+    shape = cf_inputs.SHAPES["tiny"]
+    _log("splithead vs Alg. 5 oracle")
+    inp = cf_inputs.make_inputs(shape, seed=13, batch=1, kv_len=77)
+    ref = sh.splithead_decode_block(inp["x"], inp["w_qkv"], inp["w_o"], inp["k_cache"], inp["v_cache"], 77,
+                                    shape.n_q_heads, shape.head_dim, shape.rope_base, 4)
+    check(run(shape, inp, 77, 4), ref, inp, 77, "alg5")
 
 
 def test_headline_shape_matches_oracle():
