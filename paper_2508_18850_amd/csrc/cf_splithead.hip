@@ -347,19 +347,19 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
     }
 }
 
-// One-time rearrangement of W_qkv [D, 3 * nh * HD] into per-member blocks [nh][N][D][6 * PV * 8]
-__global__ void pack_splithead_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst, int D, int nh, int HD, int N)
+// One-time rearrangement of W_qkv [D, 3 * nh * HD] into per-member blocks [nh][N][D][6 * PV * 8], 16 bytes per step
+__global__ void pack_splithead_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, int D, int nh, int HD, int N)
 {
-    const int H2 = HD / (2 * N), RW = 6 * H2;
+    const int H2 = HD / (2 * N), RW = 6 * H2 / 8;       // 16-byte pieces per packed row (h2 is a multiple of 8)
     const size_t n = (size_t)nh * N * D * RW;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-        const int e = (int)(i % RW);
+        const int e = (int)(i % RW) * 8;
         const size_t r = (i / RW) % D, m = i / ((size_t)RW * D);
         const int b = (int)(m % N), head = (int)(m / N);
         const int sec = e / H2, j = e % H2;             // sec: q lo, q hi, k lo, k hi, v lo, v hi
         const int which = sec >> 1, half = sec & 1;
         const size_t col = (size_t)which * nh * HD + (size_t)head * HD + (size_t)half * (HD / 2) + b * H2 + j;
-        dst[i] = src[r * (size_t)(3 * nh * HD) + col];
+        dst[i] = src[(r * (size_t)(3 * nh * HD) + col) / 8];
     }
 }
 
@@ -463,7 +463,7 @@ int cf_splithead_pack(cf_splithead t, const void *W_qkv, void *W_qkv_members, vo
     if ((reinterpret_cast<uintptr_t>(W_qkv) | reinterpret_cast<uintptr_t>(W_qkv_members)) & 15u) return CF_EINVAL;
     const cf_config &c = t->cfg;
     hipLaunchKernelGGL(pack_splithead_kernel, dim3(2048), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint16_t *>(W_qkv), static_cast<uint16_t *>(W_qkv_members), c.d_model, c.n_q_heads,
+                       static_cast<const uint4 *>(W_qkv), static_cast<uint4 *>(W_qkv_members), c.d_model, c.n_q_heads,
                        c.head_dim, t->N);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
