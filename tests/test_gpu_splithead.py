@@ -120,6 +120,15 @@ def test_headline_shape_matches_oracle():
     check(run(shape, inp, 4096, 8, calls=3), oracle(inp, shape, 4096, use_c=True), inp, 4096, "llama2_7b")
 
 
+def test_long_cache_matches_oracle():
+    """The longest cached length of the sweep the comparison is run on (16384 tokens: four load batches per thread in
+    the score and P.V stages, 64 KiB of scores in LDS)."""
+    shape = cf_inputs.SHAPES["llama2_7b"]
+    _log("splithead llama2_7b N=8 L=16384")
+    inp = cf_inputs.make_inputs(shape, seed=4, batch=1, kv_len=16384)
+    check(run(shape, inp, 16384, 8, calls=2), oracle(inp, shape, 16384, use_c=True), inp, 16384, "llama2_7b_16k")
+
+
 def test_same_result_as_the_split_token_kernel():
     """The two dataflows are the same function: their outputs agree to the fp16 rounding of the result and the
     difference of two fp32 summation orders (2 fp16 ulps of the largest output allowed)."""
