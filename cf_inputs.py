@@ -39,6 +39,10 @@ SHAPES = {
     "llama2_7b": BlockShape("llama2_7b", 4096, 32, 32, 128, 10000.0, 4096),
     "llama3_8b": BlockShape("llama3_8b", 4096, 32, 8, 128, 500000.0, 8192),
     "llama2_70b": BlockShape("llama2_70b", 8192, 64, 8, 128, 10000.0, 32768),
+    # MHA blocks with more heads (d_model = 128 * heads), for the sweep of the team size against the head count
+    # (the experiment with varying cluster sizes and head counts of the paper's evaluation section)
+    "mha_64h": BlockShape("mha_64h", 8192, 64, 64, 128, 10000.0, 4096),
+    "mha_128h": BlockShape("mha_128h", 16384, 128, 128, 128, 10000.0, 4096),
 }
 
 

@@ -40,3 +40,8 @@ def test_llama3_8b_gqa(batch):
 
 def test_llama2_70b_gqa_kv32768():
     run_case(cf_inputs.SHAPES["llama2_70b"], 1, 32768, seed=4000)
+
+
+def test_mha_64_heads_kv4096():
+    """64 heads x 128 at d_model 8192: the shape of the team-size sweep that runs at 4 workgroups per head."""
+    run_case(cf_inputs.SHAPES["mha_64h"], 1, 4096, seed=5000)

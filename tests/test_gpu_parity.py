@@ -290,3 +290,23 @@ def test_many_launches_are_bitwise_reproducible():
         got = bits.view(np.float16).astype(np.float64)
         assert np.abs(got - ref).max() <= 1e-2 * np.abs(ref).max() + 1e-3, (b, pos)
     blk.close()
+
+
+@pytest.mark.parametrize("heads,workgroups", [(32, 32), (32, 64), (32, 128), (32, 256), (64, 64), (64, 128), (64, 256),
+                                              (128, 128), (128, 256)])
+def test_team_sizes_and_head_counts(heads, workgroups):
+    """The team size (workgroups per head: 1, 2, 4, 8; the paper's cluster size) against the head count, as in the
+    sweep of the paper's evaluation with varying cluster sizes and numbers of heads: every combination the sweep
+    times gives the oracle's result (packed and row-major weights)."""
+    shape = cf_inputs.BlockShape("s", 512, heads, heads, 128, 10000.0, 300)
+    _log("heads=%d workgroups=%d" % (heads, workgroups))
+    inp = cf_inputs.make_inputs(shape, seed=40 + heads, batch=1, kv_len=300)
+    ref = oracle(inp, shape, 300)
+    for packed in (False, True):
+        r = Runner(shape, 1, inp["max_seq"])
+        r.blk.set_tuning(workgroups=workgroups)
+        res = r.run(inp, 300, packed=packed)
+        plan = r.blk.plan()                     # the plan of the call just made
+        assert plan["workgroups"] == workgroups and plan["team_size"] == workgroups // heads
+        check(res, ref, inp, 300, "heads%d_w%d_%s" % (heads, workgroups, "packed" if packed else "rows"))
+        r.blk.close()
