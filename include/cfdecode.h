@@ -128,6 +128,21 @@ int cf_decode_layer(cf_handle h, int32_t batch, const void *x, const void *norm_
                     void *out, void *stream);
 
 /*
+ * A stack of n_layers layers in one call: layer 0 reads x, layer l reads the hidden state layer l-1 wrote (two
+ * buffers of the handle's workspace, used in turn), the last layer writes `out`.  Each layer is cf_decode_layer
+ * with its own weights and caches and the common batch, pos, eps, residual and packed; the launch overhead the
+ * paper compares in Sec. 4.2 is that of such a stack.  This version enqueues one launch of the fused kernel per
+ * layer on `stream`.
+ *   W_qkv, W_o, k_cache, v_cache: HOST arrays of n_layers DEVICE pointers (read during the call only), each as in
+ *   cf_decode_layer; norm_weight: NULL (no RMSNorm in any layer) or a HOST array of n_layers DEVICE pointers.
+ *   x and out must differ.  Errors as for cf_decode_layer; a pointer of any layer that is null or misaligned is
+ *   CF_EINVAL before anything is enqueued; after another error the layers before the failing one have been enqueued.
+ */
+int cf_decode_stack(cf_handle h, int32_t n_layers, int32_t batch, const void *x, const void *const *norm_weight, float eps,
+                    int32_t residual, int32_t packed, const void *const *W_qkv, const void *const *W_o,
+                    void *const *k_cache, void *const *v_cache, int32_t pos, void *out, void *stream);
+
+/*
  * cf_decode_layer for a batch whose rows have different lengths (continuous batching): row b has row_pos[b]
  * cached tokens; its query and new key are rotated for position row_pos[b], it attends to its rows
  * 0 .. row_pos[b] and its new key / value go to row row_pos[b] of its cache slice.  Rows of a batch are

@@ -14,6 +14,7 @@ _LIB_PATH = os.environ.get("CFDECODE_LIB") or os.path.join(_PKG, "libcfdecode.so
 _lib = None
 
 EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_packed", "cf_decode_layer", "cf_decode_layer_rows",
+                    "cf_decode_stack",
                     "cf_pack_weights",
                     "cf_packed_sizes", "cf_status", "cf_debug_export",
                     "cf_set_tuning", "cf_get_plan", "cf_algorithmic_bytes", "cf_strerror", "cf_last_hip_error",
@@ -101,7 +102,10 @@ def load_library():
                     "cf_mla_create", "cf_mla_destroy", "cf_mla_decode", "cf_mla_status", "cf_mla_set_spin_limit",
                     "cf_mla_algorithmic_bytes"):
             getattr(lib, name).restype = ctypes.c_int
+        lib.cf_decode_stack.argtypes = [vp, i32, i32, vp, ctypes.POINTER(vp), ctypes.c_float, i32, i32, ctypes.POINTER(vp),
+                                        ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), i32, vp, vp]
         for name in ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_packed", "cf_decode_layer", "cf_decode_layer_rows",
+                     "cf_decode_stack",
                     "cf_pack_weights",
                      "cf_packed_sizes", "cf_status", "cf_debug_export",
                      "cf_set_tuning", "cf_get_plan", "cf_last_hip_error"):
@@ -182,6 +186,22 @@ class DecodeBlock:
 
     def status(self, stream=0):
         self._check(self._lib.cf_status(self._h, stream))
+
+    def decode_stack_rc(self, batch, x, norm_weights, eps, residual, packed, w_qkv, w_o, k_cache, v_cache, pos, out,
+                        stream=0) -> int:
+        """w_qkv, w_o, k_cache, v_cache: sequences of device addresses, one per layer; norm_weights: such a sequence
+        or None."""
+        n = len(w_qkv)
+        assert len(w_o) == n and len(k_cache) == n and len(v_cache) == n and (norm_weights is None or len(norm_weights) == n)
+        arr = lambda seq: (ctypes.c_void_p * n)(*[ctypes.c_void_p(int(a)) for a in seq])
+        nw = arr(norm_weights) if norm_weights is not None else None
+        return int(self._lib.cf_decode_stack(self._h, n, batch, x, nw, float(eps), int(residual), int(packed), arr(w_qkv),
+                                             arr(w_o), arr(k_cache), arr(v_cache), pos, out, stream))
+
+    def decode_stack(self, *args, **kw):
+        rc = self.decode_stack_rc(*args, **kw)
+        if rc != 0:
+            self._check(rc)
 
     def set_tuning(self, workgroups=0, k_splits=0, kv_splits=0, spin_limit_us=0):
         self._check(self._lib.cf_set_tuning(self._h, workgroups, k_splits, kv_splits, spin_limit_us))

@@ -29,6 +29,7 @@ struct cf_handle_s {
     float *dbg_q = nullptr, *dbg_attn = nullptr;
     double *inv_freq = nullptr;
     unsigned long long *dbg_t = nullptr;
+    uint16_t *chain[2] = {nullptr, nullptr};   // hidden states between the layers of a stack, [max_batch, d_model] each
     // tuning
     int tune_w = 0, tune_ks = 0, tune_ns = 0;
     int balance_rows = 0, balance_tokens = 32;   // half the length difference between even and odd splits (-1: off)
@@ -270,7 +271,9 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     const size_t freq_bytes = align_up(hd / 2 * sizeof(double), 256);
     const size_t times_bytes = align_up((size_t)8 * h->num_cu * cf::kStamps * sizeof(unsigned long long), 256);
     h->exchange_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes;
-    h->ws_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes + 2 * dbg_bytes + freq_bytes + times_bytes;
+    const size_t chain_bytes = align_up(B * c.d_model * sizeof(uint16_t), 256);
+    h->ws_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes + 2 * dbg_bytes + freq_bytes + times_bytes +
+                  2 * chain_bytes;
     e = hipMalloc(reinterpret_cast<void **>(&h->ws), h->ws_bytes);
     if (e != hipSuccess) {
         delete h;
@@ -293,6 +296,9 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     h->inv_freq = reinterpret_cast<double *>(cur);
     cur += freq_bytes;
     h->dbg_t = reinterpret_cast<unsigned long long *>(cur);
+    cur += times_bytes;
+    h->chain[0] = reinterpret_cast<uint16_t *>(cur);
+    h->chain[1] = reinterpret_cast<uint16_t *>(cur + chain_bytes);
 
     std::vector<double> freq(hd / 2);
     for (size_t i = 0; i < hd / 2; ++i) freq[i] = std::pow((double)c.rope_base, -2.0 * (double)i / (double)hd);
@@ -387,6 +393,27 @@ int cf_decode_layer_rows(cf_handle h, int32_t batch, const void *x, const void *
     if (!row_pos || (residual && x == out)) return CF_EINVAL;
     return decode_impl(h, packed != 0, batch, x, W_qkv, W_o, k_cache, v_cache, max_pos, out, stream, norm_weight, eps,
                        residual, row_pos);
+}
+
+int cf_decode_stack(cf_handle h, int32_t n_layers, int32_t batch, const void *x, const void *const *norm_weight, float eps,
+                    int32_t residual, int32_t packed, const void *const *W_qkv, const void *const *W_o,
+                    void *const *k_cache, void *const *v_cache, int32_t pos, void *out, void *stream)
+{
+    if (!h || n_layers < 1 || !W_qkv || !W_o || !k_cache || !v_cache || !x || !out || x == out) return CF_EINVAL;
+    // all layers are checked before the first one is enqueued (decode_impl checks again, per layer)
+    for (int l = 0; l < n_layers; ++l)
+        if (!aligned16(W_qkv[l]) || !aligned16(W_o[l]) || !aligned16(k_cache[l]) || !aligned16(v_cache[l]) ||
+            (norm_weight && !aligned16(norm_weight[l])))
+            return CF_EINVAL;
+    const void *in = x;
+    for (int l = 0; l < n_layers; ++l) {
+        void *dst = l == n_layers - 1 ? out : static_cast<void *>(h->chain[l & 1]);
+        const int rc = decode_impl(h, packed != 0, batch, in, W_qkv[l], W_o[l], k_cache[l], v_cache[l], pos, dst, stream,
+                                   norm_weight ? norm_weight[l] : nullptr, eps, residual);
+        if (rc != CF_OK) return rc;
+        in = dst;
+    }
+    return CF_OK;
 }
 
 int cf_packed_sizes(cf_handle h, size_t *qkv_bytes, size_t *o_bytes)
