@@ -101,6 +101,31 @@ def test_small_shapes_match_oracle(name, shape, team, kv_len):
     check(run(shape, inp, kv_len, team), oracle(inp, shape, kv_len), inp, kv_len, name)
 
 
+@pytest.mark.parametrize("team", [2, 4, 8])
+def test_pack_gives_the_documented_layout(team):
+    """cf_splithead_pack: [head][member][d_model][q lo | q hi | k lo | k hi | v lo | v hi], a member's dimensions as in
+    oracle/splithead_block.block_dims (bit-exact: the values are only moved)."""
+    from oracle import splithead_block as sh
+    from paper_2508_18850_amd import SplitHeadBlock
+    D, nh, d = 72, 3, 128
+    rng = np.random.Generator(np.random.PCG64(team))
+    w = rng.standard_normal((D, 3 * nh * d)).astype(np.float16)
+    want = np.empty((nh, team, D, 3 * d // team), dtype=np.float16)
+    for i in range(nh):
+        for b in range(team):
+            dims = sh.block_dims(b, team, d)
+            want[i, b] = np.concatenate([w[:, which * nh * d + i * d + dims] for which in range(3)], axis=1)
+    blk = SplitHeadBlock(D, nh, d, 16, 10000.0, team)
+    st = torch.cuda.current_stream().cuda_stream
+    src = torch.from_numpy(w).cuda()
+    dst = torch.full_like(src, float("nan"))
+    blk.pack(src.data_ptr(), dst.data_ptr(), st)
+    blk.status(st)
+    got = dst.cpu().numpy().reshape(want.shape)
+    blk.close()
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+
+
 def test_matches_the_block_by_block_execution_of_alg5():
     """The same bar against the oracle that takes Alg. 5's steps block by block (oracle/splithead_block.py)."""
     from oracle import splithead_block as sh
