@@ -310,3 +310,37 @@ def test_team_sizes_and_head_counts(heads, workgroups):
         assert plan["workgroups"] == workgroups and plan["team_size"] == workgroups // heads
         check(res, ref, inp, 300, "heads%d_w%d_%s" % (heads, workgroups, "packed" if packed else "rows"))
         r.blk.close()
+
+
+@pytest.mark.parametrize("d_model,nq,nkv,hd", [(520, 4, 2, 64), (1032, 3, 3, 128)])
+def test_pack_weights_gives_the_documented_layout(d_model, nq, nkv, hd):
+    """cf_pack_weights, bit-exact (the values are only moved): W_qkv_packed [(n_q + 2 n_kv)][d_model][head_dim], every
+    block followed by 256 zero bytes; W_o_packed [n_q][ceil(d_model / 512)][head_dim][512], zero past d_model."""
+    from paper_2508_18850_amd import DecodeBlock
+    rng = np.random.Generator(np.random.PCG64(d_model))
+    nqkv = (nq + 2 * nkv) * hd
+    w_qkv = rng.standard_normal((d_model, nqkv)).astype(np.float16)
+    w_o = rng.standard_normal((nq * hd, d_model)).astype(np.float16)
+    blk = DecodeBlock(d_model, nq, nkv, hd, 1, 16, 10000.0)
+    st = torch.cuda.current_stream().cuda_stream
+    qb, ob = blk.packed_sizes()
+    nblk, nch = nq + 2 * nkv, -(-d_model // 512)
+    assert qb == nblk * (d_model * hd * 2 + 256) and ob == nq * nch * hd * 512 * 2
+    a, b = torch.from_numpy(w_qkv).cuda(), torch.from_numpy(w_o).cuda()
+    pa = torch.full((qb // 2,), float("nan"), dtype=torch.float16, device="cuda")
+    pb = torch.full((ob // 2,), float("nan"), dtype=torch.float16, device="cuda")
+    blk.pack_weights(a.data_ptr(), b.data_ptr(), pa.data_ptr(), pb.data_ptr(), st)
+    blk.status(st)
+    got_q = pa.cpu().numpy().view(np.uint16).reshape(nblk, d_model * hd + 128)
+    got_o = pb.cpu().numpy().view(np.uint16).reshape(nq, nch, hd, 512)
+    blk.close()
+    for j in range(nblk):
+        want = np.ascontiguousarray(w_qkv[:, j * hd:(j + 1) * hd]).view(np.uint16).reshape(-1)
+        assert np.array_equal(got_q[j, :d_model * hd], want), j
+        assert not got_q[j, d_model * hd:].any(), "padding is not zero"
+    for i in range(nq):
+        for c in range(nch):
+            cols = min(512, d_model - 512 * c)
+            want = w_o[i * hd:(i + 1) * hd, 512 * c:512 * c + cols].view(np.uint16)
+            assert np.array_equal(got_o[i, c, :, :cols], want), (i, c)
+            assert not got_o[i, c, :, cols:].any(), "columns past d_model are not zero"
