@@ -315,7 +315,9 @@ int64_t cf_mla_algorithmic_bytes(const cf_mla_config *cfg, int32_t batch, int32_
  *   d_model] as for cf_decode_block (rows < pos read, row pos written).  Asynchronous on `stream`, no allocation.
  *   The stamp of a launch is counted on the host, so a captured launch must not be replayed.  The order of the
  *   atomic additions, and with it the last bits of the result, is not fixed.
- * cf_splithead_status / cf_splithead_set_spin_limit: as cf_team_status / cf_team_set_spin_limit.
+ * cf_splithead_status / cf_splithead_set_spin_limit: as cf_team_status / cf_team_set_spin_limit; in addition a limit
+ *   of -1 makes every launch report CF_ETIMEOUT whatever the timing (only member 0 of every team runs and gives up at
+ *   its first look for the posts of the others): for tests of the error path.  Every wait still ends.
  */
 typedef struct cf_splithead_s *cf_splithead;
 int cf_splithead_create(const cf_config *cfg, int32_t team_size, cf_splithead *out);

@@ -51,6 +51,7 @@ struct SplitArgs {
     float scale_log2e;
     uint32_t stamp;
     int D, nh, HD, N, pos, max_seq;
+    int only_member0;               // test of the error path: the other members of every team leave at once
 };
 
 __device__ __forceinline__ uint16_t f2h(float v) { return __builtin_bit_cast(uint16_t, (_Float16)v); }
@@ -110,6 +111,9 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
         b = w % N;
     }
     const int team_first = head * N;
+    // Error-path test: with its peers gone (before they touch anything) member 0 finds none of their posts, and with a
+    // wait limit of 0 it gives up at its first look: a timeout that does not depend on timing, and every wait still ends.
+    if (a.only_member0 && b != 0) return;
     Exchange x;
     x.slots = a.slots, x.cap = a.cap, x.stamp = a.stamp, x.err = a.err, x.spin_ticks = a.spin_ticks;
 
@@ -387,6 +391,7 @@ struct cf_splithead_s {
     uint32_t *arrive = nullptr, *err = nullptr;
     uint32_t launches = 0;
     long long spin_ticks = 200000000LL;
+    int only_member0 = 0;
     int last_hip = 0;
 };
 
@@ -497,6 +502,7 @@ int cf_splithead_decode(cf_splithead t, const void *x, const void *W_qkv_members
     if (++t->launches == 0) t->launches = 1;                           // a stamp is never 0
     a.stamp = t->launches;
     a.D = c.d_model, a.nh = c.n_q_heads, a.HD = c.head_dim, a.N = t->N, a.pos = pos, a.max_seq = c.max_seq;
+    a.only_member0 = t->only_member0;
     hipLaunchKernelGGL(pick(t->pv), dim3(t->W), dim3(NT), t->lds_bytes, static_cast<hipStream_t>(stream), a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -526,8 +532,9 @@ int cf_splithead_status(cf_splithead t, void *stream)
 
 int cf_splithead_set_spin_limit(cf_splithead t, int32_t spin_limit_us)
 {
-    if (!t || spin_limit_us < 0) return CF_EINVAL;
-    t->spin_ticks = (long long)spin_limit_us * 100;
+    if (!t || spin_limit_us < -1) return CF_EINVAL;
+    t->only_member0 = spin_limit_us == -1;
+    t->spin_ticks = spin_limit_us == -1 ? 0 : (long long)spin_limit_us * 100;
     return CF_OK;
 }
 
