@@ -140,3 +140,44 @@ def test_bad_arguments_enqueue_nothing():
     blk.status(st)
     assert torch.isfinite(out.float()).all()
     blk.close()
+
+
+def test_full_size_stack_of_two_layers():
+    """Llama-2-7B shape, 4096 cached tokens, RMSNorm and residual, packed weights: two layers in one call against the
+    C oracle applied layer by layer."""
+    from oracle import c_oracle
+    from paper_2508_18850_amd import DecodeBlock
+    shape = cf_inputs.SHAPES["llama2_7b"]
+    n_layers, pos, eps, batch = 2, 4096, 1e-5, 1
+    _log("full-size stack")
+    layers, gammas = make_layers(shape, n_layers, batch, pos, seed=7000)
+    dev = torch.device("cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    blk = DecodeBlock(shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, batch, layers[0]["max_seq"],
+                      shape.rope_base)
+    dv = []
+    for l, inp in enumerate(layers):
+        d = {k: torch.from_numpy(inp[k]).to(dev) for k in ("w_qkv", "w_o", "k_cache", "v_cache")}
+        nq, no = blk.packed_sizes()
+        wq = torch.empty((nq // 2,), dtype=torch.float16, device=dev)
+        wo = torch.empty((no // 2,), dtype=torch.float16, device=dev)
+        blk.pack_weights(d["w_qkv"].data_ptr(), d["w_o"].data_ptr(), wq.data_ptr(), wo.data_ptr(), st)
+        d["w_qkv"], d["w_o"], d["g"] = wq, wo, torch.from_numpy(gammas[l]).to(dev)
+        dv.append(d)
+    x = torch.from_numpy(layers[0]["x"]).to(dev)
+    out = torch.full((batch, shape.d_model), float("nan"), dtype=torch.float16, device=dev)
+    blk.decode_stack(batch, x.data_ptr(), [d["g"].data_ptr() for d in dv], eps, 1, 1, [d["w_qkv"].data_ptr() for d in dv],
+                     [d["w_o"].data_ptr() for d in dv], [d["k_cache"].data_ptr() for d in dv],
+                     [d["v_cache"].data_ptr() for d in dv], pos, out.data_ptr(), st)
+    blk.status(st)
+    got = out.cpu().numpy().astype(np.float64)
+    blk.close()
+    cur = layers[0]["x"]
+    for l, inp in enumerate(layers):
+        ref = c_oracle.decode_layer(cur, gammas[l], eps, inp["w_qkv"], inp["w_o"], inp["k_cache"], inp["v_cache"], pos,
+                                    shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.rope_base)["out"]
+        cur = ref.astype(np.float16)
+    err = np.abs(got - ref).max()
+    tol = n_layers * (1e-2 * np.abs(ref).max() + 1e-3)
+    _log("full-size stack: max|err| %.3e tol %.3e max|ref| %.3e" % (err, tol, np.abs(ref).max()))
+    assert np.isfinite(got).all() and err <= tol
