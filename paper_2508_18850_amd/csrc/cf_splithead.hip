@@ -38,6 +38,18 @@ constexpr int kRedFloats = NT * 8;  // floats of the cross-thread sum of stage 1
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 
+// Stage time stamps (100 MHz wall clock, thread 0 of every workgroup), only in builds with -DCF_STAMPS=1
+#ifndef CF_STAMPS
+#define CF_STAMPS 0
+#endif
+#if CF_STAMPS
+constexpr int kShStamps = 16;
+__device__ unsigned long long g_sh_ts[256 * kShStamps];
+#define SH_STAMP(k) do { if (threadIdx.x == 0) s_ts[k] = wall_clock64(); } while (0)
+#else
+#define SH_STAMP(k)
+#endif
+
 struct SplitArgs {
     const uint16_t *x, *wqkv, *wo;
     uint16_t *kc, *vc, *out;
@@ -96,6 +108,12 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
     extern __shared__ float smem[];
     __shared__ float s_q[SD], s_k[SD], s_v[SD], s_a[SD], s_w[NW], s_part[NW][SD];
     __shared__ uint32_t s_flag;
+#if CF_STAMPS
+    __shared__ unsigned long long s_ts[kShStamps];
+    if (threadIdx.x < kShStamps) s_ts[threadIdx.x] = 0;
+    __syncthreads();
+#endif
+    SH_STAMP(0);
     float *s_x = smem;                    // [D] the hidden state, later the partial output projection
     float *s_s = smem + a.D;              // stage 1: sums across row groups; then the scores / probabilities
     const int tid = threadIdx.x, w = blockIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -147,6 +165,7 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
                 for (int j = 0; j < 8; ++j) acc[j] = fmaf(xf, (float)wv[u][j], acc[j]);
             }
         }
+        SH_STAMP(1);            // weights consumed
         if (active) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) s_s[g * (P * 8) + c * 8 + j] = acc[j];
@@ -177,6 +196,7 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
         __syncthreads();
     }
 
+    SH_STAMP(2);                // q, k, v of the new token ready
     // ---- 2: partial scores of all tokens over the member's dimensions
     const uint16_t *kbase = a.kc + (size_t)head * a.max_seq * HD + b * H2;
     const uint16_t *vbase = a.vc + (size_t)head * a.max_seq * HD + b * H2;
@@ -215,12 +235,14 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
     }
     __syncthreads();
 
+    SH_STAMP(3);                // partial scores done
     // ---- 3: ClusterReduce(S_b, sum) over the team
     const size_t count = (size_t)pos + 1;
     cf::team::reduce_two_hops<cf::team::kSum>(
         x, team_first, N, b, count, [&](size_t i) { return s_s[i]; }, [&](size_t i, float v) { s_s[i] = v; });
     __syncthreads();
 
+    SH_STAMP(4);                // scores reduced
     // ---- 4: softmax over all tokens, A_b = P . V over the member's dimensions
     {
         float m = -3.0e38f;
@@ -233,6 +255,7 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
             l += e;
         }
         l = block_fold(l, false, s_w);         // its barriers also order the writes of s_s before the reads below
+        SH_STAMP(5);            // softmax done
         float av[SD];
 #pragma unroll
         for (int j = 0; j < SD; ++j) av[j] = 0.f;
@@ -278,6 +301,7 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
         __syncthreads();
     }
 
+    SH_STAMP(6);                // A_b done
     // ---- 5: partial output projection over the member's rows of W_o: s_x[c] = sum_j A_b[j] W_o[row_j, c]
     {
         const uint16_t *wlo = a.wo + ((size_t)head * HD + b * H2) * D;
@@ -308,6 +332,7 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
     }
     __syncthreads();
 
+    SH_STAMP(7);                // O_b done
     // ---- 6: reduce-scatter of O_b over the team (third area of the members' slots), atomicAdd across the heads
     const unsigned sl = (unsigned)((D + N - 1) / N);
     const int lo = min(b * (int)sl, D), hi = min(lo + (int)sl, D);
@@ -338,6 +363,7 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
         }
     }
 
+    SH_STAMP(8);                // O reduced over the team and added
     // ---- 7: the last head to add its slice b finishes it.  No fence: every addition above has returned before the
     // barrier, the counter is incremented after it, and the sums are fetched with an atomic exchange (which also
     // clears them), so nothing here depends on what a cache of this XCD holds.
@@ -349,6 +375,11 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
             a.out[i] = f2h(__hip_atomic_exchange(a.acc + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         if (tid == 0) __hip_atomic_store(a.arrive + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    SH_STAMP(9);
+#if CF_STAMPS
+    __syncthreads();
+    if (tid < kShStamps && w < 256) g_sh_ts[w * kShStamps + tid] = s_ts[tid];
+#endif
 }
 
 // One-time rearrangement of W_qkv [D, 3 * nh * HD] into per-member blocks [nh][N][D][6 * PV * 8], 16 bytes per step
@@ -529,6 +560,16 @@ int cf_splithead_status(cf_splithead t, void *stream)
     }
     return CF_OK;
 }
+
+#if CF_STAMPS
+// profiling library only: the stage stamps of the last launch (host buffer of 256 * 16 64-bit words)
+int cf_splithead_trace_read(void *host_dst)
+{
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(g_sh_ts), sizeof(unsigned long long) * 256 * kShStamps);
+    return e == hipSuccess ? CF_OK : CF_EHIP;
+}
+#endif
 
 int cf_splithead_set_spin_limit(cf_splithead t, int32_t spin_limit_us)
 {
