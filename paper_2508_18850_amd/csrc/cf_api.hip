@@ -83,7 +83,7 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
             if (rps < 8 && ks > 1) continue;
             if ((long)(ks - 1) * rps >= c.d_model) continue;   // no empty slice
             const int maxi = bt == 1 ? 4 : (bt <= 4 ? 2 : 1);
-            const size_t lds = ((size_t)bt * rps + (size_t)maxi * cf::kWaves * bt * hd) * sizeof(float);
+            const size_t lds = (cf::x_lds_floats(hd, bt, rps) + (size_t)maxi * cf::kWaves * bt * hd) * sizeof(float);
             if (lds > kLdsLimit) continue;
             const int dsel = TS / ks;
             const long cost = (long)(ceil_div(G, dsel) + ceil_div(2, dsel)) * rps;
@@ -100,7 +100,7 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
         p->RD = 0;
         if (p->pairmap && best % 2 == 0 && p->RB * best == c.d_model && p->RB >= 8 * h->balance_rows) {
             const int maxi = bt == 1 ? 4 : (bt <= 4 ? 2 : 1);
-            const size_t lds = ((size_t)bt * (p->RB + h->balance_rows) + (size_t)maxi * cf::kWaves * bt * hd) * sizeof(float);
+            const size_t lds = (cf::x_lds_floats(hd, bt, p->RB + h->balance_rows) + (size_t)maxi * cf::kWaves * bt * hd) * sizeof(float);
             if (lds <= kLdsLimit) p->RD = h->balance_rows;
         }
         p->RPS = p->RB + p->RD;

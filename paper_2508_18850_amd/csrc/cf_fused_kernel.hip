@@ -56,7 +56,6 @@ constexpr float kNegBig = -1.0e30f;   // stands for "no score yet"; finite so th
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));   // eight fp16 values = one 128-bit load
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // A read-only tensor that is streamed once: raw buffer resource + 128-bit non-temporal loads.
@@ -64,7 +63,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // address registers are needed per load; a lane with nothing to load passes kNoLoad,
 // which is beyond the buffer's size: the hardware then skips the access and returns zeros.
 constexpr uint32_t kNoLoad = 0x80000000u;
-#ifndef CF_STREAM_GLOBAL
 struct Stream {
     __amdgpu_buffer_rsrc_t r;
     __device__ __forceinline__ Stream(const void *base, uint32_t bytes)
@@ -74,23 +72,57 @@ struct Stream {
         return __builtin_bit_cast(h8, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 2));
     }
 };
-#else
-struct Stream {
-    const char *b;
-    __device__ __forceinline__ Stream(const void *base, uint32_t) : b((const char *)base) {}
-    __device__ __forceinline__ h8 ld(uint32_t voff, uint32_t soff) const
-    {
-        h8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (voff == kNoLoad) return z;
-        return __builtin_nontemporal_load(reinterpret_cast<const h8 *>(b + (size_t)soff + voff));
-    }
-};
-#endif
 
 __device__ __forceinline__ void unpack8(const h8 &u, float (&f)[8])
 {
 #pragma unroll
     for (int k = 0; k < 8; ++k) f[k] = (float)u[k];
+}
+
+// Batch tile 16 with head_dim 128: the two projections (Alg. 3 steps 2 and 8) are dense [16 x K] x [K x N]
+// products and run on MFMA tiles (v_mfma_f32_16x16x32_f16: A is 16 x 32, B is 32 x 16, fp32 accumulators).
+// Operand layout of that instruction: lane l holds, of A, row l % 16 and eight consecutive values of the
+// contraction index for group l / 16; of B, column l % 16 and the same eight contraction values; of the
+// result, column l % 16 and rows 4 * (l / 16) + 0..3.  The weights stay in the layout the batch-1 path
+// streams (a lane loads eight COLUMNS of one row), so eight loaded rows are transposed inside the lane
+// into eight operands of one column each (transpose8); the sixteen batch rows are the A operand.
+template <int HD, int BT>
+struct Mfma {
+    static constexpr bool on = mfma_tiles(HD, BT);
+};
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 mfma16(const h8 &a, const h8 &b, const f32x4 &c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// w[u] = row u, eight adjacent columns  ->  f[c] = column c, rows 0..7 (a 8 x 8 transpose of 16-bit values
+// inside one lane: one byte permute per result register)
+__device__ __forceinline__ void transpose8(const h8 *w, h8 (&f)[8])
+{
+#pragma unroll
+    for (int c2 = 0; c2 < 4; ++c2) {
+        u32x4 e, o;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t lo = __builtin_bit_cast(u32x4, w[2 * d])[c2], hi = __builtin_bit_cast(u32x4, w[2 * d + 1])[c2];
+            e[d] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);    // {lo.low half, hi.low half}
+            o[d] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);    // {lo.high half, hi.high half}
+        }
+        f[2 * c2] = __builtin_bit_cast(h8, e);
+        f[2 * c2 + 1] = __builtin_bit_cast(h8, o);
+    }
+}
+
+// v = hi + lo with both parts fp16: the A operand of an MFMA product whose fp32 input must not lose bits
+__device__ __forceinline__ void split_hi_lo(const float (&v)[8], h8 &hi, h8 &lo)
+{
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        hi[k] = (_Float16)v[k];
+        lo[k] = (_Float16)(v[k] - (float)hi[k]);
+    }
 }
 
 __device__ __forceinline__ float h2f(uint16_t bits) { return (float)__builtin_bit_cast(_Float16, bits); }
@@ -268,9 +300,13 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     // loads per thread and batch: the 16-row batch tile keeps 128 accumulators per thread, and anything above two
     // loads per batch spills (measured on the 8B shape, batch 16: 202 us with 8, 181 with 4, 177 with 2, 182 with 1);
     // the 4-row tile is best with 4 (8B shape, batch 4: 55.1 us with 8, 53.6 with 4, 53.7 with 2)
-    constexpr int U = BT > 4 ? 2 : (BT == 4 ? 4 : 8);
+    // With MFMA tiles (MF) a batch is eight rows per lane: one 32-row step of the contraction per wavefront.
+    constexpr bool MF = Mfma<HD, BT>::on;
+    constexpr int U = MF ? 8 : (BT > 4 ? 2 : (BT == 4 ? 4 : 8));
     constexpr int MAXI = BT == 1 ? 4 : (BT <= 4 ? 2 : 1);   // selectors whose wave partials are buffered in LDS
     const int tid = threadIdx.x, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
+    const int kg = (tid & 63) >> 4;                         // MF: contraction group of the lane (rows 8 kg .. 8 kg + 7 of a step)
+    const int lrow = 32 * wv + 8 * kg;                      // MF: first row of the lane inside a 256-row batch
     const int ks = qmod(member, p.KS, p.sh_ks);
     const int sel0 = qdiv(member, p.KS, p.sh_ks), dsel = p.DSEL;
     // slices with an even index (workgroups on the faster dies, see the workgroup mapping in the
@@ -284,14 +320,18 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     const int nsteps = (nA + nB) * nb;
     auto sel_of = [&](int si) { return si < nA ? sel0 + si * dsel : G + sel0 + (si - nA) * dsel; };
     float *xs = smem;                       // [BT][RPS]
-    float *red = smem + BT * p.RPS;         // [MAXI][NW][BT][HD]
+    // MF: x as fp16 MFMA operands, [16][XS] halves (rows padded by 16 bytes: the sixteen lanes of an operand read
+    // then fall into different banks), followed by a second array with the low parts of x * gamma (RMSNorm)
+    const int XS = xs16_stride(p.RPS);
+    _Float16 *xh = reinterpret_cast<_Float16 *>(smem), *xl = xh + 16 * XS;
+    float *red = smem + (MF ? 16 * XS : BT * p.RPS);   // [MAXI][NW][BT][HD]
     const Xbuf x1(p.p1);
     const uint32_t blkb = (uint32_t)p.D * HD * 2 + kQkvBlockPad;          // packed: bytes from one block to the next
     const Stream W(p.wqkv, (p.flags & kFlagPacked) ? (uint32_t)(p.nqkv / HD) * blkb : (uint32_t)((size_t)p.D * p.nqkv * 2));
     // row-major [D][Nqkv]: rows are Nqkv*2 bytes apart and a selector starts at column col0;
     // packed [Nqkv/HD][D][HD] (+ pad): rows are HD*2 bytes apart and a selector is one contiguous block
     const uint32_t rowb = (p.flags & kFlagPacked) ? (uint32_t)HD * 2 : (uint32_t)p.nqkv * 2;
-    const uint32_t voff0 = (uint32_t)grp * rowb + lig * 16;
+    const uint32_t voff0 = (uint32_t)(MF ? lrow : grp) * rowb + lig * 16;
 
     // A step is (selector, batch of U row groups).  Steps are loaded and consumed strictly in order,
     // so each side keeps a cursor that is advanced incrementally: no divisions, and the address
@@ -321,13 +361,13 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     // the end (all lanes switched off through their offset).  The compiler derives each wait from
     // the number of loads issued after the one it needs, taking the smallest over all paths of the
     // control flow, so a branch around loads would make every later wait drain the queue.
-    const int lim = nrows - grp;                            // row group i is inside the slice iff NG*i < lim
+    const int lim = nrows - (MF ? lrow : grp);              // row group i is inside the slice iff NG*i < lim (MF: row NG*i0 + u iff < lim)
     auto load = [&](h8(&w)[U], uint32_t voff) {
         const bool live = lc.si < nsel;
         const int g0 = live ? NG * lc.i0 : 0x40000000;      // uniform
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            w[u] = W.ld((g0 + NG * u) < lim ? voff : kNoLoad, lc.sbase + (uint32_t)u * step_b);
+            w[u] = W.ld((g0 + (MF ? u : NG * u)) < lim ? voff : kNoLoad, lc.sbase + (uint32_t)u * (MF ? rowb : step_b));
         if (live) advance(lc);
     };
 
@@ -443,17 +483,38 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     // never 0 (the value of a cleared slot): the low word plus the number of times it has wrapped
     const unsigned long long cnt = launches + 1ull;
     const uint32_t stamp = (uint32_t)(cnt + (cnt >> 32));
+    // MF: the value goes to row b, column r of the operand array as fp16; without RMSNorm that is x itself,
+    // with it the product x * gamma is kept as high + low part, so that nothing is rounded away
+    auto stage = [&](int i, float v) {
+        if constexpr (MF) {
+            const int b = i / p.RPS, r = i - b * p.RPS;
+            const _Float16 hi = (_Float16)v;
+            xh[b * XS + r] = hi;
+            if (norm) xl[b * XS + r] = (_Float16)(v - (float)hi);
+        } else {
+            xs[i] = v;
+        }
+    };
     if (x_in_regs) {
 #pragma unroll
         for (int q = 0; q < XR; ++q) {
             const int i = tid + q * NT;
-            if (i < BT * p.RPS) xs[i] = xv[q] ? h2f(xr[q]) * (norm ? h2f(gr[q]) : 1.f) : 0.f;
+            if (i < BT * p.RPS) stage(i, xv[q] ? h2f(xr[q]) * (norm ? h2f(gr[q]) : 1.f) : 0.f);
         }
     } else {
         for (int i = tid; i < BT * p.RPS; i += NT) {
             const int b = i / p.RPS, r = i - b * p.RPS;
             const bool in = b < p.B && r < nrows;
-            xs[i] = in ? h2f(p.x[(size_t)b * p.D + r0 + r]) * (norm ? h2f(gsrc[r0 + r]) : 1.f) : 0.f;
+            stage(i, in ? h2f(p.x[(size_t)b * p.D + r0 + r]) * (norm ? h2f(gsrc[r0 + r]) : 1.f) : 0.f);
+        }
+    }
+    if constexpr (MF) {
+        // columns RPS .. XS-1 of every row (an operand read may reach up to seven columns past the slice)
+        const int nz = XS - p.RPS;
+        for (int e = tid; e < 16 * nz; e += NT) {
+            const int b = e / nz, r = p.RPS + (e - b * nz);
+            xh[b * XS + r] = (_Float16)0.f;
+            xl[b * XS + r] = (_Float16)0.f;
         }
     }
     if (BT <= 4 && norm) square_rows(0);
@@ -469,11 +530,14 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     lds_barrier();
     CF_STAMP(2);            // x staged
 
-    float acc[BT][8];
+    float acc[MF ? 1 : BT][8];              // FMA tiles: [batch row][column] of this lane's row group
+    f32x4 acc4[MF ? 8 : 1];                 // MFMA tiles: [column][batch rows 4 * (lane / 16) + 0..3]
 #pragma unroll
-    for (int b = 0; b < BT; ++b)
+    for (int b = 0; b < (MF ? 1 : BT); ++b)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[b][j] = 0.f;
+#pragma unroll
+    for (int c = 0; c < (MF ? 8 : 1); ++c) acc4[c] = f32x4{0.f, 0.f, 0.f, 0.f};
     int si_first = 0;                       // selector index of the first buffered item
     int nbuf = 0;
     auto flush = [&]() {
@@ -499,17 +563,36 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     };
     auto consume = [&](const h8(&w)[U]) {
         const int i0 = cc.i0;
+        if constexpr (MF) {
+            // one step of 32 rows: operand A = x[batch row lane % 16][rows of this lane's group], operands B =
+            // the eight columns of this lane.  Rows past the slice: their weights are zero (loads switched off)
+            // and x is zero up to column XS; a group that starts past the slice reads nothing.
+            const int r = NG * i0 + lrow;
+            const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+            const int xo = (tid & 15) * XS + min(r, XS - 8);
+            const h8 ah = r < nrows ? *reinterpret_cast<const h8 *>(xh + xo) : zero;
+            h8 f[8];
+            transpose8(w, f);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            // a row past the slice has zero weights (its load was switched off) and any finite x
-            const int r = min(grp + NG * (i0 + u), p.RPS - 1);
-            float f[8];
-            unpack8(w[u], f);
+            for (int c = 0; c < 8; ++c) acc4[c] = mfma16(ah, f[c], acc4[c]);
+            if (norm) {
+                const h8 al = r < nrows ? *reinterpret_cast<const h8 *>(xl + xo) : zero;
 #pragma unroll
-            for (int b = 0; b < BT; ++b) {
-                const float xv = xs[b * p.RPS + r];
+                for (int c = 0; c < 8; ++c) acc4[c] = mfma16(al, f[c], acc4[c]);
+            }
+        } else {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) acc[b][j] = fmaf(xv, f[j], acc[b][j]);
+            for (int u = 0; u < U; ++u) {
+                // a row past the slice has zero weights (its load was switched off) and any finite x
+                const int r = min(grp + NG * (i0 + u), p.RPS - 1);
+                float f[8];
+                unpack8(w[u], f);
+#pragma unroll
+                for (int b = 0; b < BT; ++b) {
+                    const float xv = xs[b * p.RPS + r];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[b][j] = fmaf(xv, f[j], acc[b][j]);
+                }
             }
         }
     };
@@ -517,7 +600,21 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
         const int si = cc.si, i0 = cc.i0;
         if (si >= nsel) return;                     // padding step: nothing was loaded
         advance(cc);
-        if (i0 + U >= iters) {
+        if (i0 + U < iters) return;
+        if constexpr (MF) {
+            // last batch of this selector: the MFMA has already added the four row groups of the wavefront;
+            // the lane holds eight adjacent columns of batch rows 4 * kg + 0..3
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float *dst = red + ((nbuf * NW + wv) * BT + 4 * kg + r) * HD + lig * 8;
+                *reinterpret_cast<f32x4 *>(dst) = f32x4{acc4[0][r], acc4[1][r], acc4[2][r], acc4[3][r]};
+                *reinterpret_cast<f32x4 *>(dst + 4) = f32x4{acc4[4][r], acc4[5][r], acc4[6][r], acc4[7][r]};
+            }
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc4[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (nbuf == 0) si_first = si;
+            if (++nbuf == MAXI) flush();
+        } else {
             // last batch of this selector: row groups of a wavefront by shuffles; the wavefronts
             // are added in flush(), in a fixed order
 #pragma unroll
@@ -554,10 +651,15 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     // iteration: the load offset is made to depend on the accumulators the batch was folded into
     auto after_consume = [&]() {
         uint32_t v = voff0;
+        if constexpr (MF) {
 #pragma unroll
-        for (int b = 0; b < BT; ++b)
-            asm volatile("" : "+v"(v) : "v"(acc[b][0]), "v"(acc[b][1]), "v"(acc[b][2]), "v"(acc[b][3]),
-                         "v"(acc[b][4]), "v"(acc[b][5]), "v"(acc[b][6]), "v"(acc[b][7]));
+            for (int c = 0; c < 8; ++c) asm volatile("" : "+v"(v) : "v"(acc4[c]));
+        } else {
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+                asm volatile("" : "+v"(v) : "v"(acc[b][0]), "v"(acc[b][1]), "v"(acc[b][2]), "v"(acc[b][3]),
+                             "v"(acc[b][4]), "v"(acc[b][5]), "v"(acc[b][6]), "v"(acc[b][7]));
+        }
         return v;
     };
     for (int k = 0; k + 2 < nsteps2; k += 2) {
@@ -966,7 +1068,10 @@ struct OutTile {
 };
 
 // part: 0 = first half of the tile's loads, 1 = second half, 2 = all
-template <int HD>
+// MF (MFMA tiles): wavefront wv takes columns [128 (wv % 4), +128) of the chunk and rows [64 (wv / 4), +64) of the
+// item; lane (l % 16, l / 16) loads eight adjacent columns of rows 32 s + 8 (l / 16) + 0..7 for the two steps s
+// (the same lane layout as in the projection: eight rows are transposed in the lane into MFMA operands).
+template <int HD, bool MF>
 __device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs, int ch, OutTile<HD> &t, int part = 2)
 {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -980,6 +1085,19 @@ __device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs,
     const uint32_t sbase = (p.flags & kFlagPacked) ? (uint32_t)((hq * p.NCH + cbase / kOutChunk) * HD + rs * nrows) * rowb
                                     : (uint32_t)(hq * HD + rs * nrows) * rowb + (uint32_t)cbase * 2;
     const int iters = nrows / NW;
+    if constexpr (MF) {
+        static_assert(OutTile<HD>::MAXR == 16, "two steps of eight rows per lane");
+        const int lig = lane & 15, kg = lane >> 4, cb = wv & 3, kh = wv >> 2;
+        const uint32_t voffm = (cbase + 128 * cb + 8 * lig) < p.D ? (uint32_t)(8 * kg) * rowb + (uint32_t)(128 * cb + 8 * lig) * 2
+                                                                  : kNoLoad;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const bool mine = part == 2 || (part == 0) == (u < 8);
+            const int row = 64 * kh + 32 * (u >> 3) + (u & 7);          // + 8 kg: the lane's row inside the item
+            if (mine) t.w[u] = Wo.ld(row + 8 * kg < nrows ? voffm : kNoLoad, sbase + (uint32_t)row * rowb);
+        }
+        return;
+    }
 #pragma unroll
     for (int u = 0; u < OutTile<HD>::MAXR; ++u) {
         const bool mine = part == 2 || (part == 0) == (u < OutTile<HD>::MAXR / 2);
@@ -1004,7 +1122,8 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
     const int slot = hq * p.RS3 + rs;
     const int nchunk = p.CW3 / kOutChunk;
 
-    if (!prefetched) p3_load<HD>(p, hq, c3, rs, 0, tile);     // independent of the attention result
+    constexpr bool MF = Mfma<HD, BT>::on;
+    if (!prefetched) p3_load<HD, MF>(p, hq, c3, rs, 0, tile);     // independent of the attention result
 
     {
         // ---- merge of the split-KV partials (Alg. 3 steps 5-7).  Value v = (batch row, column) is handled by SG threads,
@@ -1081,7 +1200,47 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
     for (int ch = 0; ch < nchunk; ++ch) {
         const int cbase = c3 * p.CW3 + ch * kOutChunk;
         if (cbase >= p.D) break;
-        if (ch > 0) p3_load<HD>(p, hq, c3, rs, ch, tile);
+        if (ch > 0) p3_load<HD, MF>(p, hq, c3, rs, ch, tile);
+        if constexpr (MF) {
+            // [16 batch rows] x [rows of the item] x [128 columns of this wavefront]: two steps of 32 rows for each
+            // half of the rows; the attention output is split into a high and a low fp16 part (two products), so
+            // that it enters with all its fp32 bits
+            const int lig = lane & 15, kg = lane >> 4, cb = wv & 3, kh = wv >> 2;
+            f32x4 acc4[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc4[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int sstep = 0; sstep < 2; ++sstep) {
+                const int row = 64 * kh + 32 * sstep + 8 * kg;          // first of the lane's eight rows
+                float a[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) a[e] = row < nrows ? as[(lane & 15) * HD + rbeg + row + e] : 0.f;
+                h8 ahi, alo, f[8];
+                split_hi_lo(a, ahi, alo);
+                transpose8(&tile.w[8 * sstep], f);
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    acc4[c] = mfma16(ahi, f[c], acc4[c]);
+                    acc4[c] = mfma16(alo, f[c], acc4[c]);
+                }
+            }
+            // the two halves of the rows -> one partial row per batch row
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float *dst = red + ((kh * 16 + 4 * kg + r) * kOutChunk) + 128 * cb + 8 * lig;
+                *reinterpret_cast<f32x4 *>(dst) = f32x4{acc4[0][r], acc4[1][r], acc4[2][r], acc4[3][r]};
+                *reinterpret_cast<f32x4 *>(dst + 4) = f32x4{acc4[4][r], acc4[5][r], acc4[6][r], acc4[7][r]};
+            }
+            lds_barrier();
+            for (int e = tid; e < 16 * kOutChunk; e += NT) {
+                const int b = e / kOutChunk, cc = e - b * kOutChunk;
+                if (b < p.B && cbase + cc < p.D)
+                    x3.st(((size_t)slot * p.B + b) * p.D + cbase + cc, red[e] + red[16 * kOutChunk + e], stamp);
+            }
+            CF_STAMP(18);   // output partial stored
+            lds_barrier();
+            continue;
+        }
         float acc[BT][8];
 #pragma unroll
         for (int b = 0; b < BT; ++b)
@@ -1266,7 +1425,7 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
         if (member < n3) {
             int hq, c3, rs;
             p3_args(member, hq, c3, rs);
-            p3_load<HD>(p, hq, c3, rs, 0, tile, part);
+            p3_load<HD, Mfma<HD, BT>::on>(p, hq, c3, rs, 0, tile, part);
             tile_ready = true;
         }
     };
@@ -1415,7 +1574,7 @@ size_t lds_floats(const Params &p, int hd, int g, int bt)
 {
     const size_t rb = bt < 4 ? bt : 4;
     const size_t maxi = bt == 1 ? 4 : (bt <= 4 ? 2 : 1);
-    const size_t f1 = (size_t)bt * p.RPS + maxi * kWaves * bt * hd + (size_t)kWaves * bt;
+    const size_t f1 = x_lds_floats(hd, bt, p.RPS) + maxi * kWaves * bt * hd + (size_t)kWaves * bt;
     const size_t npart = g >= 8 ? (size_t)kWaves * (64 / (hd / 8)) : kWaves;      // attention partials folded through LDS
     const size_t f2 = (size_t)hd + (size_t)(g + 2) * hd + 8 + 2 * (size_t)g * npart + (size_t)g * npart * hd;
     const size_t f3 = (size_t)bt * hd + (size_t)kWaves * rb * kOutChunk;

@@ -20,6 +20,16 @@ constexpr int kCounterStride = 16;   // 64-bit words between the launch counters
 constexpr int kMaxKSplits = 64;
 constexpr int kMaxKvSplits = 64;
 
+// Batch tile 16 with head_dim 128 runs both projections on MFMA tiles; x then sits in LDS as fp16 operands,
+// [16][xs16_stride(rows of the longest split)] halves, twice (high parts, low parts of x * gamma).
+__host__ __device__ constexpr bool mfma_tiles(int head_dim, int batch_tile) { return batch_tile == 16 && head_dim == 128; }
+__host__ __device__ constexpr int xs16_stride(int rps) { return ((rps + 7) & ~7) + 8; }
+// LDS floats that hold x in phase 1
+__host__ __device__ constexpr size_t x_lds_floats(int head_dim, int batch_tile, int rps)
+{
+    return mfma_tiles(head_dim, batch_tile) ? (size_t)16 * xs16_stride(rps) : (size_t)batch_tile * rps;
+}
+
 constexpr int kFlagPacked = 1;     // weights are in the packed (per-head contiguous) layout of cf_pack_weights
 constexpr int kFlagResidual = 2;   // out = x + block output
 
