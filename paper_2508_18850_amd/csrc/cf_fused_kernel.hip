@@ -738,9 +738,31 @@ struct P2Cfg {
     static constexpr int NB = 2;                // batches in flight
 };
 
-template <int G>
+// Attention on MFMA tiles (head_dim 128, four or more query heads per KV head): the G query heads that share
+// a K/V row are the (zero-padded) 16-row edge of two dense products per 32 cached tokens,
+//   S^T = K q^T   (A = K rows, B = q, contraction over head_dim in four steps of 32),
+//   O  += P V     (A = P, B = V, contraction over the 32 tokens),
+// in place of 16 G multiply-adds per loaded 16 bytes on the vector ALU, which is what bounds the plain loop
+// from G = 4 on.  A wavefront owns every eighth tile of 32 tokens of the split.  K rows are loaded row by
+// row (16 lanes x 16 bytes), put into a tile of LDS that only this wavefront uses and read back as A operands
+// (lane l: token l % 16, eight of the 32 dimensions of a step); the result has token 4 (l / 16) + r of each
+// 16-token half in register r of lane (head l % 16).  Those eight scores of a lane are, after the softmax,
+// exactly the lane's A operand of the second product if contraction index (l / 16, e) stands for token
+// 16 (e / 4) + 4 (l / 16) + e % 4, so V rows are loaded in that order and transposed in the lane
+// (transpose8), and nothing moves between the two products.
+template <int HD, int G>
+struct AttnMfma {
+    static constexpr bool on = HD == 128 && G >= 4;
+    static constexpr int kTile = 32;                   // tokens per tile
+    static constexpr int kRowH = HD + 8;               // halves per K row in LDS (16 bytes of padding: bank spread)
+    static constexpr int kTileFloats = kTile * kRowH / 2;   // LDS floats per wavefront
+};
+
+template <int HD, int G>
 struct KvBuf {
-    h8 k[P2Cfg<G>::NB][P2Cfg<G>::U], v[P2Cfg<G>::NB][P2Cfg<G>::U];
+    static constexpr bool MA = AttnMfma<HD, G>::on;
+    static constexpr int NBd = MA ? 1 : P2Cfg<G>::NB, Ud = MA ? 8 : P2Cfg<G>::U;
+    h8 k[NBd][Ud], v[NBd][Ud];
 };
 
 template <int HD, int G>
@@ -748,6 +770,7 @@ struct P2Stream {
     static constexpr int LPR = HD / 8;
     static constexpr int NG = NT / LPR;
     static constexpr int U = P2Cfg<G>::U;
+    static constexpr bool MA = AttnMfma<HD, G>::on;
     int t0, t1, iters, grp, pos;
     uint32_t voff0;
     size_t head;
@@ -766,6 +789,31 @@ struct P2Stream {
         t1 = active ? min(t0 + p.TPS + ((s & 1) ? -p.TD : p.TD), pos_b) : 0;
         iters = t1 > t0 ? (t1 - t0 + NG - 1) / NG : 0;
         voff0 = (uint32_t)(grp * HD + lig * 8) * 2;
+        if (MA) iters = t1 > t0 ? (t1 - t0 + 32 * NW - 1) / (32 * NW) : 0;   // rounds of one 32-token tile per wavefront
+    }
+    // MFMA tiles: round `it` gives wavefront wv the tokens t0 + 32 (8 it + wv) + 0..31.  K: load u brings rows
+    // 4 u + (lane / 16); V: load u brings rows 16 (u / 4) + 4 (lane / 16) + u % 4 (the order in which the scores
+    // come out of the first product).  Eight load instructions each, lanes past the split switched off.
+    __device__ __forceinline__ void load_k(h8 (&kr)[8], int it, uint32_t dep) const
+    {
+        const int wv = threadIdx.x >> 6, rg = (threadIdx.x & 63) >> 4, lig = threadIdx.x & 15;
+        const uint32_t voff = (uint32_t)((32 * wv + rg) * HD + lig * 8) * 2 + dep;
+        const int tb = t0 + 32 * NW * it;                       // uniform
+        const int lim = t1 - 32 * wv - rg;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) kr[u] = K.ld(tb + 4 * u < lim ? voff : kNoLoad, (uint32_t)(tb + 4 * u) * HD * 2);
+    }
+    __device__ __forceinline__ void load_v(h8 (&vr)[8], int it, uint32_t dep) const
+    {
+        const int wv = threadIdx.x >> 6, rg = (threadIdx.x & 63) >> 4, lig = threadIdx.x & 15;
+        const uint32_t voff = (uint32_t)((32 * wv + 4 * rg) * HD + lig * 8) * 2 + dep;
+        const int tb = t0 + 32 * NW * it;
+        const int lim = t1 - 32 * wv - 4 * rg;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int r = 16 * (u >> 2) + (u & 3);
+            vr[u] = V.ld(tb + r < lim ? voff : kNoLoad, (uint32_t)(tb + r) * HD * 2);
+        }
     }
     // Always 2*U load instructions on a straight-line path (rows past the split: lane switched off),
     // so that the compiler's wait counts for earlier loads stay exact.
@@ -784,18 +832,25 @@ struct P2Stream {
     // the first NB batches do not depend on q: they are put in flight before q is needed; part 0
     // (two batches) before the last steps of phase 1, part 1 (the rest) once phase 1 has stored
     // its partial sums (stores queue behind every load issued before them)
-    __device__ __forceinline__ void prefetch(KvBuf<G> &buf, int part) const
+    __device__ __forceinline__ void prefetch(KvBuf<HD, G> &buf, int part) const
     {
         constexpr int NB = P2Cfg<G>::NB;
+        if constexpr (MA) {
+            if (part == 0)
+                load_k(buf.k[0], 0, 0u);
+            else
+                load_v(buf.v[0], 0, 0u);
+        } else {
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
-            if ((j < 2) == (part == 0)) load(buf.k[j], buf.v[j], j * U, voff0);
+            for (int j = 0; j < NB; ++j)
+                if ((j < 2) == (part == 0)) load(buf.k[j], buf.v[j], j * U, voff0);
+        }
     }
 };
 
 template <int HD, int G, class TailFn>
 __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s, uint32_t stamp, bool first,
-                                        const P2Stream<HD, G> &st, KvBuf<G> &buf, const EarlyQ &eq, float *smem,
+                                        const P2Stream<HD, G> &st, KvBuf<HD, G> &buf, const EarlyQ &eq, float *smem,
                                         const float *rope, TailFn &&issue_next)
 {
     constexpr int LPR = HD / 8;
@@ -803,7 +858,11 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
     constexpr int U = P2Cfg<G>::U;
     constexpr int NB = P2Cfg<G>::NB;
     constexpr int PS = HD + kP2Stride;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
+    // (the thread index is made opaque per item: everything derived from it would otherwise be computed once in
+    // front of the loop over the items, dozens of registers that are then spilled)
+    int tid = threadIdx.x;
+    if (AttnMfma<HD, G>::on) asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
     const bool last = (s == p.NS - 1);
     const Xbuf x1(p.p1), x2(p.p2);
 
@@ -818,7 +877,8 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
     // spilled registers and costs more than the larger fold (measured: 70B shape 111 -> 105 us; with 4 heads
     // per group the shuffle merge is the faster one, 32.1 against 35.1 us).
     constexpr int RGW = 64 / LPR;                               // row groups of a wavefront
-    constexpr bool kFoldRowGroups = G >= 8;
+    constexpr bool MA = AttnMfma<HD, G>::on;                    // both products on MFMA tiles: one partial per wavefront
+    constexpr bool kFoldRowGroups = G >= 8 && !MA;
     constexpr int NPART = kFoldRowGroups ? NW * RGW : NW;
     float *redm = snew + 8;                 // [G][NPART]
     float *redl = redm + G * NPART;         // [G][NPART]
@@ -847,7 +907,118 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
     // q fragments of this lane's 8 columns, pre-scaled by log2(e)/sqrt(d).  Up to GP heads stay in
     // registers; wider groups (G > GP) re-read them from LDS for every pass over a batch.
     constexpr int GP = P2Cfg<G>::GP;
+    constexpr bool kQsScaled = !MA && G > GP;                   // qs is overwritten by the scaled q
     float qf[GP][8];
+    if constexpr (MA) {
+        constexpr int RH = AttnMfma<HD, G>::kRowH;
+        _Float16 *kt = reinterpret_cast<_Float16 *>(redacc + G * NPART * HD) + wv * (AttnMfma<HD, G>::kTile * RH);
+        const int hq = lane & 15, quad = lane >> 4;             // operand row / column of the lane, contraction group
+        // B operands of K q^T: head hq (zero for hq >= G), the lane's eight of the 32 dimensions of each step,
+        // pre-scaled by log2(e)/sqrt(d), as high + low fp16 parts so that q keeps its fp32 bits.  They are the
+        // same for every wavefront and every tile: kept in LDS ([step][lane], high then low), not in registers.
+        h8 *qop = reinterpret_cast<h8 *>(redacc + G * NPART * HD + NW * AttnMfma<HD, G>::kTileFloats);
+        if (tid < 256) {
+            const int s4 = tid >> 6;
+            float a[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a[e] = hq < G ? qs[hq * HD + 32 * s4 + 8 * quad + e] * p.qk_scale_log2e : 0.f;
+            h8 hi, lo;
+            split_hi_lo(a, hi, lo);
+            qop[tid] = hi;
+            qop[256 + tid] = lo;
+        }
+        lds_barrier();
+        CF_STAMP(14);           // q ready
+        float m = kNegBig, l = 0.f;      // of head hq: running maximum (the same in the four lanes of a head), sum of this lane's tokens
+        f32x4 O[8];                      // [column of the lane][heads 4 quad + 0..3]
+#pragma unroll
+        for (int c = 0; c < 8; ++c) O[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int it = 0; it < st.iters; ++it) {
+            // ---- K rows -> this wavefront's tile in LDS -> A operands; the registers are reloaded at once
+#pragma unroll
+            for (int u = 0; u < 8; ++u) *reinterpret_cast<h8 *>(kt + (4 * u + quad) * RH + lig * 8) = buf.k[0][u];
+            __builtin_amdgcn_sched_barrier(0);
+            st.load_k(buf.k[0], it + 1, 0u);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            f32x4 S[2];
+#pragma unroll
+            for (int T = 0; T < 2; ++T) {
+                S[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4) {
+                    const h8 kf = *reinterpret_cast<const h8 *>(kt + (16 * T + hq) * RH + 32 * s4 + 8 * quad);
+                    S[T] = mfma16(kf, qop[s4 * 64 + lane], S[T]);
+                    S[T] = mfma16(kf, qop[256 + s4 * 64 + lane], S[T]);
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            // ---- online softmax of head hq over the lane's eight tokens 16 T + 4 quad + r
+            const int tb = t0 + 32 * (NW * it + wv) + 4 * quad;
+            float sc[8];
+            bool ok[8];
+            float mx = kNegBig;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                ok[e] = tb + 16 * (e >> 2) + (e & 3) < t1;
+                sc[e] = ok[e] ? S[e >> 2][e & 3] : kNegBig;
+                mx = fmaxf(mx, sc[e]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float mn = fmaxf(m, mx);
+            if (__any(mn > m)) {
+                // a maximum has grown (rare after the first tiles): rescale the sum and the accumulators; the lane
+                // holds heads 4 quad + r, whose factors are in lanes 4 quad + r
+                const float scale = __builtin_amdgcn_exp2f(m - mn);
+                l *= scale;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float sr = __shfl(scale, 4 * quad + r);
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) O[c][r] *= sr;
+                }
+                m = mn;
+            }
+            float pv[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                pv[e] = ok[e] ? __builtin_amdgcn_exp2f(sc[e] - mn) : 0.f;
+                l += pv[e];
+            }
+            h8 ph, pl;
+            split_hi_lo(pv, ph, pl);
+            // ---- O += P V
+            h8 f[8];
+            transpose8(buf.v[0], f);
+            __builtin_amdgcn_sched_barrier(0);
+            st.load_v(buf.v[0], it + 1, 0u);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                O[c] = mfma16(ph, f[c], O[c]);
+                O[c] = mfma16(pl, f[c], O[c]);
+            }
+        }
+        CF_STAMP(15);           // K/V consumed
+        if (!last) issue_next(1);
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (hq < G && quad == 0) {
+            redm[hq * NPART + wv] = m;
+            redl[hq * NPART + wv] = l;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int g = 4 * quad + r;
+            if (g < G) {
+                float *dst = redacc + (g * NPART + wv) * HD + lig * 8;
+                *reinterpret_cast<f32x4 *>(dst) = f32x4{O[0][r], O[1][r], O[2][r], O[3][r]};
+                *reinterpret_cast<f32x4 *>(dst + 4) = f32x4{O[4][r], O[5][r], O[6][r], O[7][r]};
+            }
+        }
+    } else {
     if (G > GP) {
         for (int e = tid; e < G * HD; e += NT) qs[e] *= p.qk_scale_log2e;   // qs now holds the scaled q
         lds_barrier();
@@ -990,6 +1161,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
             }
         }
     }
+    }   // !MA
     CF_STAMP(8);            // row groups of the wavefront merged
     if (last) {
         // ---- the new token: sum its key/value partials (stored at the end of phase 1, long ago by
@@ -1016,12 +1188,12 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
             float d = 0.f;
             for (int c = lane; c < HD; c += 64) d = fmaf(qs[g * HD + c], kn[c], d);
             d = wave_sum(d);
-            if (lane == 0) snew[g] = (G > P2Cfg<G>::GP) ? d : d * p.qk_scale_log2e;   // qs is pre-scaled for wide groups
+            if (lane == 0) snew[g] = kQsScaled ? d : d * p.qk_scale_log2e;
         }
         if (p.dbg_q)
             for (int e = tid; e < G * HD; e += NT)
                 p.dbg_q[((size_t)b * p.nq + team * G) * HD + e] =
-                    (G > P2Cfg<G>::GP) ? qs[e] / p.qk_scale_log2e : qs[e];
+                    kQsScaled ? qs[e] / p.qk_scale_log2e : qs[e];
     }
     lds_barrier();
     CF_STAMP(9);            // new token handled, wavefronts in step
@@ -1081,15 +1253,19 @@ __device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs,
     const int nrows = HD / p.RS3;
     const int cbase = c3 * p.CW3 + ch * kOutChunk;
     const uint32_t rowb = (p.flags & kFlagPacked) ? (uint32_t)kOutChunk * 2 : (uint32_t)p.D * 2;
-    const uint32_t voff = (cbase + lane * 8) < p.D ? (uint32_t)wv * rowb + lane * 16 : kNoLoad;
+    uint32_t voff = (cbase + lane * 8) < p.D ? (uint32_t)wv * rowb + lane * 16 : kNoLoad;
+    // (opaque to the compiler: it otherwise computes the sixteen per-row offsets of all call sites once, far
+    // ahead of the first one, and spills them)
+    asm volatile("" : "+v"(voff));
     const uint32_t sbase = (p.flags & kFlagPacked) ? (uint32_t)((hq * p.NCH + cbase / kOutChunk) * HD + rs * nrows) * rowb
                                     : (uint32_t)(hq * HD + rs * nrows) * rowb + (uint32_t)cbase * 2;
     const int iters = nrows / NW;
     if constexpr (MF) {
         static_assert(OutTile<HD>::MAXR == 16, "two steps of eight rows per lane");
         const int lig = lane & 15, kg = lane >> 4, cb = wv & 3, kh = wv >> 2;
-        const uint32_t voffm = (cbase + 128 * cb + 8 * lig) < p.D ? (uint32_t)(8 * kg) * rowb + (uint32_t)(128 * cb + 8 * lig) * 2
-                                                                  : kNoLoad;
+        uint32_t voffm = (cbase + 128 * cb + 8 * lig) < p.D ? (uint32_t)(8 * kg) * rowb + (uint32_t)(128 * cb + 8 * lig) * 2
+                                                            : kNoLoad;
+        asm volatile("" : "+v"(voffm));
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
             const bool mine = part == 2 || (part == 0) == (u < 8);
@@ -1392,7 +1568,7 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
 
     const int n2 = p.B * p.NS;                       // attention items of the team
     const int n3 = G * p.NC3 * p.RS3;                // output-projection items of the team
-    KvBuf<G> kv;
+    KvBuf<HD, G> kv;
     OutTile<HD> tile;
     const int b_first = member < n2 ? qdiv(member, p.NS, p.sh_ns) : 0;     // batch row of the first attention item
     const int pos_first = row_pos(p, b_first);
@@ -1575,8 +1751,10 @@ size_t lds_floats(const Params &p, int hd, int g, int bt)
     const size_t rb = bt < 4 ? bt : 4;
     const size_t maxi = bt == 1 ? 4 : (bt <= 4 ? 2 : 1);
     const size_t f1 = x_lds_floats(hd, bt, p.RPS) + maxi * kWaves * bt * hd + (size_t)kWaves * bt;
-    const size_t npart = g >= 8 ? (size_t)kWaves * (64 / (hd / 8)) : kWaves;      // attention partials folded through LDS
-    const size_t f2 = (size_t)hd + (size_t)(g + 2) * hd + 8 + 2 * (size_t)g * npart + (size_t)g * npart * hd;
+    const bool ma = hd == 128 && g >= 4;                                          // attention on MFMA tiles: a K tile per wavefront
+    const size_t npart = (g >= 8 && !ma) ? (size_t)kWaves * (64 / (hd / 8)) : kWaves;      // attention partials folded through LDS
+    const size_t f2 = (size_t)hd + (size_t)(g + 2) * hd + 8 + 2 * (size_t)g * npart + (size_t)g * npart * hd +
+                      (ma ? (size_t)kWaves * 32 * (hd + 8) / 2 + 2 * 256 * 4 : 0);   // K tiles, q operands
     const size_t f3 = (size_t)bt * hd + (size_t)kWaves * rb * kOutChunk;
     size_t f = f1 > f2 ? f1 : f2;
     return f > f3 ? f : f3;
