@@ -27,7 +27,6 @@ struct cf_handle_s {
     unsigned long long *done = nullptr;
     uint64_t *p1 = nullptr, *p2 = nullptr, *p3 = nullptr;
     float *dbg_q = nullptr, *dbg_attn = nullptr;
-    double *inv_freq = nullptr;
     unsigned long long *dbg_t = nullptr;
     uint16_t *chain[2] = {nullptr, nullptr};   // hidden states between the layers of a stack, [max_batch, d_model] each
     // tuning
@@ -152,7 +151,6 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
         p->CW3 = ceil_div(nch, best_nc) * cf::kOutChunk;
         p->NC3 = ceil_div(nch * cf::kOutChunk, p->CW3);
     }
-    p->NCH = h->nch;
     p->DSEL = TS / p->KS;
     auto log2_or_minus1 = [](int v) {
         for (int k = 0; k < 31; ++k)
@@ -174,7 +172,7 @@ void fill_static(const cf_handle_s *h, Params *p)
     p->p1 = h->p1;
     p->p2 = h->p2;
     p->p3 = h->p3;
-    p->inv_freq = h->inv_freq;
+    p->rope_log2_base = std::log2((double)c.rope_base);
     p->dbg_q = (c.flags & CF_FLAG_DEBUG_EXPORT) ? h->dbg_q : nullptr;
     p->dbg_attn = (c.flags & CF_FLAG_DEBUG_EXPORT) ? h->dbg_attn : nullptr;
     p->dbg_t = (c.flags & CF_FLAG_DEBUG_EXPORT) ? h->dbg_t : nullptr;
@@ -268,11 +266,10 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     const size_t p2_bytes = align_up(B * c.n_q_heads * cf::kMaxKvSplits * (hd + cf::kP2Stride) * sizeof(uint64_t), 256);
     const size_t p3_bytes = align_up((size_t)c.n_q_heads * 8 * B * c.d_model * sizeof(uint64_t), 256);
     const size_t dbg_bytes = align_up(B * c.n_q_heads * hd * sizeof(float), 256);
-    const size_t freq_bytes = align_up(hd / 2 * sizeof(double), 256);
     const size_t times_bytes = align_up((size_t)8 * h->num_cu * cf::kStamps * sizeof(unsigned long long), 256);
     h->exchange_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes;
     const size_t chain_bytes = align_up(B * c.d_model * sizeof(uint16_t), 256);
-    h->ws_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes + 2 * dbg_bytes + freq_bytes + times_bytes +
+    h->ws_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes + 2 * dbg_bytes + times_bytes +
                   2 * chain_bytes;
     e = hipMalloc(reinterpret_cast<void **>(&h->ws), h->ws_bytes);
     if (e != hipSuccess) {
@@ -293,17 +290,12 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     cur += dbg_bytes;
     h->dbg_attn = reinterpret_cast<float *>(cur);
     cur += dbg_bytes;
-    h->inv_freq = reinterpret_cast<double *>(cur);
-    cur += freq_bytes;
     h->dbg_t = reinterpret_cast<unsigned long long *>(cur);
     cur += times_bytes;
     h->chain[0] = reinterpret_cast<uint16_t *>(cur);
     h->chain[1] = reinterpret_cast<uint16_t *>(cur + chain_bytes);
 
-    std::vector<double> freq(hd / 2);
-    for (size_t i = 0; i < hd / 2; ++i) freq[i] = std::pow((double)c.rope_base, -2.0 * (double)i / (double)hd);
     e = hipMemset(h->ws, 0, h->ws_bytes);
-    if (e == hipSuccess) e = hipMemcpy(h->inv_freq, freq.data(), freq.size() * sizeof(double), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         (void)hipFree(h->ws);

@@ -204,10 +204,10 @@ struct Spin {
 // Sum of n stamped slots base, base+stride, ... in index order; spins until all are current.
 // Loads go out eight at a time (indices past n repeat the last slot and are ignored) and are consumed
 // only after all eight have been issued: written as one loop, each load was waited for on its own.
+template <int C = 8>
 __device__ __forceinline__ float ll_sum(const Params &p, const Xbuf &x, size_t base, size_t stride, int n,
                                         uint32_t stamp)
 {
-    constexpr int C = 8;
     Spin spin;
     for (;;) {
         float s = 0.f;
@@ -450,13 +450,11 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     // for the RoPE tables, below: the frequency and the position of every table entry of this thread
     constexpr int NE = RopeRows<HD, BT>::NE;
     const bool own_pos = kLayer && p.row_pos != nullptr;
-    const int32_t *psrc = own_pos ? p.row_pos : reinterpret_cast<const int32_t *>(p.inv_freq);   // any readable address
-    double inv_freq[NE];
+    const int32_t *psrc = own_pos ? p.row_pos : reinterpret_cast<const int32_t *>(p.x);   // any readable address
     int epos[NE];
 #pragma unroll
     for (int k = 0; k < NE; ++k) {
         const int e = tid + k * NT, eb = e / (HD / 2);
-        inv_freq[k] = p.inv_freq[kLayer ? e % (HD / 2) : (e < HD / 2 ? e : 0)];
         epos[k] = psrc[own_pos && eb < p.B ? eb : 0];
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -524,7 +522,8 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
         const int e = tid + k * NT, eb = e / (HD / 2), i = e % (HD / 2);
         if (eb < (own_pos ? p.B : 1)) {
             const int pos_e = own_pos ? min(max(epos[k], 0), p.pos) : p.pos;
-            rope_cos_sin(pos_e, inv_freq[k], rope[eb * HD + i], rope[eb * HD + HD / 2 + i]);
+            // (the frequency is computed here: a table in memory was one more cold page in front of the first wait)
+            rope_cos_sin(pos_e, rope_inv_freq(i, HD, p.rope_log2_base), rope[eb * HD + i], rope[eb * HD + HD / 2 + i]);
         }
     }
     lds_barrier();
@@ -1248,7 +1247,8 @@ __device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs,
 {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     // row-major [nq*HD][D], or packed [nq][ceil(D/512)][HD][512] (one contiguous tile per head and chunk)
-    const Stream Wo(p.wo, (p.flags & kFlagPacked) ? (uint32_t)((size_t)p.nq * p.NCH * HD * kOutChunk * 2)
+    const int NCH = (p.D + kOutChunk - 1) / kOutChunk;        // 512-column chunks of the output
+    const Stream Wo(p.wo, (p.flags & kFlagPacked) ? (uint32_t)((size_t)p.nq * NCH * HD * kOutChunk * 2)
                                    : (uint32_t)((size_t)p.nq * HD * p.D * 2));
     const int nrows = HD / p.RS3;
     const int cbase = c3 * p.CW3 + ch * kOutChunk;
@@ -1257,7 +1257,7 @@ __device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs,
     // (opaque to the compiler: it otherwise computes the sixteen per-row offsets of all call sites once, far
     // ahead of the first one, and spills them)
     asm volatile("" : "+v"(voff));
-    const uint32_t sbase = (p.flags & kFlagPacked) ? (uint32_t)((hq * p.NCH + cbase / kOutChunk) * HD + rs * nrows) * rowb
+    const uint32_t sbase = (p.flags & kFlagPacked) ? (uint32_t)((hq * NCH + cbase / kOutChunk) * HD + rs * nrows) * rowb
                                     : (uint32_t)(hq * HD + rs * nrows) * rowb + (uint32_t)cbase * 2;
     const int iters = nrows / NW;
     if constexpr (MF) {
@@ -1302,72 +1302,112 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
     if (!prefetched) p3_load<HD, MF>(p, hq, c3, rs, 0, tile);     // independent of the attention result
 
     {
-        // ---- merge of the split-KV partials (Alg. 3 steps 5-7).  Value v = (batch row, column) is handled by SG threads,
-        //      each folding every SG-th split with a running maximum; the SG (m, l, a) triples are then
-        //      folded in split order.  All loads of a thread go out together.
+        // ---- merge of the split-KV partials (Alg. 3 steps 5-7).  A pass handles up to NV * 512 values v = (batch row,
+        //      column).  NV == 1: value v is handled by SG threads, each folding every SG-th split with a running
+        //      maximum, MC splits per round trip; the SG (m, l, a) triples are then folded in split order through
+        //      LDS.  NV == 4 (more values than threads): a thread folds all splits of four values, so that a batch of
+        //      sixteen rows takes one pass (one round trip per MC splits) instead of four.  All loads of a round go
+        //      out together.
         const int V = p.B * HD;
-        for (int v0 = 0; v0 < V; v0 += NT) {
-            const int cv = min(NT, V - v0);
-            const int SG = max(1, min(NT / cv, p.NS));
-            const int v = tid % cv, sg = tid / cv;
-            if (sg < SG) {
-                const int b = (v0 + v) / HD, c = (v0 + v) - b * HD;
-                const size_t src = ((size_t)b * p.nq + hq) * p.NS * PS;
-                constexpr int MC = 4;       // splits polled per round (3 loads each, all in flight together)
-                float mt = kNegBig, lt = 0.f, at = 0.f;
-                for (int sb = sg; sb < p.NS; sb += MC * SG) {
-                    Spin spin;
-                    float mm[MC], ll[MC], aa[MC];
-                    for (;;) {
-                        bool ok = true;
+        auto run = [&](auto nv_c, auto mc_c) {
+            constexpr int NV = decltype(nv_c)::value, MC = decltype(mc_c)::value;
+            for (int v0 = 0; v0 < V; v0 += NT * NV) {
+                const int cv = min(NT * NV, V - v0);
+                const int SG = NV == 1 ? max(1, min(NT / cv, p.NS)) : 1;
+                const int v = NV == 1 ? tid % cv : tid, sg = NV == 1 ? tid / cv : 0;
+                if (sg < SG) {
+                    float mt[NV], lt[NV], at[NV];
+                    size_t src[NV];
+                    int col[NV];
 #pragma unroll
-                        for (int k = 0; k < MC; ++k) {
-                            const int s = sb + k * SG;
-                            const size_t o = src + (size_t)(s < p.NS ? s : sb) * PS;
-                            const u32x2 vm = x2.ld(o), vl = x2.ld(o + 1), va = x2.ld(o + kP2Stride + c);
-                            ok &= (vm.y == stamp) & (vl.y == stamp) & (va.y == stamp);
-                            mm[k] = __builtin_bit_cast(float, vm.x);
-                            ll[k] = __builtin_bit_cast(float, vl.x);
-                            aa[k] = __builtin_bit_cast(float, va.x);
-                        }
-                        if (ok || spin.expired(p)) break;
+                    for (int n = 0; n < NV; ++n) {
+                        mt[n] = kNegBig;
+                        lt[n] = 0.f;
+                        at[n] = 0.f;
+                        const int vi = min(v0 + v + n * NT, V - 1);        // a value past the end repeats the last one
+                        const int b = vi / HD;
+                        col[n] = vi - b * HD;
+                        src[n] = ((size_t)b * p.nq + hq) * p.NS * PS;
                     }
+                    for (int sb = sg; sb < p.NS; sb += MC * SG) {
+                        Spin spin;
+                        float mm[NV][MC], ll[NV][MC], aa[NV][MC];
+                        for (;;) {
+                            bool ok = true;
 #pragma unroll
-                    for (int k = 0; k < MC; ++k) {
-                        if (sb + k * SG < p.NS) {
-                            const float mn = fmaxf(mt, mm[k]);
-                            const float fa = __builtin_amdgcn_exp2f(mt - mn), fb = __builtin_amdgcn_exp2f(mm[k] - mn);
-                            lt = lt * fa + ll[k] * fb;
-                            at = at * fa + aa[k] * fb;
+                            for (int n = 0; n < NV; ++n)
+#pragma unroll
+                                for (int k = 0; k < MC; ++k) {
+                                    const int s = sb + k * SG;
+                                    const size_t o = src[n] + (size_t)(s < p.NS ? s : sb) * PS;
+                                    const u32x2 vm = x2.ld(o), vl = x2.ld(o + 1), va = x2.ld(o + kP2Stride + col[n]);
+                                    ok &= (vm.y == stamp) & (vl.y == stamp) & (va.y == stamp);
+                                    mm[n][k] = __builtin_bit_cast(float, vm.x);
+                                    ll[n][k] = __builtin_bit_cast(float, vl.x);
+                                    aa[n][k] = __builtin_bit_cast(float, va.x);
+                                }
+                            if (ok || spin.expired(p)) break;
+                        }
+#pragma unroll
+                        for (int n = 0; n < NV; ++n)
+#pragma unroll
+                            for (int k = 0; k < MC; ++k) {
+                                if (sb + k * SG < p.NS) {
+                                    const float mn = fmaxf(mt[n], mm[n][k]);
+                                    const float fa = __builtin_amdgcn_exp2f(mt[n] - mn), fb = __builtin_amdgcn_exp2f(mm[n][k] - mn);
+                                    lt[n] = lt[n] * fa + ll[n][k] * fb;
+                                    at[n] = at[n] * fa + aa[n][k] * fb;
+                                    mt[n] = mn;
+                                }
+                            }
+                    }
+                    if (NV == 1) {
+                        red[(sg * cv + v) * 3 + 0] = mt[0];
+                        red[(sg * cv + v) * 3 + 1] = lt[0];
+                        red[(sg * cv + v) * 3 + 2] = at[0];
+                    } else {
+#pragma unroll
+                        for (int n = 0; n < NV; ++n) {
+                            const int vi = v0 + v + n * NT;
+                            if (vi < V) {
+                                const float a = at[n] / lt[n];
+                                as[vi] = a;
+                                if (p.dbg_attn && c3 == 0 && rs == 0) p.dbg_attn[((size_t)(vi / HD) * p.nq + hq) * HD + col[n]] = a;
+                            }
+                        }
+                    }
+                }
+                lds_barrier();
+                if (NV == 1) {
+                    if (tid < cv) {
+                        float mt = kNegBig, lt = 0.f, at = 0.f;
+                        for (int k = 0; k < SG; ++k) {
+                            const float mk = red[(k * cv + tid) * 3], lk = red[(k * cv + tid) * 3 + 1],
+                                        ak = red[(k * cv + tid) * 3 + 2];
+                            const float mn = fmaxf(mt, mk);
+                            const float fa = __builtin_amdgcn_exp2f(mt - mn), fb = __builtin_amdgcn_exp2f(mk - mn);
+                            lt = lt * fa + lk * fb;
+                            at = at * fa + ak * fb;
                             mt = mn;
                         }
+                        const float a = at / lt;
+                        as[v0 + tid] = a;
+                        if (p.dbg_attn && c3 == 0 && rs == 0) {
+                            const int b = (v0 + tid) / HD, c = (v0 + tid) - b * HD;
+                            p.dbg_attn[((size_t)b * p.nq + hq) * HD + c] = a;
+                        }
                     }
-                }
-                red[(sg * cv + v) * 3 + 0] = mt;
-                red[(sg * cv + v) * 3 + 1] = lt;
-                red[(sg * cv + v) * 3 + 2] = at;
-            }
-            lds_barrier();
-            if (tid < cv) {
-                float mt = kNegBig, lt = 0.f, at = 0.f;
-                for (int k = 0; k < SG; ++k) {
-                    const float mk = red[(k * cv + tid) * 3], lk = red[(k * cv + tid) * 3 + 1],
-                                ak = red[(k * cv + tid) * 3 + 2];
-                    const float mn = fmaxf(mt, mk);
-                    const float fa = __builtin_amdgcn_exp2f(mt - mn), fb = __builtin_amdgcn_exp2f(mk - mn);
-                    lt = lt * fa + lk * fb;
-                    at = at * fa + ak * fb;
-                    mt = mn;
-                }
-                const float a = at / lt;
-                as[v0 + tid] = a;
-                if (p.dbg_attn && c3 == 0 && rs == 0) {
-                    const int b = (v0 + tid) / HD, c = (v0 + tid) - b * HD;
-                    p.dbg_attn[((size_t)b * p.nq + hq) * HD + c] = a;
+                    lds_barrier();
                 }
             }
-            lds_barrier();
-        }
+        };
+        using std::integral_constant;
+        // (NV == 1 with eight splits per round trip was measured and is slower than four: a round is repeated as a
+        // whole until all its stamps are current, and the partials of a team do not arrive together)
+        if (V > NT)
+            run(integral_constant<int, 4>{}, integral_constant<int, 2>{});
+        else
+            run(integral_constant<int, 1>{}, integral_constant<int, 4>{});
         for (int e = V + tid; e < BT * HD; e += NT) as[e] = 0.f;
         lds_barrier();
     }
@@ -1519,8 +1559,9 @@ __device__ __forceinline__ void final_reduce(const Params &p, uint32_t stamp, fl
         const uint16_t xres = residual_input(p, v0);
         if (s0 < spt) {
             const int n = (nslots - s0 + spt - 1) / spt;
-            smem[s0 * cb + v] = ll_sum(p, x3, (size_t)s0 * p.B * p.D + (size_t)b * p.D + c0 + c,
-                                       (size_t)spt * p.B * p.D, n, stamp);
+            const size_t base = (size_t)s0 * p.B * p.D + (size_t)b * p.D + c0 + c, stride = (size_t)spt * p.B * p.D;
+            // (more than eight slots per thread: sixteen polls in flight, one round trip instead of two)
+            smem[s0 * cb + v] = nslots > 8 * spt ? ll_sum<16>(p, x3, base, stride, n, stamp) : ll_sum<8>(p, x3, base, stride, n, stamp);
         }
         CF_STAMP(19);           // head partials arrived
         lds_barrier();
@@ -1737,13 +1778,7 @@ hipError_t launch_fused_layer(const Params &p, int hd, int g, int bt, size_t lds
 
 bool wants_layer_kernel(const Params &p)
 {
-    // CF_FORCE_LAYER_KERNEL=1 (read once): the layer kernel also for calls that need none of its steps, to
-    // compare the two builds on the same work
-    static const bool force = [] {
-        const char *e = getenv("CF_FORCE_LAYER_KERNEL");
-        return e && *e == '1';
-    }();
-    return force || p.gamma != nullptr || (p.flags & kFlagResidual) != 0 || p.row_pos != nullptr;
+    return p.gamma != nullptr || (p.flags & kFlagResidual) != 0 || p.row_pos != nullptr;
 }
 
 size_t lds_floats(const Params &p, int hd, int g, int bt)

@@ -46,7 +46,7 @@ struct Params {
     uint64_t *p1;          // [k_splits][B][Nqkv] partial projections
     uint64_t *p2;          // [B][n_q][kv_splits][head_dim + kP2Stride] split-KV partials
     uint64_t *p3;          // [n_q * row_splits][B][D] per-head partial outputs
-    const double *inv_freq;// [head_dim/2] RoPE frequencies base^(-2i/d)
+    double rope_log2_base; // log2 of the RoPE base: the kernel computes the frequencies base^(-2i/d) itself
     float *dbg_q, *dbg_attn;   // [B][n_q][head_dim] or null
     unsigned long long *dbg_t; // [W][kStamps] wall-clock stamps at phase boundaries, or null
     int D, nq, nkv, B, pos, max_seq, nqkv;
@@ -59,7 +59,7 @@ struct Params {
     int pairmap;           // workgroup -> (team, member) keeps the parity of the workgroup id in the member id
     int NS, TPS;           // attention: splits of the cached sequence, tokens per split
     int NC3, CW3, RS3;     // output projection: column blocks, columns per block, row splits per head
-    int NCH;               // number of 512-column chunks of the output
+    int reserved0;
     int flags;             // kFlagPacked, kFlagResidual
     float qk_scale_log2e;  // log2(e)/sqrt(head_dim)
     float eps;             // RMSNorm: added to the mean square

@@ -6,6 +6,12 @@
 
 namespace cf {
 
+// Frequency of RoPE pair i: base^(-2i/head_dim), from log2(base), in fp64.
+__device__ __forceinline__ double rope_inv_freq(int i, int head_dim, double log2_base)
+{
+    return exp2(-(2.0 * (double)i / (double)head_dim) * log2_base);
+}
+
 // cos and sin of pos * inv_freq, angle and range reduction in fp64.
 __device__ __forceinline__ void rope_cos_sin(int pos, double inv_freq, float &cos_out, float &sin_out)
 {
