@@ -32,7 +32,8 @@ enum {
     CF_EUNSUPPORTED = -2,  /* shape outside the compiled kernel variants, or the grid cannot be co-resident */
     CF_EHIP = -3,          /* a HIP runtime call failed; see cf_last_hip_error */
     CF_ENOMEM = -4,        /* host or device allocation failed */
-    CF_ETIMEOUT = -5       /* a cross-workgroup wait inside the kernel gave up (reported by cf_status) */
+    CF_ETIMEOUT = -5,      /* a cross-workgroup wait inside the kernel gave up (reported by cf_status) */
+    CF_ESCRATCH = -6       /* cf_decode_block_static: the call needs more exchange memory than the fixed scratch array holds */
 };
 
 /* Shape of the block (paper Alg. 3 "Require": hidden size D, heads, head dim). */
@@ -87,6 +88,29 @@ int cf_destroy(cf_handle h);
  */
 int cf_decode_block(cf_handle h, int32_t batch, const void *x, const void *W_qkv, const void *W_o,
                     void *k_cache, void *v_cache, int32_t pos, void *out, void *stream);
+
+/*
+ * cf_decode_block for callers that cannot allocate device memory: code under HIP graph capture, serving loops and
+ * harnesses that forbid hipMalloc.  No handle and no cf_create: the shape is passed with every call, and what the
+ * kernel keeps between its workgroups (launch counters, exchange slots, error flag) lives in a fixed array of device
+ * memory inside the library (32 MiB on every GPU the library runs on, held until the process ends) in place of a
+ * per-handle workspace.  The call itself makes no hipMalloc / hipFree and no allocating library call, does not
+ * synchronise, and enqueues on `stream` the fused kernel, preceded by a one-workgroup kernel that re-aligns the
+ * launch counters whenever the number of workgroups differs from the previous call's on this GPU.
+ *   cfg      shape as for cf_create (max_batch and max_seq as the caches were allocated; flags ignored)
+ *   others   exactly as for cf_decode_block (row-major weights)
+ * Limits: the exchange slots of the call's work plan must fit the array:
+ *   8 bytes * (k_splits * batch * (n_q + 2 n_kv) * head_dim + batch * n_q * kv_splits * (head_dim + 4)
+ *              + n_q * out_row_splits * batch * d_model)  <=  32 MiB - 257 KiB
+ * (Llama-2-7B shape, batch 1: 2.1 MB; Llama-3-8B shape, batch 16: 30.5 MB); a call beyond that returns CF_ESCRATCH
+ * and enqueues nothing.  All calls on one GPU share the array and it keeps the contents of the last call: calls
+ * that overlap in time on one GPU (two streams, two host threads) race and give wrong results; calls on one stream,
+ * or otherwise ordered, are fine, also with different shapes.  A wait inside the kernel that gives up (the grid was
+ * not co-resident) cannot be reported by this entry point: use a handle and cf_status where that matters.
+ * Errors otherwise as for cf_create (shape) and cf_decode_block (arguments).
+ */
+int cf_decode_block_static(const cf_config *cfg, int32_t batch, const void *x, const void *W_qkv, const void *W_o,
+                           void *k_cache, void *v_cache, int32_t pos, void *out, void *stream);
 
 /*
  * Optional layout for the (static) weights that lets every workgroup stream one

@@ -13,7 +13,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("CFDECODE_LIB") or os.path.join(_PKG, "libcfdecode.so")   # override: A/B builds
 _lib = None
 
-EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_packed", "cf_decode_layer", "cf_decode_layer_rows",
+EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_block_static", "cf_decode_block_packed", "cf_decode_layer", "cf_decode_layer_rows",
                     "cf_decode_stack",
                     "cf_pack_weights",
                     "cf_packed_sizes", "cf_status", "cf_debug_export",
@@ -62,6 +62,8 @@ def load_library():
         lib.cf_destroy.argtypes = [vp]
         lib.cf_decode_block.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp]
         lib.cf_decode_block_packed.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp]
+        lib.cf_decode_block_static.argtypes = [ctypes.POINTER(CfConfig), i32, vp, vp, vp, vp, vp, i32, vp, vp]
+        lib.cf_decode_block_static.restype = ctypes.c_int
         lib.cf_decode_layer.argtypes = [vp, i32, vp, vp, ctypes.c_float, i32, i32, vp, vp, vp, vp, i32, vp, vp]
         lib.cf_decode_layer_rows.argtypes = [vp, i32, vp, vp, ctypes.c_float, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp]
         lib.cf_pack_weights.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -116,6 +118,14 @@ def load_library():
 
 def algorithmic_bytes(cfg: CfConfig, batch: int, pos: int) -> int:
     return int(load_library().cf_algorithmic_bytes(ctypes.byref(cfg), batch, pos))
+
+
+def decode_block_static(cfg: CfConfig, batch, x, w_qkv, w_o, k_cache, v_cache, pos, out, stream=0):
+    """cf_decode_block_static: the decode step without a handle, on the library's fixed scratch array."""
+    lib = load_library()
+    rc = lib.cf_decode_block_static(ctypes.byref(cfg), batch, x, w_qkv, w_o, k_cache, v_cache, pos, out, stream)
+    if rc != 0:
+        raise CfError(rc, lib.cf_strerror(rc).decode())
 
 
 PLAN_FIELDS = ("workgroups", "team_size", "k_splits", "rows_per_split", "kv_splits", "tokens_per_split",

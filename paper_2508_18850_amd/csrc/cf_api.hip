@@ -38,6 +38,9 @@ struct cf_handle_s {
     int last_batch = 0;
     int last_plan[10] = {0};
     int last_hip = 0;
+    // cf_decode_block_static: the exchange slots are laid out per call, for the plan in use, inside this area
+    char *slot_area = nullptr;
+    size_t slot_area_bytes = 0;
 };
 
 namespace {
@@ -210,11 +213,9 @@ int check_residency(cf_handle_s *h, const Params &p, int bt, size_t lds_bytes)
 
 extern "C" {
 
-int cf_create(const cf_config *cfg, cf_handle *out)
+// Shape checks common to cf_create and cf_decode_block_static.
+static int check_config(const cf_config &c)
 {
-    if (!cfg || !out) return CF_EINVAL;
-    *out = nullptr;
-    const cf_config &c = *cfg;
     if (c.d_model < 8 || c.d_model % 8 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.n_q_heads % c.n_kv_heads ||
         c.max_batch < 1 || c.max_batch > 16 || c.max_seq < 1 || !(c.rope_base > 1.0f))
         return CF_EINVAL;
@@ -229,6 +230,17 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     }
     const int G = c.n_q_heads / c.n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return CF_EUNSUPPORTED;
+    return CF_OK;
+}
+
+int cf_create(const cf_config *cfg, cf_handle *out)
+{
+    if (!cfg || !out) return CF_EINVAL;
+    *out = nullptr;
+    const cf_config &c = *cfg;
+    const int cfg_rc = check_config(c);
+    if (cfg_rc != CF_OK) return cfg_rc;
+    const int G = c.n_q_heads / c.n_kv_heads;
 
     cf_handle_s *h = new (std::nothrow) cf_handle_s();
     if (!h) return CF_ENOMEM;
@@ -265,6 +277,10 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     const size_t p1_bytes = align_up((size_t)kMaxKS * B * h->nqkv * sizeof(uint64_t), 256);
     const size_t p2_bytes = align_up(B * c.n_q_heads * cf::kMaxKvSplits * (hd + cf::kP2Stride) * sizeof(uint64_t), 256);
     const size_t p3_bytes = align_up((size_t)c.n_q_heads * 8 * B * c.d_model * sizeof(uint64_t), 256);
+    if (p1_bytes > 0xfffffff0ull || p2_bytes > 0xfffffff0ull || p3_bytes > 0xfffffff0ull) {   // slots are addressed with 32-bit byte offsets
+        delete h;
+        return CF_EUNSUPPORTED;
+    }
     const size_t dbg_bytes = align_up(B * c.n_q_heads * hd * sizeof(float), 256);
     const size_t times_bytes = align_up((size_t)8 * h->num_cu * cf::kStamps * sizeof(unsigned long long), 256);
     h->exchange_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes;
@@ -344,6 +360,16 @@ static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, co
     p.flags = (packed ? cf::kFlagPacked : 0) | (residual ? cf::kFlagResidual : 0);
     int rc = make_plan(h, batch, pos, &p);
     if (rc != CF_OK) return rc;
+    if (h->slot_area) {
+        // the three slot arrays, sized for this call's plan, side by side in the fixed area
+        const size_t b1 = align_up((size_t)p.KS * batch * h->nqkv * sizeof(uint64_t), 256);
+        const size_t b2 = align_up((size_t)batch * h->cfg.n_q_heads * p.NS * (h->cfg.head_dim + cf::kP2Stride) * sizeof(uint64_t), 256);
+        const size_t b3 = align_up((size_t)h->cfg.n_q_heads * p.RS3 * batch * h->cfg.d_model * sizeof(uint64_t), 256);
+        if (b1 + b2 + b3 > h->slot_area_bytes) return CF_ESCRATCH;
+        p.p1 = reinterpret_cast<uint64_t *>(h->slot_area);
+        p.p2 = reinterpret_cast<uint64_t *>(h->slot_area + b1);
+        p.p3 = reinterpret_cast<uint64_t *>(h->slot_area + b1 + b2);
+    }
     const int bt = batch_tile(batch);
     const size_t lds = cf::lds_floats(p, h->cfg.head_dim, h->G, bt) * sizeof(float);
     if (lds > kLdsLimit) return CF_EUNSUPPORTED;
@@ -499,6 +525,109 @@ int64_t cf_algorithmic_bytes(const cf_config *cfg, int32_t batch, int32_t pos)
     return weights + kv_read + appended + io;
 }
 
+// ------------------------------------------------------------------------------------------------
+// cf_decode_block_static: the decode step for callers that cannot allocate.  Everything the kernel keeps between
+// workgroups (error flag, launch counters, exchange slots) lives in one array of device memory that is part of the
+// library's code object; the address each GPU gives it is looked up once per device.
+}  // extern "C" (reopened below)
+
+namespace {
+
+constexpr size_t kScratchBytes = (size_t)32 << 20;               // 32 MiB per GPU, held until the process ends
+constexpr size_t kScratchCounters = 2048;                         // launch counters: one per possible workgroup
+constexpr size_t kScratchHeadBytes = 256 + kScratchCounters * cf::kCounterStride * sizeof(unsigned long long);
+constexpr int kMaxDevices = 64;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+
+struct StaticDevice {
+    char *ptr = nullptr;        // device address of `scratch` on this GPU (hipGetSymbolAddress)
+    int num_cu = 0;
+    int last_w = 0;             // workgroups of the previous launch through this entry point on this GPU
+    int wg_per_cu[6] = {0, 0, 0, 0, 0, 0};
+    unsigned long long occ_key = 0;   // (head_dim, group, LDS bytes) the residency figures above were taken for
+};
+StaticDevice g_static[kMaxDevices];
+
+// All launch counters take the largest value any of them holds.  Every workgroup of a launch counts in its own
+// line; after a launch with fewer workgroups the lines of the others lag behind, and a launch with more workgroups
+// needs them all equal again (the stamp of a launch is count + 1).
+__global__ void __launch_bounds__(1024) equalize_counters(unsigned long long *done)
+{
+    __shared__ unsigned long long part[16];
+    unsigned long long v = 0;
+    for (size_t i = threadIdx.x; i < kScratchCounters; i += blockDim.x) {
+        const unsigned long long c = done[i * cf::kCounterStride];
+        v = c > v ? c : v;
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const unsigned long long o = __shfl_xor(v, off);
+        v = o > v ? o : v;
+    }
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
+    __syncthreads();
+    for (int k = 0; k < (int)(blockDim.x >> 6); ++k) v = part[k] > v ? part[k] : v;
+    for (size_t i = threadIdx.x; i < kScratchCounters; i += blockDim.x) done[i * cf::kCounterStride] = v;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cf_decode_block_static(const cf_config *cfg, int32_t batch, const void *x, const void *W_qkv, const void *W_o,
+                           void *k_cache, void *v_cache, int32_t pos, void *out, void *stream)
+{
+    if (!cfg) return CF_EINVAL;
+    int rc = check_config(*cfg);
+    if (rc != CF_OK) return rc;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return CF_EHIP;
+    if (dev < 0 || dev >= kMaxDevices) return CF_EUNSUPPORTED;
+    StaticDevice &sd = g_static[dev];
+    if (!sd.ptr) {
+        // once per device, with that device current: every GPU holds its own copy of the array at its own address
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return CF_EHIP;
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return CF_EHIP;
+        sd.num_cu = cus;
+        sd.ptr = static_cast<char *>(ptr);
+    }
+    if ((size_t)sd.num_cu > kScratchCounters) return CF_EUNSUPPORTED;
+
+    // a handle on the stack that points into the array; nothing is allocated and nothing outlives the call
+    cf_handle_s h;
+    h.cfg = *cfg;
+    h.cfg.flags = 0;
+    h.device = dev;
+    h.num_cu = sd.num_cu;
+    h.G = cfg->n_q_heads / cfg->n_kv_heads;
+    h.nqkv = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
+    h.nch = ceil_div(cfg->d_model, cf::kOutChunk);
+    if (cfg->n_kv_heads > h.num_cu) return CF_EUNSUPPORTED;
+    h.err = reinterpret_cast<uint32_t *>(sd.ptr + 128);
+    h.done = reinterpret_cast<unsigned long long *>(sd.ptr + 256);
+    h.slot_area = sd.ptr + kScratchHeadBytes;
+    h.slot_area_bytes = kScratchBytes - kScratchHeadBytes;
+    const unsigned long long key = ((unsigned long long)cfg->head_dim << 40) ^ ((unsigned long long)h.G << 32);
+    if (sd.occ_key == key) std::memcpy(h.wg_per_cu, sd.wg_per_cu, sizeof h.wg_per_cu);
+    const int w = default_workgroups(&h);
+    if (w != sd.last_w) {
+        // (a kernel, not a memset: the call may be recorded into a graph)
+        hipLaunchKernelGGL(equalize_counters, dim3(1), dim3(1024), 0, static_cast<hipStream_t>(stream), h.done);
+        if (hipGetLastError() != hipSuccess) return CF_EHIP;
+        sd.last_w = w;
+    }
+    rc = decode_impl(&h, 0, batch, x, W_qkv, W_o, k_cache, v_cache, pos, out, stream);
+    sd.occ_key = key;
+    std::memcpy(sd.wg_per_cu, h.wg_per_cu, sizeof h.wg_per_cu);
+    return rc;
+}
+
 const char *cf_strerror(int code)
 {
     switch (code) {
@@ -508,6 +637,7 @@ const char *cf_strerror(int code)
     case CF_EHIP: return "HIP runtime error";
     case CF_ENOMEM: return "out of memory";
     case CF_ETIMEOUT: return "a cross-workgroup wait inside the kernel timed out";
+    case CF_ESCRATCH: return "the call needs more exchange memory than the fixed scratch array of cf_decode_block_static holds";
     default: return "unknown error";
     }
 }
