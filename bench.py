@@ -44,7 +44,7 @@ def parse_args():
     ap.add_argument("--workload", default="llama2_7b", help="shape name from cf_inputs.SHAPES")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--kv-len", type=int, default=None)
-    ap.add_argument("--max-seq", type=int, default=0, help="rows of a KV-cache head slice (0 = kv_len + 1 rounded up to 128)")
+    ap.add_argument("--max-seq", type=int, default=0, help="rows of a KV-cache head slice (0 = kv_len + 9, cf_inputs.default_max_seq)")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer buffer sets to rotate over (0 = auto)")
     ap.add_argument("--workgroups", type=int, default=0)
     ap.add_argument("--k-splits", type=int, default=0)

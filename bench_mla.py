@@ -13,7 +13,7 @@ import os
 import sys
 import time
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -94,7 +94,7 @@ def main():
             t0 = time.perf_counter()
             orc.mla_decode_block(*a)
             ts.append(time.perf_counter() - t0)
-        res["cpu_baseline"] = {"value": float(np.median(ts)) * 1e6, "unit": "us/step", "cores": os.cpu_count(),
+        res["cpu_baseline"] = {"value": float(np.median(ts)) * 1e6, "unit": "us/step", "cores": len(os.sched_getaffinity(0)),
                                "kind": "oracle", "sample": "%d whole steps of the same shape (numpy fp64 oracle)" % len(ts)}
     print(json.dumps(res), flush=True)
     blk.close()

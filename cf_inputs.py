@@ -9,7 +9,7 @@ k_cache, v_cache; every tensor is drawn in float32 and rounded to fp16 with
 round-to-nearest-even.  x ~ N(0,1); weights ~ N(0, std 0.02); cached K/V rows
 [0, L) ~ N(0,1); rows >= L are fp16 NaN when `poison` is set (correctness
 runs: nothing may read them) and zero otherwise (timing runs).  The cache
-capacity max_seq is L+1 rounded up to a multiple of 128.
+capacity max_seq is L + 9 rows (default_max_seq below says why).
 """
 from __future__ import annotations
 

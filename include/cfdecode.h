@@ -85,6 +85,11 @@ int cf_destroy(cf_handle h);
  * read nor written.  No allocation and no host synchronisation happen here.
  * Errors: CF_EINVAL for null/misaligned pointers, batch outside 1..max_batch,
  * pos outside 0..max_seq-1; CF_EHIP if the launch fails.
+ * Residency: the workgroups of the launch wait for each other's partial results, so all of them must be on
+ * the GPU at the same time (one per compute unit; checked once against the kernel's occupancy).  If other work
+ * holds compute units while this kernel runs, a workgroup may never start, every wait for it runs to the spin
+ * limit (2 s by default, cf_set_tuning), the output of that call is wrong, and the only report is CF_ETIMEOUT
+ * from the next cf_status: run the step on a GPU (or partition) of its own and call cf_status where results count.
  */
 int cf_decode_block(cf_handle h, int32_t batch, const void *x, const void *W_qkv, const void *W_o,
                     void *k_cache, void *v_cache, int32_t pos, void *out, void *stream);

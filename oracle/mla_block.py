@@ -1,7 +1,7 @@
 """Plain fp64 oracle of one decode step of a Multi-Head Latent Attention block with weight absorption.
 
-TEST INFRASTRUCTURE ONLY (see oracle/decode_block.py); no HIP kernel for this block exists yet, the oracle is
-written and pinned first.
+TEST INFRASTRUCTURE ONLY (see oracle/decode_block.py): it shares nothing with the HIP kernel of this block and was
+written and pinned before it.
 
 What it computes (paper Appendix B, "weight absorption" form: the three equations
 Q = Hidden W_Q W_Up, K = Hidden W_K, V = K[:kv_lora_rank];  Z = Concat_i softmax(Q_i K^T / sqrt(d_k)) V;

@@ -59,7 +59,7 @@ def splithead_decode_block(x, w_qkv, w_o, k_cache, v_cache, pos, n_heads, head_d
             S_b, A_in = [], []
             for b in range(N):
                 dims = block_dims(b, N, d)
-                # Q_b, K_b, V_b <- H_b x W_b^QKV   (the block's columns of the head)
+                # Alg. 5 step 1: the projection restricted to the columns this block owns
                 Q_b = x[row] @ w_qkv[:, i * d + dims]
                 K_b = x[row] @ w_qkv[:, nh * d + i * d + dims]
                 V_b = x[row] @ w_qkv[:, 2 * nh * d + i * d + dims]
@@ -69,18 +69,18 @@ def splithead_decode_block(x, w_qkv, w_o, k_cache, v_cache, pos, n_heads, head_d
                 k_rot[row, i, dims], v_new[row, i, dims] = K_b, V_b
                 K_all = np.concatenate([np.asarray(k_cache[row, i, :pos][:, dims]).astype(np.float64), K_b[None, :]])
                 V_all = np.concatenate([np.asarray(v_cache[row, i, :pos][:, dims]).astype(np.float64), V_b[None, :]])
-                S_b.append(K_all @ Q_b)                            # S_b <- Q_b x (K_b^cache, K_b)^T : all tokens
+                S_b.append(K_all @ Q_b)                            # Alg. 5 step 2: partial scores of every token
                 A_in.append(V_all)
             sent = 0
             if reduce_scores:
-                S_b, sent = cc.cluster_reduce(S_b, "sum")          # complete Q K^T in every block
+                S_b, sent = cc.cluster_reduce(S_b, "sum")          # Alg. 5 step 3: every block gets the full scores
             O_b = []
             for b in range(N):
                 P = softmax(S_b[b] / np.sqrt(float(d)))            # every block: softmax over all tokens
-                A_b = P @ A_in[b]                                  # A_b <- S_b x (V_b^cache, V_b)
-                O_b.append(A_b @ w_o[i * d + block_dims(b, N, d), :])      # O_b <- A_b x W_b^O : D values
+                A_b = P @ A_in[b]                                  # Alg. 5 step 4: weighted sum of the block's value columns
+                O_b.append(A_b @ w_o[i * d + block_dims(b, N, d), :])      # Alg. 5 step 5: the block's rows of the head's W_o
             O, sent_o = cc.cluster_reduce(O_b, "sum")
-            out[row] += O[0]                                       # atomicAdd over the heads (every block holds O)
+            out[row] += O[0]                                       # Alg. 5 step 6: summed over the heads, once per head
             if sent_one is None:
                 sent_one = sent + sent_o
     return {"out": out, "k_rot": k_rot, "v_new": v_new, "sent": sent_one}
