@@ -130,3 +130,37 @@ def make_mla_inputs(shape: MlaShape, seed: int, batch: int | None = None, kv_len
             "w_up": normal((nh, n, l), n ** -0.5), "w_down": normal((nh, l, v), l ** -0.5),
             "w_o": normal((nh * v, D), (nh * v) ** -0.5), "kv_cache": cache, "pos": Lk, "batch": B, "max_seq": S,
             "shape": shape}
+
+
+# ---------------------------------------------------------------------------------------------------
+# Feed-forward block (three weight matrices), Llama-shaped
+# ---------------------------------------------------------------------------------------------------
+
+@dataclass(frozen=True)
+class FfnShape:
+    name: str
+    d_model: int
+    d_ff: int
+    batch: int = 1
+
+
+FFN_SHAPES = {
+    "tiny": FfnShape("tiny", 512, 1376),
+    "llama2_7b": FfnShape("llama2_7b", 4096, 11008),
+    "llama3_8b": FfnShape("llama3_8b", 4096, 14336),
+    "llama2_70b": FfnShape("llama2_70b", 8192, 28672),
+}
+
+
+def make_ffn_inputs(shape: FfnShape, seed: int, batch: int | None = None) -> dict:
+    """Seeded fp16 inputs of one feed-forward block: z ~ N(0,1), the three matrices [d_ff, d_model] ~ N(0, std 0.02),
+    drawn in the order z, W1, W2, W3 (fp32, rounded to fp16)."""
+    B = shape.batch if batch is None else int(batch)
+    rng = np.random.Generator(np.random.PCG64(seed))
+
+    def normal(shp, std):
+        return (rng.standard_normal(size=shp, dtype=np.float32) * np.float32(std)).astype(np.float16)
+
+    D, F = shape.d_model, shape.d_ff
+    return {"z": normal((B, D), 1.0), "w1": normal((F, D), 0.02), "w2": normal((F, D), 0.02), "w3": normal((F, D), 0.02),
+            "batch": B, "shape": shape}
