@@ -357,6 +357,39 @@ int cf_splithead_decode(cf_splithead t, const void *x, const void *W_qkv_members
 int cf_splithead_status(cf_splithead t, void *stream);
 int cf_splithead_set_spin_limit(cf_splithead t, int32_t spin_limit_us);
 
+/* ------------------------------------------------------------------------------------------------
+ * The feed-forward block of a decoder layer for one token per sequence, one kernel (paper Sec. 2.1:
+ * FFN(Z) = W3 (sigma(W1 Z) * W2 Z), three linear layers with an activation in between, * element-wise):
+ *
+ *   h = W1 z_b,  u = W2 z_b   [d_ff]      g = sigma(h) * u      out_b = g W3   [d_model]        for every batch row b
+ *
+ * All pointers are DEVICE pointers to fp16, 16-byte aligned, row-major; the caller owns them:
+ *   z [batch, d_model] read;  W1, W2, W3 [d_ff, d_model] read (row f: the weights of hidden unit f into it, for W1 and
+ *   W2, and out of it, for W3; for W1 and W2 that is the [out_features, in_features] layout of the paper's "W1 Z");
+ *   out [batch, d_model] fully overwritten.  Storage fp16, accumulation fp32; the hidden vector is never rounded.
+ * activation: CF_FFN_SILU, sigma(a) = a / (1 + exp(-a)) (the Llama-family layers whose shapes the paper measures), or
+ *   CF_FFN_GELU, a Phi(a) in its exact form (the paper's example).
+ * cf_ffn_create allocates and clears the exchange workspace (synchronous): CF_EINVAL for d_model not a multiple of 8,
+ *   sizes below 1 or an unknown activation; CF_EUNSUPPORTED for max_batch > 4, d_model > 8192, matrices of 2 GiB or more.
+ * cf_ffn_decode enqueues the kernel on `stream` (no allocation, no synchronisation; the launch can be captured and
+ *   replayed): CF_EINVAL for null or misaligned pointers and a batch outside 1..max_batch.  All workgroups must be
+ *   resident together (one per compute unit), as for cf_decode_block.
+ * cf_ffn_status / cf_ffn_set_spin_limit: as cf_team_status / cf_team_set_spin_limit.
+ */
+enum { CF_FFN_SILU = 0, CF_FFN_GELU = 1 };
+typedef struct cf_ffn_config {
+    int32_t d_model, d_ff, max_batch, activation;
+} cf_ffn_config;
+typedef struct cf_ffn_s *cf_ffn;
+int cf_ffn_create(const cf_ffn_config *cfg, cf_ffn *out);
+int cf_ffn_destroy(cf_ffn t);
+int cf_ffn_decode(cf_ffn t, int32_t batch, const void *z, const void *W1, const void *W2, const void *W3, void *out,
+                  void *stream);
+int cf_ffn_status(cf_ffn t, void *stream);
+int cf_ffn_set_spin_limit(cf_ffn t, int32_t spin_limit_us);
+/* Algorithmic HBM bytes of one call (the three matrices + z + out). */
+int64_t cf_ffn_algorithmic_bytes(const cf_ffn_config *cfg, int32_t batch);
+
 #ifdef __cplusplus
 }
 #endif

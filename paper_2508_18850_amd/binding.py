@@ -23,7 +23,9 @@ EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_blo
                     "cf_mla_create", "cf_mla_destroy", "cf_mla_decode", "cf_mla_status", "cf_mla_set_spin_limit",
                     "cf_mla_algorithmic_bytes",
                     "cf_splithead_create", "cf_splithead_destroy", "cf_splithead_pack", "cf_splithead_decode",
-                    "cf_splithead_status", "cf_splithead_set_spin_limit")
+                    "cf_splithead_status", "cf_splithead_set_spin_limit",
+                    "cf_ffn_create", "cf_ffn_destroy", "cf_ffn_decode", "cf_ffn_status", "cf_ffn_set_spin_limit",
+                    "cf_ffn_algorithmic_bytes")
 
 CF_FLAG_DEBUG_EXPORT = 1
 
@@ -38,6 +40,15 @@ class MlaConfig(ctypes.Structure):
     _fields_ = [("d_model", ctypes.c_int32), ("n_heads", ctypes.c_int32), ("nope_dim", ctypes.c_int32),
                 ("rope_dim", ctypes.c_int32), ("kv_lora_rank", ctypes.c_int32), ("v_head_dim", ctypes.c_int32),
                 ("max_batch", ctypes.c_int32), ("max_seq", ctypes.c_int32), ("rope_base", ctypes.c_float)]
+
+
+class FfnConfig(ctypes.Structure):
+    _fields_ = [("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("max_batch", ctypes.c_int32),
+                ("activation", ctypes.c_int32)]
+
+
+FFN_SILU = 0
+FFN_GELU = 1
 
 
 class CfError(RuntimeError):
@@ -103,6 +114,15 @@ def load_library():
                      "cf_team_set_spin_limit",
                     "cf_mla_create", "cf_mla_destroy", "cf_mla_decode", "cf_mla_status", "cf_mla_set_spin_limit",
                     "cf_mla_algorithmic_bytes"):
+            getattr(lib, name).restype = ctypes.c_int
+        lib.cf_ffn_create.argtypes = [ctypes.POINTER(FfnConfig), ctypes.POINTER(vp)]
+        lib.cf_ffn_destroy.argtypes = [vp]
+        lib.cf_ffn_decode.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
+        lib.cf_ffn_status.argtypes = [vp, vp]
+        lib.cf_ffn_set_spin_limit.argtypes = [vp, i32]
+        lib.cf_ffn_algorithmic_bytes.argtypes = [ctypes.POINTER(FfnConfig), i32]
+        lib.cf_ffn_algorithmic_bytes.restype = ctypes.c_int64
+        for name in ("cf_ffn_create", "cf_ffn_destroy", "cf_ffn_decode", "cf_ffn_status", "cf_ffn_set_spin_limit"):
             getattr(lib, name).restype = ctypes.c_int
         lib.cf_decode_stack.argtypes = [vp, i32, i32, vp, ctypes.POINTER(vp), ctypes.c_float, i32, i32, ctypes.POINTER(vp),
                                         ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), i32, vp, vp]
@@ -316,6 +336,48 @@ class MlaBlock:
     def close(self):
         if self._h:
             self._lib.cf_mla_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class FfnBlock:
+    """Handle of the fused feed-forward block (cf_ffn_*).  Tensors are raw device addresses of fp16 data."""
+
+    def __init__(self, d_model, d_ff, max_batch, activation=FFN_SILU):
+        self._lib = load_library()
+        self.cfg = FfnConfig(d_model, d_ff, max_batch, activation)
+        self._h = ctypes.c_void_p()
+        self._check(self._lib.cf_ffn_create(ctypes.byref(self.cfg), ctypes.byref(self._h)))
+
+    def _check(self, rc):
+        if rc != 0:
+            raise CfError(rc, self._lib.cf_strerror(rc).decode())
+
+    def decode(self, batch, z, w1, w2, w3, out, stream=0):
+        rc = self._lib.cf_ffn_decode(self._h, batch, z, w1, w2, w3, out, stream)
+        if rc != 0:
+            self._check(rc)
+
+    def decode_rc(self, batch, z, w1, w2, w3, out, stream=0) -> int:
+        return int(self._lib.cf_ffn_decode(self._h, batch, z, w1, w2, w3, out, stream))
+
+    def status(self, stream=0):
+        self._check(self._lib.cf_ffn_status(self._h, stream))
+
+    def algorithmic_bytes(self, batch) -> int:
+        return int(self._lib.cf_ffn_algorithmic_bytes(ctypes.byref(self.cfg), batch))
+
+    def set_spin_limit(self, us):
+        self._check(self._lib.cf_ffn_set_spin_limit(self._h, us))
+
+    def close(self):
+        if self._h:
+            self._lib.cf_ffn_destroy(self._h)
             self._h = ctypes.c_void_p()
 
     def __del__(self):

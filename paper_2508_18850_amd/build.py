@@ -14,7 +14,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcfdecode.so")
 TRACE_LIB = os.path.join(PKG, "libcfdecode_trace.so")
-SOURCES = ["cf_api.hip", "cf_fused_kernel.hip", "cf_team.hip", "cf_mla.hip", "cf_splithead.hip"]
+SOURCES = ["cf_api.hip", "cf_fused_kernel.hip", "cf_team.hip", "cf_mla.hip", "cf_splithead.hip", "cf_ffn.hip"]
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

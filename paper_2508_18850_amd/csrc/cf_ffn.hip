@@ -1,0 +1,490 @@
+// Feed-forward block of a decoder layer (paper Sec. 2.1, FFN(Z) = W3 (sigma(W1 Z) * W2 Z)) for one token per
+// sequence as ONE kernel for gfx950, behind the C ABI (cf_ffn_* in include/cfdecode.h).
+//
+// The paper fuses the attention block and names the FFN as the other part of a layer; here it is built the same
+// way: one launch, the hidden vector g = sigma(W1 z) * W2 z never leaves the chip, and the only exchange between
+// workgroups is the sum of the per-workgroup partial outputs (stamped {value, stamp} slots, cf_team_device.h),
+// the counterpart of the decode block's sum over heads.
+//
+// All three matrices are stored [d_ff, d_model] (row f = hidden unit f), so hidden unit f is one contiguous row in
+// each of them.  Workgroup w owns the hidden units [w F / W, (w + 1) F / W):
+//   A  h_f = W1[f] . z, u_f = W2[f] . z for its units: a row is read in 512-column pieces, one piece per wavefront
+//      step (64 lanes x 16 bytes, contiguous), the pieces of all rows dealt round-robin to the eight wavefronts;
+//      fp16 x fp16 products accumulated in fp32 (v_dot2_f32_f16), summed over the wavefront and, through LDS,
+//      over the pieces of a row in a fixed order;  g_f = sigma(h_f) u_f
+//   B  partial out = sum over its units of g_f W3[f]: thread t owns eight columns (and eight more per further
+//      4096 columns), a row of W3 is one contiguous read of the whole workgroup; no reduction inside the
+//      workgroup is needed
+//   C  every workgroup adds, in workgroup order, the partials of its own d_model / W output columns and writes fp16.
+// The first rows of W3 are requested before the last pieces of stage A are consumed, so the memory pipe does not
+// drain at the stage boundary.  All waits are bounded (CF_ETIMEOUT); all workgroups have to be resident at once.
+#include "../../include/cfdecode.h"
+#include "cf_team_device.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+namespace {
+
+using cf::team::Exchange;
+using cf::team::pair_t;
+constexpr int NT = 512;
+constexpr int NW = NT / 64;
+constexpr int kChunk = 512;            // columns of one wavefront load: 64 lanes x 8 values
+constexpr int kCounterStride = 16;
+constexpr int kMaxBatch = 4;
+constexpr uint32_t kNoLoad = 0x80000000u;
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+
+struct FfnArgs {
+    const uint16_t *z, *w1, *w2, *w3;
+    uint16_t *out;
+    uint64_t *slots;                   // [W][B][D] partial outputs
+    unsigned long long *counters;
+    uint32_t *err;
+    int D, F, B, W, act;
+    int nrmax;                         // most hidden units a workgroup owns
+    long long spin_ticks;
+};
+
+struct Stream {
+    __amdgpu_buffer_rsrc_t r;
+    __device__ __forceinline__ Stream(const void *base, uint32_t bytes)
+        : r(__builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000)) {}
+    __device__ __forceinline__ h8 ld(uint32_t voff, uint32_t soff) const
+    {
+        return __builtin_bit_cast(h8, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 2));
+    }
+};
+
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over the wavefront (the same value in every lane): four steps inside each row of 16 lanes, then the four row
+// totals are read out as scalars.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x141>(v);
+    v += dpp_move<0x140>(v);
+    const int i = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+// eight fp16 x fp16 products added to acc in fp32
+__device__ __forceinline__ float dot8(const h8 &a, const h8 &b, float acc)
+{
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        acc = __builtin_amdgcn_fdot2(h2{a[2 * k], a[2 * k + 1]}, h2{b[2 * k], b[2 * k + 1]}, acc, false);
+    return acc;
+}
+
+__device__ __forceinline__ float activate(float a, int act)
+{
+    if (act == CF_FFN_GELU) return 0.5f * a * (1.0f + erff(a * 0.70710678118654752f));
+    return a / (1.0f + __expf(-a));                    // SiLU
+}
+
+template <int BT, int NCB>     // batch tile; column blocks of 4096 per thread (d_model <= 4096 NCB)
+__global__ void __launch_bounds__(NT) fused_ffn(const FfnArgs a)
+{
+    extern __shared__ float smem[];
+    const int tid = threadIdx.x, lane = tid & 63, w = blockIdx.x;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int D = a.D, B = a.B;
+    const int NCK = (D + kChunk - 1) / kChunk;                    // pieces of a row
+    const int Dp = NCK * kChunk;
+    const int r0 = (int)((long long)w * a.F / a.W), r1 = (int)((long long)(w + 1) * a.F / a.W), nr = r1 - r0;
+    const int NU = nr * NCK;                                      // (row, piece) units of this workgroup, per matrix
+    // LDS: z as fp16 [BT][Dp]; partial dot products [2][BT][nrmax][NCK]; g [BT][nrmax]
+    _Float16 *z16 = reinterpret_cast<_Float16 *>(smem);
+    float *part = smem + BT * Dp / 2;
+    float *gl = part + 2 * BT * a.nrmax * NCK;
+
+    unsigned long long launches;
+    asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)"
+                 : "=s"(launches)
+                 : "s"(a.counters + (size_t)w * kCounterStride)
+                 : "memory");
+    const unsigned long long cnt = launches + 1ull;
+    const Exchange x = {a.slots, 0, (uint32_t)(cnt + (cnt >> 32)), a.err, a.spin_ticks};
+    const __amdgpu_buffer_rsrc_t xr = cf::team::slots_rsrc(x);
+
+    const uint32_t wbytes = (uint32_t)((size_t)a.F * D * 2);
+    const Stream W1(a.w1, wbytes), W2(a.w2, wbytes), W3(a.w3, wbytes);
+
+    // ---- stage A.  Units q = wv, wv + 8, ... of this wavefront; unit q is piece q % NCK of row q / NCK.
+    constexpr int U = 4;                                          // units per batch of loads (two loads each)
+    struct Cursor {
+        int r, c;                                                 // row (local), piece
+    };
+    // a wavefront's next unit is eight units on: branch-free (loads inside branches would make every later
+    // wait for a load drain the queue)
+    const int dr = NW / NCK, dc = NW % NCK;
+    auto advance = [&](Cursor &k) {
+        k.c += dc;
+        k.r += dr;
+        const bool wrap = k.c >= NCK;
+        k.c -= wrap ? NCK : 0;
+        k.r += wrap ? 1 : 0;
+    };
+    Cursor lc = {wv / NCK, wv % NCK};
+    Cursor cc = lc;
+    auto load = [&](h8(&p1)[U], h8(&p2)[U], uint32_t dep) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool live = lc.r < nr && lc.c * kChunk + lane * 8 < D;
+            const uint32_t voff = live ? (uint32_t)lane * 16 + dep : kNoLoad;
+            const uint32_t soff = (uint32_t)(((size_t)(r0 + lc.r) * D + (size_t)lc.c * kChunk) * 2);
+            p1[u] = W1.ld(voff, lc.r < nr ? soff : 0u);
+            p2[u] = W2.ld(voff, lc.r < nr ? soff : 0u);
+            advance(lc);
+        }
+    };
+    h8 a1[U], a2[U], b1[U], b2[U];
+    load(a1, a2, 0u);
+    // z of every batch row -> LDS as it is (fp16), zero past d_model and past the batch
+    for (int i = tid; i < BT * Dp / 8; i += NT) {
+        const int b = i / (Dp / 8), c8 = i - b * (Dp / 8);
+        uint4 v = {0u, 0u, 0u, 0u};
+        if (b < B && c8 * 8 < D) v = *reinterpret_cast<const uint4 *>(a.z + (size_t)b * D + c8 * 8);
+        *reinterpret_cast<uint4 *>(z16 + (size_t)b * Dp + c8 * 8) = v;
+    }
+    load(b1, b2, 0u);
+    lds_barrier();
+
+    auto consume = [&](const h8(&p1)[U], const h8(&p2)[U]) -> uint32_t {
+        float keep = 0.f;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool live = cc.r < nr;
+            const int c = cc.c, r = live ? cc.r : 0;
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                const h8 zc = *reinterpret_cast<const h8 *>(z16 + (size_t)b * Dp + c * kChunk + lane * 8);
+                const float d1 = wave_sum(dot8(p1[u], zc, 0.f)), d2 = wave_sum(dot8(p2[u], zc, 0.f));
+                if (live && lane == 0) {
+                    part[(b * a.nrmax + r) * NCK + c] = d1;
+                    part[((BT + b) * a.nrmax + r) * NCK + c] = d2;
+                }
+                keep += d1 + d2;
+            }
+            advance(cc);
+        }
+        // the reload of this register batch is made to follow its last use (its offset depends on the sums)
+        uint32_t dep = 0;
+        asm volatile("" : "+v"(dep) : "v"(keep));
+        return dep;
+    };
+
+    // ---- stage B set-up: thread t owns columns 8 t + 4096 cb
+    constexpr int UB = 8;                                         // rows of W3 per batch of loads
+    auto load3 = [&](h8(&p3)[NCB][UB], int row0, uint32_t dep) {
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int r = row0 + u, col = 8 * tid + 4096 * cb;
+                const bool live = r < nr && col < D;
+                p3[cb][u] = W3.ld(live ? (uint32_t)col * 2 + dep : kNoLoad, r < nr ? (uint32_t)((size_t)(r0 + r) * D * 2) : 0u);
+            }
+    };
+    h8 t3a[NCB][UB], t3b[NCB][UB];
+
+    const int nsteps = (NU + NW * U - 1) / (NW * U);             // batches of this wavefront (the same for all)
+    const int nsteps2 = max(2, (nsteps + 1) & ~1);
+    for (int k = 0; k + 2 < nsteps2; k += 2) {
+        const uint32_t d0 = consume(a1, a2);
+        load(a1, a2, d0);
+        const uint32_t d1 = consume(b1, b2);
+        load(b1, b2, d1);
+    }
+    load3(t3a, 0, 0u);                                            // the first rows of W3, before the tail of stage A
+    consume(a1, a2);
+    load3(t3b, UB, 0u);
+    consume(b1, b2);
+    lds_barrier();
+    // pieces of a row in piece order; activation; g
+    for (int e = tid; e < BT * nr; e += NT) {
+        const int b = e / nr, r = e - b * nr;
+        float h = 0.f, u = 0.f;
+        for (int c = 0; c < NCK; ++c) {
+            h += part[(b * a.nrmax + r) * NCK + c];
+            u += part[((BT + b) * a.nrmax + r) * NCK + c];
+        }
+        gl[b * a.nrmax + r] = b < B ? activate(h, a.act) * u : 0.f;
+    }
+    lds_barrier();
+
+    // ---- stage B
+    float acc[BT][NCB][8];
+#pragma unroll
+    for (int b = 0; b < BT; ++b)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[b][cb][j] = 0.f;
+    auto consume3 = [&](const h8(&p3)[NCB][UB], int row0) -> uint32_t {
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int r = min(row0 + u, nr - 1);               // a row past the end has zero weights
+                float f[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) f[j] = (float)p3[cb][u][j];
+#pragma unroll
+                for (int b = 0; b < BT; ++b) {
+                    const float g = gl[b * a.nrmax + r];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[b][cb][j] = fmaf(g, f[j], acc[b][cb][j]);
+                }
+            }
+        uint32_t dep = 0;
+#pragma unroll
+        for (int b = 0; b < BT; ++b)
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+                asm volatile("" : "+v"(dep) : "v"(acc[b][cb][0]), "v"(acc[b][cb][1]), "v"(acc[b][cb][2]), "v"(acc[b][cb][3]),
+                             "v"(acc[b][cb][4]), "v"(acc[b][cb][5]), "v"(acc[b][cb][6]), "v"(acc[b][cb][7]));
+        return dep;
+    };
+    // two batches of rows in flight; consume and reload are unconditional (a batch past the end is all zeros)
+    for (int row0 = 0; row0 < nr; row0 += 2 * UB) {
+        const uint32_t d0 = consume3(t3a, row0);
+        load3(t3a, row0 + 2 * UB, d0);
+        const uint32_t d1 = consume3(t3b, row0 + UB);
+        load3(t3b, row0 + 3 * UB, d1);
+    }
+    // ---- the partial output of this workgroup
+#pragma unroll
+    for (int b = 0; b < BT; ++b)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+            const int col = 8 * tid + 4096 * cb;
+            if (b < B && col < D) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) cf::team::put(xr, ((size_t)w * B + b) * D + col + j, acc[b][cb][j], x.stamp);
+            }
+        }
+
+    lds_barrier();              // stage C reuses the front of LDS
+    // ---- stage C: columns [c0, c0 + ncol) of every batch row, summed over the workgroups in workgroup order
+    const int cpw = (D + a.W - 1) / a.W;
+    const int c0 = w * cpw, ncol = min(cpw, D - c0);
+    if (ncol > 0) {
+        const int nv = ncol * B;                                  // values this workgroup produces (<= 512 is checked on the host)
+        const int spt = max(1, min(NT / nv, a.W));                // slots read in parallel
+        const int v = tid % nv, s0 = tid / nv;
+        const int b = v / ncol, c = v - b * ncol;
+        if (s0 < spt) {
+            constexpr int NP = 8;
+            float s = 0.f;
+            for (int k0 = s0; k0 < a.W; k0 += NP * spt) {
+                pair_t q[NP];
+                long long t0 = 0;
+                for (;;) {
+#pragma unroll
+                    for (int k = 0; k < NP; ++k) {
+                        const int slot = min(k0 + k * spt, a.W - 1);
+                        q[k] = cf::team::peek(xr, ((size_t)slot * B + b) * D + c0 + c);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    bool ok = true;
+#pragma unroll
+                    for (int k = 0; k < NP; ++k) ok &= (k0 + k * spt >= a.W) | (q[k].y == x.stamp);
+                    if (ok || cf::team::gave_up(x, t0)) break;
+                }
+#pragma unroll
+                for (int k = 0; k < NP; ++k)
+                    if (k0 + k * spt < a.W) s += __builtin_bit_cast(float, q[k].x);
+            }
+            smem[s0 * nv + v] = s;
+        }
+        lds_barrier();
+        if (tid < nv) {
+            float s = 0.f;
+            for (int k = 0; k < spt; ++k) s += smem[k * nv + tid];
+            a.out[(size_t)b * D + c0 + c] = __builtin_bit_cast(uint16_t, (_Float16)s);
+        }
+    }
+    if (tid == 0) a.counters[(size_t)w * kCounterStride] = cnt;
+}
+
+using KernelFn = void (*)(const FfnArgs);
+KernelFn pick(int bt, int d_model)
+{
+    if (d_model <= 4096) return bt == 1 ? fused_ffn<1, 1> : bt == 2 ? fused_ffn<2, 1> : fused_ffn<4, 1>;
+    return bt == 1 ? fused_ffn<1, 2> : bt == 2 ? fused_ffn<2, 2> : fused_ffn<4, 2>;
+}
+int batch_tile(int b) { return b <= 1 ? 1 : b <= 2 ? 2 : 4; }
+
+}  // namespace
+
+struct cf_ffn_s {
+    cf_ffn_config cfg;
+    int W = 0, nrmax = 0;
+    char *ws = nullptr;
+    size_t ws_bytes = 0;
+    uint32_t *err = nullptr;
+    unsigned long long *counters = nullptr;
+    uint64_t *slots = nullptr;
+    long long spin_ticks = 200000000LL;
+    int last_hip = 0;
+};
+
+static size_t lds_bytes_of(const cf_ffn_config &c, int bt, int nrmax)
+{
+    const size_t nck = (c.d_model + kChunk - 1) / kChunk, dp = nck * kChunk;
+    const size_t stages_ab = (size_t)bt * dp / 2 + 2 * (size_t)bt * nrmax * nck + (size_t)bt * nrmax;
+    return (stages_ab > (size_t)NT ? stages_ab : (size_t)NT) * sizeof(float);       // stage C: one float per thread
+}
+
+extern "C" {
+
+int cf_ffn_create(const cf_ffn_config *cfg, cf_ffn *out)
+{
+    if (!cfg || !out) return CF_EINVAL;
+    *out = nullptr;
+    const cf_ffn_config &c = *cfg;
+    if (c.d_model < 8 || c.d_model % 8 || c.d_ff < 1 || c.max_batch < 1 ||
+        (c.activation != CF_FFN_SILU && c.activation != CF_FFN_GELU))
+        return CF_EINVAL;
+    if (c.max_batch > kMaxBatch || c.d_model > 8192 || (unsigned long long)c.d_ff * c.d_model * 2 > 0x7fffffffull)
+        return CF_EUNSUPPORTED;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return CF_EHIP;
+    const int W = c.d_ff < cus ? c.d_ff : cus;
+    const int nrmax = (c.d_ff + W - 1) / W;
+    const int cpw = (c.d_model + W - 1) / W;
+    if ((size_t)cpw * c.max_batch > (size_t)NT) return CF_EUNSUPPORTED;       // stage C: one thread per output value
+    for (int bt = 1; bt <= kMaxBatch; bt *= 2) {
+        if (bt / 2 >= c.max_batch) break;
+        const size_t lds = lds_bytes_of(c, bt, nrmax);
+        if (lds > 160 * 1024 - 256) return CF_EUNSUPPORTED;
+        int per_cu = 0;
+        if ((lds > 48 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void *>(pick(bt, c.d_model)),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(pick(bt, c.d_model)), NT, lds) != hipSuccess ||
+            per_cu < 1)
+            return CF_EUNSUPPORTED;                                             // all workgroups resident, one per compute unit
+    }
+    cf_ffn t = new (std::nothrow) cf_ffn_s();
+    if (!t) return CF_ENOMEM;
+    t->cfg = c;
+    t->W = W;
+    t->nrmax = nrmax;
+    const size_t head = (256 + (size_t)W * kCounterStride * sizeof(unsigned long long) + 255) / 256 * 256;
+    const size_t slot_bytes = (size_t)W * c.max_batch * c.d_model * sizeof(uint64_t);
+    if (slot_bytes > 0xfffffff0ull) {
+        delete t;
+        return CF_EUNSUPPORTED;
+    }
+    t->ws_bytes = head + slot_bytes;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&t->ws), t->ws_bytes);
+    if (e == hipSuccess) e = hipMemset(t->ws, 0, t->ws_bytes);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        if (t->ws) (void)hipFree(t->ws);
+        delete t;
+        return e == hipErrorOutOfMemory ? CF_ENOMEM : CF_EHIP;
+    }
+    t->err = reinterpret_cast<uint32_t *>(t->ws + 128);
+    t->counters = reinterpret_cast<unsigned long long *>(t->ws + 256);
+    t->slots = reinterpret_cast<uint64_t *>(t->ws + head);
+    *out = t;
+    return CF_OK;
+}
+
+int cf_ffn_destroy(cf_ffn t)
+{
+    if (!t) return CF_EINVAL;
+    hipError_t e = hipFree(t->ws);
+    delete t;
+    return e == hipSuccess ? CF_OK : CF_EHIP;
+}
+
+int cf_ffn_decode(cf_ffn t, int32_t batch, const void *z, const void *W1, const void *W2, const void *W3, void *out,
+                  void *stream)
+{
+    if (!t || !z || !W1 || !W2 || !W3 || !out) return CF_EINVAL;
+    if (batch < 1 || batch > t->cfg.max_batch) return CF_EINVAL;
+    const void *ptrs[] = {z, W1, W2, W3, out};
+    for (const void *p : ptrs)
+        if (reinterpret_cast<uintptr_t>(p) & 15u) return CF_EINVAL;
+    FfnArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.z = static_cast<const uint16_t *>(z);
+    a.w1 = static_cast<const uint16_t *>(W1);
+    a.w2 = static_cast<const uint16_t *>(W2);
+    a.w3 = static_cast<const uint16_t *>(W3);
+    a.out = static_cast<uint16_t *>(out);
+    a.slots = t->slots;
+    a.counters = t->counters;
+    a.err = t->err;
+    a.D = t->cfg.d_model, a.F = t->cfg.d_ff, a.B = batch, a.W = t->W, a.act = t->cfg.activation;
+    a.nrmax = t->nrmax;
+    a.spin_ticks = t->spin_ticks;
+    const int bt = batch_tile(batch);
+    hipLaunchKernelGGL(pick(bt, t->cfg.d_model), dim3(t->W), dim3(NT), lds_bytes_of(t->cfg, bt, t->nrmax), static_cast<hipStream_t>(stream), a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        t->last_hip = (int)e;
+        return CF_EHIP;
+    }
+    return CF_OK;
+}
+
+int cf_ffn_status(cf_ffn t, void *stream)
+{
+    if (!t) return CF_EINVAL;
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    uint32_t flag = 0;
+    if (e == hipSuccess) e = hipMemcpy(&flag, t->err, sizeof flag, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) {
+        t->last_hip = (int)e;
+        return CF_EHIP;
+    }
+    if (flag) {
+        e = hipMemset(t->ws, 0, t->ws_bytes);        // launch counters and all stamps start afresh
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        return e == hipSuccess ? CF_ETIMEOUT : CF_EHIP;
+    }
+    return CF_OK;
+}
+
+int cf_ffn_set_spin_limit(cf_ffn t, int32_t spin_limit_us)
+{
+    if (!t || spin_limit_us < 0) return CF_EINVAL;
+    t->spin_ticks = (long long)spin_limit_us * 100;
+    return CF_OK;
+}
+
+int64_t cf_ffn_algorithmic_bytes(const cf_ffn_config *c, int32_t batch)
+{
+    if (!c) return 0;
+    return 2 * (3 * (int64_t)c->d_ff * c->d_model + 2 * (int64_t)batch * c->d_model);
+}
+
+}  // extern "C"
