@@ -7,7 +7,10 @@ steps rotate over a stack of distinct layers whose total size exceeds the 256 MB
 Infinity Cache, so weights and KV rows really come from HBM, as in a model with
 many layers.  All inputs are synthetic, generated on the device before timing.
 
-Prints ONE JSON line on stdout (details go to stderr).
+Prints ONE JSON line on stdout (details go to stderr).  With --sweep it prints one such line for every row
+of the measurement table instead (the Llama-2-7B shape at six cache lengths, the Llama-3-8B shape at batch 1, 4
+and 16, the Llama-2-70B shape and its stack of 80 distinct layers).  After the timed region, outside the events,
+one more step on the first layer is checked against the C oracle at the tolerance of the parity tests.
 """
 from __future__ import annotations
 
@@ -27,8 +30,12 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # keyed by workload name; None = not measured for that workload.
 MEASURED_TRAFFIC = {
-    # profiles/fused_decode_block_llama2_7b_kv4096_hbm_traffic.md: (100079.5 KiB fetched x 2.0000 + 2088.0 KiB written)
-    "llama2_7b_b1_kv4096": 207100000,
+    # profiles/fused_decode_block_hbm_traffic.md: (FETCH_SIZE KiB x 2.0000 + WRITE_SIZE KiB) x 1024
+    "llama2_7b_b1_kv4096": 207353856,      # 100203.0, 2088.0
+    "llama3_8b_b1_kv8192": 126311424,      # 60241.5, 2868.0
+    "llama3_8b_b4_kv8192": 239742157,      # 112921.6, 8280.0
+    "llama3_8b_b16_kv8192": 697142682,     # 325437.7, 29928.0
+    "llama2_70b_b1_kv32768": 456086118,    # 218940.3, 7516.0
 }
 
 
@@ -68,32 +75,62 @@ def parse_args():
                          "and kv_len, the first row kv_len; the algorithmic bytes count each row's own length")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg")
+    ap.add_argument("--no-check", action="store_true", help="skip the check of one step against the C oracle")
+    ap.add_argument("--sweep", action="store_true",
+                    help="one JSON line per row of the measurement table (each with --steps launches; the workload, "
+                         "batch, cache length and layer count of the row replace those given here)")
     return ap.parse_args()
 
 
+# rows of the measurement table: (workload, batch, cached tokens, layers to rotate over; 0 = enough for 3 GiB)
+SWEEP = [("llama2_7b", 1, 4096, 0), ("llama2_7b", 1, 1024, 0), ("llama2_7b", 1, 2048, 0), ("llama2_7b", 1, 8192, 0),
+         ("llama2_7b", 1, 16384, 0), ("llama2_7b", 1, 32768, 0), ("llama3_8b", 1, 8192, 0), ("llama3_8b", 4, 8192, 0),
+         ("llama3_8b", 16, 8192, 0), ("llama2_70b", 1, 32768, 0), ("llama2_70b", 1, 32768, 80)]
+
+
 def cpu_baseline(shape, batch, kv_len, budget_s):
-    """Time the plain C oracle on the host cores for the same workload (one layer)."""
+    """Time the plain C oracle on the host cores for the same workload (one layer): all cores, then one thread."""
     import numpy as np
     import cf_inputs
     from oracle import c_oracle
     inp = cf_inputs.make_inputs(shape, seed=1000, batch=batch, kv_len=kv_len, poison=False)
     args = (inp["x"], inp["w_qkv"], inp["w_o"], inp["k_cache"], inp["v_cache"], kv_len,
             shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.rope_base)
-    cores = len(os.sched_getaffinity(0))
-    c_oracle.set_num_threads(cores)
-    t0 = time.perf_counter()
-    c_oracle.decode_block(*args)                      # warm-up
-    first = time.perf_counter() - t0
-    reps = max(1, min(20, int(budget_s / max(first, 1e-3)) - 1))
-    times = []
-    for _ in range(reps):
+
+    def timed(threads, budget):
+        c_oracle.set_num_threads(threads)
         t0 = time.perf_counter()
-        c_oracle.decode_block(*args)
-        times.append(time.perf_counter() - t0)
-    med = float(np.median(times))
-    return {"value": med * 1e6, "unit": "us/step", "cores": int(c_oracle.num_threads()), "kind": "oracle",
+        c_oracle.decode_block(*args)                      # warm-up
+        first = time.perf_counter() - t0
+        reps = max(1, min(20, int(budget / max(first, 1e-3)) - 1))
+        times = []
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            c_oracle.decode_block(*args)
+            times.append(time.perf_counter() - t0)
+        return float(np.median(times)), reps, int(c_oracle.num_threads())
+
+    cores = len(os.sched_getaffinity(0))
+    med, reps, used = timed(cores, 0.6 * budget_s)
+    med1, reps1, _ = timed(1, 0.4 * budget_s)
+    c_oracle.set_num_threads(cores)
+    return {"value": med * 1e6, "unit": "us/step", "cores": used, "kind": "oracle",
             "sample": "%d full steps of the same workload (one layer, B=%d, L=%d), median; C oracle, fp64 accumulation"
-                      % (reps, batch, kv_len)}
+                      % (reps, batch, kv_len),
+            "single_thread": {"value": med1 * 1e6, "unit": "us/step", "cores": 1, "sample": "%d full steps, median" % reps1}}
+
+
+def check_against_oracle(shape, B, L, x, w_qkv, w_o, kc, vc, out):
+    """One step's output (device tensors, caches as they were before the step for rows < L) against the C oracle."""
+    import numpy as np
+    from oracle import c_oracle
+    c_oracle.set_num_threads(len(os.sched_getaffinity(0)))
+    ref = c_oracle.decode_block(x.cpu().numpy(), w_qkv.cpu().numpy(), w_o.cpu().numpy(), kc.cpu().numpy(), vc.cpu().numpy(), L,
+                                shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.rope_base)["out"]
+    got = out.cpu().numpy().astype(np.float64)
+    err, tol = float(np.abs(got - ref).max()), float(1e-2 * np.abs(ref).max() + 1e-3)
+    return {"max_abs_err": err, "tolerance": tol, "ok": bool(err <= tol),
+            "what": "one step on the first layer after the timed region, whole output, against the C oracle"}
 
 
 def main():
@@ -101,6 +138,21 @@ def main():
     if args.gpus != 1:
         log("bench.py measures one GPU only: this build has no multi-GPU path (--gpus %d refused)" % args.gpus)
         sys.exit(2)
+    if not args.sweep:
+        print(json.dumps(run_one(args)), flush=True)
+        return
+    import copy
+    for (name, batch, kv_len, layers) in SWEEP:
+        a = copy.copy(args)
+        a.workload, a.batch, a.kv_len, a.layers, a.max_seq = name, batch, kv_len, layers, 0
+        a.cpu_seconds = min(args.cpu_seconds, 6.0)
+        res = run_one(a)
+        if layers:
+            res["config"]["stack"] = "%d distinct layers; %.3f ms per pass over the stack" % (layers, res["value"] * layers / 1e3)
+        print(json.dumps(res), flush=True)
+
+
+def run_one(args):
     import torch
     import cf_inputs
     from paper_2508_18850_amd import DecodeBlock, algorithmic_bytes
@@ -158,6 +210,8 @@ def main():
         vc.zero_()
         kc[:, :, :L] = torch.randn((B, nkv, L, d), generator=gen, device=dev).half()
         vc[:, :, :L] = torch.randn((B, nkv, L, d), generator=gen, device=dev).half()
+        if i == 0 and not args.no_check:
+            first_rowmajor = (w_qkv.clone(), w_o.clone())          # for the check after the timed region
         if args.row_major:
             wq_t = carve(i, 0, wq_elems, (D, shape.n_qkv))
             wo_t = carve(i, up(wq_elems), wo_elems, (nq * d, D))
@@ -255,6 +309,18 @@ def main():
         blk.status(sh)
     assert torch.isfinite(out.float()).all(), "non-finite output"
     plan = blk.plan()
+    check = None
+    if not args.no_check and not args.ragged:
+        # outside the timed region: the first layer once more, against the oracle
+        with torch.cuda.stream(stream):
+            step(0)
+            blk.status(stream.cuda_stream)
+        torch.cuda.synchronize()
+        if args.layer:
+            log("(check skipped: the oracle leg of bench.py covers the bare block)")
+        else:
+            check = check_against_oracle(shape, B, L, x, first_rowmajor[0], first_rowmajor[1], layers[0][2], layers[0][3], out)
+            assert check["ok"], "the timed kernel disagrees with the oracle: %r" % (check,)
 
     ms_per_step = ms_total / args.steps
     us = ms_per_step * 1e3
@@ -280,10 +346,14 @@ def main():
         import numpy as np
         res["repetitions"] = {"n": len(rep_us), "median_us": float(np.median(rep_us)),
                               "p10_us": float(np.percentile(rep_us, 10)), "p90_us": float(np.percentile(rep_us, 90))}
+    if check is not None:
+        res["check"] = check
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(shape, B, L, args.cpu_seconds)
-    print(json.dumps(res), flush=True)
     blk.close()
+    del layers, arena
+    torch.cuda.empty_cache()
+    return res
 
 
 if __name__ == "__main__":
