@@ -70,6 +70,10 @@ def parse_args():
     ap.add_argument("--graph", action="store_true",
                     help="capture one pass over the rotating layers in a HIP graph and time replays of it instead of "
                          "stream launches (steps is rounded down to a multiple of the layer count)")
+    ap.add_argument("--stack", action="store_true",
+                    help="one cf_decode_stack call per pass over the rotating layers (every layer reads the hidden state "
+                         "the previous one wrote; for the bare block that is ONE launch per pass): a timed step still is "
+                         "one layer (steps is rounded down to a multiple of the layer count)")
     ap.add_argument("--ragged", action="store_true",
                     help="rows of different lengths (cf_decode_layer_rows): row b caches a seeded length between kv_len/4 "
                          "and kv_len, the first row kv_len; the algorithmic bytes count each row's own length")
@@ -268,7 +272,23 @@ def run_one(args):
         for i in range(args.warmup):
             step(i)
         blk.status(sh)
-        if args.graph:
+        if args.stack:
+            args.steps = max(1, args.steps // n_layers) * n_layers
+            n_passes = args.steps // n_layers
+            out2 = torch.empty_like(out)
+            cols = list(zip(*ptrs))
+
+            def one_pass():
+                blk.decode_stack(B, xp, [gp] * n_layers if args.layer else None, 1e-5, bool(args.layer), not args.row_major,
+                                 cols[0], cols[1], cols[2], cols[3], L, out2.data_ptr(), sh)
+
+            one_pass()
+            blk.status(sh)
+
+            def timed_region(first_step):
+                for _ in range(n_passes):
+                    one_pass()
+        elif args.graph:
             # one pass over the layers becomes one graph launch; a timed "step" still is one kernel
             args.steps = max(1, args.steps // n_layers) * n_layers
             graph = torch.cuda.CUDAGraph()
@@ -333,7 +353,8 @@ def run_one(args):
         "config": {"workload": name, "d_model": D, "n_q_heads": nq, "n_kv_heads": nkv, "head_dim": d,
                    "batch": B, "kv_len": L, "layers_rotated": n_layers,
                    "weight_layout": "row-major" if args.row_major else "packed (per-head blocks, one-time rearrangement)",
-                   "launch": "graph replay of one pass over the layers" if args.graph else "stream launches",
+                   "launch": ("one cf_decode_stack call per pass over the layers" if args.stack else
+                              "graph replay of one pass over the layers" if args.graph else "stream launches"),
                    "fused_steps": "rmsnorm + block + residual" if args.layer else "block",
                    "row_lengths": row_pos if args.ragged else "all kv_len",
                    "plan": plan},

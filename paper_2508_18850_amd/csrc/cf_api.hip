@@ -29,6 +29,7 @@ struct cf_handle_s {
     float *dbg_q = nullptr, *dbg_attn = nullptr;
     unsigned long long *dbg_t = nullptr;
     uint16_t *chain[2] = {nullptr, nullptr};   // hidden states between the layers of a stack, [max_batch, d_model] each
+    uint64_t *xslots = nullptr;                // the same between the layers of a one-launch stack: stamped fp32, [max_batch, d_model]
     // tuning
     int tune_w = 0, tune_ks = 0, tune_ns = 0;
     int balance_rows = 0, balance_tokens = 32;   // half the length difference between even and odd splits (-1: off)
@@ -285,7 +286,9 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     const size_t times_bytes = align_up((size_t)8 * h->num_cu * cf::kStamps * sizeof(unsigned long long), 256);
     h->exchange_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes;
     const size_t chain_bytes = align_up(B * c.d_model * sizeof(uint16_t), 256);
-    h->ws_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes + 2 * dbg_bytes + times_bytes +
+    const size_t xslot_bytes = align_up(B * c.d_model * sizeof(uint64_t), 256);
+    h->exchange_bytes += xslot_bytes;
+    h->ws_bytes = h->counters_bytes + p1_bytes + p2_bytes + p3_bytes + xslot_bytes + 2 * dbg_bytes + times_bytes +
                   2 * chain_bytes;
     e = hipMalloc(reinterpret_cast<void **>(&h->ws), h->ws_bytes);
     if (e != hipSuccess) {
@@ -302,6 +305,8 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     cur += p2_bytes;
     h->p3 = reinterpret_cast<uint64_t *>(cur);
     cur += p3_bytes;
+    h->xslots = reinterpret_cast<uint64_t *>(cur);
+    cur += xslot_bytes;
     h->dbg_q = reinterpret_cast<float *>(cur);
     cur += dbg_bytes;
     h->dbg_attn = reinterpret_cast<float *>(cur);
@@ -333,7 +338,7 @@ int cf_destroy(cf_handle h)
 static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, const void *W_qkv, const void *W_o,
                        void *k_cache, void *v_cache, int32_t pos, void *out, void *stream,
                        const void *norm_weight = nullptr, float eps = 0.f, int residual = 0,
-                       const int32_t *row_pos = nullptr)
+                       const int32_t *row_pos = nullptr, cf::StackArgs *stack = nullptr)
 {
     if (!h) return CF_EINVAL;
     if (reinterpret_cast<uintptr_t>(row_pos) & 3u) return CF_EINVAL;
@@ -378,7 +383,15 @@ static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, co
     const int plan[10] = {p.W, p.TS, p.KS, p.RB, p.NS, p.TPS, p.NC3, p.CW3, p.RS3, (int)lds};
     std::memcpy(h->last_plan, plan, sizeof plan);
     h->last_batch = batch;
-    hipError_t e = cf::launch_fused(p, h->cfg.head_dim, h->G, bt, lds, static_cast<hipStream_t>(stream));
+    hipError_t e;
+    if (stack) {
+        // one launch for all layers: the table of the other layers' pointers is filled in by the caller
+        stack->p = p;
+        stack->xslots = h->xslots;
+        e = cf::launch_fused_stack(*stack, h->cfg.head_dim, h->G, bt, lds, static_cast<hipStream_t>(stream));
+    } else {
+        e = cf::launch_fused(p, h->cfg.head_dim, h->G, bt, lds, static_cast<hipStream_t>(stream));
+    }
     if (e != hipSuccess) return hip_fail(h, e);
     return CF_OK;
 }
@@ -423,6 +436,30 @@ int cf_decode_stack(cf_handle h, int32_t n_layers, int32_t batch, const void *x,
         if (!aligned16(W_qkv[l]) || !aligned16(W_o[l]) || !aligned16(k_cache[l]) || !aligned16(v_cache[l]) ||
             (norm_weight && !aligned16(norm_weight[l])))
             return CF_EINVAL;
+    if (!norm_weight && !residual && h->cfg.head_dim == 128 && !h->slot_area) {
+        // The bare block: up to kMaxStackLayers layers per launch, the hidden state handed from layer to layer
+        // inside the kernel; a deeper stack takes several such launches, chained through the two buffers.
+        const void *in = x;
+        int chunk_index = 0;
+        for (int l0 = 0; l0 < n_layers; l0 += cf::kMaxStackLayers, ++chunk_index) {
+            const int n = n_layers - l0 < cf::kMaxStackLayers ? n_layers - l0 : cf::kMaxStackLayers;
+            void *dst = l0 + n == n_layers ? out : static_cast<void *>(h->chain[chunk_index & 1]);
+            cf::StackArgs a;
+            std::memset(&a, 0, sizeof a);
+            a.n_layers = n;
+            for (int l = 0; l < n; ++l) {
+                a.tab[l].wqkv = static_cast<const uint16_t *>(W_qkv[l0 + l]);
+                a.tab[l].wo = static_cast<const uint16_t *>(W_o[l0 + l]);
+                a.tab[l].kc = static_cast<uint16_t *>(k_cache[l0 + l]);
+                a.tab[l].vc = static_cast<uint16_t *>(v_cache[l0 + l]);
+            }
+            const int rc = decode_impl(h, packed != 0, batch, in, W_qkv[l0], W_o[l0], k_cache[l0], v_cache[l0], pos, dst, stream,
+                                       nullptr, 0.f, 0, nullptr, &a);
+            if (rc != CF_OK) return rc;
+            in = dst;
+        }
+        return CF_OK;
+    }
     const void *in = x;
     for (int l = 0; l < n_layers; ++l) {
         void *dst = l == n_layers - 1 ? out : static_cast<void *>(h->chain[l & 1]);

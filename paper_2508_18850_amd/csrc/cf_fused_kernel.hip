@@ -33,6 +33,7 @@
 #include "cf_params.h"
 #include "cf_rope_device.h"
 
+#include <cstddef>
 #include <cstdlib>
 #include <type_traits>
 
@@ -291,9 +292,20 @@ __shared__ unsigned long long s_ts[kStamps];
 #define CF_STAMP(k)
 #endif
 
-template <int HD, int G, int BT, class NextFn>
-__device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member, float *smem,
-                                           float *rope, unsigned long long &launches_out, NextFn &&issue_next)
+// The launch stamp of layer `layer` of a launch whose first layer has count cnt0 (never 0, the value of a
+// cleared slot: the low word plus the number of times it has wrapped).
+__device__ __forceinline__ uint32_t stamp_of(unsigned long long cnt0, int layer)
+{
+    const unsigned long long cnt = cnt0 + (unsigned long long)layer;
+    return (uint32_t)(cnt + (cnt >> 32));
+}
+
+// `layer` > 0 (a stack of layers in one launch): the input rows are what the final reduction of the previous layer
+// left in the slots xin (stamped fp32 values that are exact fp16 numbers), and cnt0 is known already.
+template <int HD, int G, int BT, bool STACK, class NextFn>
+__device__ __forceinline__ uint32_t p1_all(const Params &p, const LayerPtrs &lp, int tid0, int team, int member, float *smem,
+                                           float *rope, int layer, const uint64_t *xin, int n_layers,
+                                           unsigned long long &cnt0, NextFn &&issue_next)
 {
     constexpr int LPR = HD / 8;
     constexpr int NG = NT / LPR;
@@ -304,7 +316,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     constexpr bool MF = Mfma<HD, BT>::on;
     constexpr int U = MF ? 8 : (BT > 4 ? 2 : (BT == 4 ? 4 : 8));
     constexpr int MAXI = BT == 1 ? 4 : (BT <= 4 ? 2 : 1);   // selectors whose wave partials are buffered in LDS
-    const int tid = threadIdx.x, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
+    const int tid = tid0, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
     const int kg = (tid & 63) >> 4;                         // MF: contraction group of the lane (rows 8 kg .. 8 kg + 7 of a step)
     const int lrow = 32 * wv + 8 * kg;                      // MF: first row of the lane inside a 256-row batch
     const int ks = qmod(member, p.KS, p.sh_ks);
@@ -327,7 +339,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     float *red = smem + (MF ? 16 * XS : BT * p.RPS);   // [MAXI][NW][BT][HD]
     const Xbuf x1(p.p1);
     const uint32_t blkb = (uint32_t)p.D * HD * 2 + kQkvBlockPad;          // packed: bytes from one block to the next
-    const Stream W(p.wqkv, (p.flags & kFlagPacked) ? (uint32_t)(p.nqkv / HD) * blkb : (uint32_t)((size_t)p.D * p.nqkv * 2));
+    const Stream W(lp.wqkv, (p.flags & kFlagPacked) ? (uint32_t)(p.nqkv / HD) * blkb : (uint32_t)((size_t)p.D * p.nqkv * 2));
     // row-major [D][Nqkv]: rows are Nqkv*2 bytes apart and a selector starts at column col0;
     // packed [Nqkv/HD][D][HD] (+ pad): rows are HD*2 bytes apart and a selector is one contiguous block
     const uint32_t rowb = (p.flags & kFlagPacked) ? (uint32_t)HD * 2 : (uint32_t)p.nqkv * 2;
@@ -383,12 +395,30 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     const bool x_in_regs = BT * p.RPS <= XR * NT;
     // (all of them unconditional: a load inside a branch would be waited for at the branch's end)
     uint16_t xr[XR];
+    u32x2 xs2[XR];                                                // layer > 0: the stamped slots of the same values
     bool xv[XR];
+    const bool from_slots = STACK && layer > 0;
+    const Xbuf xsl(xin ? (const void *)xin : (const void *)p.p1);
+    // (the same number of loads on both paths, so that the waits behind this branch stay exact)
 #pragma unroll
     for (int q = 0; q < XR; ++q) {
         const int i = tid + q * NT, b = BT == 1 ? 0 : i / p.RPS, r = i - b * p.RPS;
         xv[q] = x_in_regs && i < BT * p.RPS && b < p.B && r < nrows;
-        xr[q] = p.x[xv[q] ? (size_t)b * p.D + r0 + r : 0];
+        xr[q] = 0;
+        xs2[q] = u32x2{0u, 0u};
+    }
+    if (from_slots) {
+#pragma unroll
+        for (int q = 0; q < XR; ++q) {
+            const int i = tid + q * NT, b = BT == 1 ? 0 : i / p.RPS, r = i - b * p.RPS;
+            xs2[q] = xsl.ld(xv[q] ? (size_t)b * p.D + r0 + r : 0);
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < XR; ++q) {
+            const int i = tid + q * NT, b = BT == 1 ? 0 : i / p.RPS, r = i - b * p.RPS;
+            xr[q] = p.x[xv[q] ? (size_t)b * p.D + r0 + r : 0];
+        }
     }
     // RMSNorm in front of the projection (when a weight vector is given): the projection is linear, so the
     // weights gamma go into the staged slice of x and the factor 1/sqrt(mean(x^2) + eps) of a row goes into
@@ -473,14 +503,33 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     // and the read sat at the head of the in-order return queue in front of the weights.)  The
     // value was written in an earlier launch, so a scalar load through the cache is good enough,
     // and it does not enter the vector memory queue at all.
-    unsigned long long launches;
-    asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)"
-                 : "=s"(launches)
-                 : "s"(p.done + (size_t)blockIdx.x * kCounterStride)
-                 : "memory");
-    // never 0 (the value of a cleared slot): the low word plus the number of times it has wrapped
-    const unsigned long long cnt = launches + 1ull;
-    const uint32_t stamp = (uint32_t)(cnt + (cnt >> 32));
+    if (layer == 0) {
+        unsigned long long launches;
+        asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)"
+                     : "=s"(launches)
+                     : "s"(p.done + (size_t)blockIdx.x * kCounterStride)
+                     : "memory");
+        cnt0 = launches + 1ull;
+    }
+    const uint32_t stamp = stamp_of(cnt0, layer);
+    if (from_slots) {
+        // The slots carry the stamp of the previous layer.  A workgroup whose projection nobody waits for (no
+        // column block of its own) may arrive here after its sources have moved on and stamped newer values:
+        // any stamp from the previous layer's up to the last layer's of this launch is taken.
+        const uint32_t want = stamp_of(cnt0, layer - 1);
+        Spin spin;
+        for (;;) {
+            bool ok = true;
+#pragma unroll
+            for (int q = 0; q < XR; ++q) ok &= !xv[q] | ((uint32_t)(xs2[q].y - want) <= (uint32_t)n_layers);
+            if (ok || spin.expired(p)) break;
+#pragma unroll
+            for (int q = 0; q < XR; ++q) {
+                const int i = tid + q * NT, b = BT == 1 ? 0 : i / p.RPS, r = i - b * p.RPS;
+                xs2[q] = xsl.ld(xv[q] ? (size_t)b * p.D + r0 + r : 0);
+            }
+        }
+    }
     // MF: the value goes to row b, column r of the operand array as fp16; without RMSNorm that is x itself,
     // with it the product x * gamma is kept as high + low part, so that nothing is rounded away
     auto stage = [&](int i, float v) {
@@ -497,13 +546,26 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
 #pragma unroll
         for (int q = 0; q < XR; ++q) {
             const int i = tid + q * NT;
-            if (i < BT * p.RPS) stage(i, xv[q] ? h2f(xr[q]) * (norm ? h2f(gr[q]) : 1.f) : 0.f);
+            const float xval = from_slots ? __builtin_bit_cast(float, xs2[q].x) : h2f(xr[q]);
+            if (i < BT * p.RPS) stage(i, xv[q] ? xval * (norm ? h2f(gr[q]) : 1.f) : 0.f);
         }
     } else {
+        const uint32_t want = stamp_of(cnt0, layer - 1);
         for (int i = tid; i < BT * p.RPS; i += NT) {
             const int b = i / p.RPS, r = i - b * p.RPS;
             const bool in = b < p.B && r < nrows;
-            stage(i, in ? h2f(p.x[(size_t)b * p.D + r0 + r]) * (norm ? h2f(gsrc[r0 + r]) : 1.f) : 0.f);
+            float xval = 0.f;
+            if (in && from_slots) {
+                Spin spin;
+                for (;;) {
+                    const u32x2 v = xsl.ld((size_t)b * p.D + r0 + r);
+                    xval = __builtin_bit_cast(float, v.x);
+                    if ((uint32_t)(v.y - want) <= (uint32_t)n_layers || spin.expired(p)) break;
+                }
+            } else if (in) {
+                xval = h2f(p.x[(size_t)b * p.D + r0 + r]);
+            }
+            stage(i, in ? xval * (norm ? h2f(gsrc[r0 + r]) : 1.f) : 0.f);
         }
     }
     if constexpr (MF) {
@@ -516,11 +578,11 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
         }
     }
     if (BT <= 4 && norm) square_rows(0);
-    // cos / sin of this position while the first weights are still on their way
+    // cos / sin of this position while the first weights are still on their way (the same for every layer of a stack)
 #pragma unroll
     for (int k = 0; k < NE; ++k) {
         const int e = tid + k * NT, eb = e / (HD / 2), i = e % (HD / 2);
-        if (eb < (own_pos ? p.B : 1)) {
+        if (!STACK && eb < (own_pos ? p.B : 1)) {      // (a stack builds the table once, in front of its layers)
             const int pos_e = own_pos ? min(max(epos[k], 0), p.pos) : p.pos;
             // (the frequency is computed here: a table in memory was one more cold page in front of the first wait)
             rope_cos_sin(pos_e, rope_inv_freq(i, HD, p.rope_log2_base), rope[eb * HD + i], rope[eb * HD + HD / 2 + i]);
@@ -679,7 +741,6 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, int team, int member
     consume(wb);
     finish();
     if (nbuf) flush();
-    launches_out = cnt;
     return stamp;
 }
 
@@ -697,10 +758,10 @@ struct EarlyQ {
     u32x2 v[kEarly];
     bool issued = false;
     template <int HD, int G>
-    __device__ __forceinline__ void issue(const Params &p, int team, int b)
+    __device__ __forceinline__ void issue(const Params &p, int tid0, int team, int b)
     {
         const Xbuf x1(p.p1);
-        const int e = threadIdx.x;
+        const int e = tid0;
         if (e < G * HD) {
             const int sel = e / HD, c = e - sel * HD;
             const size_t src = (size_t)b * p.nqkv + qkv_col0<HD, G>(p, team, sel) + c;
@@ -770,7 +831,7 @@ struct P2Stream {
     static constexpr int NG = NT / LPR;
     static constexpr int U = P2Cfg<G>::U;
     static constexpr bool MA = AttnMfma<HD, G>::on;
-    int t0, t1, iters, grp, pos;
+    int t0, t1, iters, grp, pos, tid;
     uint32_t voff0;
     size_t head;
     Stream K, V;
@@ -778,12 +839,13 @@ struct P2Stream {
     // read.  An inactive stream (a workgroup without an attention item) has an empty row range: its
     // loads are issued with every lane off.  A row shorter than the longest one of the batch uses the
     // same split boundaries: its splits past pos_b are empty.
-    __device__ __forceinline__ P2Stream(const Params &p, int team, int b, int s, int pos_b, bool active = true)
-        : pos(pos_b), head(((size_t)b * p.nkv + team) * p.max_seq * HD), K(p.kc + head, (uint32_t)pos_b * HD * 2),
-          V(p.vc + head, (uint32_t)pos_b * HD * 2)
+    __device__ __forceinline__ P2Stream(const Params &p, const LayerPtrs &lp, int tid0, int team, int b, int s, int pos_b,
+                                        bool active = true)
+        : pos(pos_b), tid(tid0), head(((size_t)b * p.nkv + team) * p.max_seq * HD), K(lp.kc + head, (uint32_t)pos_b * HD * 2),
+          V(lp.vc + head, (uint32_t)pos_b * HD * 2)
     {
-        const int lig = threadIdx.x % LPR;
-        grp = threadIdx.x / LPR;
+        const int lig = tid0 % LPR;
+        grp = tid0 / LPR;
         t0 = active ? s * p.TPS + ((s & 1) ? p.TD : 0) : 0;         // even splits are 2*TD tokens longer
         t1 = active ? min(t0 + p.TPS + ((s & 1) ? -p.TD : p.TD), pos_b) : 0;
         iters = t1 > t0 ? (t1 - t0 + NG - 1) / NG : 0;
@@ -795,7 +857,7 @@ struct P2Stream {
     // come out of the first product).  Eight load instructions each, lanes past the split switched off.
     __device__ __forceinline__ void load_k(h8 (&kr)[8], int it, uint32_t dep) const
     {
-        const int wv = threadIdx.x >> 6, rg = (threadIdx.x & 63) >> 4, lig = threadIdx.x & 15;
+        const int wv = tid >> 6, rg = (tid & 63) >> 4, lig = tid & 15;
         const uint32_t voff = (uint32_t)((32 * wv + rg) * HD + lig * 8) * 2 + dep;
         const int tb = t0 + 32 * NW * it;                       // uniform
         const int lim = t1 - 32 * wv - rg;
@@ -804,7 +866,7 @@ struct P2Stream {
     }
     __device__ __forceinline__ void load_v(h8 (&vr)[8], int it, uint32_t dep) const
     {
-        const int wv = threadIdx.x >> 6, rg = (threadIdx.x & 63) >> 4, lig = threadIdx.x & 15;
+        const int wv = tid >> 6, rg = (tid & 63) >> 4, lig = tid & 15;
         const uint32_t voff = (uint32_t)((32 * wv + 4 * rg) * HD + lig * 8) * 2 + dep;
         const int tb = t0 + 32 * NW * it;
         const int lim = t1 - 32 * wv - 4 * rg;
@@ -848,7 +910,7 @@ struct P2Stream {
 };
 
 template <int HD, int G, class TailFn>
-__device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s, uint32_t stamp, bool first,
+__device__ __forceinline__ void p2_item(const Params &p, const LayerPtrs &lp, int tid0, int team, int b, int s, uint32_t stamp, bool first,
                                         const P2Stream<HD, G> &st, KvBuf<HD, G> &buf, const EarlyQ &eq, float *smem,
                                         const float *rope, TailFn &&issue_next)
 {
@@ -859,7 +921,7 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
     constexpr int PS = HD + kP2Stride;
     // (the thread index is made opaque per item: everything derived from it would otherwise be computed once in
     // front of the loop over the items, dozens of registers that are then spilled)
-    int tid = threadIdx.x;
+    int tid = tid0;
     if (AttnMfma<HD, G>::on) asm volatile("" : "+v"(tid));
     const int lane = tid & 63, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
     const bool last = (s == p.NS - 1);
@@ -1180,9 +1242,9 @@ __device__ __forceinline__ void p2_item(const Params &p, int team, int b, int s,
         lds_barrier();
         const size_t row = st.head + (size_t)st.pos * HD;
         if (tid < HD)
-            p.kc[row + tid] = f2h(kn[tid]);
+            lp.kc[row + tid] = f2h(kn[tid]);
         else if (tid < 2 * HD)
-            p.vc[row + tid - HD] = f2h(vn[tid - HD]);
+            lp.vc[row + tid - HD] = f2h(vn[tid - HD]);
         for (int g = wv; g < G; g += NW) {
             float d = 0.f;
             for (int c = lane; c < HD; c += 64) d = fmaf(qs[g * HD + c], kn[c], d);
@@ -1243,12 +1305,12 @@ struct OutTile {
 // item; lane (l % 16, l / 16) loads eight adjacent columns of rows 32 s + 8 (l / 16) + 0..7 for the two steps s
 // (the same lane layout as in the projection: eight rows are transposed in the lane into MFMA operands).
 template <int HD, bool MF>
-__device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs, int ch, OutTile<HD> &t, int part = 2)
+__device__ __forceinline__ void p3_load(const Params &p, const LayerPtrs &lp, int tid0, int hq, int c3, int rs, int ch, OutTile<HD> &t, int part = 2)
 {
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int lane = tid0 & 63, wv = tid0 >> 6;
     // row-major [nq*HD][D], or packed [nq][ceil(D/512)][HD][512] (one contiguous tile per head and chunk)
     const int NCH = (p.D + kOutChunk - 1) / kOutChunk;        // 512-column chunks of the output
-    const Stream Wo(p.wo, (p.flags & kFlagPacked) ? (uint32_t)((size_t)p.nq * NCH * HD * kOutChunk * 2)
+    const Stream Wo(lp.wo, (p.flags & kFlagPacked) ? (uint32_t)((size_t)p.nq * NCH * HD * kOutChunk * 2)
                                    : (uint32_t)((size_t)p.nq * HD * p.D * 2));
     const int nrows = HD / p.RS3;
     const int cbase = c3 * p.CW3 + ch * kOutChunk;
@@ -1282,12 +1344,16 @@ __device__ __forceinline__ void p3_load(const Params &p, int hq, int c3, int rs,
 }
 
 template <int HD, int BT>
-__device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs, uint32_t stamp, OutTile<HD> &tile,
+__device__ __forceinline__ void p3_item(const Params &p, const LayerPtrs &lp, int tid0, int hq, int c3, int rs, uint32_t stamp, OutTile<HD> &tile,
                                         bool prefetched, float *smem)
 {
     constexpr int RB = BT < 4 ? BT : 4;
     constexpr int PS = HD + kP2Stride;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    // (the 16-row tile has no register to spare: the thread index is made opaque here, so that what this phase
+    // derives from it is computed here and not kept from the start of the kernel)
+    int tid = tid0;
+    if (Mfma<HD, BT>::on) asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wv = tid >> 6;
     float *as = smem;                 // [BT][HD] merged, normalised attention output of head hq
     float *red = smem + BT * HD;      // [NW][RB][512]; also the (m, l, a) triples of the merge
     const Xbuf x2(p.p2), x3(p.p3);
@@ -1299,7 +1365,7 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
     const int nchunk = p.CW3 / kOutChunk;
 
     constexpr bool MF = Mfma<HD, BT>::on;
-    if (!prefetched) p3_load<HD, MF>(p, hq, c3, rs, 0, tile);     // independent of the attention result
+    if (!prefetched) p3_load<HD, MF>(p, lp, tid, hq, c3, rs, 0, tile);     // independent of the attention result
 
     {
         // ---- merge of the split-KV partials (Alg. 3 steps 5-7).  A pass handles up to NV * 512 values v = (batch row,
@@ -1416,7 +1482,7 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
     for (int ch = 0; ch < nchunk; ++ch) {
         const int cbase = c3 * p.CW3 + ch * kOutChunk;
         if (cbase >= p.D) break;
-        if (ch > 0) p3_load<HD, MF>(p, hq, c3, rs, ch, tile);
+        if (ch > 0) p3_load<HD, MF>(p, lp, tid, hq, c3, rs, ch, tile);
         if constexpr (MF) {
             // [16 batch rows] x [rows of the item] x [128 columns of this wavefront]: two steps of 32 rows for each
             // half of the rows; the attention output is split into a high and a low fp16 part (two products), so
@@ -1524,12 +1590,12 @@ __device__ __forceinline__ void p3_item(const Params &p, int hq, int c3, int rs,
 // does with atomicAdd), then writes fp16.
 // ---------------------------------------------------------------------------
 // The residual input of output value v0 + threadIdx.x of this workgroup (0 when there is none).
-__device__ __forceinline__ uint16_t residual_input(const Params &p, int v0)
+__device__ __forceinline__ uint16_t residual_input(const Params &p, int tid0, int v0)
 {
     const int cpw = (p.D + p.W - 1) / p.W;
     const int c0 = blockIdx.x * cpw;
     const int ncol = min(cpw, p.D - c0);
-    const int i = v0 + (int)threadIdx.x;
+    const int i = v0 + tid0;
     uint16_t r = 0;
     if (kLayer && (p.flags & kFlagResidual) && ncol > 0 && i < ncol * p.B) {
         const int b = i / ncol, c = i - b * ncol;
@@ -1538,9 +1604,11 @@ __device__ __forceinline__ uint16_t residual_input(const Params &p, int v0)
     return r;
 }
 
-__device__ __forceinline__ void final_reduce(const Params &p, uint32_t stamp, float *smem)
+// xout != null (a layer of a stack that is not the last): the result, rounded to fp16 as `out` would hold it, goes to
+// the slots the next layer's projection reads its input from, not to `out`.
+__device__ __forceinline__ void final_reduce(const Params &p, int tid0, uint32_t stamp, float *smem, uint64_t *xout = nullptr)
 {
-    const int tid = threadIdx.x;
+    const int tid = tid0;
     const Xbuf x3(p.p3);
     const int nslots = p.nq * p.RS3;
     const int cpw = (p.D + p.W - 1) / p.W;
@@ -1556,7 +1624,7 @@ __device__ __forceinline__ void final_reduce(const Params &p, uint32_t stamp, fl
         // the residual input of the value this thread writes below (threads tid < cb have v == tid), on its
         // way while the partials are polled.  (Fetching it before phase 3 was tried: a load inside a branch
         // there makes every later wait for the output-projection tile drain the queue.)
-        const uint16_t xres = residual_input(p, v0);
+        const uint16_t xres = residual_input(p, tid0, v0);
         if (s0 < spt) {
             const int n = (nslots - s0 + spt - 1) / spt;
             const size_t base = (size_t)s0 * p.B * p.D + (size_t)b * p.D + c0 + c, stride = (size_t)spt * p.B * p.D;
@@ -1568,21 +1636,31 @@ __device__ __forceinline__ void final_reduce(const Params &p, uint32_t stamp, fl
         if (tid < cb) {
             float sum = kLayer && (p.flags & kFlagResidual) ? h2f(xres) : 0.f;
             for (int k = 0; k < spt; ++k) sum += smem[k * cb + tid];
-            p.out[(size_t)b * p.D + c0 + c] = f2h(sum);
+            if (xout)
+                Xbuf(xout).st((size_t)b * p.D + c0 + c, h2f(f2h(sum)), stamp);
+            else
+                p.out[(size_t)b * p.D + c0 + c] = f2h(sum);
         }
         lds_barrier();
     }
 }
 
-template <int HD, int G, int BT>
-__global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
+// One launch = n_layers decode steps in a row (1 for the plain entry points).  Layer l > 0 takes its weights and
+// caches from tab[l] and its input from the slots xslots, where the final reduction of layer l - 1 left its result;
+// the last layer writes `out`.  Nothing separates the layers but those slots: a workgroup goes on as soon as the
+// rows of the input it needs have arrived.  The exchange areas need no second set: a workgroup can post values of
+// layer l + 1 only after it has taken in that layer's input, which exists only when every workgroup has finished
+// reading what layer l exchanged.
+template <int HD, int G, int BT, bool STACK>
+__device__ __forceinline__ void decode_steps(const Params &p0, const LayerPtrs *tab, int n_layers_in, uint64_t *xslots)
 {
+    const int n_layers = STACK ? n_layers_in : 1;
     extern __shared__ float smem[];
     {
         // The compiler loads each kernel argument shortly before its first use: several dependent
         // round trips to cold memory in a row at the start of every launch.  One word of every 64-byte
         // line of the argument block is read here, all at once, so the later reads hit the scalar cache.
-        static_assert(sizeof(Params) <= 256, "one load per 64-byte line of the argument block below");
+        static_assert(sizeof(Params) == 256, "one load per 64-byte line of the argument block below");
         auto ka = __builtin_amdgcn_kernarg_segment_ptr();
         uint32_t t0, t1, t2, t3;
         asm volatile("s_load_dword %0, %4, 0x0\n\ts_load_dword %1, %4, 0x40\n\ts_load_dword %2, %4, 0x80\n\t"
@@ -1595,9 +1673,6 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
     // Workgroup w runs on die (XCD) w % 8, and the odd dies get about a tenth less memory
     // bandwidth than the even ones.  With pairmap a team sits on one pair of dies, members with an
     // even index on the even die: those take the longer slices and splits.
-    const int w = blockIdx.x;
-    const int team = p.pairmap ? qmod(w >> 1, p.nkv, p.sh_nkv) : qmod(w, p.nkv, p.sh_nkv);
-    const int member = p.pairmap ? qdiv(w >> 1, p.nkv, p.sh_nkv) * 2 + (w & 1) : qdiv(w, p.nkv, p.sh_nkv);
 #if CF_STAMPS
     if (tid < kStamps) s_ts[tid] = 0;       // same wavefront as thread 0: ordered before its stamps
 #endif
@@ -1607,8 +1682,36 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
         s_ts[7] = ((unsigned long long)__builtin_amdgcn_s_getreg(63508) << 32) | (unsigned)__builtin_amdgcn_s_getreg(63492);
 #endif
 
+    unsigned long long cnt0 = 0;
+    if (STACK) {
+        // the RoPE table is the same for all layers (one position; a stack has no per-row positions): built here,
+        // outside the loop, so that its fp64 constants do not become loop-invariant registers
+        for (int e = tid; e < HD / 2; e += NT)
+            rope_cos_sin(p0.pos, rope_inv_freq(e, HD, p0.rope_log2_base), s_rope[e], s_rope[HD / 2 + e]);
+        lds_barrier();
+    }
+    for (int layer = 0; layer < n_layers; ++layer) {
+    // In a stack the parameters are read through a pointer to the kernel's argument block that is made opaque per
+    // layer (as are the thread and workgroup index below): whatever depends only on them is loop-invariant, and
+    // the compiler would otherwise compute all of it once in front of the loop over the layers and keep it in
+    // registers, hundreds of values, across every phase.
+    typedef const __attribute__((address_space(4))) Params *KernargParams;
+    KernargParams pk = (KernargParams)__builtin_amdgcn_kernarg_segment_ptr();      // StackArgs begins with Params
+    if (STACK) asm volatile("" : "+s"(pk));
+    const Params &p = STACK ? *(const Params *)pk : p0;
     const int n2 = p.B * p.NS;                       // attention items of the team
     const int n3 = G * p.NC3 * p.RS3;                // output-projection items of the team
+    // (in a stack the thread index is made opaque per layer: everything derived from it would otherwise be computed
+    // once in front of the loop over the layers and be kept in registers across all phases)
+    int tl = threadIdx.x, w = blockIdx.x;
+    if (STACK) asm volatile("" : "+v"(tl), "+s"(w));
+    const int team = p.pairmap ? qmod(w >> 1, p.nkv, p.sh_nkv) : qmod(w, p.nkv, p.sh_nkv);
+    const int member = p.pairmap ? qdiv(w >> 1, p.nkv, p.sh_nkv) * 2 + (w & 1) : qdiv(w, p.nkv, p.sh_nkv);
+    // weights and caches of this layer (layer 0, and the only layer of a plain call: those of the parameters);
+    // a reference into the argument block either way, so that each pointer is fetched where it is used
+    static_assert(offsetof(Params, wo) == offsetof(Params, wqkv) + 8 && offsetof(Params, kc) == offsetof(Params, wqkv) + 16 &&
+                      offsetof(Params, vc) == offsetof(Params, wqkv) + 24, "Params holds a LayerPtrs");
+    const LayerPtrs &lp = (STACK && layer > 0) ? tab[layer] : *reinterpret_cast<const LayerPtrs *>(&p.wqkv);
     KvBuf<HD, G> kv;
     OutTile<HD> tile;
     const int b_first = member < n2 ? qdiv(member, p.NS, p.sh_ns) : 0;     // batch row of the first attention item
@@ -1617,17 +1720,19 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
     // (with positions per row the stream is set up only where phase 1 first needs it: the position comes from
     // memory, and waiting for it here would hold up the first weight loads)
     const bool own_pos = kLayer && p.row_pos != nullptr;
-    P2Stream<HD, G> st2(p, team, b_first, s_first, own_pos ? 0 : p.pos, member < n2 && !own_pos);
+    P2Stream<HD, G> st2(p, lp, tl, team, b_first, s_first, own_pos ? 0 : p.pos, member < n2 && !own_pos);
 
     // ---- phase 1 (projection); its last step already starts the K/V stream of phase 2
     EarlyQ eq;
-    unsigned long long launch_count;
-    const uint32_t stamp = p1_all<HD, G, BT>(p, team, member, smem, s_rope, launch_count,
+    const uint32_t stamp = p1_all<HD, G, BT, STACK>(p, lp, tl, team, member, smem, s_rope, STACK ? layer : 0, xslots, n_layers, cnt0,
                                              [&](int stage) {
-                                                 if (own_pos) st2 = P2Stream<HD, G>(p, team, b_first, s_first, pos_first, member < n2);
+                                                 if (own_pos) st2 = P2Stream<HD, G>(p, lp, tl, team, b_first, s_first, pos_first, member < n2);
                                                  st2.prefetch(kv, 0);
                                              });
-    if (member < n2) eq.issue<HD, G>(p, team, qdiv(member, p.NS, p.sh_ns));   // a first look at the team's q partials
+    // a first look at the team's q partials (in a stack only for one batch row and attention on the vector ALU: no
+    // registers are left for the sixteen pairs there, they would be spilled as they arrive)
+    if (member < n2 && !(STACK && (AttnMfma<HD, G>::on || BT > 1)))
+        eq.issue<HD, G>(p, tl, team, qdiv(member, p.NS, p.sh_ns));
     st2.prefetch(kv, 1);
     CF_STAMP(1);
     // ---- phase 2 (attention); the last item already starts the W_o stream of phase 3
@@ -1642,7 +1747,7 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
         if (member < n3) {
             int hq, c3, rs;
             p3_args(member, hq, c3, rs);
-            p3_load<HD, Mfma<HD, BT>::on>(p, hq, c3, rs, 0, tile, part);
+            p3_load<HD, Mfma<HD, BT>::on>(p, lp, tl, hq, c3, rs, 0, tile, part);
             tile_ready = true;
         }
     };
@@ -1650,12 +1755,12 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
         const bool first = (it == member), final_item = (it + p.TS >= n2);
         if (!first) {
             const int b_it = qdiv(it, p.NS, p.sh_ns);
-            st2 = P2Stream<HD, G>(p, team, b_it, qmod(it, p.NS, p.sh_ns), row_pos(p, b_it));
+            st2 = P2Stream<HD, G>(p, lp, tl, team, b_it, qmod(it, p.NS, p.sh_ns), row_pos(p, b_it));
             st2.prefetch(kv, 0);
             st2.prefetch(kv, 1);
         }
         // stage 1: first half of the output-projection tile, stage 2: second half
-        p2_item<HD, G>(p, team, qdiv(it, p.NS, p.sh_ns), qmod(it, p.NS, p.sh_ns), stamp, first, st2, kv, eq, smem,
+        p2_item<HD, G>(p, lp, tl, team, qdiv(it, p.NS, p.sh_ns), qmod(it, p.NS, p.sh_ns), stamp, first, st2, kv, eq, smem,
                        s_rope + (kLayer && p.row_pos ? qdiv(it, p.NS, p.sh_ns) * HD : 0), [&](int stage) {
             if (final_item) p3_prefetch(stage - 1);
         });
@@ -1666,19 +1771,35 @@ __global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
     for (int it = member; it < n3; it += p.TS) {
         int hq, c3, rs;
         p3_args(it, hq, c3, rs);
-        p3_item<HD, BT>(p, hq, c3, rs, stamp, tile, tile_ready && it == member, smem);
+        p3_item<HD, BT>(p, lp, tl, hq, c3, rs, stamp, tile, tile_ready && it == member, smem);
     }
     CF_STAMP(4);
     // ---- phase 4 (sum over heads)
-    final_reduce(p, stamp, smem);
+    final_reduce(p, tl, stamp, smem, STACK && layer + 1 < n_layers ? xslots : nullptr);
     CF_STAMP(5);
-    if (tid == 0) p.done[(size_t)blockIdx.x * kCounterStride] = launch_count;   // launches completed
+    }   // layers
+    if (tid == 0) p0.done[(size_t)blockIdx.x * kCounterStride] = cnt0 + (unsigned long long)(n_layers - 1);   // steps completed
 #if CF_STAMPS
     CF_STAMP(6);
     lds_barrier();
-    if (p.dbg_t && tid < kStamps) p.dbg_t[(size_t)blockIdx.x * kStamps + tid] = s_ts[tid];
+    if (p0.dbg_t && tid < kStamps) p0.dbg_t[(size_t)blockIdx.x * kStamps + tid] = s_ts[tid];
 #endif
 }
+
+template <int HD, int G, int BT>
+__global__ void __launch_bounds__(NT) CF_KERNEL(const Params p)
+{
+    decode_steps<HD, G, BT, false>(p, nullptr, 1, nullptr);
+}
+
+#if !CF_LAYER
+// A stack of layers in one launch: the argument block carries the table of per-layer pointers by value.
+template <int HD, int G, int BT>
+__global__ void __launch_bounds__(NT) fused_decode_stack(const StackArgs a)
+{
+    decode_steps<HD, G, BT, true>(a.p, a.tab, a.n_layers, a.xslots);
+}
+#endif
 
 #if !CF_LAYER
 // One-time rearrangement of the weights into per-head contiguous blocks (16 bytes per thread step).
@@ -1740,6 +1861,34 @@ KernelFn pick(int hd, int g, int bt)
     if (hd == 128) return pick_g<128>(g, bt);
     return nullptr;
 }
+
+#if !CF_LAYER
+using StackFn = void (*)(const StackArgs);
+
+template <int G>
+StackFn pick_stack_bt(int bt)
+{
+    switch (bt) {
+    case 1: return fused_decode_stack<128, G, 1>;
+    case 4: return fused_decode_stack<128, G, 4>;
+    case 16: return fused_decode_stack<128, G, 16>;
+    default: return nullptr;
+    }
+}
+
+// (head_dim 128 only: the shapes whose stacks are worth one launch)
+StackFn pick_stack(int hd, int g, int bt)
+{
+    if (hd != 128) return nullptr;
+    switch (g) {
+    case 1: return pick_stack_bt<1>(bt);
+    case 2: return pick_stack_bt<2>(bt);
+    case 4: return pick_stack_bt<4>(bt);
+    case 8: return pick_stack_bt<8>(bt);
+    default: return nullptr;
+    }
+}
+#endif
 
 }  // namespace
 
@@ -1808,6 +1957,26 @@ hipError_t launch_pack(const uint16_t *wqkv, const uint16_t *wo, uint16_t *wqkv_
                        reinterpret_cast<uint4 *>(wqkv_p), D, nqkv, hd);
     hipLaunchKernelGGL(pack_o_kernel, dim3(2048), dim3(256), 0, stream, reinterpret_cast<const uint4 *>(wo),
                        reinterpret_cast<uint4 *>(wo_p), D, nq, hd);
+    return hipGetLastError();
+}
+
+hipError_t launch_fused_stack(const StackArgs &a, int hd, int g, int bt, size_t lds_bytes, hipStream_t stream)
+{
+    StackFn fn = pick_stack(hd, g, bt);
+    if (!fn || wants_layer_kernel(a.p) || a.n_layers < 1 || a.n_layers > kMaxStackLayers) return hipErrorInvalidDeviceFunction;
+    // all workgroups must be resident, as for the one-layer kernel
+    int per_cu = 0;
+    if (lds_bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fn), kThreads, lds_bytes);
+    if (e != hipSuccess) return e;
+    int dev = 0, cus = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    if ((long)per_cu * cus < a.p.W) return hipErrorLaunchOutOfResources;
+    hipLaunchKernelGGL(fn, dim3(a.p.W), dim3(kThreads), lds_bytes, stream, a);
     return hipGetLastError();
 }
 

@@ -34,11 +34,17 @@ constexpr int kFlagPacked = 1;     // weights are in the packed (per-head contig
 constexpr int kFlagResidual = 2;   // out = x + block output
 
 // Everything the fused kernel needs, passed by value (256 bytes: four 64-byte lines, fetched together at kernel start).
+struct LayerPtrs {             // what differs from layer to layer of a stack
+    const uint16_t *wqkv, *wo;
+    uint16_t *kc, *vc;
+};
 struct Params {
-    const uint16_t *x, *wqkv, *wo;
+    const uint16_t *x;
+    const uint16_t *wqkv, *wo; // these four in the order of LayerPtrs: the kernel reads them as one
+    uint16_t *kc, *vc;
     const int32_t *row_pos;    // [B] tokens cached for each batch row (at most pos), or null: pos for every row
     const uint16_t *gamma;     // [D] RMSNorm weight applied to x in front of the projection, or null: x is used as it is
-    uint16_t *kc, *vc, *out;
+    uint16_t *out;
     // workspace
     unsigned long long *done;  // [workgroups][kCounterStride]: launches that workgroup w has completed
     uint32_t *err;         // set to 1 when a spin gave up
@@ -66,6 +72,16 @@ struct Params {
     uint32_t spin_ticks;   // wait limit in 100 MHz ticks (at most 42 s)
 };
 
+// A stack of layers in one launch (cf_decode_stack without RMSNorm and residual): the pointers of every layer travel
+// by value in the kernel's argument block, behind the parameters of the first layer.
+constexpr int kMaxStackLayers = 88;        // 256 + 16 + 88 * 32 bytes = 3088 of the 4096 an argument block may have
+struct StackArgs {
+    Params p;                  // everything of layer 0, and what all layers share
+    uint64_t *xslots;          // [B][D] stamped fp32: the hidden state between two layers
+    int n_layers, reserved;
+    LayerPtrs tab[kMaxStackLayers];
+};
+
 // The kernel exists twice: the block alone, and the block with the RMSNorm prologue, the residual epilogue
 // and per-row positions
 // (a translation unit of its own, compiled from the same source with -DCF_LAYER=1, so that the block kernel
@@ -74,6 +90,9 @@ bool wants_layer_kernel(const Params &p);
 // Launch the variant for (head_dim, group size, batch tile).  Returns a hipError_t.
 hipError_t launch_fused(const Params &p, int head_dim, int group, int batch_tile, size_t lds_bytes,
                         hipStream_t stream);
+// The block kernel over a.n_layers layers in one launch (a.p must not ask for RMSNorm, residual or per-row positions).
+hipError_t launch_fused_stack(const StackArgs &a, int head_dim, int group, int batch_tile, size_t lds_bytes,
+                              hipStream_t stream);
 // Workgroups of that variant that fit on one CU with `lds_bytes` of LDS each (0 = variant missing).
 hipError_t max_workgroups_per_cu(int head_dim, int group, int batch_tile, size_t lds_bytes, bool layer, int *out);
 // the same two for the layer kernel (defined by the -DCF_LAYER=1 translation unit; called by the two above)
