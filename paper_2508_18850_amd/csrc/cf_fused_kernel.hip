@@ -54,6 +54,10 @@ constexpr bool kLayer = CF_LAYER != 0;
 constexpr int NT = kThreads;
 constexpr int NW = kWaves;
 constexpr float kNegBig = -1.0e30f;   // stands for "no score yet"; finite so that differences never give NaN
+#ifndef CF_PREFETCH_NEXT_LAYER
+#define CF_PREFETCH_NEXT_LAYER 1
+#endif
+constexpr bool kPrefetchNextLayer = CF_PREFETCH_NEXT_LAYER != 0;   // stack kernel: next layer's first weights during the tail
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));   // eight fp16 values = one 128-bit load
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -300,12 +304,35 @@ __device__ __forceinline__ uint32_t stamp_of(unsigned long long cnt0, int layer)
     return (uint32_t)(cnt + (cnt >> 32));
 }
 
+// The two batches of weight rows that phase 1 keeps in flight, and the cursor of the next batch to load.  They live
+// outside p1_all so that, in a stack of layers, the first two batches of the NEXT layer can be requested while the
+// current layer still exchanges its last partial results (its memory pipe would idle otherwise).
+template <int HD, int BT>
+struct P1Cfg {
+    static constexpr bool MF = Mfma<HD, BT>::on;
+    static constexpr int U = MF ? 8 : (BT > 4 ? 2 : (BT == 4 ? 4 : 8));     // loads per thread and batch
+};
+// How many of the two batches a stack requests ahead for its next layer: what the registers of the variant allow
+// (none with the 16-row tile, one where the attention or a second query head per KV head takes the room).
+template <int HD, int G, int BT>
+struct P1Ahead {
+    static constexpr int n = !kPrefetchNextLayer || BT > 4 ? 0 : (G >= 2 && BT == 1 ? 1 : 2);
+};
+template <int HD, int BT>
+struct P1Regs {
+    h8 wa[P1Cfg<HD, BT>::U], wb[P1Cfg<HD, BT>::U];
+    int si = 0, i0 = 0;
+    uint32_t sbase = 0;
+};
+
 // `layer` > 0 (a stack of layers in one launch): the input rows are what the final reduction of the previous layer
 // left in the slots xin (stamped fp32 values that are exact fp16 numbers), and cnt0 is known already.
-template <int HD, int G, int BT, bool STACK, class NextFn>
+// PART 0: the whole phase (`primed`: its first two batches are in flight already, requested by PART 1 and 2);
+// PART 1 / 2: only request the first / second batch of this layer's weights into rg and return.
+template <int HD, int G, int BT, bool STACK, int PART, class NextFn>
 __device__ __forceinline__ uint32_t p1_all(const Params &p, const LayerPtrs &lp, int tid0, int team, int member, float *smem,
                                            float *rope, int layer, const uint64_t *xin, int n_layers,
-                                           unsigned long long &cnt0, NextFn &&issue_next)
+                                           unsigned long long &cnt0, P1Regs<HD, BT> &rg, bool primed, NextFn &&issue_next)
 {
     constexpr int LPR = HD / 8;
     constexpr int NG = NT / LPR;
@@ -313,8 +340,8 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, const LayerPtrs &lp,
     // loads per batch spills (measured on the 8B shape, batch 16: 202 us with 8, 181 with 4, 177 with 2, 182 with 1);
     // the 4-row tile is best with 4 (8B shape, batch 4: 55.1 us with 8, 53.6 with 4, 53.7 with 2)
     // With MFMA tiles (MF) a batch is eight rows per lane: one 32-row step of the contraction per wavefront.
-    constexpr bool MF = Mfma<HD, BT>::on;
-    constexpr int U = MF ? 8 : (BT > 4 ? 2 : (BT == 4 ? 4 : 8));
+    constexpr bool MF = P1Cfg<HD, BT>::MF;
+    constexpr int U = P1Cfg<HD, BT>::U;
     constexpr int MAXI = BT == 1 ? 4 : (BT <= 4 ? 2 : 1);   // selectors whose wave partials are buffered in LDS
     const int tid = tid0, wv = tid >> 6, lig = tid % LPR, grp = tid / LPR;
     const int kg = (tid & 63) >> 4;                         // MF: contraction group of the lane (rows 8 kg .. 8 kg + 7 of a step)
@@ -367,8 +394,10 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, const LayerPtrs &lp,
         }
     };
     const int nsel = nA + nB;
-    Cursor lc = {0, 0, nsteps > 0 ? blk_base(0) : 0u};      // next step to load
-    Cursor cc = lc;                                         // next step to consume
+    Cursor cc = {0, 0, nsteps > 0 ? blk_base(0) : 0u};      // next step to consume
+    Cursor lc = cc;                                         // next step to load
+    constexpr int AHEAD = STACK ? P1Ahead<HD, G, BT>::n : 0;
+    if (PART == 2 || (PART == 0 && primed && AHEAD > 0)) lc = Cursor{rg.si, rg.i0, rg.sbase};
     // Every call issues exactly U load instructions on one straight-line path, also for a step past
     // the end (all lanes switched off through their offset).  The compiler derives each wait from
     // the number of loads issued after the one it needs, taking the smallest over all paths of the
@@ -387,8 +416,20 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, const LayerPtrs &lp,
     // Kernel start: the first batch of weights goes out at once, then the small loads (this slice of
     // x, the RoPE frequencies), then the second batch.  Loads return in order: x arrives right behind
     // the first batch and is staged into LDS while the second one streams.
-    h8 wa[U], wb[U];
-    load(wa, voff0);
+    h8(&wa)[U] = rg.wa;
+    h8(&wb)[U] = rg.wb;
+    if (PART != 0) {
+        // (`primed` here means "there is a next layer"; without one the loads go out with every lane off: the
+        // registers are written either way, so that what they held does not stay alive through the caller's loop)
+        load(PART == 1 ? wa : wb, primed ? voff0 : kNoLoad);
+        rg.si = lc.si;
+        rg.i0 = lc.i0;
+        rg.sbase = lc.sbase;
+        return 0u;
+    }
+    // (a stack past its first layer has both batches in flight: the branch costs the other path, the first layer
+    // of a stack, some exactness of its waits, nothing else)
+    if (!(AHEAD >= 1 && primed)) load(wa, voff0);
     __builtin_amdgcn_sched_barrier(0);
     CF_STAMP(12);           // first weight batch issued
     constexpr int XR = BT + 1;                                    // x values per thread kept in registers
@@ -488,7 +529,7 @@ __device__ __forceinline__ uint32_t p1_all(const Params &p, const LayerPtrs &lp,
         epos[k] = psrc[own_pos && eb < p.B ? eb : 0];
     }
     __builtin_amdgcn_sched_barrier(0);
-    load(wb, voff0);
+    if (!(AHEAD >= 2 && primed)) load(wb, voff0);
     __builtin_amdgcn_sched_barrier(0);
     CF_STAMP(21);           // second weight batch issued
     if (BT > 4 && norm)     // large batches: four rows at a time, each group waits for its loads
@@ -1606,7 +1647,8 @@ __device__ __forceinline__ uint16_t residual_input(const Params &p, int tid0, in
 
 // xout != null (a layer of a stack that is not the last): the result, rounded to fp16 as `out` would hold it, goes to
 // the slots the next layer's projection reads its input from, not to `out`.
-__device__ __forceinline__ void final_reduce(const Params &p, int tid0, uint32_t stamp, float *smem, uint64_t *xout = nullptr)
+template <class HookFn>
+__device__ __forceinline__ void final_reduce(const Params &p, int tid0, uint32_t stamp, float *smem, uint64_t *xout, HookFn &&after_polls)
 {
     const int tid = tid0;
     const Xbuf x3(p.p3);
@@ -1633,6 +1675,7 @@ __device__ __forceinline__ void final_reduce(const Params &p, int tid0, uint32_t
         }
         CF_STAMP(19);           // head partials arrived
         lds_barrier();
+        if (v0 == 0) after_polls();
         if (tid < cb) {
             float sum = kLayer && (p.flags & kFlagResidual) ? h2f(xres) : 0.f;
             for (int k = 0; k < spt; ++k) sum += smem[k * cb + tid];
@@ -1683,6 +1726,8 @@ __device__ __forceinline__ void decode_steps(const Params &p0, const LayerPtrs *
 #endif
 
     unsigned long long cnt0 = 0;
+    P1Regs<HD, BT> rg;
+    bool primed = false;
     if (STACK) {
         // the RoPE table is the same for all layers (one position; a stack has no per-row positions): built here,
         // outside the loop, so that its fp64 constants do not become loop-invariant registers
@@ -1724,8 +1769,11 @@ __device__ __forceinline__ void decode_steps(const Params &p0, const LayerPtrs *
 
     // ---- phase 1 (projection); its last step already starts the K/V stream of phase 2
     EarlyQ eq;
-    const uint32_t stamp = p1_all<HD, G, BT, STACK>(p, lp, tl, team, member, smem, s_rope, STACK ? layer : 0, xslots, n_layers, cnt0,
-                                             [&](int stage) {
+    // (without batches requested ahead the registers of the two batches belong to this layer alone)
+    P1Regs<HD, BT> rg_layer;
+    P1Regs<HD, BT> &rgu = (STACK && P1Ahead<HD, G, BT>::n > 0) ? rg : rg_layer;
+    const uint32_t stamp = p1_all<HD, G, BT, STACK, 0>(p, lp, tl, team, member, smem, s_rope, STACK ? layer : 0, xslots, n_layers, cnt0,
+                                             rgu, primed, [&](int stage) {
                                                  if (own_pos) st2 = P2Stream<HD, G>(p, lp, tl, team, b_first, s_first, pos_first, member < n2);
                                                  st2.prefetch(kv, 0);
                                              });
@@ -1767,6 +1815,10 @@ __device__ __forceinline__ void decode_steps(const Params &p0, const LayerPtrs *
     }
     if (member >= n2) p3_prefetch(2);
     CF_STAMP(3);
+    const bool more = STACK && layer + 1 < n_layers;
+    auto no_next = [](int) {};
+    const LayerPtrs &lpn = STACK ? tab[more ? layer + 1 : layer] : lp;
+    constexpr int AHEAD = STACK ? P1Ahead<HD, G, BT>::n : 0;
     // ---- phase 3 (output projection, per-head partials)
     for (int it = member; it < n3; it += p.TS) {
         int hq, c3, rs;
@@ -1775,7 +1827,18 @@ __device__ __forceinline__ void decode_steps(const Params &p0, const LayerPtrs *
     }
     CF_STAMP(4);
     // ---- phase 4 (sum over heads)
-    final_reduce(p, tl, stamp, smem, STACK && layer + 1 < n_layers ? xslots : nullptr);
+    // In a stack the first two batches of the next layer's weights are requested here: one before the partial
+    // outputs of the heads are waited for, one once they have arrived (behind both, their polls would queue for
+    // the time the batches take to stream in).
+    // (measured on the 7B shape, us per layer: this placement 36.5; both batches before the wait 37.6; the first
+    // one already after the merge of the attention partials 37.7; none 37.6)
+    if (AHEAD >= 1)
+        p1_all<HD, G, BT, STACK, 1>(p, lpn, tl, team, member, smem, s_rope, 0, nullptr, n_layers, cnt0, rg, more, no_next);
+    final_reduce(p, tl, stamp, smem, more ? xslots : nullptr, [&]() {
+        if (AHEAD >= 2)
+            p1_all<HD, G, BT, STACK, 2>(p, lpn, tl, team, member, smem, s_rope, 0, nullptr, n_layers, cnt0, rg, more, no_next);
+    });
+    primed = more;
     CF_STAMP(5);
     }   // layers
     if (tid == 0) p0.done[(size_t)blockIdx.x * kCounterStride] = cnt0 + (unsigned long long)(n_layers - 1);   // steps completed
