@@ -9,7 +9,8 @@ many layers.  All inputs are synthetic, generated on the device before timing.
 
 Prints ONE JSON line on stdout (details go to stderr).  With --sweep it prints one such line for every row
 of the measurement table instead (the Llama-2-7B shape at six cache lengths, the Llama-3-8B shape at batch 1, 4
-and 16, the Llama-2-70B shape and its stack of 80 distinct layers).  After the timed region, outside the events,
+and 16, the Llama-2-70B shape and its stack of 80 distinct layers, and four rows in which one cf_decode_stack call
+runs all layers of a pass in a single launch).  After the timed region, outside the events,
 one more step on the first layer is checked against the C oracle at the tolerance of the parity tests.
 """
 from __future__ import annotations
@@ -86,10 +87,14 @@ def parse_args():
     return ap.parse_args()
 
 
-# rows of the measurement table: (workload, batch, cached tokens, layers to rotate over; 0 = enough for 3 GiB)
-SWEEP = [("llama2_7b", 1, 4096, 0), ("llama2_7b", 1, 1024, 0), ("llama2_7b", 1, 2048, 0), ("llama2_7b", 1, 8192, 0),
-         ("llama2_7b", 1, 16384, 0), ("llama2_7b", 1, 32768, 0), ("llama3_8b", 1, 8192, 0), ("llama3_8b", 4, 8192, 0),
-         ("llama3_8b", 16, 8192, 0), ("llama2_70b", 1, 32768, 0), ("llama2_70b", 1, 32768, 80)]
+# rows of the measurement table: (workload, batch, cached tokens, layers to rotate over; 0 = enough for 3 GiB,
+# one cf_decode_stack call per pass over the layers instead of one launch per layer)
+SWEEP = [("llama2_7b", 1, 4096, 0, False), ("llama2_7b", 1, 1024, 0, False), ("llama2_7b", 1, 2048, 0, False),
+         ("llama2_7b", 1, 8192, 0, False), ("llama2_7b", 1, 16384, 0, False), ("llama2_7b", 1, 32768, 0, False),
+         ("llama3_8b", 1, 8192, 0, False), ("llama3_8b", 4, 8192, 0, False), ("llama3_8b", 16, 8192, 0, False),
+         ("llama2_70b", 1, 32768, 0, False), ("llama2_70b", 1, 32768, 80, False),
+         ("llama2_7b", 1, 4096, 32, True), ("llama3_8b", 1, 8192, 32, True), ("llama3_8b", 16, 8192, 32, True),
+         ("llama2_70b", 1, 32768, 80, True)]
 
 
 def cpu_baseline(shape, batch, kv_len, budget_s):
@@ -146,9 +151,9 @@ def main():
         print(json.dumps(run_one(args)), flush=True)
         return
     import copy
-    for (name, batch, kv_len, layers) in SWEEP:
+    for (name, batch, kv_len, layers, stack) in SWEEP:
         a = copy.copy(args)
-        a.workload, a.batch, a.kv_len, a.layers, a.max_seq = name, batch, kv_len, layers, 0
+        a.workload, a.batch, a.kv_len, a.layers, a.max_seq, a.stack = name, batch, kv_len, layers, 0, stack
         a.cpu_seconds = min(args.cpu_seconds, 6.0)
         res = run_one(a)
         if layers:
@@ -361,7 +366,8 @@ def run_one(args):
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.layer or args.ragged) else MEASURED_TRAFFIC.get(name),
                      "algorithmic_bytes": alg_bytes,
-                     "kernel": "fused_decode_layer" if (args.layer or args.ragged) else "fused_decode_block"},
+                     "kernel": "fused_decode_layer" if (args.layer or args.ragged) else
+                               "fused_decode_stack" if (args.stack and d == 128) else "fused_decode_block"},
     }
     if args.reps > 1:
         import numpy as np

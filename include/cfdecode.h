@@ -342,8 +342,9 @@ int64_t cf_mla_algorithmic_bytes(const cf_mla_config *cfg, int32_t batch, int32_
  *   team_size) values, "lo" the member's dimensions below head_dim / 2 and "hi" their RoPE partners.  Asynchronous.
  * cf_splithead_decode: x [1, d_model], W_o, k_cache, v_cache [1, n_heads, max_seq, head_dim], pos and out [1,
  *   d_model] as for cf_decode_block (rows < pos read, row pos written).  Asynchronous on `stream`, no allocation.
- *   The stamp of a launch is counted on the host, so a captured launch must not be replayed.  The order of the
- *   atomic additions, and with it the last bits of the result, is not fixed.
+ *   The stamp of a launch is counted on the device (every workgroup counts the launches it has completed), so a
+ *   captured launch can be replayed.  The order of the atomic additions, and with it the last bits of the result, is
+ *   not fixed.
  * cf_splithead_status / cf_splithead_set_spin_limit: as cf_team_status / cf_team_set_spin_limit; in addition a limit
  *   of -1 makes every launch report CF_ETIMEOUT whatever the timing (only member 0 of every team runs and gives up at
  *   its first look for the posts of the others): for tests of the error path.  Every wait still ends.

@@ -34,6 +34,7 @@ using cf::team::Exchange;
 using cf::team::pair_t;
 constexpr int NT = 512;             // threads per workgroup
 constexpr int NW = NT / 64;
+constexpr int kDoneStride = 16;     // 64-bit words between the launch counts of two workgroups (one 128-byte line each)
 constexpr int kRedFloats = NT * 8;  // floats of the cross-thread sum of stage 1
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -57,11 +58,11 @@ struct SplitArgs {
     float *acc;                     // [D] fp32, zero between launches
     uint32_t *arrive;               // [N] arrivals per column slice, zero between launches
     uint32_t *err;
+    unsigned long long *done;       // [W][kDoneStride] launches completed, one line per workgroup
     size_t cap;                     // pairs per exchange area
     long long spin_ticks;
     double log2_base;
     float scale_log2e;
-    uint32_t stamp;
     int D, nh, HD, N, pos, max_seq;
     int only_member0;               // test of the error path: the other members of every team leave at once
 };
@@ -132,8 +133,18 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
     // Error-path test: with its peers gone (before they touch anything) member 0 finds none of their posts, and with a
     // wait limit of 0 it gives up at its first look: a timeout that does not depend on timing, and every wait still ends.
     if (a.only_member0 && b != 0) return;
+    // The launch stamp comes from device memory, not from the host: every workgroup keeps the number of launches it
+    // has completed in a line of its own (all hold the same number), so a launch recorded once in a graph stamps
+    // each of its replays afresh.  Written by the previous launch, hence a scalar load through the cache will do.
+    unsigned long long launches;
+    asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)"
+                 : "=s"(launches)
+                 : "s"(a.done + (size_t)w * kDoneStride)
+                 : "memory");
+    launches += 1ull;
     Exchange x;
-    x.slots = a.slots, x.cap = a.cap, x.stamp = a.stamp, x.err = a.err, x.spin_ticks = a.spin_ticks;
+    x.slots = a.slots, x.cap = a.cap, x.err = a.err, x.spin_ticks = a.spin_ticks;
+    x.stamp = (uint32_t)(launches + (launches >> 32));        // never 0, the value of a cleared slot
 
     // ---- 1: projection.  Thread (row group g = tid / P, piece c = tid % P) walks rows g, g + RPP, ...
     for (int v = tid; v < D / 8; v += NT) {
@@ -375,6 +386,7 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
             a.out[i] = f2h(__hip_atomic_exchange(a.acc + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         if (tid == 0) __hip_atomic_store(a.arrive + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    if (tid == 0) a.done[(size_t)w * kDoneStride] = launches;
     SH_STAMP(9);
 #if CF_STAMPS
     __syncthreads();
@@ -420,7 +432,7 @@ struct cf_splithead_s {
     uint64_t *slots = nullptr;
     float *acc = nullptr;
     uint32_t *arrive = nullptr, *err = nullptr;
-    uint32_t launches = 0;
+    unsigned long long *done = nullptr;
     long long spin_ticks = 200000000LL;
     int only_member0 = 0;
     int last_hip = 0;
@@ -462,8 +474,8 @@ int cf_splithead_create(const cf_config *cfg, int32_t team_size, cf_splithead *o
     t->cfg = c, t->N = N, t->W = W, t->pv = pv, t->lds_bytes = lds;
     t->cap = (size_t)c.max_seq + 1 > (size_t)c.d_model ? (size_t)c.max_seq + 1 : (size_t)c.d_model;
     const size_t nslots = (size_t)W * cf::team::kMaxRounds * t->cap;
-    const size_t head = 512 + (size_t)c.d_model * sizeof(float);
-    const size_t head_al = (head + 255) / 256 * 256;
+    const size_t acc_end = (512 + (size_t)c.d_model * sizeof(float) + 255) / 256 * 256;
+    const size_t head_al = acc_end + (size_t)W * kDoneStride * sizeof(unsigned long long);
     t->ws_bytes = head_al + nslots * sizeof(uint64_t);
     if (nslots * sizeof(uint64_t) > 0xfffffff0ull) {
         delete t;
@@ -480,6 +492,7 @@ int cf_splithead_create(const cf_config *cfg, int32_t team_size, cf_splithead *o
     t->err = reinterpret_cast<uint32_t *>(t->ws + 128);
     t->arrive = reinterpret_cast<uint32_t *>(t->ws + 256);
     t->acc = reinterpret_cast<float *>(t->ws + 512);
+    t->done = reinterpret_cast<unsigned long long *>(t->ws + acc_end);
     t->slots = reinterpret_cast<uint64_t *>(t->ws + head_al);
     *out = t;
     return CF_OK;
@@ -526,12 +539,10 @@ int cf_splithead_decode(cf_splithead t, const void *x, const void *W_qkv_members
     a.kc = static_cast<uint16_t *>(k_cache);
     a.vc = static_cast<uint16_t *>(v_cache);
     a.out = static_cast<uint16_t *>(out);
-    a.slots = t->slots, a.acc = t->acc, a.arrive = t->arrive, a.err = t->err, a.cap = t->cap;
+    a.slots = t->slots, a.acc = t->acc, a.arrive = t->arrive, a.err = t->err, a.done = t->done, a.cap = t->cap;
     a.spin_ticks = t->spin_ticks;
     a.log2_base = std::log2((double)c.rope_base);
     a.scale_log2e = 1.4426950408889634f / std::sqrt((float)c.head_dim);
-    if (++t->launches == 0) t->launches = 1;                           // a stamp is never 0
-    a.stamp = t->launches;
     a.D = c.d_model, a.nh = c.n_q_heads, a.HD = c.head_dim, a.N = t->N, a.pos = pos, a.max_seq = c.max_seq;
     a.only_member0 = t->only_member0;
     hipLaunchKernelGGL(pick(t->pv), dim3(t->W), dim3(NT), t->lds_bytes, static_cast<hipStream_t>(stream), a);

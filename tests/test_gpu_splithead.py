@@ -175,6 +175,51 @@ def test_same_result_as_the_split_token_kernel():
     assert np.abs(got - want).max() <= 2 * 2.0 ** -10 * np.abs(want).max()
 
 
+def test_captured_launch_replays():
+    """The launch stamp is counted on the device, so a launch recorded once in a HIP graph stays valid on every replay:
+    three replays, with eager launches and synchronisation between them, each compared with the oracle (the atomic
+    additions over the heads make the last bits vary, so not bit for bit) and each appended row with the eager one."""
+    from paper_2508_18850_amd import SplitHeadBlock
+    shape, team, pos = mha(1024, 16, 128), 4, 300
+    inp = cf_inputs.make_inputs(shape, seed=77, batch=1, kv_len=pos)
+    ref = oracle(inp, shape, pos)
+    dev = torch.device("cuda:0")
+    blk = SplitHeadBlock(shape.d_model, shape.n_q_heads, shape.head_dim, inp["max_seq"], shape.rope_base, team)
+    t = {k: torch.from_numpy(inp[k]).to(dev) for k in ("x", "w_qkv", "w_o", "k_cache", "v_cache")}
+    w_members = torch.empty_like(t["w_qkv"])
+    out = torch.full((1, shape.d_model), float("nan"), dtype=torch.float16, device=dev)
+    s = torch.cuda.Stream()
+
+    def launch(stream):
+        blk.decode(t["x"].data_ptr(), w_members.data_ptr(), t["w_o"].data_ptr(), t["k_cache"].data_ptr(),
+                   t["v_cache"].data_ptr(), pos, out.data_ptr(), stream)
+
+    with torch.cuda.stream(s):
+        blk.pack(t["w_qkv"].data_ptr(), w_members.data_ptr(), s.cuda_stream)
+        launch(s.cuda_stream)
+        blk.status(s.cuda_stream)
+    torch.cuda.synchronize()
+    k_eager = t["k_cache"][:, :, pos].clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        launch(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        t["k_cache"][:, :, pos].zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        blk.status(0)
+        res = {"out": out.cpu().numpy(), "k_cache": t["k_cache"].cpu().numpy(), "v_cache": t["v_cache"].cpu().numpy()}
+        check(res, ref, inp, pos, "replay %d" % rep)
+        assert torch.equal(t["k_cache"][:, :, pos], k_eager)
+        launch(torch.cuda.current_stream().cuda_stream)          # eager launches move the device-side count on as well
+        launch(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        blk.status(0)
+    blk.close()
+
+
 def test_unsupported_and_invalid_arguments():
     from paper_2508_18850_amd import SplitHeadBlock, CfError
     for args, code in (((512, 8, 64, 256, 10000.0, 8), -2),      # 64 / (2 * 8) = 4 dimensions per half: below one 16-byte piece
