@@ -25,6 +25,9 @@ def main():
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--kv-len", type=int, default=None)
     ap.add_argument("--layers", type=int, default=0)
+    ap.add_argument("--ranges", type=int, default=0,
+                    help="limit on the token ranges per batch row (cf_mla_set_splits); a non-zero value also selects the "
+                         "token-range kernel at batch 1 and 2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     import numpy as np
@@ -38,6 +41,8 @@ def main():
     dev = torch.device("cuda:0")
     D, nh, n, r, l, v = shape.d_model, shape.n_heads, shape.nope_dim, shape.rope_dim, shape.kv_lora_rank, shape.v_head_dim
     blk = MlaBlock(D, nh, n, r, l, v, B, S, shape.rope_base)
+    if args.ranges:
+        blk.set_splits(args.ranges)
     alg = blk.algorithmic_bytes(B, Lk)
     layer_bytes = 2 * (D * (nh * (n + r) + l + r) + nh * n * l + nh * l * v + nh * v * D + B * S * (l + r))
     n_layers = args.layers or max(8, -(-2 ** 30 // layer_bytes))            # >= 1 GiB of distinct buffers
@@ -81,7 +86,8 @@ def main():
            "warmup": args.warmup, "higher_is_better": False, "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
            "config": {"workload": "%s_b%d_kv%d" % (shape.name, B, Lk), "layers_rotated": n_layers},
            "roofline": {"bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
-                        "traffic": None, "algorithmic_bytes": alg, "kernel": "fused_mla_decode"}}
+                        "traffic": None, "algorithmic_bytes": alg,
+                        "kernel": "fused_mla_heads" if (B <= 2 and not args.ranges) else "fused_mla_decode"}}
     if not args.no_cpu_baseline:
         from oracle import mla_block as orc
         inp = cf_inputs.make_mla_inputs(shape, seed=1000, batch=B, kv_len=Lk, poison=False)

@@ -304,9 +304,20 @@ int cf_team_set_spin_limit(cf_team t, int32_t spin_limit_us);
  *   W_down [n_heads, kv_lora_rank, v_head_dim]; W_o [n_heads * v_head_dim, d_model];
  *   kv_cache [batch, max_seq, kv_lora_rank + rope_dim]: rows < pos read, row pos written; out [batch, d_model].
  * Storage fp16, accumulation fp32.  Asynchronous on `stream`; no allocation, no host synchronisation.
- * This first kernel is written for kv_lora_rank 512, rope_dim 64, n_heads <= 16 (16 workgroups per head, all
- * resident), batch <= 4, nope_dim a multiple of 8 up to 128, v_head_dim a multiple of 8 up to 128, d_model a
- * multiple of 32, at most 8192 and at most 128 * n_heads: cf_mla_create returns CF_EUNSUPPORTED otherwise.  cf_mla_status is cf_status for this handle.
+ * The kernel is written for kv_lora_rank 512, rope_dim 64, n_heads <= 16 (one MFMA tile of heads; 16 workgroups per
+ * head, all resident), batch <= 16 (the batch of Appendix C), nope_dim a multiple of 8 up to 128, v_head_dim a
+ * multiple of 8 up to 128, d_model a multiple of 32, at most 8192 and at most 128 * n_heads: cf_mla_create returns
+ * CF_EUNSUPPORTED otherwise.  cf_mla_status is cf_status for this handle.
+ * Two kernels: up to batch 2 every head scans the cached rows itself (16 workgroups per head, vector arithmetic);
+ *   from batch 3 on the unit of work of the attention stage is a range of cached rows of one batch row, for a group of
+ *   heads at once, as two products on MFMA tiles.
+ * cf_mla_set_splits: upper limit on the number of token ranges a batch row's cached rows are divided into; 0 = chosen
+ *   by the library, at most 32.  A non-zero limit also selects the token-range kernel at batch 1 and 2.  For tests of
+ *   the range logic and for measurements; CF_EINVAL outside 0..32.
+ * cf_mla_debug_export: intermediate results of the last call on this handle, copied to the host buffer as fp32 after
+ *   synchronising `stream`: what = 0: q_lat [batch, n_heads, kv_lora_rank] (Alg. 4's absorbed query); 1: q_rope
+ *   [batch, n_heads, rope_dim] (rotated); 2: z [batch, n_heads, kv_lora_rank] (the attention result in the latent
+ *   space, before W_Down).  `bytes` must equal the tensor size (CF_EINVAL otherwise, and before any call).
  */
 typedef struct cf_mla_config {
     int32_t d_model, n_heads, nope_dim, rope_dim, kv_lora_rank, v_head_dim;
@@ -321,6 +332,8 @@ int cf_mla_decode(cf_mla t, int32_t batch, const void *x, const void *W_q, const
                   const void *W_down, const void *W_o, void *kv_cache, int32_t pos, void *out, void *stream);
 int cf_mla_status(cf_mla t, void *stream);
 int cf_mla_set_spin_limit(cf_mla t, int32_t spin_limit_us);   /* as cf_team_set_spin_limit */
+int cf_mla_set_splits(cf_mla t, int32_t max_splits);
+int cf_mla_debug_export(cf_mla t, int32_t what, void *host_dst, size_t bytes, void *stream);
 /* Algorithmic HBM bytes of one call (all weights + cached rows + appended rows + x + out). */
 int64_t cf_mla_algorithmic_bytes(const cf_mla_config *cfg, int32_t batch, int32_t pos);
 

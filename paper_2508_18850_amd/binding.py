@@ -21,7 +21,7 @@ EXPORTED_SYMBOLS = ("cf_create", "cf_destroy", "cf_decode_block", "cf_decode_blo
                     "cf_team_create", "cf_team_destroy", "cf_team_reduce", "cf_team_gather", "cf_team_status",
                     "cf_team_set_spin_limit",
                     "cf_mla_create", "cf_mla_destroy", "cf_mla_decode", "cf_mla_status", "cf_mla_set_spin_limit",
-                    "cf_mla_algorithmic_bytes",
+                    "cf_mla_algorithmic_bytes", "cf_mla_set_splits", "cf_mla_debug_export",
                     "cf_splithead_create", "cf_splithead_destroy", "cf_splithead_pack", "cf_splithead_decode",
                     "cf_splithead_status", "cf_splithead_set_spin_limit",
                     "cf_ffn_create", "cf_ffn_destroy", "cf_ffn_decode", "cf_ffn_status", "cf_ffn_set_spin_limit",
@@ -99,6 +99,8 @@ def load_library():
         lib.cf_mla_decode.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
         lib.cf_mla_status.argtypes = [vp, vp]
         lib.cf_mla_set_spin_limit.argtypes = [vp, i32]
+        lib.cf_mla_set_splits.argtypes = [vp, i32]
+        lib.cf_mla_debug_export.argtypes = [vp, i32, vp, ctypes.c_size_t, vp]
         lib.cf_mla_algorithmic_bytes.argtypes = [ctypes.POINTER(MlaConfig), i32, i32]
         lib.cf_mla_algorithmic_bytes.restype = ctypes.c_int64
         lib.cf_splithead_create.argtypes = [ctypes.POINTER(CfConfig), i32, ctypes.POINTER(vp)]
@@ -113,7 +115,7 @@ def load_library():
         for name in ("cf_team_create", "cf_team_destroy", "cf_team_reduce", "cf_team_gather", "cf_team_status",
                      "cf_team_set_spin_limit",
                     "cf_mla_create", "cf_mla_destroy", "cf_mla_decode", "cf_mla_status", "cf_mla_set_spin_limit",
-                    "cf_mla_algorithmic_bytes"):
+                    "cf_mla_set_splits", "cf_mla_debug_export"):
             getattr(lib, name).restype = ctypes.c_int
         lib.cf_ffn_create.argtypes = [ctypes.POINTER(FfnConfig), ctypes.POINTER(vp)]
         lib.cf_ffn_destroy.argtypes = [vp]
@@ -332,6 +334,14 @@ class MlaBlock:
 
     def set_spin_limit(self, us):
         self._check(self._lib.cf_mla_set_spin_limit(self._h, us))
+
+    def set_splits(self, max_splits):
+        self._check(self._lib.cf_mla_set_splits(self._h, max_splits))
+
+    def debug_export(self, what, host_array, stream=0):
+        """what 0: q_lat, 1: q_rope, 2: z of the last call, into a C-contiguous float32 numpy array of that shape."""
+        assert host_array.dtype.name == "float32" and host_array.flags["C_CONTIGUOUS"]
+        self._check(self._lib.cf_mla_debug_export(self._h, what, host_array.ctypes.data, host_array.nbytes, stream))
 
     def close(self):
         if self._h:

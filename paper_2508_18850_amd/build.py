@@ -14,7 +14,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcfdecode.so")
 TRACE_LIB = os.path.join(PKG, "libcfdecode_trace.so")
-SOURCES = ["cf_api.hip", "cf_fused_kernel.hip", "cf_team.hip", "cf_mla.hip", "cf_splithead.hip", "cf_ffn.hip"]
+SOURCES = ["cf_api.hip", "cf_fused_kernel.hip", "cf_team.hip", "cf_mla.hip", "cf_mla_heads.hip", "cf_splithead.hip", "cf_ffn.hip"]
 # -ffp-contract=on: multiply-adds are fused where one source expression holds both, never across statements at the
 # optimiser's choice, so every instantiation of a template rounds alike (the multi-layer kernel and the single-block
 # kernel then give the same bits); measured cost against the default "fast": none to 0.2 us per step.

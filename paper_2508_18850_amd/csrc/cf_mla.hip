@@ -2,22 +2,24 @@
 // kernel for gfx950, behind the C ABI (cf_mla_* in include/cfdecode.h).
 //
 // Alg. 4 runs one cluster per head and moves data between its blocks with three ClusterGathers and three
-// ClusterReduces.  Here a head is a team of 16 co-resident workgroups and every hand-over is one hop through
-// stamped {value, stamp} slots in global memory (cf_team_device.h), five hops in all; every weight matrix is read
-// in contiguous rows:
+// ClusterReduces.  Here 16 co-resident workgroups per head share the weights of that head, every hand-over is one
+// hop through stamped {value, stamp} slots in global memory (cf_team_device.h), five hops in all, and every weight
+// matrix is read in contiguous rows:
 //
 //   A  projections        [q | kv_new] = x [W_Q | W_KV]           16 row slices x 16 column blocks, partial sums
-//   B  up-projection      q_lat_i = q_nope_i W_Up[i]              member j: 1/16 of the kv_lora_rank columns
-//   C  attention          partial softmax over 1/16 of the tokens  (m, l, acc[kv_lora_rank]) per member;
-//                         the last member appends the new row and counts the new token
-//   D  merge + down-proj. member j merges 1/16 of the latent dimensions of the 16 partials and multiplies them
-//                         by the same rows of W_Down[i]: a partial of a_i per member (summed by the reader)
+//   B  up-projection      q_lat_i = q_nope_i W_Up[i]              member j: 1/16 of the kv_lora_rank columns; the same
+//                         workgroups finish q_rope_i and the new cache row (sum of the partials, RoPE, append)
+//   C  attention          unit of work = (batch row, token range), NOT the head: all heads share every cached row
+//                         (one latent "head": MQA), so the scores and the weighted sums of the 16 heads against a tile
+//                         of 128 rows are two dense products on MFMA tiles; a row is read from HBM once for all heads
+//   D  merge + down-proj. (head i, member j): merges 1/16 of the latent dimensions of the range partials (Alg. 4's
+//                         online-softmax reduction) and multiplies them by the same rows of W_Down[i]
 //   E1 output projection  rows of W_O of head i, 1/16 of the output columns per member: a partial of out per head
 //   E2 sum over heads     every workgroup: 1/W of the output columns (the paper's atomicAdd)
 //
-// Each stage requests its weights before it waits for its input.  All waits are bounded (CF_ETIMEOUT), all
-// workgroups have to be resident at once.
-#include "../../include/cfdecode.h"
+// Each stage requests its weights (or cached rows) before it waits for its input.  All waits are bounded
+// (CF_ETIMEOUT), all workgroups have to be resident at once.
+#include "cf_mla_internal.h"
 #include "cf_rope_device.h"
 #include "cf_team_device.h"
 
@@ -25,6 +27,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <vector>
 
 namespace {
 
@@ -34,27 +37,39 @@ constexpr int NT = 512;             // threads per workgroup
 constexpr int NW = NT / 64;
 constexpr int TS = 16;              // workgroups per head (team)
 constexpr int KS = 16;              // row slices of the projections
-constexpr int L = 512;              // kv_lora_rank the lane mapping is written for: 16 lanes x 32 values per cached row
-constexpr int R = 64;               // rope_dim: 16 lanes x 4 values
-constexpr int MAXB = 4;             // largest batch
+constexpr int L = 512;              // kv_lora_rank the lane mapping is written for
+constexpr int R = 64;               // rope_dim
+constexpr int LR = L + R;
+constexpr int HT = 16;              // heads of one MFMA tile: the most the kernel takes
+constexpr int MAXBATCH = 16;
 constexpr int MAXCOLS = 256;        // projection columns per column block
-constexpr int MAXA = 2048;          // floats of the largest stage buffer per batch row
 constexpr int kCounterStride = 16;
-constexpr int NPART = NW * 4;       // attention partials of a workgroup: four row groups per wavefront
-constexpr size_t kDynLds = (size_t)NPART * (L + 2) * sizeof(float);
+constexpr int kTile = 128;          // cached rows per attention tile of a workgroup
+constexpr int kSteps = LR / 32;     // MFMA steps of a score product (contraction over 576 dimensions)
+constexpr int kQops = kSteps * 64;  // 16-byte query operands (one per step and lane)
+constexpr int PS = kTile + 8;       // row stride (fp16 values) of the probabilities in LDS
+constexpr int QS = LR + 8;          // row stride (floats) of the fp32 query in LDS
+constexpr int kPart = 2 + L;        // slots of an attention partial per head: m, l, acc[L]
+constexpr int kMaxSplits = 32;      // token ranges per batch row at most
+constexpr size_t kLdsFloats = 24576;    // 96 KiB: the largest stage (A at batch 16)
 constexpr float kNegBig = -1.0e30f;
+constexpr int kHeadsBatch = 2;      // up to this batch cf_mla_decode runs the head-team kernel (measured cross-over)
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct MlaArgs {
     const uint16_t *x, *wq, *wkv, *wup, *wdown, *wo;
     uint16_t *cache, *out;
+    float *zdbg;                    // [B][nh][L]: the normalised latent vectors z of the call (for cf_mla_debug_export)
     uint64_t *slots;
     unsigned long long *counters;
     uint32_t *err;
-    size_t x1, x2, x3, x5, x6;      // first slot of each exchange area
+    size_t x1, xq, xkv, x3, xs, x5, x6;     // first slot of each exchange area
     int D, nh, n, v, B, pos, max_seq, W;
+    int NS, tps, HG;                // token ranges per batch row, cached rows per range, heads per attention item
     int cq, ckv;                    // 16-byte pieces (8 columns) of W_Q / W_KV per column block
     float scale_log2e;              // log2(e) / sqrt(nope_dim + rope_dim)
     double log2_base;
@@ -64,65 +79,126 @@ struct MlaArgs {
 __device__ __forceinline__ float h2f(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
 __device__ __forceinline__ uint16_t f2h(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v)
+// v_mfma_f32_16x16x32_f16.  Lane l holds, of A, row l % 16 and eight values of the contraction index for group
+// l / 16; of B, column l % 16 and the same eight contraction values; of the result, column l % 16 and rows
+// 4 * (l / 16) + 0..3.
+__device__ __forceinline__ f32x4 mfma16(const h8 &a, const h8 &b, const f32x4 &c)
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 
-// Sum over the wavefront, the same value in every lane: four data-parallel-primitive steps inside each row of
-// 16 lanes, then the four row totals are read out as scalars (no trip through the LDS crossbar).
-__device__ __forceinline__ float wave_sum(float v)
+// w[u] = row u, eight adjacent columns  ->  f[c] = column c, rows 0..7 (8 x 8 transpose of 16-bit values in a lane)
+__device__ __forceinline__ void transpose8(const h8 *w, h8 (&f)[8])
 {
-    v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
-    v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
-    v += dpp_move<0x141>(v);   // row_half_mirror
-    v += dpp_move<0x140>(v);   // row_mirror
-    const int i = __builtin_bit_cast(int, v);
-    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 0));
-    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 16));
-    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 32));
-    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(i, 48));
-    return (r0 + r1) + (r2 + r3);
+#pragma unroll
+    for (int c2 = 0; c2 < 4; ++c2) {
+        u32x4 e, o;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t lo = __builtin_bit_cast(u32x4, w[2 * d])[c2], hi = __builtin_bit_cast(u32x4, w[2 * d + 1])[c2];
+            e[d] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);    // {lo.low half, hi.low half}
+            o[d] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);    // {lo.high half, hi.high half}
+        }
+        f[2 * c2] = __builtin_bit_cast(h8, e);
+        f[2 * c2 + 1] = __builtin_bit_cast(h8, o);
+    }
 }
 
-// Sum of the n stamped values at idx, idx + stride, ... (in that order); polls go out sixteen at a time (the
-// teams and the row slices have 16 members: one round trip).
-__device__ __forceinline__ float take_sum(const Exchange &x, __amdgpu_buffer_rsrc_t r, size_t idx, size_t stride, int n)
+// Sums of NV sets of n <= 16 stamped values each: set v is idx[v], idx[v] + stride, ... (added in that order).
+// All NV * 16 polls are in flight together: one round trip when the values are there.
+template <int NV>
+__device__ __forceinline__ void take_sums(const Exchange &x, __amdgpu_buffer_rsrc_t r, const size_t (&idx)[NV], size_t stride,
+                                          int n, float (&out)[NV])
 {
     constexpr int NP = 16;
-    float s = 0.f;
-    for (int k0 = 0; k0 < n; k0 += NP) {
-        pair_t q[NP];
-        long long t0 = 0;
-        for (;;) {
-#pragma unroll
-            for (int k = 0; k < NP; ++k) q[k] = cf::team::peek(r, idx + (size_t)min(k0 + k, n - 1) * stride);
-            __builtin_amdgcn_sched_barrier(0);
-            bool ok = true;
-#pragma unroll
-            for (int k = 0; k < NP; ++k) ok &= q[k].y == x.stamp;
-            if (ok || cf::team::gave_up(x, t0)) break;
-        }
-#pragma unroll
-        for (int k = 0; k < NP; ++k)
-            if (k0 + k < n) s += __builtin_bit_cast(float, q[k].x);
-    }
-    return s;
-}
-
-// The stamped value at idx (one poll per try).
-__device__ __forceinline__ float take1(const Exchange &x, __amdgpu_buffer_rsrc_t r, size_t idx)
-{
+    pair_t q[NV][NP];
     long long t0 = 0;
     for (;;) {
-        const pair_t q = cf::team::peek(r, idx);
-        if (q.y == x.stamp) return __builtin_bit_cast(float, q.x);
-        if (cf::team::gave_up(x, t0)) return 0.f;
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+            for (int k = 0; k < NP; ++k) q[v][k] = cf::team::peek(r, idx[v] + (size_t)min(k, n - 1) * stride);
+        __builtin_amdgcn_sched_barrier(0);
+        bool ok = true;
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+            for (int k = 0; k < NP; ++k) ok &= q[v][k].y == x.stamp;
+        if (ok || cf::team::gave_up(x, t0)) break;
+    }
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < NP; ++k)
+            if (k < n) s += __builtin_bit_cast(float, q[v][k].x);
+        out[v] = s;
     }
 }
 
-__device__ __forceinline__ void lds_sync() { __syncthreads(); }
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() would also wait for every outstanding global
+// access of the wavefront (vmcnt(0)): for the write-through stores of the last hand-over to reach memory and for the
+// loads a stage keeps in flight across it.  Nothing here passes data between the threads of a workgroup through
+// global memory.
+__device__ __forceinline__ void lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Product of the B rows of `in` (LDS, row b at in + b * ld_in, nrows values each) with a [nrows x PCS * 8] block of
+// fp16 weights that the threads hold in registers: thread (piece pc = tid % PCS, batch quad bq, row group rg) has
+// rows rg, rg + RG, ... of piece pc in wr[].  The partial sums of the row groups are added inside the wavefront by
+// shuffles and across wavefronts through s_red ([NW][BT][PCS * 8] floats); sink(b, column, sum) gets the result.
+// All threads of the workgroup call; contains barriers.
+template <int BT, int PCS, int RPT, class Sink>
+__device__ __forceinline__ void small_product(const h8 (&wr)[RPT], const float *in, int ld_in, int nrows, int B, float *s_red,
+                                              Sink &&sink)
+{
+    constexpr int BQ = BT / 4, G = PCS * BQ, RG = NT / G;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int pc = tid % PCS, bq = (tid / PCS) % BQ, rg = tid / G;
+    float acc[4][8];
+#pragma unroll
+    for (int bb = 0; bb < 4; ++bb)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[bb][c] = 0.f;
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+        const int row = min(rg + RG * k, nrows - 1);                 // rows past the block carry zero weights
+#pragma unroll
+        for (int bb = 0; bb < 4; ++bb) {
+            const float xin = in[min(4 * bq + bb, B - 1) * ld_in + row];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[bb][c] = fmaf(xin, (float)wr[k][c], acc[bb][c]);
+        }
+    }
+#pragma unroll
+    for (int bb = 0; bb < 4; ++bb)
+        if (BT > 4 || bb < B) {                                       // (BT == 4: the same for all threads)
+#pragma unroll
+            for (int off = G; off < 64; off <<= 1)
+#pragma unroll
+                for (int c = 0; c < 8; ++c) acc[bb][c] += __shfl_xor(acc[bb][c], off);
+            if (lane < G) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) s_red[(wv * BT + 4 * bq + bb) * (PCS * 8) + pc * 8 + c] = acc[bb][c];
+            }
+        }
+    lds_sync();
+    for (int i = tid; i < B * PCS * 8; i += NT) {
+        const int b = i / (PCS * 8), cc = i % (PCS * 8);
+        float sum = 0.f;
+#pragma unroll
+        for (int w8 = 0; w8 < NW; ++w8) sum += s_red[(w8 * BT + b) * (PCS * 8) + cc];
+        sink(b, cc, sum);
+    }
+}
+
+// Dimension of a cached row that contraction slot (step m, lane group g, element 0) of a score product stands for:
+// a lane reads 32 contiguous bytes of the row in two steps, the four groups of a token one 128-byte line.
+__device__ __forceinline__ int score_dim(int m, int g) { return 64 * (m >> 1) + 16 * g + 8 * (m & 1); }
 
 // Stage time stamps of every workgroup, only in builds with -DCF_STAMPS=1 (the profiling library).
 #ifndef CF_STAMPS
@@ -136,16 +212,16 @@ __device__ unsigned long long g_mla_ts[256 * kMlaStamps];
 #define MLA_STAMP(k)
 #endif
 
+// BT: batch rows the register tiles are written for (4 or 16)
+template <int BT>
 __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
 {
-    __shared__ float s_a[MAXB * MAXA];                  // stage buffers, reused from stage to stage
-    __shared__ float s_b[MAXB * (L + R)];
-    __shared__ float s_red[NW * (L + 2)];
-    extern __shared__ float s_part[];                   // [NPART][L + 2] attention partials of the row groups (dynamic)
-    __shared__ float s_small[R + MAXB];                 // cos, sin of the rotary angles; score of the new token per row
+    constexpr int BQ = BT / 4;
+    extern __shared__ float smem[];                     // carved anew by every stage
+    __shared__ float s_rope[R];                         // cos, sin of the rotary angles
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, w = blockIdx.x;
     const int head = w / TS, j = w % TS;
-    const int B = a.B, nr = a.n + R, CQq = a.nh * nr, CQ = CQq + L + R;
+    const int B = a.B, nr = a.n + R, CQq = a.nh * nr, CQ = CQq + LR;
 #if CF_STAMPS
     __shared__ unsigned long long s_ts[kMlaStamps];
     if (tid < kMlaStamps) s_ts[tid] = 0;
@@ -160,439 +236,505 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     const unsigned long long cnt = launches + 1ull;
     const Exchange x = {a.slots, 0, (uint32_t)(cnt + (cnt >> 32)), a.err, a.spin_ticks};
     const __amdgpu_buffer_rsrc_t r = cf::team::slots_rsrc(x);
+    if (tid < R / 2) {
+        const double inv_freq = exp2(-2.0 * (double)tid / (double)R * a.log2_base);
+        cf::rope_cos_sin(a.pos, inv_freq, s_rope[tid], s_rope[R / 2 + tid]);
+    }
+
+    constexpr int LJ = L / TS;                                         // latent dimensions per member: 32
+    constexpr int RPT_B = (128 * 4 * BQ + NT - 1) / NT;                // rows per thread: W_Up (nope_dim <= 128),
+    constexpr int RPT_D = (LJ * 16 * BQ + NT - 1) / NT;                //   W_Down slice (LJ rows),
+    constexpr int RPT_E = (128 * 16 * BQ + NT - 1) / NT;               //   W_O (v_head_dim <= 128 rows)
+    constexpr int G4 = 4 * BQ, RG4 = NT / G4, G16 = 16 * BQ, RG16 = NT / G16;
 
     // ---- A: partial projections.  Work item (kb, cb): rows [kb*RK, +RK) of x, column block cb of W_Q and of W_KV.
     //      A thread owns one 16-byte piece (8 columns) of the block and every 16th row of the slice: lanes run
     //      along the columns, so a row of the block is one contiguous read; the two row groups of a wavefront
-    //      are added by a shuffle, the eight wavefronts through LDS.
-    const int RK = a.D / KS;
-    const int qv = CQq / 8, kvv = (L + R) / 8;                        // 16-byte pieces of a row of W_Q / W_KV
-    for (int item = w; item < KS * 16; item += a.W) {
-        const int kb = item / 16, cb = item % 16;
-        const int pv = tid % 32, g = tid / 32;                        // piece of the block, row group 0..15
-        const bool isq = pv < a.cq;
-        const int piece = isq ? cb * a.cq + pv : cb * a.ckv + (pv - a.cq);
-        const bool live = pv < a.cq + a.ckv && piece < (isq ? qv : kvv);
-        const h8 *wp = reinterpret_cast<const h8 *>(isq ? a.wq : a.wkv) + piece;
-        const size_t ld = isq ? qv : kvv;                             // row stride in pieces
-        float acc[MAXB][8];
+    //      are added by a shuffle, the eight wavefronts through LDS (eight batch rows at a time).
+    {
+        constexpr int RB = BT < 8 ? BT : 8;
+        float *s_x = smem;                                             // [BT][RK], RK <= 512
+        float *s_red = smem + BT * 512;                                // [NW][RB][MAXCOLS]
+        const int RK = a.D / KS;
+        const int qv = CQq / 8, kvv = LR / 8;                          // 16-byte pieces of a row of W_Q / W_KV
+        for (int item = w; item < KS * 16; item += a.W) {
+            const int kb = item / 16, cb = item % 16;
+            const int pv = tid % 32, g = tid / 32;                     // piece of the block, row group 0..15
+            const bool isq = pv < a.cq;
+            const int piece = isq ? cb * a.cq + pv : cb * a.ckv + (pv - a.cq);
+            const bool live = pv < a.cq + a.ckv && piece < (isq ? qv : kvv);
+            const h8 *wp = reinterpret_cast<const h8 *>(isq ? a.wq : a.wkv) + piece;
+            const size_t ld = isq ? qv : kvv;                          // row stride in pieces
+            h8 wr[8];                                                   // eight rows of this thread in flight
+            auto request = [&](int r0) {
 #pragma unroll
-        for (int b = 0; b < MAXB; ++b)
-#pragma unroll
-            for (int c = 0; c < 8; ++c) acc[b][c] = 0.f;
-        h8 wr[8];                                                      // eight rows of this thread in flight
-        auto request = [&](int r0) {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int rr = r0 + 16 * k;
-                wr[k] = (live && rr < RK) ? wp[(size_t)(kb * RK + rr) * ld] : h8{0, 0, 0, 0, 0, 0, 0, 0};
-            }
-        };
-        request(g);                                                    // the first weights go out before the slice of x
-        lds_sync();                                                    // (all threads, whatever their row group)
-        for (int i = tid; i < B * RK; i += NT) s_b[i] = h2f(a.x[(size_t)(i / RK) * a.D + kb * RK + i % RK]);
-        lds_sync();
-        for (int r0 = g; r0 < RK; r0 += 16 * 8) {
-            if (r0 != g) request(r0);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int rr = min(r0 + 16 * k, RK - 1);
-#pragma unroll
-                for (int b = 0; b < MAXB; ++b) {
-                    const float xv = b < B ? s_b[b * RK + rr] : 0.f;
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) acc[b][c] = fmaf(xv, (float)wr[k][c], acc[b][c]);
+                for (int k = 0; k < 8; ++k) {
+                    const int rr = r0 + 16 * k;
+                    wr[k] = (live && rr < RK) ? wp[(size_t)(kb * RK + rr) * ld] : h8{0, 0, 0, 0, 0, 0, 0, 0};
                 }
-            }
-        }
-        // (all shuffles of a row first, then the stores: a store between two shuffles makes each one wait for the last)
+            };
+            request(g);                                                 // the first weights go out before the slice of x
+            lds_sync();                                                 // (all threads, whatever their row group)
+            for (int i = tid; i < B * RK; i += NT) s_x[i] = h2f(a.x[(size_t)(i / RK) * a.D + kb * RK + i % RK]);
+            lds_sync();
+            // RB batch rows per pass (the accumulators of 16 rows do not fit beside the weights); a slice of up to
+            // 128 rows is one batch of loads and stays in registers over the passes
+            for (int b0 = 0; b0 < B; b0 += RB) {
+                float acc[RB][8];
 #pragma unroll
-        for (int b = 0; b < MAXB; ++b)
-            if (b < B) {
+                for (int bb = 0; bb < RB; ++bb)
 #pragma unroll
-                for (int c = 0; c < 8; ++c) acc[b][c] += __shfl_xor(acc[b][c], 32);
-                if (lane < 32) {
+                    for (int c = 0; c < 8; ++c) acc[bb][c] = 0.f;
+                for (int r0 = g; r0 < RK; r0 += 16 * 8) {
+                    if (r0 != g || (b0 > 0 && RK > 16 * 8)) request(r0);
 #pragma unroll
-                    for (int c = 0; c < 8; ++c) s_a[(wv * MAXB + b) * MAXCOLS + pv * 8 + c] = acc[b][c];
+                    for (int k = 0; k < 8; ++k) {
+                        const int rr = min(r0 + 16 * k, RK - 1);
+                        float wf[8];
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) wf[c] = (float)wr[k][c];
+#pragma unroll
+                        for (int bb = 0; bb < RB; ++bb) {
+                            const float xv = s_x[min(b0 + bb, B - 1) * RK + rr];
+#pragma unroll
+                            for (int c = 0; c < 8; ++c) acc[bb][c] = fmaf(xv, wf[c], acc[bb][c]);
+                        }
+                    }
                 }
-            }
-        lds_sync();
-        for (int i = tid; i < B * MAXCOLS; i += NT) {
-            const int b = i / MAXCOLS, cc = i % MAXCOLS, p2 = cc / 8;
-            const bool q2 = p2 < a.cq;
-            const int piece2 = q2 ? cb * a.cq + p2 : cb * a.ckv + (p2 - a.cq);
-            if (p2 < a.cq + a.ckv && piece2 < (q2 ? qv : kvv)) {
-                float sum = 0.f;
+                // (all shuffles of a row first, then the stores: a store between two shuffles makes each one wait)
 #pragma unroll
-                for (int w8 = 0; w8 < NW; ++w8) sum += s_a[(w8 * MAXB + b) * MAXCOLS + cc];
-                const int gcol = (q2 ? 0 : CQq) + piece2 * 8 + cc % 8;
-                cf::team::put(r, a.x1 + ((size_t)kb * B + b) * CQ + gcol, sum, x.stamp);
+                for (int bb = 0; bb < RB; ++bb)
+                    if (b0 + bb < B) {
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) acc[bb][c] += __shfl_xor(acc[bb][c], 32);
+                        if (lane < 32) {
+#pragma unroll
+                            for (int c = 0; c < 8; ++c) s_red[(wv * RB + bb) * MAXCOLS + pv * 8 + c] = acc[bb][c];
+                        }
+                    }
+                lds_sync();
+                for (int i = tid; i < RB * MAXCOLS; i += NT) {
+                    const int bb = i / MAXCOLS, b = b0 + bb, cc = i % MAXCOLS, p2 = cc / 8;
+                    const bool q2 = p2 < a.cq;
+                    const int piece2 = q2 ? cb * a.cq + p2 : cb * a.ckv + (p2 - a.cq);
+                    if (b < B && p2 < a.cq + a.ckv && piece2 < (q2 ? qv : kvv)) {
+                        float sum = 0.f;
+#pragma unroll
+                        for (int w8 = 0; w8 < NW; ++w8) sum += s_red[(w8 * RB + bb) * MAXCOLS + cc];
+                        const int gcol = (q2 ? 0 : CQq) + piece2 * 8 + cc % 8;
+                        cf::team::put(r, a.x1 + ((size_t)kb * B + b) * CQ + gcol, sum, x.stamp);
+                    }
+                }
+                lds_sync();
             }
         }
     }
 
     MLA_STAMP(1);           // A done
-    // ---- B: up-projection of head `head`, columns [LJ*j, +LJ) of the latent dimension
-    constexpr int LJ = L / TS;                                        // 32
-    // (the weights of a stage do not depend on what the stage waits for: they are requested first)
-    const int pcB = tid % 4, rowB = tid / 4;                          // nope_dim <= 128: one (row, piece) per thread
-    const h8 wupr = rowB < a.n ? *reinterpret_cast<const h8 *>(a.wup + ((size_t)head * a.n + rowB) * L + LJ * j + pcB * 8)
-                               : h8{0, 0, 0, 0, 0, 0, 0, 0};
-    lds_sync();
-    for (int i = tid; i < B * a.n; i += NT) {
-        const int b = i / a.n, c = i % a.n;
-        s_a[i] = take_sum(x, r, a.x1 + (size_t)b * CQ + head * nr + c, (size_t)B * CQ, KS);
-    }
-    lds_sync();
-    MLA_STAMP(2);           // q_nope arrived
+    // ---- B: member j of head `head`: columns [LJ*j, +LJ) of the up-projection; RoPE pairs 2j, 2j + 1 of the head's
+    //      rotary query; and, spread over all workgroups, the new cache row (latent dimensions w, w + W, ..., rotary
+    //      pairs w, w + W, ...): sums of the KS partials, RoPE, the append (Sec. 2.1) and a copy in fp32 for stage C.
     {
-        // W_Up[head] rows x this member's 32 columns: four 16-byte pieces per row; lanes with the same piece are
-        // added by shuffles, the wavefronts through LDS
+        constexpr int NVB = BT == 4 ? 2 : 5;
+        // (the weights do not depend on what the stage waits for: they are requested first)
+        h8 wupr[RPT_B];
+        {
+            const int pc = tid % 4, rg = tid / G4;
 #pragma unroll
-        for (int b = 0; b < MAXB; ++b)
-            if (b < B) {
-                const float qv2 = rowB < a.n ? s_a[b * a.n + rowB] : 0.f;
-                float t[8];
-#pragma unroll
-                for (int c = 0; c < 8; ++c) t[c] = qv2 * (float)wupr[c];
-#pragma unroll
-                for (int off = 4; off < 64; off <<= 1)
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) t[c] += __shfl_xor(t[c], off);
-                if (lane < 4) {
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) s_b[(wv * MAXB + b) * LJ + pcB * 8 + c] = t[c];
-                }
+            for (int k = 0; k < RPT_B; ++k) {
+                const int row = rg + RG4 * k;
+                wupr[k] = row < a.n ? *reinterpret_cast<const h8 *>(a.wup + ((size_t)head * a.n + row) * L + LJ * j + pc * 8)
+                                    : h8{0, 0, 0, 0, 0, 0, 0, 0};
             }
-        lds_sync();
-        if (tid < LJ * B) {
-            const int b = tid / LJ, cc = tid % LJ;
-            float sum = 0.f;
-            for (int w8 = 0; w8 < NW; ++w8) sum += s_b[(w8 * MAXB + b) * LJ + cc];
-            cf::team::put(r, a.x2 + ((size_t)b * a.nh + head) * L + LJ * j + cc, sum, x.stamp);
         }
+        float *s_job = smem;                                           // sums of the jobs below
+        const int nlat = w < L ? (L - w + a.W - 1) / a.W : 0, npair = w < R / 2 ? (R / 2 - w + a.W - 1) / a.W : 0;
+        const int J0 = B * a.n, J1 = J0 + 4 * B, J2 = J1 + B * nlat, J3 = J2 + 2 * B * npair;
+        float *s_red = smem + (J3 + 3) / 4 * 4;                        // [NW][BT][LJ]
+        auto job_slot = [&](int i) -> size_t {                          // the first of the KS partials of job i
+            if (i < J0) return a.x1 + (size_t)(i / a.n) * CQ + head * nr + i % a.n;
+            i -= J0;
+            if (i < 4 * B) {
+                const int k = i % 4;                                    // lo of pair 2j, 2j + 1, then their partners
+                return a.x1 + (size_t)(i / 4) * CQ + head * nr + a.n + (k >> 1) * (R / 2) + 2 * j + (k & 1);
+            }
+            i -= 4 * B;
+            if (i < B * nlat) return a.x1 + (size_t)(i / nlat) * CQ + CQq + w + a.W * (i % nlat);
+            i -= B * nlat;
+            const int k = i % (2 * npair);                              // (lo, hi) of pair w + W * (k / 2)
+            return a.x1 + (size_t)(i / (2 * npair)) * CQ + CQq + L + w + a.W * (k >> 1) + (R / 2) * (k & 1);
+        };
+        lds_sync();
+        for (int i0 = tid; i0 < J3; i0 += NT * NVB) {
+            size_t idx[NVB];
+            float sum[NVB];
+#pragma unroll
+            for (int v = 0; v < NVB; ++v) idx[v] = job_slot(min(i0 + NT * v, J3 - 1));
+            take_sums<NVB>(x, r, idx, (size_t)B * CQ, KS, sum);
+#pragma unroll
+            for (int v = 0; v < NVB; ++v)
+                if (i0 + NT * v < J3) s_job[i0 + NT * v] = sum[v];
+        }
+        lds_sync();
+        MLA_STAMP(2);           // q_nope, q_rope and the new row summed
+        for (int i = tid; i < 2 * B; i += NT) {                         // rotary query, pairs (p, p + R/2)
+            const int b = i / 2, pp = i % 2, p = 2 * j + pp;
+            const float lo = s_job[J0 + 4 * b + pp], hi = s_job[J0 + 4 * b + 2 + pp], c = s_rope[p], sn = s_rope[R / 2 + p];
+            const size_t dst = a.xq + ((size_t)b * a.nh + head) * LR + L + p;
+            cf::team::put(r, dst, lo * c - hi * sn, x.stamp);
+            cf::team::put(r, dst + R / 2, hi * c + lo * sn, x.stamp);
+        }
+        for (int i = tid; i < B * nlat; i += NT) {                      // latent part of the new row
+            const int b = i / nlat, d = w + a.W * (i % nlat);
+            const float v = s_job[J1 + i];
+            cf::team::put(r, a.xkv + (size_t)b * LR + d, v, x.stamp);
+            a.cache[((size_t)b * a.max_seq + a.pos) * LR + d] = f2h(v);
+        }
+        for (int i = tid; i < B * npair; i += NT) {                     // rotary part of the new row
+            const int b = i / npair, p = w + a.W * (i % npair);
+            const float lo = s_job[J2 + 2 * i], hi = s_job[J2 + 2 * i + 1], c = s_rope[p], sn = s_rope[R / 2 + p];
+            const float rl = lo * c - hi * sn, rh = hi * c + lo * sn;
+            cf::team::put(r, a.xkv + (size_t)b * LR + L + p, rl, x.stamp);
+            cf::team::put(r, a.xkv + (size_t)b * LR + L + p + R / 2, rh, x.stamp);
+            uint16_t *row = a.cache + ((size_t)b * a.max_seq + a.pos) * LR + L + p;
+            row[0] = f2h(rl);
+            row[R / 2] = f2h(rh);
+        }
+        small_product<BT, 4, RPT_B>(wupr, s_job, a.n, a.n, B, s_red, [&](int b, int cc, float sum) {
+            cf::team::put(r, a.xq + ((size_t)b * a.nh + head) * LR + LJ * j + cc, sum, x.stamp);
+        });
     }
 
     MLA_STAMP(3);           // B done
-    // ---- C: attention over the tokens [t0, t1) of this member; the last member also takes the new token
-    lds_sync();
-    const bool last = j == TS - 1;
-    const int tps = (a.pos + TS - 1) / TS;
-    const int t0 = min(j * tps, a.pos), t1 = min(t0 + tps, a.pos);
-    // s_a: [B][L + R] the query in the latent space and its rotated rotary part; s_b: [B][L + R] the new row.
-    // First what has been there since stage A (the rotary part of the query, the new row) and the angles, last the
-    // latent query, which the other members of the team are still producing.
-    if (tid < R / 2) {
-        const double inv_freq = exp2(-2.0 * (double)tid / (double)R * a.log2_base);
-        cf::rope_cos_sin(a.pos, inv_freq, s_small[tid], s_small[R / 2 + tid]);
-    }
-    for (int i = tid; i < B * R; i += NT) {
-        const int b = i / R, d = i % R;
-        s_a[b * (L + R) + L + d] = take_sum(x, r, a.x1 + (size_t)b * CQ + head * nr + a.n + d, (size_t)B * CQ, KS);
-    }
-    if (last)
-        for (int i = tid; i < B * (L + R); i += NT) {
-            const int b = i / (L + R), d = i % (L + R);
-            s_b[i] = take_sum(x, r, a.x1 + (size_t)b * CQ + CQq + d, (size_t)B * CQ, KS);
-        }
-    for (int i = tid; i < B * L; i += NT) {
-        const int b = i / L, d = i % L;
-        s_a[b * (L + R) + d] = take1(x, r, a.x2 + ((size_t)b * a.nh + head) * L + d);
-    }
-    lds_sync();
-    for (int i = tid; i < B * (R / 2); i += NT) {                     // RoPE on the rotary parts (pairs d, d + R/2)
-        const int b = i / (R / 2), d = i % (R / 2);
-        const float c = s_small[d], sn = s_small[R / 2 + d];
-        float *q = s_a + b * (L + R) + L;
-        const float lo = q[d], hi = q[d + R / 2];
-        q[d] = lo * c - hi * sn;
-        q[d + R / 2] = hi * c + lo * sn;
-        if (last) {
-            float *k = s_b + b * (L + R) + L;
-            const float klo = k[d], khi = k[d + R / 2];
-            k[d] = klo * c - khi * sn;
-            k[d + R / 2] = khi * c + klo * sn;
-        }
-    }
-    lds_sync();
-    MLA_STAMP(4);           // query arrived and rotated
-    if (last)                                                         // append (Sec. 2.1): row pos of every sequence
-        for (int i = tid; i < B * (L + R); i += NT) {
-            const int b = i / (L + R), d = i % (L + R);
-            a.cache[((size_t)b * a.max_seq + a.pos) * (L + R) + d] = f2h(s_b[i]);
-        }
-    for (int b = 0; b < B; ++b) {
-        const float *q = s_a + b * (L + R);
-        // A row of the cache is handled by 16 lanes (a wavefront takes four rows at a time): lane li of a row group
-        // owns the latent dimensions 128 k + 8 li .. + 8 (k < 4) and the rotary dimensions 4 li .. + 4, so a row's
-        // score needs only the four in-row steps of a cross-lane sum and one exponential serves 36 multiply-adds.
-        const int li = lane & 15, rg = lane >> 4;
-        float ql[4][8], qr4[4];
+    // ---- C: attention.  Work item (b, s): cached rows [t0, t1) of batch row b against the queries of all heads.
+    //      A tile is 128 rows.  Scores: wavefront wv takes 16 rows, S^T = K Q^T as one 16 x 16 tile (rows = tokens,
+    //      columns = heads), the contraction over the 576 dimensions in 18 steps with the query as a pair of fp16
+    //      operands (value = hi + lo, so the fp32 query loses nothing).  Online softmax per head over the tile (the
+    //      wavefronts exchange their maxima through LDS).  Weighted sum: wavefront (kq, th) takes the latent
+    //      dimensions [128 kq, +128) and the rows [64 th, +64) of the tile: A = probabilities (fp16, from LDS),
+    //      B = the rows themselves, eight at a time transposed inside the lane.  The item with s = 0 also scores
+    //      the new token (its row is taken in fp32 from stage B).
+    {
+        h8 *qop_hi = reinterpret_cast<h8 *>(smem);                      // [kSteps][64]
+        h8 *qop_lo = qop_hi + kQops;
+        float *s_m = smem + 2 * kQops * 4;                              // [NW][HT] maxima of the wavefronts' rows
+        float *s_l = s_m + NW * HT;                                     // [NW][HT] sums of the wavefronts' probabilities
+        float *s_M = s_l + NW * HT;                                     // [HT]
+        float *s_kn = s_M + HT;                                         // [LR] the new row
+        _Float16 *sP = reinterpret_cast<_Float16 *>(s_kn + LR);         // [HT][PS]
+        float *sO = s_kn + LR + HT * PS / 2;                            // [HT][L], at the end of an item
+        float *s_q = sO;                                                // [HT][QS], at its start
+        const int g = lane >> 4, c = lane & 15, kq = wv & 3, th = wv >> 2;
+        const int ngroups = (a.nh + a.HG - 1) / a.HG;
+        for (int it = w; it < B * a.NS * ngroups; it += a.W) {
+            const int hg = it % ngroups, b = it / ngroups / a.NS, s = it / ngroups % a.NS;
+            const int h0 = hg * a.HG, h1 = min(h0 + a.HG, a.nh);        // the heads of this item
+            const int t0 = min(s * a.tps, a.pos), t1 = min(t0 + a.tps, a.pos);
+            const uint16_t *rows = a.cache + (size_t)b * a.max_seq * LR;
+            h8 kS[kSteps], kV[2][8];
+            // Rows past the range are read from its last row (finite data) and get probability 0.
+            auto issue_s = [&](int T0) {
+                const uint16_t *row = rows + (size_t)min(T0 + 16 * wv + c, t1 - 1) * LR;
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
+                for (int m = 0; m < kSteps; ++m) kS[m] = *reinterpret_cast<const h8 *>(row + score_dim(m, g));
+            };
+            auto issue_v = [&](int T0) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c) ql[k][c] = q[128 * k + 8 * li + c] * a.scale_log2e;
+                for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) qr4[c] = q[L + 4 * li + c] * a.scale_log2e;
-        float m = kNegBig, lsum = 0.f, acc[4][8];
+                    for (int u = 0; u < 8; ++u)
+                        kV[ks][u] = *reinterpret_cast<const h8 *>(
+                            rows + (size_t)min(T0 + 64 * th + 32 * ks + 8 * g + u, t1 - 1) * LR + 128 * kq + 8 * c);
+            };
+            if (t1 > t0) issue_s(t0);                                   // (uniform) the rows do not wait for the query
+            lds_sync();                                                 // the previous item has left LDS
+            MLA_STAMP(13);
+            {
+                // the query of the item's heads, [head][LR] fp32 scaled by log2(e) / sqrt(d_k): consecutive lanes poll
+                // consecutive slots
+                constexpr int NQ = HT * LR / NT;
+                const int nq = (h1 - h0) * LR;
+                const size_t src = a.xq + ((size_t)b * a.nh + h0) * LR;
+                pair_t q[NQ];
+                long long tw = 0;
+                for (;;) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
+                    for (int k = 0; k < NQ; ++k) {
+                        q[k] = pair_t{0u, x.stamp};
+                        if (NT * k < nq) q[k] = cf::team::peek(r, src + min(tid + NT * k, nq - 1));       // (uniform)
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    bool ok = true;
 #pragma unroll
-            for (int c = 0; c < 8; ++c) acc[k][c] = 0.f;
-        const uint16_t *rows = a.cache + (size_t)b * a.max_seq * (L + R);
-        // Two rows per row group and batch, two batches in flight.  Rows past the split are read from its last row
-        // (finite data) and count for nothing.
-        constexpr int UR = 4, RPB = NW * 4;                            // rows of the workgroup per sub-batch
-        h8 kl[2][UR][4];
-        h4 kr[2][UR];
-        const int myrow = wv * 4 + rg;
-        auto request = [&](int buf, int t) {
+                    for (int k = 0; k < NQ; ++k) ok &= q[k].y == x.stamp;
+                    if (ok || cf::team::gave_up(x, tw)) break;
+                }
 #pragma unroll
-            for (int u = 0; u < UR; ++u) {
-                const uint16_t *row = rows + (size_t)min(t + myrow + u * RPB, t1 - 1) * (L + R);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) kl[buf][u][k] = *reinterpret_cast<const h8 *>(row + 128 * k + 8 * li);
-                kr[buf][u] = *reinterpret_cast<const h4 *>(row + L + 4 * li);
+                for (int k = 0; k < NQ; ++k) {
+                    const int i = tid + NT * k;
+                    if (i < nq) s_q[(h0 + i / LR) * QS + i % LR] = __builtin_bit_cast(float, q[k].x) * a.scale_log2e;
+                }
             }
-        };
-        auto use = [&](int buf, int t) {
-            float d[UR];
-#pragma unroll
-            for (int u = 0; u < UR; ++u) {
-                float dd = 0.f;
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) dd = fmaf(ql[k][c], (float)kl[buf][u][k][c], dd);
-#pragma unroll
-                for (int c = 0; c < 4; ++c) dd = fmaf(qr4[c], (float)kr[buf][u][c], dd);
-                d[u] = dd;
+            if (s == 0) {                                               // the new row, for the score of the new token
+                for (int i0 = tid; i0 < LR; i0 += NT) {
+                    long long tw = 0;
+                    for (;;) {
+                        const pair_t q = cf::team::peek(r, a.xkv + (size_t)b * LR + i0);
+                        if (q.y == x.stamp || cf::team::gave_up(x, tw)) {
+                            s_kn[i0] = __builtin_bit_cast(float, q.x);
+                            break;
+                        }
+                    }
+                }
             }
+            lds_sync();
+            // query operands: entry e = (step m, lane (g2, head c2)) holds the eight dimensions score_dim(m, g2) + 0..7
+            // of head c2 as fp16 pairs (value = hi + lo); heads outside the item's group are zero
+            for (int e = tid; e < kQops; e += NT) {
+                const int m = e >> 6, g2 = (e >> 4) & 3, c2 = e & 15;
+                const bool mine = c2 >= h0 && c2 < h1;
+                const float *src = s_q + (mine ? c2 : h0) * QS + score_dim(m, g2);
+                h8 hi, lo;
 #pragma unroll
-            for (int u = 0; u < UR; ++u) {                             // sum over the 16 lanes of the row
-                d[u] += dpp_move<0xB1>(d[u]);
-                d[u] += dpp_move<0x4E>(d[u]);
-                d[u] += dpp_move<0x141>(d[u]);
-                d[u] += dpp_move<0x140>(d[u]);
+                for (int i = 0; i < 8; ++i) {
+                    const float v = mine ? src[i] : 0.f;
+                    hi[i] = (_Float16)v;
+                    lo[i] = (_Float16)(v - (float)hi[i]);
+                }
+                qop_hi[e] = hi;
+                qop_lo[e] = lo;
             }
-            float mn = m;
+            if (s == 0) {
+                // score of the new token: 32 lanes per head, 18 dimensions each
+                const int h = min(h0 + (tid >> 5), h1 - 1), part = tid & 31;
+                float d = 0.f;
 #pragma unroll
-            for (int u = 0; u < UR; ++u) {
-                d[u] = (t + myrow + u * RPB < t1) ? d[u] : kNegBig;
-                mn = fmaxf(mn, d[u]);
+                for (int k = 0; k < LR / 32; ++k) d = fmaf(s_q[h * QS + part * (LR / 32) + k], s_kn[part * (LR / 32) + k], d);
+#pragma unroll
+                for (int off = 1; off < 32; off <<= 1) d += __shfl_xor(d, off);
+                if (part == 0 && h0 + (tid >> 5) < h1) cf::team::put(r, a.xs + (size_t)b * a.nh + h, d, x.stamp);
             }
-            const float f = __builtin_amdgcn_exp2f(m - mn);
-            m = mn;
-            lsum *= f;
+            if (t1 > t0) issue_v(t0);
+            lds_sync();
+            MLA_STAMP(4);           // query operands built
+            if (t1 > t0) {                                              // uniform over the workgroup
+                float M = kNegBig, lw = 0.f;                            // of head c: running maximum; sum over this lane's rows
+                f32x4 O[8];                                             // [jj][rr]: head 4 g + rr, dimension 128 kq + 8 c + jj
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
+                for (int jj = 0; jj < 8; ++jj) O[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int T0 = t0; T0 < t1; T0 += kTile) {
+                    f32x4 S = {0.f, 0.f, 0.f, 0.f};                     // rows = tokens T0 + 16 wv + 4 g + rr, column = head c
 #pragma unroll
-                for (int c = 0; c < 8; ++c) acc[k][c] *= f;
+                    for (int m = 0; m < kSteps; ++m) {
+                        S = mfma16(kS[m], qop_hi[m * 64 + lane], S);
+                        S = mfma16(kS[m], qop_lo[m * 64 + lane], S);
+                    }
+                    float mx = kNegBig;
 #pragma unroll
-            for (int u = 0; u < UR; ++u) {
-                const float pw = (t + myrow + u * RPB < t1) ? __builtin_amdgcn_exp2f(d[u] - mn) : 0.f;
-                lsum += pw;
+                    for (int rr = 0; rr < 4; ++rr) {
+                        S[rr] = (T0 + 16 * wv + 4 * g + rr < t1) ? S[rr] : kNegBig;
+                        mx = fmaxf(mx, S[rr]);
+                    }
+                    mx = fmaxf(mx, __shfl_xor(mx, 16));
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));
+                    if (lane < HT) s_m[wv * HT + c] = mx;
+                    lds_sync();
+                    float mt = s_m[c];
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
+                    for (int w8 = 1; w8 < NW; ++w8) mt = fmaxf(mt, s_m[w8 * HT + c]);
+                    const float Mn = fmaxf(M, mt);                      // > kNegBig: the tile has a row inside the range
+                    const float f = __builtin_amdgcn_exp2f(M - Mn);
+                    M = Mn;
+                    float psum = 0.f;
+                    h4 ph;
 #pragma unroll
-                    for (int c = 0; c < 8; ++c) acc[k][c] = fmaf(pw, (float)kl[buf][u][k][c], acc[k][c]);
+                    for (int rr = 0; rr < 4; ++rr) {
+                        const float pw = __builtin_amdgcn_exp2f(S[rr] - Mn);
+                        ph[rr] = (_Float16)pw;
+                        psum += pw;
+                    }
+                    lw = fmaf(lw, f, psum);
+                    *reinterpret_cast<uint2 *>(sP + c * PS + 16 * wv + 4 * g) = __builtin_bit_cast(uint2, ph);
+                    float fr[4];                                        // factor of the heads this lane accumulates
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) fr[rr] = __shfl(f, 4 * g + rr);
+#pragma unroll
+                    for (int jj = 0; jj < 8; ++jj)
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr) O[jj][rr] *= fr[rr];
+                    lds_sync();
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        const h8 pa = *reinterpret_cast<const h8 *>(sP + c * PS + 64 * th + 32 * ks + 8 * g);
+                        h8 f8[8];
+                        transpose8(kV[ks], f8);
+#pragma unroll
+                        for (int jj = 0; jj < 8; ++jj) O[jj] = mfma16(pa, f8[jj], O[jj]);
+                    }
+                    if (T0 + kTile < t1) {                              // (after the products: one tile's rows in registers)
+                        issue_s(T0 + kTile);
+                        issue_v(T0 + kTile);
+                    }
+                }
+                MLA_STAMP(11);          // rows consumed
+                lw += __shfl_xor(lw, 16);
+                lw += __shfl_xor(lw, 32);
+                if (lane < HT) {
+                    s_l[wv * HT + c] = lw;
+                    if (wv == 0) s_M[c] = M;
+                }
+                // the two halves of the tile rows are added through LDS (all wavefronts hold the same maxima)
+                if (th == 1) {
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        float *dst = sO + (4 * g + rr) * L + 128 * kq + 8 * c;
+                        *reinterpret_cast<float4 *>(dst) = make_float4(O[0][rr], O[1][rr], O[2][rr], O[3][rr]);
+                        *reinterpret_cast<float4 *>(dst + 4) = make_float4(O[4][rr], O[5][rr], O[6][rr], O[7][rr]);
+                    }
+                }
+                lds_sync();
+                if (th == 0) {
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        float *dst = sO + (4 * g + rr) * L + 128 * kq + 8 * c;
+                        const float4 lo4 = *reinterpret_cast<const float4 *>(dst), hi4 = *reinterpret_cast<const float4 *>(dst + 4);
+                        *reinterpret_cast<float4 *>(dst) =
+                            make_float4(O[0][rr] + lo4.x, O[1][rr] + lo4.y, O[2][rr] + lo4.z, O[3][rr] + lo4.w);
+                        *reinterpret_cast<float4 *>(dst + 4) =
+                            make_float4(O[4][rr] + hi4.x, O[5][rr] + hi4.y, O[6][rr] + hi4.z, O[7][rr] + hi4.w);
+                    }
+                }
+                lds_sync();
+                MLA_STAMP(12);          // wavefronts merged
+                const size_t dst = a.x3 + ((size_t)b * a.NS + s) * HT * kPart;
+                for (int i = h0 * L + tid; i < h1 * L; i += NT)
+                    cf::team::put(r, dst + (size_t)(i / L) * kPart + 2 + i % L, sO[i], x.stamp);
+                if (tid >= h0 && tid < h1) {
+                    float ls = 0.f;
+#pragma unroll
+                    for (int w8 = 0; w8 < NW; ++w8) ls += s_l[w8 * HT + tid];
+                    cf::team::put(r, dst + (size_t)tid * kPart, s_M[tid], x.stamp);
+                    cf::team::put(r, dst + (size_t)tid * kPart + 1, ls, x.stamp);
+                }
             }
-        };
-        if (t1 > t0) {                                                 // uniform over the workgroup
-            constexpr int step = RPB * UR;
-            request(0, t0);
-            for (int t = t0; t < t1; t += 2 * step) {
-                request(1, t + step);
-                use(0, t);
-                request(0, t + 2 * step);
-                use(1, t + step);
-            }
-        }
-        MLA_STAMP(11);          // rows consumed
-        // every row group of every wavefront leaves its (m, l, acc) in LDS: 32 partials, folded below
-        lds_sync();
-        {
-            float *part = s_part + (wv * 4 + rg) * (L + 2);
-            if (li == 0) {
-                part[0] = m;
-                part[1] = lsum;
-            }
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-#pragma unroll
-                for (int c = 0; c < 8; ++c) part[2 + 128 * k + 8 * li + c] = acc[k][c];
-        }
-        MLA_STAMP(12);          // row groups merged
-        if (last && wv == 0) {                                        // score of the new token (its row is not rounded)
-            const float *kn = s_b + b * (L + R);
-            float d = 0.f;
-#pragma unroll
-            for (int k = 0; k < 4; ++k)
-#pragma unroll
-                for (int c = 0; c < 8; ++c) d = fmaf(ql[k][c], kn[128 * k + 8 * li + c], d);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) d = fmaf(qr4[c], kn[L + 4 * li + c], d);
-            d += dpp_move<0xB1>(d);
-            d += dpp_move<0x4E>(d);
-            d += dpp_move<0x141>(d);
-            d += dpp_move<0x140>(d);
-            if (lane == 0) s_small[R + b] = d;
-        }
-        lds_sync();
-        {
-            const int d = tid;                                         // one latent dimension per thread
-            float M = last ? s_small[R + b] : kNegBig;
-            for (int w8 = 0; w8 < NPART; ++w8) M = fmaxf(M, s_part[w8 * (L + 2)]);
-            float Ls = 0.f, A = 0.f;
-            for (int w8 = 0; w8 < NPART; ++w8) {
-                const float f = __builtin_amdgcn_exp2f(s_part[w8 * (L + 2)] - M);
-                Ls = fmaf(s_part[w8 * (L + 2) + 1], f, Ls);
-                A = fmaf(s_part[w8 * (L + 2) + 2 + d], f, A);
-            }
-            if (last) {
-                const float f = __builtin_amdgcn_exp2f(s_small[R + b] - M);
-                Ls += f;
-                A = fmaf(s_b[b * (L + R) + d], f, A);
-            }
-            const size_t dst = a.x3 + (((size_t)b * a.nh + head) * TS + j) * (L + 2);
-            if (d == 0) {
-                cf::team::put(r, dst, M, x.stamp);
-                cf::team::put(r, dst + 1, Ls, x.stamp);
-            }
-            cf::team::put(r, dst + 2 + d, A, x.stamp);
         }
     }
 
     MLA_STAMP(5);           // C done
-    // ---- D: merge latent dimensions [LJ*j, +LJ) of the team's partials (online softmax, Alg. 4 steps 8-10) and
-    //      multiply them by the same rows of W_Down[head]: a partial of a_head per member, no hop in between
-    const int pcsD = a.v / 8, pcD = tid % 16, rowD = tid / 16;        // thread = (row of the slice, 16-byte piece)
-    const h8 wdr = pcD < pcsD ? *reinterpret_cast<const h8 *>(a.wdown + ((size_t)head * L + LJ * j + rowD) * a.v + pcD * 8)
-                              : h8{0, 0, 0, 0, 0, 0, 0, 0};
-    lds_sync();
-    if (tid < LJ * B) {
-        const int b = tid / LJ, d = LJ * j + tid % LJ;
-        const size_t src = a.x3 + ((size_t)b * a.nh + head) * TS * (L + 2);
-        pair_t qm[TS], ql2[TS], qa[TS];
-        long long tw = 0;
-        for (;;) {                                                     // all 48 polls of this thread in one go
-#pragma unroll
-            for (int s2 = 0; s2 < TS; ++s2) {
-                qm[s2] = cf::team::peek(r, src + (size_t)s2 * (L + 2));
-                ql2[s2] = cf::team::peek(r, src + (size_t)s2 * (L + 2) + 1);
-                qa[s2] = cf::team::peek(r, src + (size_t)s2 * (L + 2) + 2 + d);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            bool ok = true;
-#pragma unroll
-            for (int s2 = 0; s2 < TS; ++s2) ok &= (qm[s2].y == x.stamp) & (ql2[s2].y == x.stamp) & (qa[s2].y == x.stamp);
-            if (ok || cf::team::gave_up(x, tw)) break;
-        }
-        float M = kNegBig;
-#pragma unroll
-        for (int s2 = 0; s2 < TS; ++s2) M = fmaxf(M, __builtin_bit_cast(float, qm[s2].x));
-        float Ls = 0.f, A = 0.f;
-#pragma unroll
-        for (int s2 = 0; s2 < TS; ++s2) {
-            const float f = __builtin_amdgcn_exp2f(__builtin_bit_cast(float, qm[s2].x) - M);
-            Ls = fmaf(__builtin_bit_cast(float, ql2[s2].x), f, Ls);
-            A = fmaf(__builtin_bit_cast(float, qa[s2].x), f, A);
-        }
-        s_b[b * LJ + tid % LJ] = A / Ls;                               // z[b][LJ*j + ...]
-    }
-    lds_sync();
-    MLA_STAMP(6);           // z slice merged
+    // ---- D: merge latent dimensions [LJ*j, +LJ) of head `head` over the token ranges and the new token (online
+    //      softmax, Alg. 4 steps 8-10) and multiply them by the same rows of W_Down[head]: a partial of a_head per
+    //      member, no hop in between
     {
-        // rows [LJ*j, +LJ) of W_Down[head], all v columns: one contiguous block (requested above)
+        float *s_z = smem;                                              // [B][LJ]
+        float *s_red = smem + BT * LJ;                                  // [NW][BT][128]
+        h8 wdr[RPT_D];
+        {
+            const int pc = tid % 16, rg = tid / G16;
 #pragma unroll
-        for (int b = 0; b < MAXB; ++b)
-            if (b < B) {
-                const float zv = s_b[b * LJ + rowD];
-                float t[8];
-#pragma unroll
-                for (int c = 0; c < 8; ++c) t[c] = zv * (float)wdr[c];
-#pragma unroll
-                for (int c = 0; c < 8; ++c) t[c] += __shfl_xor(t[c], 16);
-#pragma unroll
-                for (int c = 0; c < 8; ++c) t[c] += __shfl_xor(t[c], 32);
-                if (lane < 16) {
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) s_red[(wv * MAXB + b) * 128 + pcD * 8 + c] = t[c];
-                }
+            for (int k = 0; k < RPT_D; ++k) {
+                const int row = rg + RG16 * k;
+                wdr[k] = (pc < a.v / 8 && row < LJ)
+                             ? *reinterpret_cast<const h8 *>(a.wdown + ((size_t)head * L + LJ * j + row) * a.v + pc * 8)
+                             : h8{0, 0, 0, 0, 0, 0, 0, 0};
             }
-        lds_sync();
-        for (int i = tid; i < B * a.v; i += NT) {
-            const int b = i / a.v, c = i % a.v;
-            float sum = 0.f;
-#pragma unroll
-            for (int w8 = 0; w8 < NW; ++w8) sum += s_red[(w8 * MAXB + b) * 128 + c];
-            cf::team::put(r, a.x5 + (((size_t)b * a.nh + head) * TS + j) * a.v + c, sum, x.stamp);
         }
+        lds_sync();
+        const int n_used = (a.pos + a.tps - 1) / a.tps;
+        if (tid < LJ * B) {
+            // lane sl of a group of 32 fetches the maximum and the sum of range sl (at most 32 ranges) and the group
+            // shares them by shuffles; every lane fetches its own dimension of all ranges: one round trip in all
+            const int b = tid / LJ, sl = tid % LJ, d = LJ * j + sl, nu1 = max(n_used, 1);
+            pair_t qa[kMaxSplits], qm, ql, qn, qc;
+            long long tw = 0;
+            for (;;) {
+                const size_t mine = a.x3 + (((size_t)b * a.NS + min(sl, nu1 - 1)) * HT + head) * kPart;
+                qm = cf::team::peek(r, mine);
+                ql = cf::team::peek(r, mine + 1);
+                qn = cf::team::peek(r, a.xs + (size_t)b * a.nh + head);
+                qc = cf::team::peek(r, a.xkv + (size_t)b * LR + d);
+#pragma unroll
+                for (int k = 0; k < kMaxSplits; ++k)
+                    qa[k] = cf::team::peek(r, a.x3 + (((size_t)b * a.NS + min(k, nu1 - 1)) * HT + head) * kPart + 2 + d);
+                __builtin_amdgcn_sched_barrier(0);
+                bool ok = (qn.y == x.stamp) & (qc.y == x.stamp) & ((sl >= n_used) | ((qm.y == x.stamp) & (ql.y == x.stamp)));
+#pragma unroll
+                for (int k = 0; k < kMaxSplits; ++k) ok &= (k >= n_used) | (qa[k].y == x.stamp);
+                if (ok || cf::team::gave_up(x, tw)) break;
+            }
+            const float snew = __builtin_bit_cast(float, qn.x);
+            const float ms = sl < n_used ? __builtin_bit_cast(float, qm.x) : kNegBig;
+            float M = fmaxf(ms, snew);
+#pragma unroll
+            for (int off = 1; off < LJ; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
+            const float fs = sl < n_used ? __builtin_amdgcn_exp2f(ms - M) : 0.f;
+            float Ls = __builtin_bit_cast(float, ql.x) * fs;
+#pragma unroll
+            for (int off = 1; off < LJ; off <<= 1) Ls += __shfl_xor(Ls, off);
+            const float fn = __builtin_amdgcn_exp2f(snew - M);          // the new token: weight 1 at its own score
+            Ls += fn;
+            float A = __builtin_bit_cast(float, qc.x) * fn;
+#pragma unroll
+            for (int k = 0; k < kMaxSplits; ++k) {
+                const float fk = __shfl(fs, (lane & 32) + k);
+                A = fmaf(k < n_used ? __builtin_bit_cast(float, qa[k].x) : 0.f, fk, A);
+            }
+            const float z = A / Ls;
+            s_z[b * LJ + sl] = z;
+            a.zdbg[((size_t)b * a.nh + head) * L + d] = z;
+        }
+        lds_sync();
+        MLA_STAMP(6);           // z slice merged
+        small_product<BT, 16, RPT_D>(wdr, s_z, LJ, LJ, B, s_red, [&](int b, int cc, float sum) {
+            if (cc < a.v) cf::team::put(r, a.x5 + (((size_t)b * a.nh + head) * TS + j) * a.v + cc, sum, x.stamp);
+        });
     }
     MLA_STAMP(7);           // D done
 
     // ---- E1: rows of W_O that belong to this head, column block j of the output: a partial of out per head
-    const int dpE = a.D / 8, pcsE = (dpE + TS - 1) / TS;                // 16-byte pieces of an output row; per member
-    const int pcE = tid % 16, rgE = tid / 16;                         // 32 row groups
-    auto wo_rows = [&](int p0, h8 (&wr)[4]) {                          // v <= 128: at most four rows per thread
-        const int piece = j * pcsE + p0 + pcE;
-        const bool live = p0 + pcE < pcsE && piece < dpE;
+    {
+        constexpr int NVE = BT == 4 ? 1 : 4;
+        float *s_a = smem;                                              // [B][v]
+        float *s_red = smem + BT * 128;                                 // [NW][BT][128]
+        const int dpE = a.D / 8, pcsE = (dpE + TS - 1) / TS;            // 16-byte pieces of an output row; per member
+        h8 wor[RPT_E];
+        auto wo_rows = [&](int p0) {
+            const int pc = tid % 16, rg = tid / G16;
+            const int piece = j * pcsE + p0 + pc;
+            const bool live = p0 + pc < pcsE && piece < dpE;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int row = rgE + 32 * k;
-            wr[k] = (live && row < a.v) ? *reinterpret_cast<const h8 *>(a.wo + ((size_t)head * a.v + row) * a.D + piece * 8)
-                                        : h8{0, 0, 0, 0, 0, 0, 0, 0};
-        }
-    };
-    h8 wor[4];
-    wo_rows(0, wor);
-    lds_sync();
-    for (int i = tid; i < B * a.v; i += NT) {
-        const int b = i / a.v, c = i % a.v;
-        s_b[i] = take_sum(x, r, a.x5 + ((size_t)b * a.nh + head) * TS * a.v + c, (size_t)a.v, TS);
-    }
-    lds_sync();
-    MLA_STAMP(8);           // a_head arrived
-    for (int p0 = 0; p0 < pcsE; p0 += 16) {
-        if (p0 > 0) wo_rows(p0, wor);
-        float acc[MAXB][8];
+            for (int k = 0; k < RPT_E; ++k) {
+                const int row = rg + RG16 * k;
+                wor[k] = (live && row < a.v) ? *reinterpret_cast<const h8 *>(a.wo + ((size_t)head * a.v + row) * a.D + piece * 8)
+                                             : h8{0, 0, 0, 0, 0, 0, 0, 0};
+            }
+        };
+        wo_rows(0);
+        lds_sync();
+        for (int i0 = tid; i0 < B * a.v; i0 += NT * NVE) {
+            size_t idx[NVE];
+            float sum[NVE];
 #pragma unroll
-        for (int b = 0; b < MAXB; ++b)
+            for (int v = 0; v < NVE; ++v) {
+                const int i = min(i0 + NT * v, B * a.v - 1);
+                idx[v] = a.x5 + ((size_t)(i / a.v) * a.nh + head) * TS * a.v + i % a.v;
+            }
+            take_sums<NVE>(x, r, idx, (size_t)a.v, TS, sum);
 #pragma unroll
-            for (int c = 0; c < 8; ++c) acc[b][c] = 0.f;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int row = min(rgE + 32 * k, a.v - 1);
-#pragma unroll
-            for (int b = 0; b < MAXB; ++b)
-                if (b < B) {
-                    const float av = s_b[b * a.v + row];
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) acc[b][c] = fmaf(av, (float)wor[k][c], acc[b][c]);
-                }
+            for (int v = 0; v < NVE; ++v)
+                if (i0 + NT * v < B * a.v) s_a[i0 + NT * v] = sum[v];
         }
         lds_sync();
-#pragma unroll
-        for (int b = 0; b < MAXB; ++b)
-            if (b < B) {
-#pragma unroll
-                for (int c = 0; c < 8; ++c) acc[b][c] += __shfl_xor(acc[b][c], 16);
-#pragma unroll
-                for (int c = 0; c < 8; ++c) acc[b][c] += __shfl_xor(acc[b][c], 32);
-                if (lane < 16) {
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) s_red[(wv * MAXB + b) * 128 + pcE * 8 + c] = acc[b][c];
-                }
+        MLA_STAMP(8);           // a_head arrived
+        for (int p0 = 0; p0 < pcsE; p0 += 16) {
+            if (p0 > 0) {
+                lds_sync();
+                wo_rows(p0);
             }
-        lds_sync();
-        for (int i = tid; i < B * 128; i += NT) {
-            const int b = i / 128, cc = i % 128, piece2 = j * pcsE + p0 + cc / 8;
-            if (p0 + cc / 8 < pcsE && piece2 < dpE) {
-                float sum = 0.f;
-#pragma unroll
-                for (int w8 = 0; w8 < NW; ++w8) sum += s_red[(w8 * MAXB + b) * 128 + cc];
-                cf::team::put(r, a.x6 + ((size_t)b * a.nh + head) * a.D + piece2 * 8 + cc % 8, sum, x.stamp);
-            }
+            small_product<BT, 16, RPT_E>(wor, s_a, a.v, a.v, B, s_red, [&](int b, int cc, float sum) {
+                const int piece2 = j * pcsE + p0 + cc / 8;
+                if (p0 + cc / 8 < pcsE && piece2 < dpE)
+                    cf::team::put(r, a.x6 + ((size_t)b * a.nh + head) * a.D + piece2 * 8 + cc % 8, sum, x.stamp);
+            });
         }
     }
     MLA_STAMP(10);          // E1 done
@@ -602,8 +744,12 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         const int CW = (a.D + a.W - 1) / a.W;
         if (tid < B * CW) {
             const int b = tid / CW, col = CW * w + tid % CW;
-            if (col < a.D)
-                a.out[(size_t)b * a.D + col] = f2h(take_sum(x, r, a.x6 + (size_t)b * a.nh * a.D + col, (size_t)a.D, a.nh));
+            if (col < a.D) {
+                const size_t idx[1] = {a.x6 + (size_t)b * a.nh * a.D + col};
+                float sum[1];
+                take_sums<1>(x, r, idx, (size_t)a.D, a.nh, sum);
+                a.out[(size_t)b * a.D + col] = f2h(sum[0]);
+            }
         }
     }
     if (tid == 0) a.counters[(size_t)w * kCounterStride] = cnt;
@@ -614,6 +760,10 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
 #endif
 }
 
+using MlaFn = void (*)(const MlaArgs);
+
+MlaFn pick(int batch) { return batch <= 4 ? fused_mla_decode<4> : fused_mla_decode<16>; }
+
 }  // namespace
 
 struct cf_mla_s {
@@ -622,12 +772,40 @@ struct cf_mla_s {
     char *ws = nullptr;
     size_t ws_bytes = 0;
     uint64_t *slots = nullptr;
+    float *zdbg = nullptr, *qdbg = nullptr;
     unsigned long long *counters = nullptr;
     uint32_t *err = nullptr;
-    size_t x1 = 0, x2 = 0, x3 = 0, x5 = 0, x6 = 0;
+    size_t x1 = 0, xq = 0, xkv = 0, x3 = 0, xs = 0, x5 = 0, x6 = 0;
     long long spin_ticks = 200000000LL;
+    int max_splits = 0;             // 0: chosen by the library
+    int last_batch = 0;
+    bool last_heads = false;        // the last call ran the head-team kernel
     int last_hip = 0;
 };
+
+namespace {
+
+// token ranges of a call: NS ranges of tps cached rows per batch row; and the heads per attention item: as few as
+// the number of workgroups allows (an item fetches the queries and publishes the partial results of its heads only:
+// per workgroup that traffic, not the arithmetic, is what takes time)
+void plan_splits(const cf_mla_s *t, int batch, int pos, int *ns, int *tps, int *hg)
+{
+    int cap = t->W / batch;
+    cap = cap < 1 ? 1 : cap > kMaxSplits ? kMaxSplits : cap;
+    if (t->max_splits > 0 && t->max_splits < cap) cap = t->max_splits;
+    int per = (pos + cap - 1) / cap;
+    per = (per + 15) / 16 * 16;
+    if (per < 64 && t->max_splits == 0) per = 64;     // below half a tile more ranges only add partials
+    if (per < 16) per = 16;
+    *tps = per;
+    const int n = (pos + per - 1) / per;
+    *ns = n < 1 ? 1 : n;                              // range 0 always exists: it scores the new token
+    int groups = 1;
+    while (2 * groups <= t->cfg.n_heads && batch * *ns * 2 * groups <= t->W) groups *= 2;
+    *hg = (t->cfg.n_heads + groups - 1) / groups;
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -639,38 +817,48 @@ int cf_mla_create(const cf_mla_config *cfg, cf_mla *out)
     if (c.d_model < 16 || c.n_heads < 1 || c.nope_dim < 1 || c.v_head_dim < 1 || c.max_batch < 1 || c.max_seq < 1 ||
         !(c.rope_base > 1.f))
         return CF_EINVAL;
-    // what this first kernel is written for
+    // what the kernel is written for
     const int W = c.n_heads * TS;
     const int CQq = c.n_heads * (c.nope_dim + R);
-    const int cq = (CQq / 8 + 15) / 16, ckv = ((L + R) / 8 + 15) / 16;     // 16-byte pieces per column block
-    if (c.kv_lora_rank != L || c.rope_dim != R || c.max_batch > MAXB || c.d_model % (2 * KS) || c.d_model / KS > NT ||
-        c.v_head_dim % 8 || c.v_head_dim > 128 || cq + ckv > 32 || c.nope_dim % 8 ||
+    const int cq = (CQq / 8 + 15) / 16, ckv = (LR / 8 + 15) / 16;          // 16-byte pieces per column block
+    if (c.kv_lora_rank != L || c.rope_dim != R || c.max_batch > MAXBATCH || c.n_heads > HT || c.d_model % (2 * KS) ||
+        c.d_model / KS > NT || c.v_head_dim % 8 || c.v_head_dim > 128 || cq + ckv > 32 || c.nope_dim % 8 ||
         c.nope_dim > 128 || c.d_model > 8 * W || c.d_model % 8)
         return CF_EUNSUPPORTED;
     int dev = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return CF_EHIP;
     if (W > prop.multiProcessorCount) return CF_EUNSUPPORTED;        // all workgroups resident, one per compute unit
-    int per_cu = 0;
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(fused_mla_decode), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)kDynLds) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fused_mla_decode), NT, kDynLds) !=
-            hipSuccess || per_cu < 1)
-        return CF_EUNSUPPORTED;
+    const size_t lds = kLdsFloats * sizeof(float);
+    for (int batch : {1, MAXBATCH}) {
+        int per_cu = 0;
+        const void *fn = reinterpret_cast<const void *>(pick(batch));
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, NT, lds) != hipSuccess || per_cu < 1)
+            return CF_EUNSUPPORTED;
+    }
+    if (!cf::mla::heads_prepare()) return CF_EUNSUPPORTED;
     cf_mla t = new (std::nothrow) cf_mla_s();
     if (!t) return CF_ENOMEM;
     t->cfg = c;
     t->W = W;
-    const size_t B = c.max_batch, CQ = (size_t)CQq + L + R;
+    const size_t B = c.max_batch, CQ = (size_t)CQq + LR, items = (size_t)(W > c.max_batch ? W : c.max_batch);
     t->x1 = 0;
-    t->x2 = t->x1 + (size_t)KS * B * CQ;
-    t->x3 = t->x2 + B * c.n_heads * L;
-    t->x5 = t->x3 + B * c.n_heads * TS * (L + 2);
+    t->xq = t->x1 + (size_t)KS * B * CQ;
+    t->xkv = t->xq + B * c.n_heads * LR;
+    t->x3 = t->xkv + B * LR;
+    t->xs = t->x3 + items * HT * kPart;
+    t->x5 = t->xs + B * c.n_heads;
     t->x6 = t->x5 + B * c.n_heads * TS * c.v_head_dim;
-    const size_t nslots = t->x6 + B * c.n_heads * c.d_model;
+    size_t hfirst[5];
+    const size_t hslots = cf::mla::heads_layout(c, c.max_batch < cf::mla::kHeadsMaxBatch ? c.max_batch : cf::mla::kHeadsMaxBatch, hfirst);
+    const size_t rslots = t->x6 + B * c.n_heads * c.d_model;
+    const size_t nslots = rslots > hslots ? rslots : hslots;         // the two kernels use the same slots, never together
     const size_t head = 256 + (size_t)W * kCounterStride * sizeof(unsigned long long);
     const size_t head_al = (head + 255) / 256 * 256;
-    t->ws_bytes = head_al + nslots * sizeof(uint64_t);
+    const size_t slot_bytes = (nslots * sizeof(uint64_t) + 255) / 256 * 256;
+    const size_t zbytes = (B * c.n_heads * L * sizeof(float) + 255) / 256 * 256;
+    t->ws_bytes = head_al + slot_bytes + zbytes + B * c.n_heads * LR * sizeof(float);
     if (nslots * sizeof(uint64_t) > 0xfffffff0ull) {
         delete t;
         return CF_EUNSUPPORTED;
@@ -686,6 +874,8 @@ int cf_mla_create(const cf_mla_config *cfg, cf_mla *out)
     t->err = reinterpret_cast<uint32_t *>(t->ws + 128);
     t->counters = reinterpret_cast<unsigned long long *>(t->ws + 256);
     t->slots = reinterpret_cast<uint64_t *>(t->ws + head_al);
+    t->zdbg = reinterpret_cast<float *>(t->ws + head_al + slot_bytes);
+    t->qdbg = reinterpret_cast<float *>(t->ws + head_al + slot_bytes + zbytes);
     *out = t;
     return CF_OK;
 }
@@ -707,6 +897,38 @@ int cf_mla_decode(cf_mla t, int32_t batch, const void *x, const void *W_q, const
     for (const void *p : ptrs)
         if (reinterpret_cast<uintptr_t>(p) & 15u) return CF_EINVAL;
     const cf_mla_config &c = t->cfg;
+    if (batch <= kHeadsBatch && t->max_splits == 0) {
+        // one or two batch rows: the head-team kernel (every head scans the cached rows itself; see cf_mla_heads.hip)
+        cf::mla::HeadsArgs h;
+        std::memset(&h, 0, sizeof h);
+        h.x = static_cast<const uint16_t *>(x);
+        h.wq = static_cast<const uint16_t *>(W_q);
+        h.wkv = static_cast<const uint16_t *>(W_kv);
+        h.wup = static_cast<const uint16_t *>(W_up);
+        h.wdown = static_cast<const uint16_t *>(W_down);
+        h.wo = static_cast<const uint16_t *>(W_o);
+        h.cache = static_cast<uint16_t *>(kv_cache);
+        h.out = static_cast<uint16_t *>(out);
+        h.qdbg = t->qdbg, h.zdbg = t->zdbg;
+        h.slots = t->slots, h.counters = t->counters, h.err = t->err;
+        size_t first[5];
+        (void)cf::mla::heads_layout(c, batch, first);
+        h.x1 = first[0], h.x2 = first[1], h.x3 = first[2], h.x5 = first[3], h.x6 = first[4];
+        h.D = c.d_model, h.nh = c.n_heads, h.n = c.nope_dim, h.v = c.v_head_dim, h.B = batch, h.pos = pos;
+        h.max_seq = c.max_seq, h.W = t->W;
+        h.cq = (c.n_heads * (c.nope_dim + R) / 8 + 15) / 16;
+        h.ckv = (LR / 8 + 15) / 16;
+        h.scale_log2e = 1.4426950408889634f / std::sqrt((float)(c.nope_dim + R));
+        h.log2_base = std::log2((double)c.rope_base);
+        h.spin_ticks = t->spin_ticks;
+        t->last_batch = batch, t->last_heads = true;
+        const int e = cf::mla::heads_launch(h, stream);
+        if (e != (int)hipSuccess) {
+            t->last_hip = e;
+            return CF_EHIP;
+        }
+        return CF_OK;
+    }
     MlaArgs a;
     std::memset(&a, 0, sizeof a);
     a.x = static_cast<const uint16_t *>(x);
@@ -717,19 +939,22 @@ int cf_mla_decode(cf_mla t, int32_t batch, const void *x, const void *W_q, const
     a.wo = static_cast<const uint16_t *>(W_o);
     a.cache = static_cast<uint16_t *>(kv_cache);
     a.out = static_cast<uint16_t *>(out);
+    a.zdbg = t->zdbg;
     a.slots = t->slots;
     a.counters = t->counters;
     a.err = t->err;
     // the exchange areas are laid out for max_batch; a smaller batch uses the front of each
-    a.x1 = t->x1, a.x2 = t->x2, a.x3 = t->x3, a.x5 = t->x5, a.x6 = t->x6;
+    a.x1 = t->x1, a.xq = t->xq, a.xkv = t->xkv, a.x3 = t->x3, a.xs = t->xs, a.x5 = t->x5, a.x6 = t->x6;
     a.D = c.d_model, a.nh = c.n_heads, a.n = c.nope_dim, a.v = c.v_head_dim, a.B = batch, a.pos = pos;
     a.max_seq = c.max_seq, a.W = t->W;
+    plan_splits(t, batch, pos, &a.NS, &a.tps, &a.HG);
     a.cq = (c.n_heads * (c.nope_dim + R) / 8 + 15) / 16;
-    a.ckv = ((L + R) / 8 + 15) / 16;
+    a.ckv = (LR / 8 + 15) / 16;
     a.scale_log2e = 1.4426950408889634f / std::sqrt((float)(c.nope_dim + R));
     a.log2_base = std::log2((double)c.rope_base);
     a.spin_ticks = t->spin_ticks;
-    hipLaunchKernelGGL(fused_mla_decode, dim3(t->W), dim3(NT), kDynLds, static_cast<hipStream_t>(stream), a);
+    t->last_batch = batch, t->last_heads = false;
+    hipLaunchKernelGGL(pick(batch), dim3(t->W), dim3(NT), kLdsFloats * sizeof(float), static_cast<hipStream_t>(stream), a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         t->last_hip = (int)e;
@@ -752,6 +977,48 @@ int cf_mla_status(cf_mla t, void *stream)
         e = hipMemset(t->ws, 0, t->ws_bytes);        // launch counters and all stamps start afresh
         if (e == hipSuccess) e = hipDeviceSynchronize();
         return e == hipSuccess ? CF_ETIMEOUT : CF_EHIP;
+    }
+    return CF_OK;
+}
+
+int cf_mla_set_splits(cf_mla t, int32_t max_splits)
+{
+    if (!t || max_splits < 0 || max_splits > kMaxSplits) return CF_EINVAL;
+    t->max_splits = max_splits;
+    return CF_OK;
+}
+
+int cf_mla_debug_export(cf_mla t, int32_t what, void *host_dst, size_t bytes, void *stream)
+{
+    if (!t || !host_dst || what < 0 || what > 2 || t->last_batch < 1) return CF_EINVAL;
+    const size_t B = t->last_batch, nh = t->cfg.n_heads;
+    const size_t per = what == 1 ? R : L;
+    if (bytes != B * nh * per * sizeof(float)) return CF_EINVAL;
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    if (e == hipSuccess && what == 2) e = hipMemcpy(host_dst, t->zdbg, bytes, hipMemcpyDeviceToHost);
+    if (e == hipSuccess && what != 2 && t->last_heads) {
+        std::vector<float> q(B * nh * LR);
+        e = hipMemcpy(q.data(), t->qdbg, q.size() * sizeof(float), hipMemcpyDeviceToHost);
+        float *dst = static_cast<float *>(host_dst);
+        if (e == hipSuccess)
+            for (size_t i = 0; i < B * nh; ++i)
+                std::memcpy(dst + i * per, q.data() + i * LR + (what == 1 ? L : 0), per * sizeof(float));
+    } else if (e == hipSuccess && what != 2) {
+        // the query of the last call still sits in its exchange slots: [b][head][L + R] {value, stamp} pairs
+        std::vector<uint64_t> pairs(B * nh * LR);
+        e = hipMemcpy(pairs.data(), t->slots + t->xq, pairs.size() * sizeof(uint64_t), hipMemcpyDeviceToHost);
+        float *dst = static_cast<float *>(host_dst);
+        if (e == hipSuccess)
+            for (size_t b = 0; b < B; ++b)
+                for (size_t h = 0; h < nh; ++h)
+                    for (size_t k = 0; k < per; ++k) {
+                        const uint32_t bits = (uint32_t)pairs[(b * nh + h) * LR + (what == 1 ? L : 0) + k];
+                        std::memcpy(dst + (b * nh + h) * per + k, &bits, sizeof bits);
+                    }
+    }
+    if (e != hipSuccess) {
+        t->last_hip = (int)e;
+        return CF_EHIP;
     }
     return CF_OK;
 }
