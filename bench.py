@@ -31,7 +31,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/),
 # keyed by workload name; None = not measured for that workload.
 MEASURED_TRAFFIC = {
-    # profiles/fused_decode_block_hbm_traffic.md: (FETCH_SIZE KiB x 2.0000 + WRITE_SIZE KiB) x 1024
+    # profiles/fused_decode_block_llama2_7b_kv4096_hbm_traffic.md and profiles/fused_decode_block_gqa_shapes.md:
+    # (FETCH_SIZE KiB x 2.0000 + WRITE_SIZE KiB) x 1024, measured on fused_decode_block (one launch per layer)
     "llama2_7b_b1_kv4096": 207353856,      # 100203.0, 2088.0
     "llama3_8b_b1_kv8192": 126311424,      # 60241.5, 2868.0
     "llama3_8b_b4_kv8192": 239742157,      # 112921.6, 8280.0
@@ -364,7 +365,7 @@ def run_one(args):
                    "row_lengths": row_pos if args.ragged else "all kv_len",
                    "plan": plan},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.layer or args.ragged) else MEASURED_TRAFFIC.get(name),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if (args.layer or args.ragged or args.stack) else MEASURED_TRAFFIC.get(name),
                      "algorithmic_bytes": alg_bytes,
                      "kernel": "fused_decode_layer" if (args.layer or args.ragged) else
                                "fused_decode_stack" if (args.stack and d == 128) else "fused_decode_block"},
