@@ -275,15 +275,23 @@ __global__ void __launch_bounds__(NT) fused_ffn(const FfnArgs a)
         const uint32_t d1 = consume3(t3b, row0 + UB);
         load3(t3b, row0 + 3 * UB, d1);
     }
-    // ---- the partial output of this workgroup
+    // ---- the partial output of this workgroup.  A thread holds eight adjacent columns; stored from there, one store
+    //      instruction would touch 64 lines with 8 bytes each.  The values pass through LDS (4096 columns at a time) so
+    //      that consecutive lanes write consecutive slots.
 #pragma unroll
     for (int b = 0; b < BT; ++b)
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) {
-            const int col = 8 * tid + 4096 * cb;
-            if (b < B && col < D) {
+            if (b < B) {                                          // (uniform)
+                lds_barrier();
+                *reinterpret_cast<float4 *>(smem + 8 * tid) = make_float4(acc[b][cb][0], acc[b][cb][1], acc[b][cb][2], acc[b][cb][3]);
+                *reinterpret_cast<float4 *>(smem + 8 * tid + 4) = make_float4(acc[b][cb][4], acc[b][cb][5], acc[b][cb][6], acc[b][cb][7]);
+                lds_barrier();
 #pragma unroll
-                for (int j = 0; j < 8; ++j) cf::team::put(xr, ((size_t)w * B + b) * D + col + j, acc[b][cb][j], x.stamp);
+                for (int j = 0; j < 8; ++j) {
+                    const int col = 4096 * cb + NT * j + tid;
+                    if (col < D) cf::team::put(xr, ((size_t)w * B + b) * D + col, smem[NT * j + tid], x.stamp);
+                }
             }
         }
 
@@ -356,7 +364,7 @@ static size_t lds_bytes_of(const cf_ffn_config &c, int bt, int nrmax)
 {
     const size_t nck = (c.d_model + kChunk - 1) / kChunk, dp = nck * kChunk;
     const size_t stages_ab = (size_t)bt * dp / 2 + 2 * (size_t)bt * nrmax * nck + (size_t)bt * nrmax;
-    return (stages_ab > (size_t)NT ? stages_ab : (size_t)NT) * sizeof(float);       // stage C: one float per thread
+    return (stages_ab > (size_t)(8 * NT) ? stages_ab : (size_t)(8 * NT)) * sizeof(float);       // the partial output on its way out: 4096 floats
 }
 
 extern "C" {
