@@ -11,7 +11,9 @@ Prints ONE JSON line on stdout (details go to stderr).  With --sweep it prints o
 of the measurement table instead (the Llama-2-7B shape at six cache lengths, the Llama-3-8B shape at batch 1, 4
 and 16, the Llama-2-70B shape and its stack of 80 distinct layers, and four rows in which one cf_decode_stack call
 runs all layers of a pass in a single launch).  After the timed region, outside the events,
-one more step on the first layer is checked against the C oracle at the tolerance of the parity tests.
+one more step on the first layer is checked against the C oracle at the tolerance of the parity tests, and the
+same layers are run once more with one cf_decode_stack launch per pass ("one_launch_stack" in the line; `value` is
+always the one-launch-per-layer figure).
 """
 from __future__ import annotations
 
@@ -82,6 +84,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg")
     ap.add_argument("--no-check", action="store_true", help="skip the check of one step against the C oracle")
+    ap.add_argument("--no-stack-line", action="store_true",
+                    help="skip the extra measurement of the same layers with one launch per pass (\"one_launch_stack\")")
     ap.add_argument("--sweep", action="store_true",
                     help="one JSON line per row of the measurement table (each with --steps launches; the workload, "
                          "batch, cache length and layer count of the row replace those given here)")
@@ -278,6 +282,7 @@ def run_one(args):
         for i in range(args.warmup):
             step(i)
         blk.status(sh)
+        plain = False
         if args.stack:
             args.steps = max(1, args.steps // n_layers) * n_layers
             n_passes = args.steps // n_layers
@@ -312,6 +317,8 @@ def run_one(args):
                 for _ in range(n_replays):
                     graph.replay()
         else:
+            plain = not (args.layer or args.ragged)
+
             def timed_region(first_step):
                 for i in range(args.steps):
                     step(first_step + i)
@@ -333,6 +340,34 @@ def run_one(args):
             torch.cuda.synchronize()
             rep_us.append(ea.elapsed_time(eb) / args.steps * 1e3)
         blk.status(sh)
+        one_launch = None
+        if plain and d == 128 and not args.sweep and not args.no_stack_line:
+            # the same layers once more with ONE launch per pass (cf_decode_stack): reported beside the headline,
+            # never as `value`
+            out2 = torch.empty_like(out)
+            cols = list(zip(*ptrs))
+
+            def one_pass():
+                blk.decode_stack(B, xp, None, 1e-5, False, not args.row_major, cols[0], cols[1], cols[2], cols[3], L,
+                                 out2.data_ptr(), sh)
+
+            one_pass()
+            blk.status(sh)
+            n_passes = max(1, args.steps // n_layers)
+            ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            ea.record(stream)
+            for _ in range(n_passes):
+                one_pass()
+            eb.record(stream)
+            torch.cuda.synchronize()
+            blk.status(sh)
+            us_layer = ea.elapsed_time(eb) / (n_passes * n_layers) * 1e3
+            one_launch = {"us_per_layer": us_layer, "layers_per_launch": n_layers, "passes": n_passes,
+                          "achieved_GBps": alg_bytes / (us_layer * 1e-6) / 1e9,
+                          "frac": alg_bytes / (us_layer * 1e-6) / 1e9 / HBM_PEAK_GBS, "kernel": "fused_decode_stack",
+                          "what": "all layers of a pass in one launch (cf_decode_stack, every layer reads the hidden state "
+                                  "the previous one wrote)"}
     assert torch.isfinite(out.float()).all(), "non-finite output"
     plan = blk.plan()
     check = None
@@ -374,6 +409,8 @@ def run_one(args):
         import numpy as np
         res["repetitions"] = {"n": len(rep_us), "median_us": float(np.median(rep_us)),
                               "p10_us": float(np.percentile(rep_us, 10)), "p90_us": float(np.percentile(rep_us, 90))}
+    if one_launch is not None:
+        res["one_launch_stack"] = one_launch
     if check is not None:
         res["check"] = check
     if not args.no_cpu_baseline:
