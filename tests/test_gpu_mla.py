@@ -149,11 +149,13 @@ def test_full_size_deepseek_v2_lite_shape():
         check(run(shape, inp, shape.kv_len, max_splits), ref, inp, shape.kv_len, "%s (range limit %d)" % (shape.name, max_splits))
 
 
-def test_full_size_deepseek_v2_lite_shape_batch_16():
-    """The batch of the paper's Appendix C at a shorter cache (the oracle's time grows with batch x cached rows)."""
+@pytest.mark.parametrize("batch,kv_len", [(16, 4096), (4, 4096), (16, 1000)])
+def test_full_size_deepseek_v2_lite_shape_batched(batch, kv_len):
+    """The batch of the paper's Appendix C (16) and batch 4 in the configuration bench_mla.py times, and a cache length
+    that is no multiple of the tile."""
     shape = cf_inputs.MLA_SHAPES["deepseek_v2_lite"]
-    inp = cf_inputs.make_mla_inputs(shape, seed=1001, batch=16, kv_len=1024)
-    check(run(shape, inp, 1024), oracle(shape, inp, 1024), inp, 1024, shape.name + " B=16")
+    inp = cf_inputs.make_mla_inputs(shape, seed=1001, batch=batch, kv_len=kv_len)
+    check(run(shape, inp, kv_len), oracle(shape, inp, kv_len), inp, kv_len, "%s B=%d L=%d" % (shape.name, batch, kv_len))
 
 
 def test_unsupported_shapes_and_bad_arguments_are_refused():
