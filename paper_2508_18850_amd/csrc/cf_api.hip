@@ -89,7 +89,10 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
             const size_t lds = (cf::x_lds_floats(hd, bt, rps) + (size_t)maxi * cf::kWaves * bt * hd) * sizeof(float);
             if (lds > kLdsLimit) continue;
             const int dsel = TS / ks;
-            const long cost = (long)(ceil_div(G, dsel) + ceil_div(2, dsel)) * rps;
+            // rows a member streams, plus what its consumers pay for every further slice: KS partial sums per projected
+            // value to fetch, for every batch row (weighed by measurements on the grouped-query shapes: the
+            // Llama-3-8B shape takes 8 slices from batch 3 on, 16 below; the Llama-2-70B shape stays at 16)
+            const long cost = (long)(ceil_div(G, dsel) + ceil_div(2, dsel)) * rps + 12L * ks * (bt < 4 ? bt : 4);
             if (!best || cost < best_cost) {
                 best = ks;
                 best_cost = cost;
