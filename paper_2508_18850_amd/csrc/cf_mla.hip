@@ -67,7 +67,7 @@ struct MlaArgs {
     uint64_t *slots;
     unsigned long long *counters;
     uint32_t *err;
-    size_t x1, xq, xkv, x3, xs, x5, x6;     // first slot of each exchange area
+    size_t x1, xq, xkv, x3, xs, x5, x6, xqn, xa;     // first slot of each exchange area
     int D, nh, n, v, B, pos, max_seq, W;
     int NS, tps, HG;                // token ranges per batch row, cached rows per range, heads per attention item
     int cq, ckv;                    // 16-byte pieces (8 columns) of W_Q / W_KV per column block
@@ -134,6 +134,30 @@ __device__ __forceinline__ void take_sums(const Exchange &x, __amdgpu_buffer_rsr
             if (k < n) s += __builtin_bit_cast(float, q[v][k].x);
         out[v] = s;
     }
+}
+
+// All threads: fetch cnt <= 4 * NT stamped values into LDS, value i (at slot_of(i)) to dst[i]; all polls of a thread are
+// in flight together (one round trip).  No barrier inside.
+template <class SlotOf>
+__device__ __forceinline__ void fetch4(const Exchange &x, __amdgpu_buffer_rsrc_t r, int cnt, float *dst, SlotOf &&slot_of)
+{
+    pair_t q[4];
+    long long t0 = 0;
+    for (;;) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            q[k] = pair_t{0u, x.stamp};
+            if (NT * k < cnt) q[k] = cf::team::peek(r, slot_of(min((int)threadIdx.x + NT * k, cnt - 1)));     // (uniform)
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        bool ok = true;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) ok &= q[k].y == x.stamp;
+        if (ok || cf::team::gave_up(x, t0)) break;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        if ((int)threadIdx.x + NT * k < cnt) dst[threadIdx.x + NT * k] = __builtin_bit_cast(float, q[k].x);
 }
 
 // Workgroup barrier that orders LDS accesses only.  __syncthreads() would also wait for every outstanding global
@@ -349,10 +373,19 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         }
         float *s_job = smem;                                           // sums of the jobs below
         const int nlat = w < L ? (L - w + a.W - 1) / a.W : 0, npair = w < R / 2 ? (R / 2 - w + a.W - 1) / a.W : 0;
-        const int J0 = B * a.n, J1 = J0 + 4 * B, J2 = J1 + B * nlat, J3 = J2 + 2 * B * npair;
+        // 16-row tile: the sums of q_nope go in two levels (this member adds the KS partials of 1/16 of the head's
+        // nope dimensions and publishes them, then fetches all of them): 16 times fewer polls per workgroup, which at
+        // this batch outweighs the extra hand-over
+        constexpr bool TWO = BT == 16;
+        const int cpm = (a.n + TS - 1) / TS;                           // nope dimensions per member (two levels)
+        const int J0 = TWO ? B * cpm : B * a.n, J1 = J0 + 4 * B, J2 = J1 + B * nlat, J3 = J2 + 2 * B * npair;
         float *s_red = smem + (J3 + 3) / 4 * 4;                        // [NW][BT][LJ]
+        float *s_qn = TWO ? s_red + NW * BT * LJ : s_job;               // [B][n] q_nope of this head
         auto job_slot = [&](int i) -> size_t {                          // the first of the KS partials of job i
-            if (i < J0) return a.x1 + (size_t)(i / a.n) * CQ + head * nr + i % a.n;
+            if (i < J0) {
+                const int b = TWO ? i / cpm : i / a.n, c = TWO ? min(cpm * j + i % cpm, a.n - 1) : i % a.n;
+                return a.x1 + (size_t)b * CQ + head * nr + c;
+            }
             i -= J0;
             if (i < 4 * B) {
                 const int k = i % 4;                                    // lo of pair 2j, 2j + 1, then their partners
@@ -376,6 +409,17 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
                 if (i0 + NT * v < J3) s_job[i0 + NT * v] = sum[v];
         }
         lds_sync();
+        if (TWO) {
+            for (int i = tid; i < J0; i += NT) {
+                const int b = i / cpm, c = cpm * j + i % cpm;
+                if (c < a.n) cf::team::put(r, a.xqn + ((size_t)b * a.nh + head) * 128 + c, s_job[i], x.stamp);
+            }
+            for (int i0 = 0; i0 < B * a.n; i0 += 4 * NT)
+                fetch4(x, r, min(4 * NT, B * a.n - i0), s_qn + i0, [&](int i) {
+                    return a.xqn + ((size_t)((i0 + i) / a.n) * a.nh + head) * 128 + (i0 + i) % a.n;
+                });
+            lds_sync();
+        }
         MLA_STAMP(2);           // q_nope, q_rope and the new row summed
         for (int i = tid; i < 2 * B; i += NT) {                         // rotary query, pairs (p, p + R/2)
             const int b = i / 2, pp = i % 2, p = 2 * j + pp;
@@ -400,7 +444,7 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
             row[0] = f2h(rl);
             row[R / 2] = f2h(rh);
         }
-        small_product<BT, 4, RPT_B>(wupr, s_job, a.n, a.n, B, s_red, [&](int b, int cc, float sum) {
+        small_product<BT, 4, RPT_B>(wupr, s_qn, a.n, a.n, B, s_red, [&](int b, int cc, float sum) {
             cf::team::put(r, a.xq + ((size_t)b * a.nh + head) * LR + LJ * j + cc, sum, x.stamp);
         });
     }
@@ -710,18 +754,34 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         };
         wo_rows(0);
         lds_sync();
-        for (int i0 = tid; i0 < B * a.v; i0 += NT * NVE) {
-            size_t idx[NVE];
-            float sum[NVE];
-#pragma unroll
-            for (int v = 0; v < NVE; ++v) {
-                const int i = min(i0 + NT * v, B * a.v - 1);
-                idx[v] = a.x5 + ((size_t)(i / a.v) * a.nh + head) * TS * a.v + i % a.v;
+        if constexpr (BT == 16) {
+            // two levels as for q_nope: this member adds the TS partials of 1/16 of the head's dimensions
+            const int cpv = (a.v + TS - 1) / TS;
+            for (int i = tid; i < B * cpv; i += NT) {
+                const int b = i / cpv, c = cpv * j + i % cpv;
+                size_t idx[1] = {a.x5 + ((size_t)b * a.nh + head) * TS * a.v + min(c, a.v - 1)};
+                float sum[1];
+                take_sums<1>(x, r, idx, (size_t)a.v, TS, sum);
+                if (c < a.v) cf::team::put(r, a.xa + ((size_t)b * a.nh + head) * 128 + c, sum[0], x.stamp);
             }
-            take_sums<NVE>(x, r, idx, (size_t)a.v, TS, sum);
+            for (int i0 = 0; i0 < B * a.v; i0 += 4 * NT)
+                fetch4(x, r, min(4 * NT, B * a.v - i0), s_a + i0, [&](int i) {
+                    return a.xa + ((size_t)((i0 + i) / a.v) * a.nh + head) * 128 + (i0 + i) % a.v;
+                });
+        } else {
+            for (int i0 = tid; i0 < B * a.v; i0 += NT * NVE) {
+                size_t idx[NVE];
+                float sum[NVE];
 #pragma unroll
-            for (int v = 0; v < NVE; ++v)
-                if (i0 + NT * v < B * a.v) s_a[i0 + NT * v] = sum[v];
+                for (int v = 0; v < NVE; ++v) {
+                    const int i = min(i0 + NT * v, B * a.v - 1);
+                    idx[v] = a.x5 + ((size_t)(i / a.v) * a.nh + head) * TS * a.v + i % a.v;
+                }
+                take_sums<NVE>(x, r, idx, (size_t)a.v, TS, sum);
+#pragma unroll
+                for (int v = 0; v < NVE; ++v)
+                    if (i0 + NT * v < B * a.v) s_a[i0 + NT * v] = sum[v];
+            }
         }
         lds_sync();
         MLA_STAMP(8);           // a_head arrived
@@ -775,7 +835,7 @@ struct cf_mla_s {
     float *zdbg = nullptr, *qdbg = nullptr;
     unsigned long long *counters = nullptr;
     uint32_t *err = nullptr;
-    size_t x1 = 0, xq = 0, xkv = 0, x3 = 0, xs = 0, x5 = 0, x6 = 0;
+    size_t x1 = 0, xq = 0, xkv = 0, x3 = 0, xs = 0, x5 = 0, x6 = 0, xqn = 0, xa = 0;
     long long spin_ticks = 200000000LL;
     int max_splits = 0;             // 0: chosen by the library
     int last_batch = 0;
@@ -852,7 +912,9 @@ int cf_mla_create(const cf_mla_config *cfg, cf_mla *out)
     t->x6 = t->x5 + B * c.n_heads * TS * c.v_head_dim;
     size_t hfirst[5];
     const size_t hslots = cf::mla::heads_layout(c, c.max_batch < cf::mla::kHeadsMaxBatch ? c.max_batch : cf::mla::kHeadsMaxBatch, hfirst);
-    const size_t rslots = t->x6 + B * c.n_heads * c.d_model;
+    t->xqn = t->x6 + B * c.n_heads * c.d_model;                  // [B][heads][128] summed q_nope (16-row tile)
+    t->xa = t->xqn + B * c.n_heads * 128;                         // [B][heads][128] summed a_head (16-row tile)
+    const size_t rslots = t->xa + B * c.n_heads * 128;
     const size_t nslots = rslots > hslots ? rslots : hslots;         // the two kernels use the same slots, never together
     const size_t head = 256 + (size_t)W * kCounterStride * sizeof(unsigned long long);
     const size_t head_al = (head + 255) / 256 * 256;
@@ -944,7 +1006,7 @@ int cf_mla_decode(cf_mla t, int32_t batch, const void *x, const void *W_q, const
     a.counters = t->counters;
     a.err = t->err;
     // the exchange areas are laid out for max_batch; a smaller batch uses the front of each
-    a.x1 = t->x1, a.xq = t->xq, a.xkv = t->xkv, a.x3 = t->x3, a.xs = t->xs, a.x5 = t->x5, a.x6 = t->x6;
+    a.x1 = t->x1, a.xq = t->xq, a.xkv = t->xkv, a.x3 = t->x3, a.xs = t->xs, a.x5 = t->x5, a.x6 = t->x6, a.xqn = t->xqn, a.xa = t->xa;
     a.D = c.d_model, a.nh = c.n_heads, a.n = c.nope_dim, a.v = c.v_head_dim, a.B = batch, a.pos = pos;
     a.max_seq = c.max_seq, a.W = t->W;
     plan_splits(t, batch, pos, &a.NS, &a.tps, &a.HG);
