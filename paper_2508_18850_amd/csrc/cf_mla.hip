@@ -278,78 +278,139 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     {
         constexpr int RB = BT < 8 ? BT : 8;
         float *s_x = smem;                                             // [BT][RK], RK <= 512
-        float *s_red = smem + BT * 512;                                // [NW][RB][MAXCOLS]
+        float *s_red = smem + BT * 512;                                // [NW][RB][MAXCOLS]; 16-row tile: [4][BT][MAXCOLS]
         const int RK = a.D / KS;
         const int qv = CQq / 8, kvv = LR / 8;                          // 16-byte pieces of a row of W_Q / W_KV
         for (int item = w; item < KS * 16; item += a.W) {
             const int kb = item / 16, cb = item % 16;
-            const int pv = tid % 32, g = tid / 32;                     // piece of the block, row group 0..15
-            const bool isq = pv < a.cq;
-            const int piece = isq ? cb * a.cq + pv : cb * a.ckv + (pv - a.cq);
-            const bool live = pv < a.cq + a.ckv && piece < (isq ? qv : kvv);
-            const h8 *wp = reinterpret_cast<const h8 *>(isq ? a.wq : a.wkv) + piece;
-            const size_t ld = isq ? qv : kvv;                          // row stride in pieces
-            h8 wr[8];                                                   // eight rows of this thread in flight
-            auto request = [&](int r0) {
+            if constexpr (BT == 16) {
+                // Matrix cores: one 16 x 16 x 32 step per 32 rows of the slice and eight columns: A = x (batch rows by
+                // slice rows, fp16 as given), B = eight rows of a 16-byte piece of the weights, transposed inside
+                // the lane; fp32 accumulation.  Wavefront wv takes the pieces [16 (wv & 1), +16) of the block and the
+                // steps wv / 2, wv / 2 + 4, ...; the four wavefronts of a piece set are added through LDS.
+                const int g = lane >> 4, c = lane & 15, pv = 16 * (wv & 1) + c, sw = wv >> 1;
+                const bool isq = pv < a.cq;
+                const int piece = isq ? cb * a.cq + pv : cb * a.ckv + (pv - a.cq);
+                const bool live = pv < a.cq + a.ckv && piece < (isq ? qv : kvv);
+                const h8 *wp = reinterpret_cast<const h8 *>(isq ? a.wq : a.wkv) + piece;
+                const size_t ld = isq ? qv : kvv;                      // row stride in pieces
+                h8 wr[8];
+                auto request = [&](int st) {
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const int rr = r0 + 16 * k;
-                    wr[k] = (live && rr < RK) ? wp[(size_t)(kb * RK + rr) * ld] : h8{0, 0, 0, 0, 0, 0, 0, 0};
-                }
-            };
-            request(g);                                                 // the first weights go out before the slice of x
-            lds_sync();                                                 // (all threads, whatever their row group)
-            for (int i = tid; i < B * RK; i += NT) s_x[i] = h2f(a.x[(size_t)(i / RK) * a.D + kb * RK + i % RK]);
-            lds_sync();
-            // RB batch rows per pass (the accumulators of 16 rows do not fit beside the weights); a slice of up to
-            // 128 rows is one batch of loads and stays in registers over the passes
-            for (int b0 = 0; b0 < B; b0 += RB) {
-                float acc[RB][8];
-#pragma unroll
-                for (int bb = 0; bb < RB; ++bb)
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) acc[bb][c] = 0.f;
-                for (int r0 = g; r0 < RK; r0 += 16 * 8) {
-                    if (r0 != g || (b0 > 0 && RK > 16 * 8)) request(r0);
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        const int rr = min(r0 + 16 * k, RK - 1);
-                        float wf[8];
-#pragma unroll
-                        for (int c = 0; c < 8; ++c) wf[c] = (float)wr[k][c];
-#pragma unroll
-                        for (int bb = 0; bb < RB; ++bb) {
-                            const float xv = s_x[min(b0 + bb, B - 1) * RK + rr];
-#pragma unroll
-                            for (int c = 0; c < 8; ++c) acc[bb][c] = fmaf(xv, wf[c], acc[bb][c]);
-                        }
+                    for (int u = 0; u < 8; ++u) {
+                        const int rr = 32 * st + 8 * g + u;
+                        wr[u] = (live && rr < RK) ? wp[(size_t)(kb * RK + rr) * ld] : h8{0, 0, 0, 0, 0, 0, 0, 0};
                     }
-                }
-                // (all shuffles of a row first, then the stores: a store between two shuffles makes each one wait)
-#pragma unroll
-                for (int bb = 0; bb < RB; ++bb)
-                    if (b0 + bb < B) {
-#pragma unroll
-                        for (int c = 0; c < 8; ++c) acc[bb][c] += __shfl_xor(acc[bb][c], 32);
-                        if (lane < 32) {
-#pragma unroll
-                            for (int c = 0; c < 8; ++c) s_red[(wv * RB + bb) * MAXCOLS + pv * 8 + c] = acc[bb][c];
-                        }
-                    }
+                };
+                request(sw);                                            // the first weights go out before the slice of x
                 lds_sync();
-                for (int i = tid; i < RB * MAXCOLS; i += NT) {
-                    const int bb = i / MAXCOLS, b = b0 + bb, cc = i % MAXCOLS, p2 = cc / 8;
+                for (int i = tid; i < B * RK; i += NT) s_x[i] = h2f(a.x[(size_t)(i / RK) * a.D + kb * RK + i % RK]);
+                lds_sync();
+                f32x4 acc[8];                                           // [jj][rr]: batch row 4 g + rr, column 8 pv + jj
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) acc[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int st = sw; 32 * st < RK; st += 4) {
+                    if (st != sw) request(st);
+                    h8 xa;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int rr = 32 * st + 8 * g + i;
+                        xa[i] = (c < B && rr < RK) ? (_Float16)s_x[c * RK + rr] : (_Float16)0.f;
+                    }
+                    h8 f8[8];
+                    transpose8(wr, f8);
+#pragma unroll
+                    for (int jj = 0; jj < 8; ++jj) acc[jj] = mfma16(xa, f8[jj], acc[jj]);
+                }
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    float *dst = s_red + (sw * BT + 4 * g + rr) * MAXCOLS + pv * 8;
+                    *reinterpret_cast<float4 *>(dst) = make_float4(acc[0][rr], acc[1][rr], acc[2][rr], acc[3][rr]);
+                    *reinterpret_cast<float4 *>(dst + 4) = make_float4(acc[4][rr], acc[5][rr], acc[6][rr], acc[7][rr]);
+                }
+                lds_sync();
+                for (int i = tid; i < BT * MAXCOLS; i += NT) {
+                    const int b = i / MAXCOLS, cc = i % MAXCOLS, p2 = cc / 8;
                     const bool q2 = p2 < a.cq;
                     const int piece2 = q2 ? cb * a.cq + p2 : cb * a.ckv + (p2 - a.cq);
                     if (b < B && p2 < a.cq + a.ckv && piece2 < (q2 ? qv : kvv)) {
                         float sum = 0.f;
 #pragma unroll
-                        for (int w8 = 0; w8 < NW; ++w8) sum += s_red[(w8 * RB + bb) * MAXCOLS + cc];
+                        for (int k4 = 0; k4 < 4; ++k4) sum += s_red[(k4 * BT + b) * MAXCOLS + cc];
                         const int gcol = (q2 ? 0 : CQq) + piece2 * 8 + cc % 8;
                         cf::team::put(r, a.x1 + ((size_t)kb * B + b) * CQ + gcol, sum, x.stamp);
                     }
                 }
                 lds_sync();
+            } else {
+                const int pv = tid % 32, g = tid / 32;                     // piece of the block, row group 0..15
+                const bool isq = pv < a.cq;
+                const int piece = isq ? cb * a.cq + pv : cb * a.ckv + (pv - a.cq);
+                const bool live = pv < a.cq + a.ckv && piece < (isq ? qv : kvv);
+                const h8 *wp = reinterpret_cast<const h8 *>(isq ? a.wq : a.wkv) + piece;
+                const size_t ld = isq ? qv : kvv;                          // row stride in pieces
+                h8 wr[8];                                                   // eight rows of this thread in flight
+                auto request = [&](int r0) {
+    #pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const int rr = r0 + 16 * k;
+                        wr[k] = (live && rr < RK) ? wp[(size_t)(kb * RK + rr) * ld] : h8{0, 0, 0, 0, 0, 0, 0, 0};
+                    }
+                };
+                request(g);                                                 // the first weights go out before the slice of x
+                lds_sync();                                                 // (all threads, whatever their row group)
+                for (int i = tid; i < B * RK; i += NT) s_x[i] = h2f(a.x[(size_t)(i / RK) * a.D + kb * RK + i % RK]);
+                lds_sync();
+                // RB batch rows per pass (the accumulators of 16 rows do not fit beside the weights); a slice of up to
+                // 128 rows is one batch of loads and stays in registers over the passes
+                for (int b0 = 0; b0 < B; b0 += RB) {
+                    float acc[RB][8];
+    #pragma unroll
+                    for (int bb = 0; bb < RB; ++bb)
+    #pragma unroll
+                        for (int c = 0; c < 8; ++c) acc[bb][c] = 0.f;
+                    for (int r0 = g; r0 < RK; r0 += 16 * 8) {
+                        if (r0 != g || (b0 > 0 && RK > 16 * 8)) request(r0);
+    #pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            const int rr = min(r0 + 16 * k, RK - 1);
+                            float wf[8];
+    #pragma unroll
+                            for (int c = 0; c < 8; ++c) wf[c] = (float)wr[k][c];
+    #pragma unroll
+                            for (int bb = 0; bb < RB; ++bb) {
+                                const float xv = s_x[min(b0 + bb, B - 1) * RK + rr];
+    #pragma unroll
+                                for (int c = 0; c < 8; ++c) acc[bb][c] = fmaf(xv, wf[c], acc[bb][c]);
+                            }
+                        }
+                    }
+                    // (all shuffles of a row first, then the stores: a store between two shuffles makes each one wait)
+    #pragma unroll
+                    for (int bb = 0; bb < RB; ++bb)
+                        if (b0 + bb < B) {
+    #pragma unroll
+                            for (int c = 0; c < 8; ++c) acc[bb][c] += __shfl_xor(acc[bb][c], 32);
+                            if (lane < 32) {
+    #pragma unroll
+                                for (int c = 0; c < 8; ++c) s_red[(wv * RB + bb) * MAXCOLS + pv * 8 + c] = acc[bb][c];
+                            }
+                        }
+                    lds_sync();
+                    for (int i = tid; i < RB * MAXCOLS; i += NT) {
+                        const int bb = i / MAXCOLS, b = b0 + bb, cc = i % MAXCOLS, p2 = cc / 8;
+                        const bool q2 = p2 < a.cq;
+                        const int piece2 = q2 ? cb * a.cq + p2 : cb * a.ckv + (p2 - a.cq);
+                        if (b < B && p2 < a.cq + a.ckv && piece2 < (q2 ? qv : kvv)) {
+                            float sum = 0.f;
+    #pragma unroll
+                            for (int w8 = 0; w8 < NW; ++w8) sum += s_red[(w8 * RB + bb) * MAXCOLS + cc];
+                            const int gcol = (q2 ? 0 : CQq) + piece2 * 8 + cc % 8;
+                            cf::team::put(r, a.x1 + ((size_t)kb * B + b) * CQ + gcol, sum, x.stamp);
+                        }
+                    }
+                    lds_sync();
+                }
             }
         }
     }
@@ -359,7 +420,7 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
     //      rotary query; and, spread over all workgroups, the new cache row (latent dimensions w, w + W, ..., rotary
     //      pairs w, w + W, ...): sums of the KS partials, RoPE, the append (Sec. 2.1) and a copy in fp32 for stage C.
     {
-        constexpr int NVB = BT == 4 ? 2 : 5;
+        constexpr int NVB = BT == 4 ? 2 : 1;        // (16-row tile: at most 256 jobs, see J3 below)
         // (the weights do not depend on what the stage waits for: they are requested first)
         h8 wupr[RPT_B];
         {
