@@ -44,14 +44,15 @@ constexpr int HT = 16;              // heads of one MFMA tile: the most the kern
 constexpr int MAXBATCH = 16;
 constexpr int MAXCOLS = 256;        // projection columns per column block
 constexpr int kCounterStride = 16;
-constexpr int kTile = 128;          // cached rows per attention tile of a workgroup
+constexpr int kTile = 64;           // cached rows per attention tile of a workgroup (held in LDS)
+constexpr int KSTR = LR + 8;        // row stride (fp16 values) of the tile in LDS
 constexpr int kSteps = LR / 32;     // MFMA steps of a score product (contraction over 576 dimensions)
 constexpr int kQops = kSteps * 64;  // 16-byte query operands (one per step and lane)
 constexpr int PS = kTile + 8;       // row stride (fp16 values) of the probabilities in LDS
 constexpr int QS = LR + 8;          // row stride (floats) of the fp32 query in LDS
 constexpr int kPart = 2 + L;        // slots of an attention partial per head: m, l, acc[L]
 constexpr int kMaxSplits = 32;      // token ranges per batch row at most
-constexpr size_t kLdsFloats = 24576;    // 96 KiB: the largest stage (A at batch 16)
+constexpr size_t kLdsFloats = 29440;    // 115 KiB: the largest stage (C: query operands, a tile of rows, the rest)
 constexpr float kNegBig = -1.0e30f;
 constexpr int kHeadsBatch = 2;      // up to this batch cf_mla_decode runs the head-team kernel (measured cross-over)
 
@@ -512,13 +513,15 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
 
     MLA_STAMP(3);           // B done
     // ---- C: attention.  Work item (b, s): cached rows [t0, t1) of batch row b against the queries of all heads.
-    //      A tile is 128 rows.  Scores: wavefront wv takes 16 rows, S^T = K Q^T as one 16 x 16 tile (rows = tokens,
-    //      columns = heads), the contraction over the 576 dimensions in 18 steps with the query as a pair of fp16
-    //      operands (value = hi + lo, so the fp32 query loses nothing).  Online softmax per head over the tile (the
-    //      wavefronts exchange their maxima through LDS).  Weighted sum: wavefront (kq, th) takes the latent
-    //      dimensions [128 kq, +128) and the rows [64 th, +64) of the tile: A = probabilities (fp16, from LDS),
-    //      B = the rows themselves, eight at a time transposed inside the lane.  The item with s = 0 also scores
-    //      the new token (its row is taken in fp32 from stage B).
+    //      A tile is 64 rows, read from memory once and kept in LDS for both products (read twice, the second
+    //      read of a row misses the L2 at batch 16 and the stage is bound by that traffic).  Scores: wavefronts
+    //      0..3 take 16 rows each, S^T = K Q^T as one 16 x 16 tile (rows = tokens, columns = heads), the contraction
+    //      over the 576 dimensions in 18 steps with the query as a pair of fp16 operands (value = hi + lo, so the
+    //      fp32 query loses nothing).  Online softmax per head over the tile (the wavefronts exchange their maxima
+    //      through LDS).  Weighted sum: wavefront (kq, th) takes the latent dimensions [128 kq, +128) and the rows
+    //      [32 th, +32) of the tile: A = probabilities (fp16, from LDS), B = the rows themselves, eight at a time
+    //      transposed inside the lane.  The item with s = 0 also scores the new token (its row is taken in fp32
+    //      from stage B).
     {
         h8 *qop_hi = reinterpret_cast<h8 *>(smem);                      // [kSteps][64]
         h8 *qop_lo = qop_hi + kQops;
@@ -529,6 +532,7 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
         _Float16 *sP = reinterpret_cast<_Float16 *>(s_kn + LR);         // [HT][PS]
         float *sO = s_kn + LR + HT * PS / 2;                            // [HT][L], at the end of an item
         float *s_q = sO;                                                // [HT][QS], at its start
+        _Float16 *sK = reinterpret_cast<_Float16 *>(sO);                // [kTile][KSTR] cached rows, between the two
         const int g = lane >> 4, c = lane & 15, kq = wv & 3, th = wv >> 2;
         const int ngroups = (a.nh + a.HG - 1) / a.HG;
         for (int it = w; it < B * a.NS * ngroups; it += a.W) {
@@ -536,22 +540,26 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
             const int h0 = hg * a.HG, h1 = min(h0 + a.HG, a.nh);        // the heads of this item
             const int t0 = min(s * a.tps, a.pos), t1 = min(t0 + a.tps, a.pos);
             const uint16_t *rows = a.cache + (size_t)b * a.max_seq * LR;
-            h8 kS[kSteps], kV[2][8];
-            // Rows past the range are read from its last row (finite data) and get probability 0.
-            auto issue_s = [&](int T0) {
-                const uint16_t *row = rows + (size_t)min(T0 + 16 * wv + c, t1 - 1) * LR;
+            // A tile of rows goes from memory to LDS once (a thread carries nine 16-byte pieces of it, requested a
+            // tile ahead); both products take their operands from there.  Rows past the range are read from its last
+            // row (finite data) and get probability 0.
+            constexpr int kPieces = kTile * (LR / 8) / NT;              // 9
+            h8 kr[kPieces];
+            auto request = [&](int T0) {
 #pragma unroll
-                for (int m = 0; m < kSteps; ++m) kS[m] = *reinterpret_cast<const h8 *>(row + score_dim(m, g));
+                for (int k = 0; k < kPieces; ++k) {
+                    const int pc = tid + NT * k, row = pc / (LR / 8), col = pc % (LR / 8);
+                    kr[k] = *reinterpret_cast<const h8 *>(rows + (size_t)min(T0 + row, t1 - 1) * LR + 8 * col);
+                }
             };
-            auto issue_v = [&](int T0) {
+            auto deposit = [&]() {
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        kV[ks][u] = *reinterpret_cast<const h8 *>(
-                            rows + (size_t)min(T0 + 64 * th + 32 * ks + 8 * g + u, t1 - 1) * LR + 128 * kq + 8 * c);
+                for (int k = 0; k < kPieces; ++k) {
+                    const int pc = tid + NT * k, row = pc / (LR / 8), col = pc % (LR / 8);
+                    *reinterpret_cast<h8 *>(sK + row * KSTR + 8 * col) = kr[k];
+                }
             };
-            if (t1 > t0) issue_s(t0);                                   // (uniform) the rows do not wait for the query
+            if (t1 > t0) request(t0);                                   // (uniform) the rows do not wait for the query
             lds_sync();                                                 // the previous item has left LDS
             MLA_STAMP(13);
             {
@@ -619,7 +627,6 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
                 for (int off = 1; off < 32; off <<= 1) d += __shfl_xor(d, off);
                 if (part == 0 && h0 + (tid >> 5) < h1) cf::team::put(r, a.xs + (size_t)b * a.nh + h, d, x.stamp);
             }
-            if (t1 > t0) issue_v(t0);
             lds_sync();
             MLA_STAMP(4);           // query operands built
             if (t1 > t0) {                                              // uniform over the workgroup
@@ -628,38 +635,47 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
 #pragma unroll
                 for (int jj = 0; jj < 8; ++jj) O[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
                 for (int T0 = t0; T0 < t1; T0 += kTile) {
+                    deposit();
+                    if (T0 + kTile < t1) request(T0 + kTile);
+                    lds_sync();
                     f32x4 S = {0.f, 0.f, 0.f, 0.f};                     // rows = tokens T0 + 16 wv + 4 g + rr, column = head c
+                    if (wv < kTile / 16) {                              // (uniform per wavefront)
+                        const _Float16 *krow = sK + (16 * wv + c) * KSTR;
 #pragma unroll
-                    for (int m = 0; m < kSteps; ++m) {
-                        S = mfma16(kS[m], qop_hi[m * 64 + lane], S);
-                        S = mfma16(kS[m], qop_lo[m * 64 + lane], S);
-                    }
-                    float mx = kNegBig;
+                        for (int m = 0; m < kSteps; ++m) {
+                            const h8 ka = *reinterpret_cast<const h8 *>(krow + score_dim(m, g));
+                            S = mfma16(ka, qop_hi[m * 64 + lane], S);
+                            S = mfma16(ka, qop_lo[m * 64 + lane], S);
+                        }
+                        float mx = kNegBig;
 #pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) {
-                        S[rr] = (T0 + 16 * wv + 4 * g + rr < t1) ? S[rr] : kNegBig;
-                        mx = fmaxf(mx, S[rr]);
+                        for (int rr = 0; rr < 4; ++rr) {
+                            S[rr] = (T0 + 16 * wv + 4 * g + rr < t1) ? S[rr] : kNegBig;
+                            mx = fmaxf(mx, S[rr]);
+                        }
+                        mx = fmaxf(mx, __shfl_xor(mx, 16));
+                        mx = fmaxf(mx, __shfl_xor(mx, 32));
+                        if (lane < HT) s_m[wv * HT + c] = mx;
                     }
-                    mx = fmaxf(mx, __shfl_xor(mx, 16));
-                    mx = fmaxf(mx, __shfl_xor(mx, 32));
-                    if (lane < HT) s_m[wv * HT + c] = mx;
                     lds_sync();
                     float mt = s_m[c];
 #pragma unroll
-                    for (int w8 = 1; w8 < NW; ++w8) mt = fmaxf(mt, s_m[w8 * HT + c]);
+                    for (int w4 = 1; w4 < kTile / 16; ++w4) mt = fmaxf(mt, s_m[w4 * HT + c]);
                     const float Mn = fmaxf(M, mt);                      // > kNegBig: the tile has a row inside the range
                     const float f = __builtin_amdgcn_exp2f(M - Mn);
                     M = Mn;
-                    float psum = 0.f;
-                    h4 ph;
+                    if (wv < kTile / 16) {
+                        float psum = 0.f;
+                        h4 ph;
 #pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) {
-                        const float pw = __builtin_amdgcn_exp2f(S[rr] - Mn);
-                        ph[rr] = (_Float16)pw;
-                        psum += pw;
+                        for (int rr = 0; rr < 4; ++rr) {
+                            const float pw = __builtin_amdgcn_exp2f(S[rr] - Mn);
+                            ph[rr] = (_Float16)pw;
+                            psum += pw;
+                        }
+                        lw = fmaf(lw, f, psum);
+                        *reinterpret_cast<uint2 *>(sP + c * PS + 16 * wv + 4 * g) = __builtin_bit_cast(uint2, ph);
                     }
-                    lw = fmaf(lw, f, psum);
-                    *reinterpret_cast<uint2 *>(sP + c * PS + 16 * wv + 4 * g) = __builtin_bit_cast(uint2, ph);
                     float fr[4];                                        // factor of the heads this lane accumulates
 #pragma unroll
                     for (int rr = 0; rr < 4; ++rr) fr[rr] = __shfl(f, 4 * g + rr);
@@ -668,18 +684,17 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
 #pragma unroll
                         for (int rr = 0; rr < 4; ++rr) O[jj][rr] *= fr[rr];
                     lds_sync();
+                    {
+                        const h8 pa = *reinterpret_cast<const h8 *>(sP + c * PS + 32 * th + 8 * g);
+                        h8 vr[8], f8[8];
 #pragma unroll
-                    for (int ks = 0; ks < 2; ++ks) {
-                        const h8 pa = *reinterpret_cast<const h8 *>(sP + c * PS + 64 * th + 32 * ks + 8 * g);
-                        h8 f8[8];
-                        transpose8(kV[ks], f8);
+                        for (int u = 0; u < 8; ++u)
+                            vr[u] = *reinterpret_cast<const h8 *>(sK + (32 * th + 8 * g + u) * KSTR + 128 * kq + 8 * c);
+                        transpose8(vr, f8);
 #pragma unroll
                         for (int jj = 0; jj < 8; ++jj) O[jj] = mfma16(pa, f8[jj], O[jj]);
                     }
-                    if (T0 + kTile < t1) {                              // (after the products: one tile's rows in registers)
-                        issue_s(T0 + kTile);
-                        issue_v(T0 + kTile);
-                    }
+                    lds_sync();                                         // the tile is consumed: the next one may land
                 }
                 MLA_STAMP(11);          // rows consumed
                 lw += __shfl_xor(lw, 16);
@@ -758,8 +773,10 @@ __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
                 qn = cf::team::peek(r, a.xs + (size_t)b * a.nh + head);
                 qc = cf::team::peek(r, a.xkv + (size_t)b * LR + d);
 #pragma unroll
-                for (int k = 0; k < kMaxSplits; ++k)
-                    qa[k] = cf::team::peek(r, a.x3 + (((size_t)b * a.NS + min(k, nu1 - 1)) * HT + head) * kPart + 2 + d);
+                for (int k = 0; k < kMaxSplits; ++k) {
+                    qa[k] = pair_t{0u, x.stamp};
+                    if (k < nu1) qa[k] = cf::team::peek(r, a.x3 + (((size_t)b * a.NS + k) * HT + head) * kPart + 2 + d);     // (uniform)
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 bool ok = (qn.y == x.stamp) & (qc.y == x.stamp) & ((sl >= n_used) | ((qm.y == x.stamp) & (ql.y == x.stamp)));
 #pragma unroll
@@ -916,7 +933,7 @@ void plan_splits(const cf_mla_s *t, int batch, int pos, int *ns, int *tps, int *
     if (t->max_splits > 0 && t->max_splits < cap) cap = t->max_splits;
     int per = (pos + cap - 1) / cap;
     per = (per + 15) / 16 * 16;
-    if (per < 64 && t->max_splits == 0) per = 64;     // below half a tile more ranges only add partials
+    if (per < 64 && t->max_splits == 0) per = 64;     // below a tile more ranges only add partials
     if (per < 16) per = 16;
     *tps = per;
     const int n = (pos + per - 1) / per;
