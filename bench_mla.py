@@ -27,7 +27,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0)
     ap.add_argument("--ranges", type=int, default=0,
                     help="limit on the token ranges per batch row (cf_mla_set_splits); a non-zero value also selects the "
-                         "token-range kernel at batch 1 and 2")
+                         "token-range kernel at batch 1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     import numpy as np

@@ -308,11 +308,11 @@ int cf_team_set_spin_limit(cf_team t, int32_t spin_limit_us);
  * head, all resident), batch <= 16 (the batch of Appendix C), nope_dim a multiple of 8 up to 128, v_head_dim a
  * multiple of 8 up to 128, d_model a multiple of 32, at most 8192 and at most 128 * n_heads: cf_mla_create returns
  * CF_EUNSUPPORTED otherwise.  cf_mla_status is cf_status for this handle.
- * Two kernels: up to batch 2 every head scans the cached rows itself (16 workgroups per head, vector arithmetic);
- *   from batch 3 on the unit of work of the attention stage is a range of cached rows of one batch row, for a group of
+ * Two kernels: at batch 1 every head scans the cached rows itself (16 workgroups per head, vector arithmetic);
+ *   from batch 2 on the unit of work of the attention stage is a range of cached rows of one batch row, for a group of
  *   heads at once, as two products on MFMA tiles.
  * cf_mla_set_splits: upper limit on the number of token ranges a batch row's cached rows are divided into; 0 = chosen
- *   by the library, at most 32.  A non-zero limit also selects the token-range kernel at batch 1 and 2.  For tests of
+ *   by the library, at most 32.  A non-zero limit also selects the token-range kernel at batch 1.  For tests of
  *   the range logic and for measurements; CF_EINVAL outside 0..32.
  * cf_mla_debug_export: intermediate results of the last call on this handle, copied to the host buffer as fp32 after
  *   synchronising `stream`: what = 0: q_lat [batch, n_heads, kv_lora_rank] (Alg. 4's absorbed query); 1: q_rope

@@ -54,7 +54,7 @@ constexpr int kPart = 2 + L;        // slots of an attention partial per head: m
 constexpr int kMaxSplits = 32;      // token ranges per batch row at most
 constexpr size_t kLdsFloats = 29440;    // 115 KiB: the largest stage (C: query operands, a tile of rows, the rest)
 constexpr float kNegBig = -1.0e30f;
-constexpr int kHeadsBatch = 2;      // up to this batch cf_mla_decode runs the head-team kernel (measured cross-over)
+constexpr int kHeadsBatch = 1;      // up to this batch cf_mla_decode runs the head-team kernel (measured cross-over)
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));

@@ -79,9 +79,9 @@ def oracle(shape, inp, pos):
 
 
 def both_kernels(batch):
-    """Range limits to run a case with: 0 = the library's choice (the head-team kernel up to batch 2), 32 = the
+    """Range limits to run a case with: 0 = the library's choice (the head-team kernel at batch 1), 32 = the
     token-range kernel with its default ranges."""
-    return (0, 32) if batch <= 2 else (0,)
+    return (0, 32) if batch <= 1 else (0,)
 
 
 CASES = [
@@ -108,13 +108,15 @@ def test_small_shapes_match_oracle(name, shape, batch, kv_len):
         check(run(shape, inp, kv_len, max_splits), ref, inp, kv_len, "%s (range limit %d)" % (name, max_splits))
 
 
-@pytest.mark.parametrize("pos", [0, 1, 15, 16, 17, 127, 128])
+@pytest.mark.parametrize("pos", [0, 1, 15, 16, 17, 63, 64, 65, 127, 128, 129])
 def test_edge_positions(pos):
-    """Empty cache, fewer tokens than members of a team, the boundaries of the token split."""
+    """Empty cache, fewer tokens than members of a team, the boundaries of the token split and of the 64-row tile."""
     shape = cf_inputs.MlaShape("s", 128, 2, 32, 64, 512, 32, 10000.0, 0)
-    for max_splits in both_kernels(2):
-        inp = cf_inputs.make_mla_inputs(shape, seed=62 + pos, batch=2, kv_len=pos)
-        check(run(shape, inp, pos, max_splits), oracle(shape, inp, pos), inp, pos, "pos %d (range limit %d)" % (pos, max_splits))
+    for batch in (1, 2):
+        for max_splits in both_kernels(batch):
+            inp = cf_inputs.make_mla_inputs(shape, seed=62 + pos, batch=batch, kv_len=pos)
+            check(run(shape, inp, pos, max_splits), oracle(shape, inp, pos), inp, pos,
+                  "pos %d batch %d (range limit %d)" % (pos, batch, max_splits))
 
 
 @pytest.mark.parametrize("max_splits,kv_len,batch", [(1, 700, 2), (3, 700, 2), (32, 700, 1), (5, 1000, 6), (1, 129, 16)])
