@@ -3,8 +3,6 @@
 #include "cf_params.h"
 
 #include <cmath>
-#include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -257,15 +255,6 @@ int cf_create(const cf_config *cfg, cf_handle *out)
     if (!h) return CF_ENOMEM;
     h->cfg = c;
     h->G = G;
-    // CF_BALANCE="rows,tokens": half the length difference between the splits of workgroups on even
-    // and odd dies, for experiments; "-1" keeps the plain workgroup mapping and equal splits
-    if (const char *e = std::getenv("CF_BALANCE")) {
-        int r = 0, t = 0;
-        const int n = std::sscanf(e, "%d,%d", &r, &t);
-        if (n >= 1) h->balance_rows = r < 0 ? -1 : (r / 8) * 8;
-        if (n >= 2) h->balance_tokens = t < 0 ? 0 : t;
-        if (h->balance_rows < 0) h->balance_tokens = 0;
-    }
     h->nqkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     h->nch = ceil_div(c.d_model, cf::kOutChunk);
 
