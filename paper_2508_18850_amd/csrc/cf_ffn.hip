@@ -19,6 +19,7 @@
 // The first rows of W3 are requested before the last pieces of stage A are consumed, so the memory pipe does not
 // drain at the stage boundary.  All waits are bounded (CF_ETIMEOUT); all workgroups have to be resident at once.
 #include "../../include/cfdecode.h"
+#include "cf_mfma_device.h"
 #include "cf_team_device.h"
 
 #include <cmath>
@@ -33,10 +34,15 @@ constexpr int NT = 512;
 constexpr int NW = NT / 64;
 constexpr int kChunk = 512;            // columns of one wavefront load: 64 lanes x 8 values
 constexpr int kCounterStride = 16;
-constexpr int kMaxBatch = 4;
+constexpr int kMaxBatch = 16;          // the batch of Appendix C
+constexpr int kVectorBatch = 4;        // up to this batch the vector-unit kernel runs, above it the MFMA kernel
+constexpr int kNC = 16;                // MFMA kernel: column slices of the output (workgroups per slice of hidden units)
 constexpr uint32_t kNoLoad = 0x80000000u;
 
-typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+using cf::mfma::f32x4;
+using cf::mfma::h8;
+using cf::mfma::mfma16;
+using cf::mfma::transpose8;
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 
 struct FfnArgs {
@@ -48,6 +54,9 @@ struct FfnArgs {
     int D, F, B, W, act;
     int nrmax;                         // most hidden units a workgroup owns
     long long spin_ticks;
+    // MFMA kernel only
+    size_t xg, xp;                     // first slot of g [d_ff][B] and of the partial outputs [NF][B][D]
+    int NF, CW, nRp;                   // slices of hidden units; columns per column slice; units of a slice, padded to 32
 };
 
 struct Stream {
@@ -338,6 +347,234 @@ __global__ void __launch_bounds__(NT) fused_ffn(const FfnArgs a)
     if (tid == 0) a.counters[(size_t)w * kCounterStride] = cnt;
 }
 
+// ---------------------------------------------------------------------------------------------------------------------
+// Batch 5..16: the same block on matrix cores, with the work cut in two directions.  One partial output per workgroup
+// (as above) would be W x B x d_model stamped pairs, 134 MB at batch 16; here the W workgroups form NF = W / 16 slices
+// of hidden units times 16 slices of output columns:
+//   A  as above, workgroup w owns the hidden units [w F / W, (w + 1) F / W): h = W1 z, u = W2 z as 16 x 16 x 32 MFMA
+//      steps, A = sixteen rows of the weights (a lane reads 32 contiguous bytes of a row per pair of steps, four
+//      lanes one 128-byte line), B = z in fp16 as given, held in registers for the 512 columns of a wavefront; the
+//      eight wavefronts (eight column pieces) are added through LDS; g = sigma(h) u goes to stamped slots [d_ff][B]
+//   G  workgroup (fi, ci) fetches g of slice fi (the units of 16 workgroups) and keeps it in LDS as fp16 pairs
+//      (value = hi + lo, so fp32 g loses nothing)
+//   B  partial out [B][columns of slice ci] = g W3[slice fi]: A = g, B = eight rows of a 16-byte piece of W3
+//      transposed inside the lane; wavefront (cg, ks) takes 128 columns and every (8 / groups)-th step of 32 units;
+//      the wavefronts of a column group are added through LDS; the partial goes to slots [NF][B][d_model]
+//   C  workgroup (fi, ci) adds the NF partials of 1/NF of the columns of slice ci, in slice order, and writes fp16.
+// Two hand-overs instead of one, NF partials per output value instead of W.
+template <int NTL>     // row tiles of 16 hidden units a workgroup can own (4 or 8)
+__global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
+{
+    extern __shared__ float smem[];
+    const int tid = threadIdx.x, lane = tid & 63, w = blockIdx.x;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+    const int D = a.D, B = a.B;
+    const int r0 = (int)((long long)w * a.F / a.W), nr = (int)((long long)(w + 1) * a.F / a.W) - r0;
+    const int fi = w / kNC, ci = w % kNC;
+    const int R0 = (int)((long long)(fi * kNC) * a.F / a.W), nR = (int)((long long)(fi * kNC + kNC) * a.F / a.W) - R0;
+
+    unsigned long long launches;
+    asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)"
+                 : "=s"(launches)
+                 : "s"(a.counters + (size_t)w * kCounterStride)
+                 : "memory");
+    const unsigned long long cnt = launches + 1ull;
+    const Exchange x = {a.slots, 0, (uint32_t)(cnt + (cnt >> 32)), a.err, a.spin_ticks};
+    const __amdgpu_buffer_rsrc_t xr = cf::team::slots_rsrc(x);
+    const uint32_t wbytes = (uint32_t)((size_t)a.F * D * 2);
+    const Stream W1(a.w1, wbytes), W2(a.w2, wbytes), W3(a.w3, wbytes);
+
+    // ---- stage A.  Contraction slot (step m, group g, element e) of a 512-column piece stands for column
+    //      64 (m / 2) + 16 g + 8 (m % 2) + e of the piece.
+    {
+        const int NCK = (D + kChunk - 1) / kChunk;
+        f32x4 acc[NTL][2];                                        // [tile][matrix]: units 16 t + 4 g + rr, batch row c
+#pragma unroll
+        for (int t = 0; t < NTL; ++t) acc[t][0] = acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const uint32_t lane_off = (uint32_t)c * (uint32_t)D * 2u + 32u * g;
+        for (int piece = wv; piece < NCK; piece += NW) {          // (uniform per wavefront)
+            h8 zb[16];
+            uint32_t colok = 0;                                   // bit m: this lane's columns of step m exist
+#pragma unroll
+            for (int m = 0; m < 16; ++m) {
+                const int col = kChunk * piece + 64 * (m >> 1) + 16 * g + 8 * (m & 1);
+                colok |= col < D ? 1u << m : 0u;
+                uint4 v = {0u, 0u, 0u, 0u};
+                if (c < B && col < D) v = *reinterpret_cast<const uint4 *>(a.z + (size_t)c * D + col);
+                zb[m] = __builtin_bit_cast(h8, v);
+            }
+            // a task is half the steps of one tile of one matrix: eight loads, eight products; two tasks in flight
+            auto request = [&](h8(&wr)[8], int task) {
+                const int t = task >> 2, mat = (task >> 1) & 1, half = task & 1;
+                const bool live = 16 * t + c < nr;                // rows past the workgroup's units are not read
+                const uint32_t soff = 16 * t < nr ? (uint32_t)(((size_t)(r0 + 16 * t) * D + (size_t)kChunk * piece) * 2) : 0u;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int m = 8 * half + k;
+                    const uint32_t voff = (live && (colok >> m & 1u)) ? lane_off + 128u * (m >> 1) + 16u * (m & 1) : kNoLoad;
+                    wr[k] = mat ? W2.ld(voff, soff) : W1.ld(voff, soff);
+                }
+            };
+            auto consume = [&](const h8(&wr)[8], int task) {
+                const int t = task >> 2, mat = (task >> 1) & 1, half = task & 1;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) acc[t][mat] = mfma16(wr[k], zb[8 * half + k], acc[t][mat]);
+            };
+            h8 wa[8], wb[8];
+            request(wa, 0);
+            request(wb, 1);
+#pragma unroll
+            for (int task = 0; task < 4 * NTL; task += 2) {
+                consume(wa, task);
+                if (task + 2 < 4 * NTL) request(wa, task + 2);
+                consume(wb, task + 1);
+                if (task + 3 < 4 * NTL) request(wb, task + 3);
+            }
+        }
+        float4 *part = reinterpret_cast<float4 *>(smem);          // [NW][NTL][2][64 lanes]
+#pragma unroll
+        for (int t = 0; t < NTL; ++t)
+#pragma unroll
+            for (int mat = 0; mat < 2; ++mat)
+                part[((wv * NTL + t) * 2 + mat) * 64 + lane] =
+                    make_float4(acc[t][mat][0], acc[t][mat][1], acc[t][mat][2], acc[t][mat][3]);
+        lds_barrier();
+        for (int e = tid; e < nr * B; e += NT) {                  // consecutive threads, consecutive slots
+            const int unit = e / B, b = e - unit * B;
+            const int t = unit >> 4, l = 16 * ((unit >> 2) & 3) + b, rr = unit & 3;
+            float h = 0.f, u = 0.f;
+#pragma unroll
+            for (int w8 = 0; w8 < NW; ++w8) {
+                h += smem[(((w8 * NTL + t) * 2 + 0) * 64 + l) * 4 + rr];
+                u += smem[(((w8 * NTL + t) * 2 + 1) * 64 + l) * 4 + rr];
+            }
+            cf::team::put(xr, a.xg + (size_t)(r0 + unit) * B + b, activate(h, a.act) * u, x.stamp);
+        }
+        lds_barrier();
+    }
+
+    // ---- stage B set-up: the first rows of W3 are requested before g is waited for
+    const int CW = a.CW, c0 = ci * CW, CWi = max(0, min(CW, D - c0));
+    const int ncg = (CW + 127) / 128, ncgp = ncg <= 1 ? 1 : ncg <= 2 ? 2 : ncg <= 4 ? 4 : 8, KSPL = NW / ncgp;
+    const int cg = wv % ncgp, ks = wv / ncgp;
+    const int nst = (nR + 31) / 32;
+    const int colp = 128 * cg + 8 * c;                            // first of this lane's eight columns in the slice
+    const bool colok = colp < CWi;
+    const uint32_t base3 = (uint32_t)(8 * g) * (uint32_t)D * 2u + (uint32_t)(c0 + colp) * 2u;
+    auto request3 = [&](h8(&wr)[8], int s) {
+        const uint32_t soff = s < nst ? (uint32_t)((size_t)(R0 + 32 * s) * D * 2) : 0u;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool live = colok && s < nst && 32 * s + 8 * g + u < nR;
+            wr[u] = W3.ld(live ? base3 + (uint32_t)u * (uint32_t)D * 2u : kNoLoad, soff);
+        }
+    };
+    h8 ra[8], rb[8];
+    request3(ra, ks);
+    request3(rb, ks + KSPL);
+
+    // ---- G: g of the slice into LDS as fp16 pairs [16][nRp] (zero past the batch and past the slice)
+    _Float16 *ghi = reinterpret_cast<_Float16 *>(smem), *glo = ghi + 16 * a.nRp;
+    for (int i = tid; i < 16 * a.nRp; i += NT) reinterpret_cast<uint32_t *>(smem)[i] = 0u;
+    lds_barrier();
+    for (int i0 = 0; i0 < nR * B; i0 += 8 * NT) {
+        const int cntv = min(8 * NT, nR * B - i0);
+        pair_t q[8];
+        long long t0 = 0;
+        for (;;) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                q[k] = pair_t{0u, x.stamp};
+                if (NT * k < cntv) q[k] = cf::team::peek(xr, a.xg + (size_t)R0 * B + i0 + min(tid + NT * k, cntv - 1));   // (uniform)
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            bool ok = true;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) ok &= q[k].y == x.stamp;
+            if (ok || cf::team::gave_up(x, t0)) break;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int i = i0 + tid + NT * k;
+            if (tid + NT * k < cntv) {
+                const int unit = i / B, b = i - unit * B;
+                const float v = __builtin_bit_cast(float, q[k].x);
+                const _Float16 hi = (_Float16)v;
+                ghi[b * a.nRp + unit] = hi;
+                glo[b * a.nRp + unit] = (_Float16)(v - (float)hi);
+            }
+        }
+    }
+    lds_barrier();
+
+    // ---- stage B
+    f32x4 o[8];                                                   // [jj][rr]: batch row 4 g + rr, column colp + jj
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) o[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto consume3 = [&](const h8(&wr)[8], int s) {
+        const int at = c * a.nRp + 32 * min(s, nst - 1) + 8 * g;  // (a step past the end has zero weights)
+        const h8 ah = *reinterpret_cast<const h8 *>(ghi + at), al = *reinterpret_cast<const h8 *>(glo + at);
+        h8 f8[8];
+        transpose8(wr, f8);
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            o[jj] = mfma16(ah, f8[jj], o[jj]);
+            o[jj] = mfma16(al, f8[jj], o[jj]);
+        }
+    };
+    for (int s = ks; s < nst; s += 2 * KSPL) {                    // (uniform per wavefront; no barrier inside)
+        consume3(ra, s);
+        request3(ra, s + 2 * KSPL);
+        consume3(rb, s + KSPL);
+        request3(rb, s + 3 * KSPL);
+    }
+    lds_barrier();                                                // g is consumed: the sums of the wavefronts overlay it
+    {
+        const int CWp = 128 * ncgp;
+        float *red = smem;                                        // [KSPL][16][CWp]
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            float *dst = red + (size_t)(ks * 16 + 4 * g + rr) * CWp + colp;
+            *reinterpret_cast<float4 *>(dst) = make_float4(o[0][rr], o[1][rr], o[2][rr], o[3][rr]);
+            *reinterpret_cast<float4 *>(dst + 4) = make_float4(o[4][rr], o[5][rr], o[6][rr], o[7][rr]);
+        }
+        lds_barrier();
+        for (int e = tid; e < B * CWi; e += NT) {
+            const int b = e / CWi, col = e - b * CWi;
+            float sum = 0.f;
+            for (int k = 0; k < KSPL; ++k) sum += red[(size_t)(k * 16 + b) * CWp + col];
+            cf::team::put(xr, a.xp + ((size_t)fi * B + b) * D + c0 + col, sum, x.stamp);
+        }
+    }
+
+    // ---- stage C: columns [c0 + fi cpf, + cpf) of slice ci, summed over the NF slices of hidden units in slice order
+    {
+        const int cpf = (CW + a.NF - 1) / a.NF;
+        const int q0 = fi * cpf, nq = max(0, min(cpf, CWi - q0));
+        if (tid < nq * B) {
+            const int b = tid / nq, col = c0 + q0 + tid - b * nq;
+            pair_t q[16];
+            long long t0 = 0;
+            for (;;) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) q[k] = cf::team::peek(xr, a.xp + ((size_t)min(k, a.NF - 1) * B + b) * D + col);
+                __builtin_amdgcn_sched_barrier(0);
+                bool ok = true;
+#pragma unroll
+                for (int k = 0; k < 16; ++k) ok &= q[k].y == x.stamp;
+                if (ok || cf::team::gave_up(x, t0)) break;
+            }
+            float sum = 0.f;
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                if (k < a.NF) sum += __builtin_bit_cast(float, q[k].x);
+            a.out[(size_t)b * D + col] = __builtin_bit_cast(uint16_t, (_Float16)sum);
+        }
+    }
+    if (tid == 0) a.counters[(size_t)w * kCounterStride] = cnt;
+}
+
 using KernelFn = void (*)(const FfnArgs);
 KernelFn pick(int bt, int d_model)
 {
@@ -345,12 +582,15 @@ KernelFn pick(int bt, int d_model)
     return bt == 1 ? fused_ffn<1, 2> : bt == 2 ? fused_ffn<2, 2> : fused_ffn<4, 2>;
 }
 int batch_tile(int b) { return b <= 1 ? 1 : b <= 2 ? 2 : 4; }
+KernelFn pick_tiles(int nrmax) { return nrmax <= 64 ? fused_ffn_tiles<4> : fused_ffn_tiles<8>; }
 
 }  // namespace
 
 struct cf_ffn_s {
     cf_ffn_config cfg;
     int W = 0, nrmax = 0;
+    int NF = 0, CW = 0, nRp = 0;       // MFMA kernel (max_batch > 4)
+    size_t xg = 0, xp = 0, lds_tiles = 0;
     char *ws = nullptr;
     size_t ws_bytes = 0;
     uint32_t *err = nullptr;
@@ -386,8 +626,9 @@ int cf_ffn_create(const cf_ffn_config *cfg, cf_ffn *out)
     const int W = c.d_ff < cus ? c.d_ff : cus;
     const int nrmax = (c.d_ff + W - 1) / W;
     const int cpw = (c.d_model + W - 1) / W;
-    if ((size_t)cpw * c.max_batch > (size_t)NT) return CF_EUNSUPPORTED;       // stage C: one thread per output value
-    for (int bt = 1; bt <= kMaxBatch; bt *= 2) {
+    const int vbatch = c.max_batch < kVectorBatch ? c.max_batch : kVectorBatch;
+    if ((size_t)cpw * vbatch > (size_t)NT) return CF_EUNSUPPORTED;            // stage C: one thread per output value
+    for (int bt = 1; bt <= kVectorBatch; bt *= 2) {
         if (bt / 2 >= c.max_batch) break;
         const size_t lds = lds_bytes_of(c, bt, nrmax);
         if (lds > 160 * 1024 - 256) return CF_EUNSUPPORTED;
@@ -398,13 +639,36 @@ int cf_ffn_create(const cf_ffn_config *cfg, cf_ffn *out)
             per_cu < 1)
             return CF_EUNSUPPORTED;                                             // all workgroups resident, one per compute unit
     }
+    // the MFMA kernel: 16 column slices times W / 16 slices of hidden units
+    const int NF = W / kNC, CW = ((c.d_model + kNC - 1) / kNC + 7) / 8 * 8, nRp = (kNC * nrmax + 31) / 32 * 32;
+    size_t lds_tiles = 0;
+    if (c.max_batch > kVectorBatch) {
+        if (W % kNC || nrmax > 128 || (size_t)((CW + NF - 1) / NF) * c.max_batch > (size_t)NT) return CF_EUNSUPPORTED;
+        const size_t part = (size_t)(nrmax <= 64 ? 4 : 8) * 16384, gbytes = 64 * (size_t)nRp, red = 65536;
+        lds_tiles = part > gbytes ? part : gbytes;
+        lds_tiles = lds_tiles > red ? lds_tiles : red;
+        int per_cu = 0;
+        if (lds_tiles > 160 * 1024 - 256 ||
+            hipFuncSetAttribute(reinterpret_cast<const void *>(pick_tiles(nrmax)), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_tiles) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(pick_tiles(nrmax)), NT,
+                                                         lds_tiles) != hipSuccess ||
+            per_cu < 1)
+            return CF_EUNSUPPORTED;
+    }
     cf_ffn t = new (std::nothrow) cf_ffn_s();
     if (!t) return CF_ENOMEM;
     t->cfg = c;
     t->W = W;
     t->nrmax = nrmax;
+    t->NF = NF, t->CW = CW, t->nRp = nRp, t->lds_tiles = lds_tiles;
+    t->xg = 0;
+    t->xp = (size_t)c.d_ff * c.max_batch;
     const size_t head = (256 + (size_t)W * kCounterStride * sizeof(unsigned long long) + 255) / 256 * 256;
-    const size_t slot_bytes = (size_t)W * c.max_batch * c.d_model * sizeof(uint64_t);
+    const size_t vb = c.max_batch < kVectorBatch ? c.max_batch : kVectorBatch;
+    const size_t slots_vector = (size_t)W * vb * c.d_model;                   // the two kernels use the same slots, never together
+    const size_t slots_tiles = c.max_batch > kVectorBatch ? t->xp + (size_t)NF * c.max_batch * c.d_model : 0;
+    const size_t slot_bytes = (slots_vector > slots_tiles ? slots_vector : slots_tiles) * sizeof(uint64_t);
     if (slot_bytes > 0xfffffff0ull) {
         delete t;
         return CF_EUNSUPPORTED;
@@ -454,8 +718,14 @@ int cf_ffn_decode(cf_ffn t, int32_t batch, const void *z, const void *W1, const 
     a.D = t->cfg.d_model, a.F = t->cfg.d_ff, a.B = batch, a.W = t->W, a.act = t->cfg.activation;
     a.nrmax = t->nrmax;
     a.spin_ticks = t->spin_ticks;
-    const int bt = batch_tile(batch);
-    hipLaunchKernelGGL(pick(bt, t->cfg.d_model), dim3(t->W), dim3(NT), lds_bytes_of(t->cfg, bt, t->nrmax), static_cast<hipStream_t>(stream), a);
+    if (batch > kVectorBatch) {
+        a.xg = t->xg, a.xp = t->xp, a.NF = t->NF, a.CW = t->CW, a.nRp = t->nRp;
+        hipLaunchKernelGGL(pick_tiles(t->nrmax), dim3(t->W), dim3(NT), t->lds_tiles, static_cast<hipStream_t>(stream), a);
+    } else {
+        const int bt = batch_tile(batch);
+        hipLaunchKernelGGL(pick(bt, t->cfg.d_model), dim3(t->W), dim3(NT), lds_bytes_of(t->cfg, bt, t->nrmax),
+                           static_cast<hipStream_t>(stream), a);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         t->last_hip = (int)e;

@@ -19,6 +19,7 @@
 //
 // Each stage requests its weights (or cached rows) before it waits for its input.  All waits are bounded
 // (CF_ETIMEOUT), all workgroups have to be resident at once.
+#include "cf_mfma_device.h"
 #include "cf_mla_internal.h"
 #include "cf_rope_device.h"
 #include "cf_team_device.h"
@@ -56,10 +57,12 @@ constexpr size_t kLdsFloats = 29440;    // 115 KiB: the largest stage (C: query 
 constexpr float kNegBig = -1.0e30f;
 constexpr int kHeadsBatch = 1;      // up to this batch cf_mla_decode runs the head-team kernel (measured cross-over)
 
-typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+using cf::mfma::f32x4;
+using cf::mfma::h8;
+using cf::mfma::mfma16;
+using cf::mfma::transpose8;
+using cf::mfma::u32x4;
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct MlaArgs {
     const uint16_t *x, *wq, *wkv, *wup, *wdown, *wo;
@@ -79,31 +82,6 @@ struct MlaArgs {
 
 __device__ __forceinline__ float h2f(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
 __device__ __forceinline__ uint16_t f2h(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
-
-// v_mfma_f32_16x16x32_f16.  Lane l holds, of A, row l % 16 and eight values of the contraction index for group
-// l / 16; of B, column l % 16 and the same eight contraction values; of the result, column l % 16 and rows
-// 4 * (l / 16) + 0..3.
-__device__ __forceinline__ f32x4 mfma16(const h8 &a, const h8 &b, const f32x4 &c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
-}
-
-// w[u] = row u, eight adjacent columns  ->  f[c] = column c, rows 0..7 (8 x 8 transpose of 16-bit values in a lane)
-__device__ __forceinline__ void transpose8(const h8 *w, h8 (&f)[8])
-{
-#pragma unroll
-    for (int c2 = 0; c2 < 4; ++c2) {
-        u32x4 e, o;
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            const uint32_t lo = __builtin_bit_cast(u32x4, w[2 * d])[c2], hi = __builtin_bit_cast(u32x4, w[2 * d + 1])[c2];
-            e[d] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);    // {lo.low half, hi.low half}
-            o[d] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);    // {lo.high half, hi.high half}
-        }
-        f[2 * c2] = __builtin_bit_cast(h8, e);
-        f[2 * c2 + 1] = __builtin_bit_cast(h8, o);
-    }
-}
 
 // Sums of NV sets of n <= 16 stamped values each: set v is idx[v], idx[v] + stride, ... (added in that order).
 // All NV * 16 polls are in flight together: one round trip when the values are there.

@@ -66,8 +66,27 @@ def test_batches(batch):
     _run(SMALL[4], batch, 1, seed=210 + batch, scale_rows=True, max_batch=4)
 
 
+@pytest.mark.parametrize("shape", SMALL[:6], ids=[s.name for s in SMALL[:6]])
+@pytest.mark.parametrize("batch", [5, 16])
+def test_tile_kernel_small_shapes(shape, batch):
+    """Batch above 4 runs the MFMA kernel: ragged d_model, one to twelve column pieces, one to four column groups per
+    slice, slices of hidden units that end inside a 32-unit step."""
+    _run(shape, batch, batch % 2, seed=220 + batch, scale_rows=True)
+
+
+@pytest.mark.parametrize("batch", [7, 9, 12])
+def test_tile_kernel_batches(batch):
+    _run(cf_inputs.FfnShape("f_h", 2048, 2500), batch, 0, seed=230 + batch, scale_rows=True, max_batch=16)
+
+
 def test_two_calls_in_a_row_and_a_smaller_batch():
     _run(SMALL[0], 2, 0, seed=300, max_batch=4, calls=3)
+
+
+def test_both_kernels_on_one_handle():
+    """A handle for batch 16 runs the vector kernel at batch 3 and the MFMA kernel at batch 6, on the same slots."""
+    _run(SMALL[1], 6, 0, seed=310, max_batch=16, calls=2)
+    _run(SMALL[1], 3, 0, seed=311, max_batch=16, calls=2)
 
 
 @pytest.mark.parametrize("name", ["llama2_7b", "llama3_8b", "llama2_70b"])
@@ -77,6 +96,11 @@ def test_full_size(name):
 
 def test_full_size_batch4():
     _run(cf_inputs.FFN_SHAPES["llama2_7b"], 4, 0, seed=401, scale_rows=True)
+
+
+@pytest.mark.parametrize("name,batch", [("llama2_7b", 16), ("llama3_8b", 8), ("llama2_70b", 16)])
+def test_full_size_tile_kernel(name, batch):
+    _run(cf_inputs.FFN_SHAPES[name], batch, 0, seed=402, scale_rows=True)
 
 
 def test_closed_forms_on_the_gpu():
@@ -104,7 +128,7 @@ def test_refused_arguments():
         with pytest.raises(CfError) as e:
             FfnBlock(*args)
         assert e.value.code == -1
-    for args in ((512, 64, 5, 0), (16384, 64, 1, 0)):
+    for args in ((512, 64, 17, 0), (16384, 64, 1, 0), (512, 100, 5, 0)):
         with pytest.raises(CfError) as e:
             FfnBlock(*args)
         assert e.value.code == -2
