@@ -35,7 +35,9 @@ constexpr int NW = NT / 64;
 constexpr int kChunk = 512;            // columns of one wavefront load: 64 lanes x 8 values
 constexpr int kCounterStride = 16;
 constexpr int kMaxBatch = 16;          // the batch of Appendix C
-constexpr int kVectorBatch = 4;        // up to this batch the vector-unit kernel runs, above it the MFMA kernel
+constexpr int kVectorBatch = 4;        // the largest batch of the vector-unit kernel
+constexpr int kTilesFrom = 3;          // from this batch on the MFMA kernel runs where the shape allows it (measured:
+                                       // Llama-2-7B shape, batch 2 / 3 / 4: 52.4 / 73.1 / 75.2 us against 55.5 / 56.3 / 57.0)
 constexpr int kNC = 16;                // MFMA kernel: column slices of the output (workgroups per slice of hidden units)
 constexpr uint32_t kNoLoad = 0x80000000u;
 
@@ -642,8 +644,9 @@ int cf_ffn_create(const cf_ffn_config *cfg, cf_ffn *out)
     // the MFMA kernel: 16 column slices times W / 16 slices of hidden units
     const int NF = W / kNC, CW = ((c.d_model + kNC - 1) / kNC + 7) / 8 * 8, nRp = (kNC * nrmax + 31) / 32 * 32;
     size_t lds_tiles = 0;
-    if (c.max_batch > kVectorBatch) {
-        if (W % kNC || nrmax > 128 || (size_t)((CW + NF - 1) / NF) * c.max_batch > (size_t)NT) return CF_EUNSUPPORTED;
+    const bool tiles_fit = W % kNC == 0 && nrmax <= 128 && (size_t)((CW + (NF > 0 ? NF : 1) - 1) / (NF > 0 ? NF : 1)) * c.max_batch <= (size_t)NT;
+    if (c.max_batch > kVectorBatch && !tiles_fit) return CF_EUNSUPPORTED;
+    if (c.max_batch >= kTilesFrom && tiles_fit) {
         const size_t part = (size_t)(nrmax <= 64 ? 4 : 8) * 16384, gbytes = 64 * (size_t)nRp, red = 65536;
         lds_tiles = part > gbytes ? part : gbytes;
         lds_tiles = lds_tiles > red ? lds_tiles : red;
@@ -667,7 +670,7 @@ int cf_ffn_create(const cf_ffn_config *cfg, cf_ffn *out)
     const size_t head = (256 + (size_t)W * kCounterStride * sizeof(unsigned long long) + 255) / 256 * 256;
     const size_t vb = c.max_batch < kVectorBatch ? c.max_batch : kVectorBatch;
     const size_t slots_vector = (size_t)W * vb * c.d_model;                   // the two kernels use the same slots, never together
-    const size_t slots_tiles = c.max_batch > kVectorBatch ? t->xp + (size_t)NF * c.max_batch * c.d_model : 0;
+    const size_t slots_tiles = lds_tiles ? t->xp + (size_t)NF * c.max_batch * c.d_model : 0;
     const size_t slot_bytes = (slots_vector > slots_tiles ? slots_vector : slots_tiles) * sizeof(uint64_t);
     if (slot_bytes > 0xfffffff0ull) {
         delete t;
@@ -718,7 +721,7 @@ int cf_ffn_decode(cf_ffn t, int32_t batch, const void *z, const void *W1, const 
     a.D = t->cfg.d_model, a.F = t->cfg.d_ff, a.B = batch, a.W = t->W, a.act = t->cfg.activation;
     a.nrmax = t->nrmax;
     a.spin_ticks = t->spin_ticks;
-    if (batch > kVectorBatch) {
+    if (batch >= kTilesFrom && t->lds_tiles) {
         a.xg = t->xg, a.xp = t->xp, a.NF = t->NF, a.CW = t->CW, a.nRp = t->nRp;
         hipLaunchKernelGGL(pick_tiles(t->nrmax), dim3(t->W), dim3(NT), t->lds_tiles, static_cast<hipStream_t>(stream), a);
     } else {
