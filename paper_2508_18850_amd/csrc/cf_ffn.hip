@@ -349,6 +349,18 @@ __global__ void __launch_bounds__(NT) fused_ffn(const FfnArgs a)
     if (tid == 0) a.counters[(size_t)w * kCounterStride] = cnt;
 }
 
+// Stage time stamps of every workgroup, only in builds with -DCF_STAMPS=1 (the profiling library).
+#ifndef CF_STAMPS
+#define CF_STAMPS 0
+#endif
+#if CF_STAMPS
+constexpr int kFfnStamps = 16;
+__device__ unsigned long long g_ffn_ts[256 * kFfnStamps];
+#define FFN_STAMP(k) do { if (threadIdx.x == 0) s_ts[k] = wall_clock64(); } while (0)
+#else
+#define FFN_STAMP(k)
+#endif
+
 // ---------------------------------------------------------------------------------------------------------------------
 // Batch 5..16: the same block on matrix cores, with the work cut in two directions.  One partial output per workgroup
 // (as above) would be W x B x d_model stamped pairs, 134 MB at batch 16; here the W workgroups form NF = W / 16 slices
@@ -364,7 +376,7 @@ __global__ void __launch_bounds__(NT) fused_ffn(const FfnArgs a)
 //      the wavefronts of a column group are added through LDS; the partial goes to slots [NF][B][d_model]
 //   C  workgroup (fi, ci) adds the NF partials of 1/NF of the columns of slice ci, in slice order, and writes fp16.
 // Two hand-overs instead of one, NF partials per output value instead of W.
-template <int NTL>     // row tiles of 16 hidden units a workgroup can own (4 or 8)
+template <int NTL>     // row tiles of 16 hidden units a workgroup owns at most (1..8)
 __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
 {
     extern __shared__ float smem[];
@@ -375,6 +387,11 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
     const int r0 = (int)((long long)w * a.F / a.W), nr = (int)((long long)(w + 1) * a.F / a.W) - r0;
     const int fi = w / kNC, ci = w % kNC;
     const int R0 = (int)((long long)(fi * kNC) * a.F / a.W), nR = (int)((long long)(fi * kNC + kNC) * a.F / a.W) - R0;
+#if CF_STAMPS
+    __shared__ unsigned long long s_ts[kFfnStamps];
+    if (tid < kFfnStamps) s_ts[tid] = 0;
+#endif
+    FFN_STAMP(0);
 
     unsigned long long launches;
     asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)"
@@ -434,6 +451,7 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
                 if (task + 3 < 4 * NTL) request(wb, task + 3);
             }
         }
+        FFN_STAMP(1);       // products of stage A done
         float4 *part = reinterpret_cast<float4 *>(smem);          // [NW][NTL][2][64 lanes]
 #pragma unroll
         for (int t = 0; t < NTL; ++t)
@@ -455,6 +473,7 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
         }
         lds_barrier();
     }
+    FFN_STAMP(2);           // g published
 
     // ---- stage B set-up: the first rows of W3 are requested before g is waited for
     const int CW = a.CW, c0 = ci * CW, CWi = max(0, min(CW, D - c0));
@@ -473,31 +492,30 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
         }
     };
     h8 ra[8], rb[8];
-    request3(ra, ks);
-    request3(rb, ks + KSPL);
 
     // ---- G: g of the slice into LDS as fp16 pairs [16][nRp] (zero past the batch and past the slice)
     _Float16 *ghi = reinterpret_cast<_Float16 *>(smem), *glo = ghi + 16 * a.nRp;
     for (int i = tid; i < 16 * a.nRp; i += NT) reinterpret_cast<uint32_t *>(smem)[i] = 0u;
     lds_barrier();
-    for (int i0 = 0; i0 < nR * B; i0 += 8 * NT) {
-        const int cntv = min(8 * NT, nR * B - i0);
-        pair_t q[8];
+    constexpr int NPG = 24;                                       // polls of a thread in one round trip
+    for (int i0 = 0; i0 < nR * B; i0 += NPG * NT) {
+        const int cntv = min(NPG * NT, nR * B - i0);
+        pair_t q[NPG];
         long long t0 = 0;
         for (;;) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < NPG; ++k) {
                 q[k] = pair_t{0u, x.stamp};
                 if (NT * k < cntv) q[k] = cf::team::peek(xr, a.xg + (size_t)R0 * B + i0 + min(tid + NT * k, cntv - 1));   // (uniform)
             }
             __builtin_amdgcn_sched_barrier(0);
             bool ok = true;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) ok &= q[k].y == x.stamp;
+            for (int k = 0; k < NPG; ++k) ok &= q[k].y == x.stamp;
             if (ok || cf::team::gave_up(x, t0)) break;
         }
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < NPG; ++k) {
             const int i = i0 + tid + NT * k;
             if (tid + NT * k < cntv) {
                 const int unit = i / B, b = i - unit * B;
@@ -508,7 +526,10 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
             }
         }
     }
+    request3(ra, ks);                                             // (after the polls: what is requested before them returns before them)
+    request3(rb, ks + KSPL);
     lds_barrier();
+    FFN_STAMP(3);           // g of the slice arrived
 
     // ---- stage B
     f32x4 o[8];                                                   // [jj][rr]: batch row 4 g + rr, column colp + jj
@@ -531,6 +552,7 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
         consume3(rb, s + KSPL);
         request3(rb, s + 3 * KSPL);
     }
+    FFN_STAMP(4);           // products of stage B done (this wavefront)
     lds_barrier();                                                // g is consumed: the sums of the wavefronts overlay it
     {
         const int CWp = 128 * ncgp;
@@ -550,6 +572,7 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
         }
     }
 
+    FFN_STAMP(5);           // partial output published
     // ---- stage C: columns [c0 + fi cpf, + cpf) of slice ci, summed over the NF slices of hidden units in slice order
     {
         const int cpf = (CW + a.NF - 1) / a.NF;
@@ -575,6 +598,11 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
         }
     }
     if (tid == 0) a.counters[(size_t)w * kCounterStride] = cnt;
+    FFN_STAMP(6);
+#if CF_STAMPS
+    lds_barrier();
+    if (tid < kFfnStamps && w < 256) g_ffn_ts[w * kFfnStamps + tid] = s_ts[tid];
+#endif
 }
 
 using KernelFn = void (*)(const FfnArgs);
@@ -584,7 +612,13 @@ KernelFn pick(int bt, int d_model)
     return bt == 1 ? fused_ffn<1, 2> : bt == 2 ? fused_ffn<2, 2> : fused_ffn<4, 2>;
 }
 int batch_tile(int b) { return b <= 1 ? 1 : b <= 2 ? 2 : 4; }
-KernelFn pick_tiles(int nrmax) { return nrmax <= 64 ? fused_ffn_tiles<4> : fused_ffn_tiles<8>; }
+int row_tiles(int nrmax) { return (nrmax + 15) / 16; }
+KernelFn pick_tiles(int nrmax)
+{
+    static const KernelFn fn[8] = {fused_ffn_tiles<1>, fused_ffn_tiles<2>, fused_ffn_tiles<3>, fused_ffn_tiles<4>,
+                                   fused_ffn_tiles<5>, fused_ffn_tiles<6>, fused_ffn_tiles<7>, fused_ffn_tiles<8>};
+    return fn[row_tiles(nrmax) - 1];
+}
 
 }  // namespace
 
@@ -642,12 +676,12 @@ int cf_ffn_create(const cf_ffn_config *cfg, cf_ffn *out)
             return CF_EUNSUPPORTED;                                             // all workgroups resident, one per compute unit
     }
     // the MFMA kernel: 16 column slices times W / 16 slices of hidden units
-    const int NF = W / kNC, CW = ((c.d_model + kNC - 1) / kNC + 7) / 8 * 8, nRp = (kNC * nrmax + 31) / 32 * 32;
+    const int NF = W / kNC, CW = ((c.d_model + kNC - 1) / kNC + 7) / 8 * 8, nRp = (kNC * nrmax + 31) / 32 * 32 + 8;     // (+ 8: the rows of g in LDS start in different banks)
     size_t lds_tiles = 0;
     const bool tiles_fit = W % kNC == 0 && nrmax <= 128 && (size_t)((CW + (NF > 0 ? NF : 1) - 1) / (NF > 0 ? NF : 1)) * c.max_batch <= (size_t)NT;
     if (c.max_batch > kVectorBatch && !tiles_fit) return CF_EUNSUPPORTED;
     if (c.max_batch >= kTilesFrom && tiles_fit) {
-        const size_t part = (size_t)(nrmax <= 64 ? 4 : 8) * 16384, gbytes = 64 * (size_t)nRp, red = 65536;
+        const size_t part = (size_t)row_tiles(nrmax) * 16384, gbytes = 64 * (size_t)nRp, red = 65536;
         lds_tiles = part > gbytes ? part : gbytes;
         lds_tiles = lds_tiles > red ? lds_tiles : red;
         int per_cu = 0;
@@ -754,6 +788,16 @@ int cf_ffn_status(cf_ffn t, void *stream)
     }
     return CF_OK;
 }
+
+#if CF_STAMPS
+// profiling library only: the stage stamps of the last launch of the MFMA kernel (host buffer of 256 * 16 64-bit words)
+int cf_ffn_trace_read(void *host_dst)
+{
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(g_ffn_ts), sizeof(unsigned long long) * 256 * kFfnStamps);
+    return e == hipSuccess ? CF_OK : CF_EHIP;
+}
+#endif
 
 int cf_ffn_set_spin_limit(cf_ffn t, int32_t spin_limit_us)
 {
