@@ -87,7 +87,7 @@ def main():
            "config": {"workload": "%s_b%d_kv%d" % (shape.name, B, Lk), "layers_rotated": n_layers},
            "roofline": {"bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
                         "traffic": None, "algorithmic_bytes": alg,
-                        "kernel": "fused_mla_heads" if (B <= 2 and not args.ranges) else "fused_mla_decode"}}
+                        "kernel": "fused_mla_heads" if (B <= 1 and not args.ranges) else "fused_mla_decode"}}
     if not args.no_cpu_baseline:
         from oracle import mla_block as orc
         inp = cf_inputs.make_mla_inputs(shape, seed=1000, batch=B, kv_len=Lk, poison=False)
