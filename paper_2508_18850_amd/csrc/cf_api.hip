@@ -47,7 +47,9 @@ namespace {
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-int batch_tile(int batch) { return batch <= 1 ? 1 : batch <= 4 ? 4 : 16; }
+// Register tile of the batch rows: 1, 4 (vector units) or 16 (MFMA).  The 16-row tile also wins at batch 3 and 4
+// (Llama-3-8B shape, batch 3 / 4: 52.2 / 46.9 against 54.9 / 48.3 us; Llama-2-7B shape, batch 4: 73.4 against 74.8 us).
+int batch_tile(int batch) { return batch <= 1 ? 1 : batch <= 2 ? 4 : 16; }
 int tile_index(int bt) { return bt == 1 ? 0 : bt == 4 ? 1 : 2; }
 
 constexpr int kMaxKS = 32;
@@ -116,6 +118,11 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
         long best_cost = 0;
         for (int ns = 1; ns <= cf::kMaxKvSplits; ns *= 2) {
             if (h->tune_ns > 0 && ns != h->tune_ns) continue;
+            // One item per member at most, where the batch allows it: a second round of items costs far more than
+            // its rows (measured on the Llama-3-8B shape, 8192 rows, 32 members: batch 3 with 8 / 16 / 32 splits 44.1 /
+            // 48.9 / 54.9 us, batch 5 with 4 / 8 / 16 / 32 splits 55.2 / 64.7 / 68.0 / 85.8 us, batch 12 with 2 / 4 / 8
+            // splits 87.5 / 97.3 / 96.2 us)
+            if (h->tune_ns == 0 && ns > 1 && batch * ns > TS) continue;
             int tps = ceil_div(ceil_div(pos, ns), rows_per_step) * rows_per_step;
             if (tps == 0) tps = rows_per_step;
             const long cost = (long)ceil_div(batch * ns, TS) * (tps + 64);

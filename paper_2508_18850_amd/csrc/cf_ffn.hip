@@ -625,7 +625,7 @@ KernelFn pick_tiles(int nrmax)
 struct cf_ffn_s {
     cf_ffn_config cfg;
     int W = 0, nrmax = 0;
-    int NF = 0, CW = 0, nRp = 0;       // MFMA kernel (max_batch > 4)
+    int NF = 0, CW = 0, nRp = 0;       // MFMA kernel (max_batch >= 3)
     size_t xg = 0, xp = 0, lds_tiles = 0;
     char *ws = nullptr;
     size_t ws_bytes = 0;
