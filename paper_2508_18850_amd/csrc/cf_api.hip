@@ -122,7 +122,9 @@ int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
             // its rows (measured on the Llama-3-8B shape, 8192 rows, 32 members: batch 3 with 8 / 16 / 32 splits 44.1 /
             // 48.9 / 54.9 us, batch 5 with 4 / 8 / 16 / 32 splits 55.2 / 64.7 / 68.0 / 85.8 us, batch 12 with 2 / 4 / 8
             // splits 87.5 / 97.3 / 96.2 us)
-            if (h->tune_ns == 0 && ns > 1 && batch * ns > TS) continue;
+            // (with more batch rows than members there are several rounds anyway and the cost below decides: Llama-2-7B
+            // shape, 8 members, batch 12: 160.2 us with 2 splits, three full rounds, against 167.8 us with 1)
+            if (h->tune_ns == 0 && ns > 1 && batch * ns > TS && batch <= TS) continue;
             int tps = ceil_div(ceil_div(pos, ns), rows_per_step) * rows_per_step;
             if (tps == 0) tps = rows_per_step;
             const long cost = (long)ceil_div(batch * ns, TS) * (tps + 64);
