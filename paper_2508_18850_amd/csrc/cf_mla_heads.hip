@@ -418,12 +418,20 @@ __global__ void __launch_bounds__(NT) fused_mla_heads(const cf::mla::HeadsArgs a
         lds_sync();
         {
             const int d = tid;                                         // one latent dimension per thread
-            float M = last ? s_small[R + b] : kNegBig;
-            for (int w8 = 0; w8 < NPART; ++w8) M = fmaxf(M, s_part[w8 * (L + 2)]);
-            float Ls = 0.f, A = 0.f;
+            // lane w8 of every wavefront takes the maximum and the sum of partial w8; the factors then reach the
+            // threads as scalars (one exponential per lane in place of one per thread and partial)
+            static_assert(NPART <= 64, "one lane per partial");
+            const float pm = lane < NPART ? s_part[lane * (L + 2)] : kNegBig;
+            const float pl = lane < NPART ? s_part[lane * (L + 2) + 1] : 0.f;
+            float M = pm;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
+            if (last) M = fmaxf(M, s_small[R + b]);
+            const float fw = __builtin_amdgcn_exp2f(pm - M);           // (0 for the lanes past the partials)
+            float Ls = wave_sum(pl * fw), A = 0.f;
+#pragma unroll
             for (int w8 = 0; w8 < NPART; ++w8) {
-                const float f = __builtin_amdgcn_exp2f(s_part[w8 * (L + 2)] - M);
-                Ls = fmaf(s_part[w8 * (L + 2) + 1], f, Ls);
+                const float f = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, fw), w8));
                 A = fmaf(s_part[w8 * (L + 2) + 2 + d], f, A);
             }
             if (last) {
