@@ -37,7 +37,7 @@ MEASURED_TRAFFIC = {
     # (FETCH_SIZE KiB x 2.0000 + WRITE_SIZE KiB) x 1024, measured on fused_decode_block (one launch per layer)
     "llama2_7b_b1_kv4096": 207353856,      # 100203.0, 2088.0
     "llama3_8b_b1_kv8192": 126311424,      # 60241.5, 2868.0
-    "llama3_8b_b4_kv8192": 236295724,      # 112194.8, 6744.0
+    "llama3_8b_b4_kv8192": 236295724,      # 112006.8, 6744.0
     "llama3_8b_b16_kv8192": 682216448,     # 321221.5, 23784.0
     "llama2_70b_b1_kv32768": 456086118,    # 218940.3, 7516.0
 }
