@@ -312,6 +312,22 @@ def test_team_sizes_and_head_counts(heads, workgroups):
         r.blk.close()
 
 
+@pytest.mark.parametrize("batch", [3, 5, 6, 12])
+def test_batches_that_do_not_divide_the_team(batch):
+    """Batches between the powers of two on a grouped-query shape with 32 workgroups per KV head: the plan keeps the
+    attention items (batch rows x KV splits) within one per member, and the result is the oracle's."""
+    shape = cf_inputs.BlockShape("s", 1024, 32, 8, 128, 500000.0, 2100)
+    _log("batch %d" % batch)
+    inp = cf_inputs.make_inputs(shape, seed=70 + batch, batch=batch, kv_len=2100)
+    r = Runner(shape, batch, inp["max_seq"])
+    res = r.run(inp, 2100, out_fill=float("nan"), packed=True)
+    plan = r.blk.plan()
+    _log("plan %s" % plan)
+    assert plan["kv_splits"] * batch <= plan["team_size"], plan
+    check(res, oracle(inp, shape, 2100), inp, 2100, "b%d" % batch)
+    r.blk.close()
+
+
 @pytest.mark.parametrize("d_model,nq,nkv,hd", [(520, 4, 2, 64), (1032, 3, 3, 128)])
 def test_pack_weights_gives_the_documented_layout(d_model, nq, nkv, hd):
     """cf_pack_weights, bit-exact (the values are only moved): W_qkv_packed [(n_q + 2 n_kv)][d_model][head_dim], every
