@@ -39,6 +39,7 @@ constexpr int kVectorBatch = 4;        // the largest batch of the vector-unit k
 constexpr int kTilesFrom = 3;          // from this batch on the MFMA kernel runs where the shape allows it (measured:
                                        // Llama-2-7B shape, batch 2 / 3 / 4: 52.4 / 73.1 / 75.2 us against 55.5 / 56.3 / 57.0)
 constexpr int kNC = 16;                // MFMA kernel: column slices of the output (workgroups per slice of hidden units)
+constexpr int kStageRow = 256 + 8;     // MFMA kernel: row stride (fp16 values) of a wavefront's staging area in LDS
 constexpr uint32_t kNoLoad = 0x80000000u;
 
 using cf::mfma::f32x4;
@@ -404,53 +405,66 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
     const uint32_t wbytes = (uint32_t)((size_t)a.F * D * 2);
     const Stream W1(a.w1, wbytes), W2(a.w2, wbytes), W3(a.w3, wbytes);
 
-    // ---- stage A.  Contraction slot (step m, group g, element e) of a 512-column piece stands for column
-    //      64 (m / 2) + 16 g + 8 (m % 2) + e of the piece.
+    // ---- stage A.  A task is sixteen weight rows by 256 columns of one matrix.  The rows are read as they lie in
+    //      memory (a load instruction of a wavefront is two rows of 512 contiguous bytes; read in the layout of the MFMA
+    //      operand, sixteen rows of 64 bytes per instruction, the same bytes took 4.8 us longer at batch 16) and pass
+    //      through a staging area in LDS that belongs to the wavefront alone: no barrier, LDS operations of a wavefront
+    //      execute in order.  Contraction slot (step m, group g, element e) of a 512-column piece is its column
+    //      32 m + 8 g + e.
     {
         const int NCK = (D + kChunk - 1) / kChunk;
         f32x4 acc[NTL][2];                                        // [tile][matrix]: units 16 t + 4 g + rr, batch row c
 #pragma unroll
         for (int t = 0; t < NTL; ++t) acc[t][0] = acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-        const uint32_t lane_off = (uint32_t)c * (uint32_t)D * 2u + 32u * g;
+        _Float16 *stg = reinterpret_cast<_Float16 *>(smem) + (size_t)wv * 16 * kStageRow;      // [16][kStageRow]
+        const int hi = lane >> 5, lp = lane & 31;
         for (int piece = wv; piece < NCK; piece += NW) {          // (uniform per wavefront)
             h8 zb[16];
-            uint32_t colok = 0;                                   // bit m: this lane's columns of step m exist
 #pragma unroll
             for (int m = 0; m < 16; ++m) {
-                const int col = kChunk * piece + 64 * (m >> 1) + 16 * g + 8 * (m & 1);
-                colok |= col < D ? 1u << m : 0u;
+                const int col = kChunk * piece + 32 * m + 8 * g;
                 uint4 v = {0u, 0u, 0u, 0u};
                 if (c < B && col < D) v = *reinterpret_cast<const uint4 *>(a.z + (size_t)c * D + col);
                 zb[m] = __builtin_bit_cast(h8, v);
             }
-            // a task is half the steps of one tile of one matrix: eight loads, eight products; two tasks in flight
+            // two tasks in flight; load k of a task: rows 2 k and 2 k + 1 of the tile, 32 lanes each
             auto request = [&](h8(&wr)[8], int task) {
                 const int t = task >> 2, mat = (task >> 1) & 1, half = task & 1;
-                const bool live = 16 * t + c < nr;                // rows past the workgroup's units are not read
+                const bool colok = kChunk * piece + 256 * half + 8 * lp < D;
                 const uint32_t soff = 16 * t < nr ? (uint32_t)(((size_t)(r0 + 16 * t) * D + (size_t)kChunk * piece) * 2) : 0u;
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    const int m = 8 * half + k;
-                    const uint32_t voff = (live && (colok >> m & 1u)) ? lane_off + 128u * (m >> 1) + 16u * (m & 1) : kNoLoad;
+                    const int row = 2 * k + hi;                    // rows past the workgroup's units are not read
+                    const uint32_t voff = (colok && 16 * t + row < nr) ? (uint32_t)row * (uint32_t)D * 2u + 512u * half + 16u * lp : kNoLoad;
                     wr[k] = mat ? W2.ld(voff, soff) : W1.ld(voff, soff);
                 }
             };
-            auto consume = [&](const h8(&wr)[8], int task) {
+            auto stage = [&](const h8(&wr)[8]) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) *reinterpret_cast<h8 *>(stg + (2 * k + hi) * kStageRow + 8 * lp) = wr[k];
+            };
+            auto consume = [&](int task) {
                 const int t = task >> 2, mat = (task >> 1) & 1, half = task & 1;
 #pragma unroll
-                for (int k = 0; k < 8; ++k) acc[t][mat] = mfma16(wr[k], zb[8 * half + k], acc[t][mat]);
+                for (int k = 0; k < 8; ++k) {
+                    const h8 wop = *reinterpret_cast<const h8 *>(stg + c * kStageRow + 32 * k + 8 * g);
+                    acc[t][mat] = mfma16(wop, zb[8 * half + k], acc[t][mat]);
+                }
             };
             h8 wa[8], wb[8];
             request(wa, 0);
             request(wb, 1);
 #pragma unroll
             for (int task = 0; task < 4 * NTL; task += 2) {
-                consume(wa, task);
+                stage(wa);
                 if (task + 2 < 4 * NTL) request(wa, task + 2);
-                consume(wb, task + 1);
+                consume(task);
+                stage(wb);
                 if (task + 3 < 4 * NTL) request(wb, task + 3);
+                consume(task + 1);
             }
         }
+        lds_barrier();                                            // the staging areas are left: the sums below overlay them
         FFN_STAMP(1);       // products of stage A done
         float4 *part = reinterpret_cast<float4 *>(smem);          // [NW][NTL][2][64 lanes]
 #pragma unroll
@@ -684,6 +698,8 @@ int cf_ffn_create(const cf_ffn_config *cfg, cf_ffn *out)
         const size_t part = (size_t)row_tiles(nrmax) * 16384, gbytes = 64 * (size_t)nRp, red = 65536;
         lds_tiles = part > gbytes ? part : gbytes;
         lds_tiles = lds_tiles > red ? lds_tiles : red;
+        const size_t staging = (size_t)NW * 16 * kStageRow * sizeof(uint16_t);
+        lds_tiles = lds_tiles > staging ? lds_tiles : staging;
         int per_cu = 0;
         if (lds_tiles > 160 * 1024 - 256 ||
             hipFuncSetAttribute(reinterpret_cast<const void *>(pick_tiles(nrmax)), hipFuncAttributeMaxDynamicSharedMemorySize,
