@@ -387,9 +387,9 @@ int cf_splithead_set_spin_limit(cf_splithead t, int32_t spin_limit_us);
  *   sizes below 1 or an unknown activation; CF_EUNSUPPORTED for max_batch > 16 (the batch of Appendix C), d_model >
  *   8192, matrices of 2 GiB or more; with max_batch > 4 also for fewer workgroups than a multiple of 16 (d_ff below
  *   the number of compute units and not a multiple of 16) and for more than 128 hidden units per workgroup.
- *   Two kernels: the products on the vector units with one partial output per workgroup (batch 1 and 2; also 3 and 4
- *   where the second kernel does not take the shape), and from batch 3 on the products on MFMA tiles, the workgroups cut
- *   into slices of hidden units times slices of output columns.
+ *   Two kernels: the products on the vector units with one partial output per workgroup (batch 1; also 2 to 4 where
+ *   the second kernel does not take the shape), and from batch 2 on the products on MFMA tiles, the workgroups cut into
+ *   slices of hidden units times slices of output columns.
  * cf_ffn_decode enqueues the kernel on `stream` (no allocation, no synchronisation; the launch can be captured and
  *   replayed): CF_EINVAL for null or misaligned pointers and a batch outside 1..max_batch.  All workgroups must be
  *   resident together (one per compute unit), as for cf_decode_block.

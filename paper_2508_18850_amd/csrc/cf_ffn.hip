@@ -36,8 +36,8 @@ constexpr int kChunk = 512;            // columns of one wavefront load: 64 lane
 constexpr int kCounterStride = 16;
 constexpr int kMaxBatch = 16;          // the batch of Appendix C
 constexpr int kVectorBatch = 4;        // the largest batch of the vector-unit kernel
-constexpr int kTilesFrom = 3;          // from this batch on the MFMA kernel runs where the shape allows it (measured:
-                                       // Llama-2-7B shape, batch 2 / 3 / 4: 52.4 / 73.1 / 75.2 us against 55.5 / 56.3 / 57.0)
+constexpr int kTilesFrom = 2;          // from this batch on the MFMA kernel runs where the shape allows it (measured:
+                                       // Llama-2-7B shape, batch 1 / 2 / 4: 46.5 / 52.3 / 75.2 us against 47.8 / 47.8 / 49.0)
 constexpr int kNC = 16;                // MFMA kernel: column slices of the output (workgroups per slice of hidden units)
 constexpr int kStageRow = 256 + 8;     // MFMA kernel: row stride (fp16 values) of a wavefront's staging area in LDS
 constexpr uint32_t kNoLoad = 0x80000000u;
@@ -363,13 +363,13 @@ __device__ unsigned long long g_ffn_ts[256 * kFfnStamps];
 #endif
 
 // ---------------------------------------------------------------------------------------------------------------------
-// Batch 5..16: the same block on matrix cores, with the work cut in two directions.  One partial output per workgroup
+// Batch 2..16: the same block on matrix cores, with the work cut in two directions.  One partial output per workgroup
 // (as above) would be W x B x d_model stamped pairs, 134 MB at batch 16; here the W workgroups form NF = W / 16 slices
 // of hidden units times 16 slices of output columns:
 //   A  as above, workgroup w owns the hidden units [w F / W, (w + 1) F / W): h = W1 z, u = W2 z as 16 x 16 x 32 MFMA
-//      steps, A = sixteen rows of the weights (a lane reads 32 contiguous bytes of a row per pair of steps, four
-//      lanes one 128-byte line), B = z in fp16 as given, held in registers for the 512 columns of a wavefront; the
-//      eight wavefronts (eight column pieces) are added through LDS; g = sigma(h) u goes to stamped slots [d_ff][B]
+//      steps, A = sixteen rows of the weights (read as they lie in memory and brought into the operand layout through
+//      LDS), B = z in fp16 as given, held in registers for the 512 columns of a wavefront; the eight wavefronts
+//      (eight column pieces) are added through LDS; g = sigma(h) u goes to stamped slots [d_ff][B]
 //   G  workgroup (fi, ci) fetches g of slice fi (the units of 16 workgroups) and keeps it in LDS as fp16 pairs
 //      (value = hi + lo, so fp32 g loses nothing)
 //   B  partial out [B][columns of slice ci] = g W3[slice fi]: A = g, B = eight rows of a 16-byte piece of W3
@@ -639,7 +639,7 @@ KernelFn pick_tiles(int nrmax)
 struct cf_ffn_s {
     cf_ffn_config cfg;
     int W = 0, nrmax = 0;
-    int NF = 0, CW = 0, nRp = 0;       // MFMA kernel (max_batch >= 3)
+    int NF = 0, CW = 0, nRp = 0;       // MFMA kernel (max_batch >= 2)
     size_t xg = 0, xp = 0, lds_tiles = 0;
     char *ws = nullptr;
     size_t ws_bytes = 0;
