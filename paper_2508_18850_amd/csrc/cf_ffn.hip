@@ -380,7 +380,7 @@ __device__ unsigned long long g_ffn_ts[256 * kFfnStamps];
 template <int NTL>     // row tiles of 16 hidden units a workgroup owns at most (1..8)
 __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
 {
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     const int tid = threadIdx.x, lane = tid & 63, w = blockIdx.x;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, c = lane & 15;
@@ -388,6 +388,7 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
     const int r0 = (int)((long long)w * a.F / a.W), nr = (int)((long long)(w + 1) * a.F / a.W) - r0;
     const int fi = w / kNC, ci = w % kNC;
     const int R0 = (int)((long long)(fi * kNC) * a.F / a.W), nR = (int)((long long)(fi * kNC + kNC) * a.F / a.W) - R0;
+    const uint32_t inv_b = (uint32_t)((0x100000000ull + (unsigned)B - 1) / (unsigned)B);     // n / B = umulhi(n, inv_b) for n < 2^28
 #if CF_STAMPS
     __shared__ unsigned long long s_ts[kFfnStamps];
     if (tid < kFfnStamps) s_ts[tid] = 0;
@@ -475,7 +476,7 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
                     make_float4(acc[t][mat][0], acc[t][mat][1], acc[t][mat][2], acc[t][mat][3]);
         lds_barrier();
         for (int e = tid; e < nr * B; e += NT) {                  // consecutive threads, consecutive slots
-            const int unit = e / B, b = e - unit * B;
+            const int unit = (int)__umulhi((uint32_t)e, inv_b), b = e - unit * B;
             const int t = unit >> 4, l = 16 * ((unit >> 2) & 3) + b, rr = unit & 3;
             float h = 0.f, u = 0.f;
 #pragma unroll
@@ -509,7 +510,7 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
 
     // ---- G: g of the slice into LDS as fp16 pairs [16][nRp] (zero past the batch and past the slice)
     _Float16 *ghi = reinterpret_cast<_Float16 *>(smem), *glo = ghi + 16 * a.nRp;
-    for (int i = tid; i < 16 * a.nRp; i += NT) reinterpret_cast<uint32_t *>(smem)[i] = 0u;
+    for (int i = tid; i < 4 * a.nRp; i += NT) reinterpret_cast<uint4 *>(smem)[i] = uint4{0u, 0u, 0u, 0u};
     lds_barrier();
     constexpr int NPG = 24;                                       // polls of a thread in one round trip
     for (int i0 = 0; i0 < nR * B; i0 += NPG * NT) {
@@ -532,7 +533,7 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
         for (int k = 0; k < NPG; ++k) {
             const int i = i0 + tid + NT * k;
             if (tid + NT * k < cntv) {
-                const int unit = i / B, b = i - unit * B;
+                const int unit = (int)__umulhi((uint32_t)i, inv_b), b = i - unit * B;
                 const float v = __builtin_bit_cast(float, q[k].x);
                 const _Float16 hi = (_Float16)v;
                 ghi[b * a.nRp + unit] = hi;
