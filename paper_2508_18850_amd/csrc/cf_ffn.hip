@@ -512,6 +512,10 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
     _Float16 *ghi = reinterpret_cast<_Float16 *>(smem), *glo = ghi + 16 * a.nRp;
     for (int i = tid; i < 4 * a.nRp; i += NT) reinterpret_cast<uint4 *>(smem)[i] = uint4{0u, 0u, 0u, 0u};
     lds_barrier();
+    // The first two steps of W3 go out before the polls: the polls return behind them, about when g has arrived anyway
+    // (all polls of a thread in one round; with two more steps ahead, or with three poll rounds, this order lost).
+    request3(ra, ks);
+    request3(rb, ks + KSPL);
     constexpr int NPG = 24;                                       // polls of a thread in one round trip
     for (int i0 = 0; i0 < nR * B; i0 += NPG * NT) {
         const int cntv = min(NPG * NT, nR * B - i0);
@@ -541,8 +545,6 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
             }
         }
     }
-    request3(ra, ks);                                             // (after the polls: what is requested before them returns before them)
-    request3(rb, ks + KSPL);
     lds_barrier();
     FFN_STAMP(3);           // g of the slice arrived
 
