@@ -388,7 +388,9 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
     const int r0 = (int)((long long)w * a.F / a.W), nr = (int)((long long)(w + 1) * a.F / a.W) - r0;
     const int fi = w / kNC, ci = w % kNC;
     const int R0 = (int)((long long)(fi * kNC) * a.F / a.W), nR = (int)((long long)(fi * kNC + kNC) * a.F / a.W) - R0;
-    const uint32_t inv_b = (uint32_t)((0x100000000ull + (unsigned)B - 1) / (unsigned)B);     // n / B = umulhi(n, inv_b) for n < 2^28
+    // n / B for n < 2^28 without a division (B = 1: the reciprocal does not fit 32 bits)
+    const uint32_t inv_b = B > 1 ? (uint32_t)((0x100000000ull + (unsigned)B - 1) / (unsigned)B) : 0u;
+    auto div_b = [&](int n) { return B > 1 ? (int)__umulhi((uint32_t)n, inv_b) : n; };
 #if CF_STAMPS
     __shared__ unsigned long long s_ts[kFfnStamps];
     if (tid < kFfnStamps) s_ts[tid] = 0;
@@ -476,7 +478,7 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
                     make_float4(acc[t][mat][0], acc[t][mat][1], acc[t][mat][2], acc[t][mat][3]);
         lds_barrier();
         for (int e = tid; e < nr * B; e += NT) {                  // consecutive threads, consecutive slots
-            const int unit = (int)__umulhi((uint32_t)e, inv_b), b = e - unit * B;
+            const int unit = div_b(e), b = e - unit * B;
             const int t = unit >> 4, l = 16 * ((unit >> 2) & 3) + b, rr = unit & 3;
             float h = 0.f, u = 0.f;
 #pragma unroll
@@ -537,7 +539,7 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
         for (int k = 0; k < NPG; ++k) {
             const int i = i0 + tid + NT * k;
             if (tid + NT * k < cntv) {
-                const int unit = (int)__umulhi((uint32_t)i, inv_b), b = i - unit * B;
+                const int unit = div_b(i), b = i - unit * B;
                 const float v = __builtin_bit_cast(float, q[k].x);
                 const _Float16 hi = (_Float16)v;
                 ghi[b * a.nRp + unit] = hi;
