@@ -119,7 +119,7 @@ __device__ __forceinline__ float activate(float a, int act)
 template <int BT, int NCB>     // batch tile; column blocks of 4096 per thread (d_model <= 4096 NCB)
 __global__ void __launch_bounds__(NT) fused_ffn(const FfnArgs a)
 {
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     const int tid = threadIdx.x, lane = tid & 63, w = blockIdx.x;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int D = a.D, B = a.B;

@@ -1698,7 +1698,7 @@ template <int HD, int G, int BT, bool STACK>
 __device__ __forceinline__ void decode_steps(const Params &p0, const LayerPtrs *tab, int n_layers_in, uint64_t *xslots)
 {
     const int n_layers = STACK ? n_layers_in : 1;
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     {
         // The compiler loads each kernel argument shortly before its first use: several dependent
         // round trips to cold memory in a row at the start of every launch.  One word of every 64-byte

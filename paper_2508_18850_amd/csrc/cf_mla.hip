@@ -220,7 +220,7 @@ template <int BT>
 __global__ void __launch_bounds__(NT) fused_mla_decode(const MlaArgs a)
 {
     constexpr int BQ = BT / 4;
-    extern __shared__ float smem[];                     // carved anew by every stage
+    extern __shared__ __align__(16) float smem[];                    // carved anew by every stage
     __shared__ float s_rope[R];                         // cos, sin of the rotary angles
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, w = blockIdx.x;
     const int head = w / TS, j = w % TS;

@@ -119,7 +119,7 @@ __global__ void __launch_bounds__(NT) fused_mla_heads(const cf::mla::HeadsArgs a
     __shared__ float s_a[MAXB * MAXA];                  // stage buffers, reused from stage to stage
     __shared__ float s_b[MAXB * (L + R)];
     __shared__ float s_red[NW * (L + 2)];
-    extern __shared__ float s_part[];                   // [NPART][L + 2] attention partials of the row groups (dynamic)
+    extern __shared__ __align__(16) float s_part[];                  // [NPART][L + 2] attention partials of the row groups (dynamic)
     __shared__ float s_small[R + MAXB];                 // cos, sin of the rotary angles; score of the new token per row
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, w = blockIdx.x;
     const int head = w / TS, j = w % TS;

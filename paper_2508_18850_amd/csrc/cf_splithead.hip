@@ -106,7 +106,7 @@ __global__ void __launch_bounds__(NT) fused_decode_splithead(const SplitArgs a)
     constexpr int P = 6 * PV;             // 16-byte pieces of a packed weight row: q lo, q hi, k lo, k hi, v lo, v hi
     constexpr int RPP = NT / P;           // weight rows per pass of the workgroup
     constexpr int UT = 8 / PV;            // cached rows per thread and batch: 16 loads in flight
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     __shared__ float s_q[SD], s_k[SD], s_v[SD], s_a[SD], s_w[NW], s_part[NW][SD];
     __shared__ uint32_t s_flag;
 #if CF_STAMPS
