@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC = {
     # profiles/fused_decode_block_llama2_7b_kv4096_hbm_traffic.md and profiles/fused_decode_block_gqa_shapes.md:
     # (FETCH_SIZE KiB x 2.0000 + WRITE_SIZE KiB) x 1024, measured on fused_decode_block (one launch per layer)
-    "llama2_7b_b1_kv4096": 207353856,      # 100203.0, 2088.0
+    "llama2_7b_b1_kv4096": 207280105,      # 100167.0, 2088.0
     "llama3_8b_b1_kv8192": 126311424,      # 60241.5, 2868.0
     "llama3_8b_b4_kv8192": 236295724,      # 112006.8, 6744.0
     "llama3_8b_b16_kv8192": 682216448,     # 321221.5, 23784.0
