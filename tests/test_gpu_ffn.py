@@ -106,6 +106,47 @@ def test_full_size_tile_kernel(name, batch):
     _run(cf_inputs.FFN_SHAPES[name], batch, 0, seed=402, scale_rows=True)
 
 
+@pytest.mark.parametrize("batch", [1, 6])
+def test_captured_launch_replays(batch):
+    """The launch stamp is counted on the device, so a launch recorded once in a HIP graph stays valid on every replay
+    (batch 1: the vector kernel, batch 6: the MFMA kernel): three replays, with eager launches and synchronisation
+    between them, each bit for bit the eager result (all sums are taken in a fixed order)."""
+    from paper_2508_18850_amd import FfnBlock
+    dev = torch.device("cuda:0")
+    shape = SMALL[1]
+    inp = cf_inputs.make_ffn_inputs(shape, seed=600 + batch, batch=batch)
+    t = {k: torch.from_numpy(inp[k]).to(dev) for k in ("z", "w1", "w2", "w3")}
+    out = torch.full((batch, shape.d_model), float("nan"), dtype=torch.float16, device=dev)
+    blk = FfnBlock(shape.d_model, shape.d_ff, batch, 0)
+    s = torch.cuda.Stream()
+
+    def launch(stream):
+        blk.decode(batch, t["z"].data_ptr(), t["w1"].data_ptr(), t["w2"].data_ptr(), t["w3"].data_ptr(), out.data_ptr(), stream)
+
+    with torch.cuda.stream(s):
+        launch(s.cuda_stream)
+        blk.status(s.cuda_stream)
+    torch.cuda.synchronize()
+    eager = out.clone()
+    ref = orc.ffn_block(inp["z"], inp["w1"], inp["w2"], inp["w3"], 0)["out"]
+    assert np.abs(eager.cpu().numpy().astype(np.float64) - ref).max() <= 1e-2 * np.abs(ref).max() + 1e-3
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        launch(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        blk.status(0)
+        assert torch.equal(out, eager), "replay %d" % rep
+        launch(torch.cuda.current_stream().cuda_stream)          # eager launches move the device-side count on as well
+        launch(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        blk.status(0)
+    blk.close()
+
+
 def test_closed_forms_on_the_gpu():
     """W1 = 0 gives sigma(0) = 0 everywhere: out = 0; z = 0 likewise."""
     from paper_2508_18850_amd import FfnBlock

@@ -160,6 +160,51 @@ def test_full_size_deepseek_v2_lite_shape_batched(batch, kv_len):
     check(run(shape, inp, kv_len), oracle(shape, inp, kv_len), inp, kv_len, "%s B=%d L=%d" % (shape.name, batch, kv_len))
 
 
+@pytest.mark.parametrize("batch", [1, 5])
+def test_captured_launch_replays(batch):
+    """The launch stamp is counted on the device, so a launch recorded once in a HIP graph stays valid on every replay
+    (batch 1: the head-team kernel, batch 5: the token-range kernel): three replays, with eager launches and
+    synchronisation between them, each bit for bit the eager result, output and appended row."""
+    from paper_2508_18850_amd import MlaBlock
+    shape, pos = cf_inputs.MlaShape("s", 320, 5, 48, 64, 512, 64, 10000.0, 0), 200
+    inp = cf_inputs.make_mla_inputs(shape, seed=90 + batch, batch=batch, kv_len=pos)
+    dev = torch.device("cuda:0")
+    blk = MlaBlock(shape.d_model, shape.n_heads, shape.nope_dim, shape.rope_dim, shape.kv_lora_rank, shape.v_head_dim,
+                   batch, inp["max_seq"], shape.rope_base)
+    t = {k: torch.from_numpy(inp[k]).to(dev) for k in ("x", "w_q", "w_kv", "w_up", "w_down", "w_o", "kv_cache")}
+    out = torch.full((batch, shape.d_model), float("nan"), dtype=torch.float16, device=dev)
+    s = torch.cuda.Stream()
+
+    def launch(stream):
+        blk.decode(batch, t["x"].data_ptr(), t["w_q"].data_ptr(), t["w_kv"].data_ptr(), t["w_up"].data_ptr(),
+                   t["w_down"].data_ptr(), t["w_o"].data_ptr(), t["kv_cache"].data_ptr(), pos, out.data_ptr(), stream)
+
+    with torch.cuda.stream(s):
+        launch(s.cuda_stream)
+        blk.status(s.cuda_stream)
+    torch.cuda.synchronize()
+    eager, row_eager = out.clone(), t["kv_cache"][:, pos].clone()
+    ref = oracle(shape, inp, pos)
+    assert np.abs(eager.cpu().numpy().astype(np.float64) - ref["out"]).max() <= 1e-2 * np.abs(ref["out"]).max() + 1e-3
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        launch(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        t["kv_cache"][:, pos].zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        blk.status(0)
+        assert torch.equal(out, eager), "replay %d" % rep
+        assert torch.equal(t["kv_cache"][:, pos], row_eager), "replay %d" % rep
+        launch(torch.cuda.current_stream().cuda_stream)          # eager launches move the device-side count on as well
+        launch(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        blk.status(0)
+    blk.close()
+
+
 def test_unsupported_shapes_and_bad_arguments_are_refused():
     from paper_2508_18850_amd import MlaBlock, CfError
     with pytest.raises(CfError) as e:
