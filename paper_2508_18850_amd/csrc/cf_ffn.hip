@@ -442,9 +442,18 @@ __global__ void __launch_bounds__(NT) fused_ffn_tiles(const FfnArgs a)
                     wr[k] = mat ? W2.ld(voff, soff) : W1.ld(voff, soff);
                 }
             };
+            // (the fences and the wave barrier emit nothing: they keep the compiler from moving the reads of other
+            // lanes' values across the writes, which it might, seeing that a thread's own addresses differ)
+            auto wave_sync = [&]() {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            };
             auto stage = [&](const h8(&wr)[8]) {
+                wave_sync();                                       // the previous task's operands have been read
 #pragma unroll
                 for (int k = 0; k < 8; ++k) *reinterpret_cast<h8 *>(stg + (2 * k + hi) * kStageRow + 8 * lp) = wr[k];
+                wave_sync();
             };
             auto consume = [&](int task) {
                 const int t = task >> 2, mat = (task >> 1) & 1, half = task & 1;
