@@ -101,7 +101,7 @@ def test_full_size_batch4():
     _run(cf_inputs.FFN_SHAPES["llama2_7b"], 4, 0, seed=401, scale_rows=True)
 
 
-@pytest.mark.parametrize("name,batch", [("llama2_7b", 16), ("llama3_8b", 8), ("llama2_70b", 16)])
+@pytest.mark.parametrize("name,batch", [("llama2_7b", 2), ("llama2_7b", 16), ("llama3_8b", 8), ("llama2_70b", 16)])
 def test_full_size_tile_kernel(name, batch):
     _run(cf_inputs.FFN_SHAPES[name], batch, 0, seed=402, scale_rows=True)
 
