@@ -49,7 +49,9 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Register tile of the batch rows: 1, 4 (vector units) or 16 (MFMA).  The 16-row tile also wins at batch 3 and 4
 // (Llama-3-8B shape, batch 3 / 4: 52.2 / 46.9 against 54.9 / 48.3 us; Llama-2-7B shape, batch 4: 73.4 against 74.8 us).
-int batch_tile(int batch) { return batch <= 1 ? 1 : batch <= 2 ? 4 : 16; }
+// Without MFMA tiles (head_dim 64) the 16-row tile is the vector variant with 128 accumulators per thread: there the
+// 4-row tile keeps batch 3 and 4.
+int batch_tile(int batch, int head_dim) { return batch <= 1 ? 1 : batch <= (cf::mfma_tiles(head_dim, 16) ? 2 : 4) ? 4 : 16; }
 int tile_index(int bt) { return bt == 1 ? 0 : bt == 4 ? 1 : 2; }
 
 constexpr int kMaxKS = 32;
@@ -68,7 +70,7 @@ int default_workgroups(const cf_handle_s *h)
 int make_plan(const cf_handle_s *h, int batch, int pos, Params *p)
 {
     const cf_config &c = h->cfg;
-    const int hd = c.head_dim, G = h->G, bt = batch_tile(batch);
+    const int hd = c.head_dim, G = h->G, bt = batch_tile(batch, c.head_dim);
     const int W = default_workgroups(h);
     if (W <= 0) return CF_EUNSUPPORTED;
     const int TS = W / c.n_kv_heads;
@@ -383,7 +385,7 @@ static int decode_impl(cf_handle h, int packed, int32_t batch, const void *x, co
         p.p2 = reinterpret_cast<uint64_t *>(h->slot_area + b1);
         p.p3 = reinterpret_cast<uint64_t *>(h->slot_area + b1 + b2);
     }
-    const int bt = batch_tile(batch);
+    const int bt = batch_tile(batch, h->cfg.head_dim);
     const size_t lds = cf::lds_floats(p, h->cfg.head_dim, h->G, bt) * sizeof(float);
     if (lds > kLdsLimit) return CF_EUNSUPPORTED;
     rc = check_residency(h, p, bt, lds);
