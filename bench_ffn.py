@@ -19,6 +19,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+# HBM bytes per launch from rocprofv3 counters, (FETCH_SIZE KiB x 2.0000 + WRITE_SIZE KiB) x 1024
+# (profiles/fused_ffn_kernel_trace_and_traffic.md); None where no counter run exists
+MEASURED_TRAFFIC = {
+    "ffn_llama2_7b_b1": 290456166,      # 137720.3, 8208.0
+    "ffn_llama2_7b_b16": 304258662,     # 143711.8, 9704.0
+}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--steps", type=int, default=1000)
@@ -81,13 +89,15 @@ def main():
     err, tol = float(np.abs(got - ref).max()), float(1e-2 * np.abs(ref).max() + 1e-3)
     assert err <= tol, "the timed kernel disagrees with the oracle: %g > %g" % (err, tol)
     us = e0.elapsed_time(e1) / args.steps * 1e3
+    tiles = B >= 2 and min(F, torch.cuda.get_device_properties(0).multi_processor_count) % 16 == 0 and -(-F // 256) <= 128
     achieved = alg / (us * 1e-6) / 1e9
     res = {"metric": "us per fused feed-forward step", "value": us, "unit": "us/step", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "higher_is_better": False, "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
            "config": {"workload": "ffn_%s_b%d" % (shape.name, B), "d_model": D, "d_ff": F, "layers_rotated": n_layers,
                       "activation": "gelu" if act else "silu"},
            "roofline": {"bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
-                        "traffic": None, "algorithmic_bytes": alg, "kernel": "fused_ffn"},
+                        "traffic": MEASURED_TRAFFIC.get("ffn_%s_b%d" % (shape.name, B)), "algorithmic_bytes": alg,
+                        "kernel": "fused_ffn_tiles" if tiles else "fused_ffn"},
            "check": {"max_abs_err": err, "tolerance": tol}}
     if not args.no_cpu_baseline:
         zc = z.cpu().numpy()

@@ -18,6 +18,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+# HBM bytes per launch from rocprofv3 counters, (FETCH_SIZE KiB x 2.0000 + WRITE_SIZE KiB) x 1024
+# (profiles/fused_mla_deepseek_v2_lite_kv4096.md), DeepSeek-V2-Lite shape; None where no counter run exists
+MEASURED_TRAFFIC = {
+    "b16_kv4096": 243688448,            # 100782.5, 36412.0
+}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--steps", type=int, default=2000)
@@ -86,7 +93,8 @@ def main():
            "warmup": args.warmup, "higher_is_better": False, "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
            "config": {"workload": "%s_b%d_kv%d" % (shape.name, B, Lk), "layers_rotated": n_layers},
            "roofline": {"bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
-                        "traffic": None, "algorithmic_bytes": alg,
+                        "traffic": MEASURED_TRAFFIC.get("b%d_kv%d" % (B, Lk)) if not args.ranges else None,
+                        "algorithmic_bytes": alg,
                         "kernel": "fused_mla_heads" if (B <= 1 and not args.ranges) else "fused_mla_decode"}}
     if not args.no_cpu_baseline:
         from oracle import mla_block as orc
